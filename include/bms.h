@@ -1,0 +1,152 @@
+/*
+ * bms.h -- C ABI of the MI355X-native matrix-based bulk minibatch sampler.
+ *
+ * The library samples k minibatches in one call ("bulk sampling", Sec. 4.1.4 / 4.2.4
+ * and Eq. 1 of arxiv 2311.02909): the per-minibatch selection matrices Q are stacked,
+ * P = Q A is formed against the CSR adjacency A resident in device memory, each row of
+ * P is sampled by inverse-transform sampling (SAMPLE), and the sampled adjacency of
+ * every layer is produced by row/column extraction (EXTRACT) -- the loop of Alg. 1.
+ * Inputs follow the problem statement at the head of Sec. 4: A in {0,1}^{n x n},
+ * Q^L given as the list of minibatch vertices, b, s; the output is the list of sampled
+ * adjacency matrices A^0..A^{L-1}, stacked over the k minibatches.
+ *
+ * Conventions
+ *   - Every function returns BMS_OK (0) or a negative BMS_E* code, never throws and
+ *     never aborts.  On error *out is left untouched; bms_last_error() gives detail.
+ *   - Hop h = 0..L-1 counts outward from the seed vertices: hop 0 is the paper's layer
+ *     L (the batch vertices), params[0] applies there.
+ *   - Pointers marked "device" are HIP device pointers on the current device; "host"
+ *     are ordinary host pointers.  `batches` may be either (detected).
+ *   - Work is enqueued on opts->stream; a call returns after the stream has drained
+ *     (it reads the output sizes back), so result pointers are immediately readable
+ *     by any stream that is ordered after that point.
+ *   - A handle is not thread-safe; different handles may be used from different threads.
+ *     One bms_csr must not be used by two sampling calls at the same time (it owns the
+ *     scratch memory both would use).
+ *   - Randomness is a stateless counter hash of (seed, hop, mb_base + minibatch index,
+ *     vertex, draw index): a call is a pure function of its arguments, and one call with
+ *     k minibatches equals k calls with one minibatch each and mb_base advanced.
+ */
+#ifndef BMS_H
+#define BMS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BMS_OK 0
+#define BMS_EINVAL (-1)  /* null pointer, k/b/L < 1, a parameter < 1, bad hop index, unknown flag   */
+#define BMS_ERANGE (-2)  /* seed vertex outside [0,n) or repeated inside one minibatch              */
+#define BMS_EFORMAT (-3) /* CSR not monotone, row not strictly ascending, column outside [0,n)      */
+#define BMS_ENOMEM (-4)  /* device or host allocation failed, or scratch limit too small            */
+#define BMS_EHIP (-5)    /* a HIP runtime call failed                                               */
+
+/* where the arrays handed to bms_csr_load live */
+#define BMS_HOST 0          /* host arrays, copied to the device                                    */
+#define BMS_DEVICE_BORROW 1 /* device arrays, used in place; caller keeps them alive and unchanged  */
+#define BMS_DEVICE_COPY 2   /* device arrays, copied                                                */
+
+/* bms_opts.flags */
+#define BMS_LADIES_SQUARED 1u /* LADIES column weight e_v^2 (definition in Sec. 2.2) instead of e_v   */
+#define BMS_PROFILE 2u        /* record per-stage device times, see bms_result_stage                  */
+
+typedef struct bms_csr bms_csr;       /* adjacency matrix on the device + reusable scratch            */
+typedef struct bms_result bms_result; /* owns every device buffer its hop views point to              */
+
+typedef struct bms_opts {   /* zero-initialised = defaults                                            */
+    void *stream;           /* hipStream_t to enqueue on; NULL = the null stream                      */
+    int32_t mb_base;        /* random-stream index of minibatch 0 (shards / single-minibatch replays) */
+    uint32_t flags;         /* BMS_* flags above                                                      */
+    bms_result *recycle;    /* result of an earlier call whose buffers may be reused; it becomes the  */
+                            /* returned handle (its old contents are overwritten); NULL = allocate    */
+    int64_t scratch_limit;  /* bytes of scratch the call may hold in the csr handle; 0 = 32 GiB        */
+} bms_opts;
+
+/*
+ * One hop of a bulk sample: the stacked sampled adjacency A^l of Eq. 1 in CSR form.
+ * Every pointer is a device pointer owned by the result, valid until bms_free(result)
+ * or until the result is recycled.
+ *   rows of minibatch i   : [mb_rowoff[i], mb_rowoff[i+1])   (hop 0: i*b .. (i+1)*b, caller's order;
+ *                                                             later hops: ascending vertex id)
+ *   row_vertex[r]         : global vertex of stacked row r (the frontier, i.e. the nonzero of Q's row)
+ *   rowptr[r]..rowptr[r+1]: entries of row r in col
+ *   col[e]                : column index LOCAL to the row's minibatch, ascending inside a row
+ *   col_vertex[mb_coloff[i] + c] : global vertex of local column c of minibatch i, ascending in c;
+ *                           these are the rows of the next hop ("empty columns removed", Sec. 4.1.3)
+ *   p_off/p_col/p_cnt     : LADIES only (else NULL, pnnz 0): the row of P = Q A of each minibatch before
+ *                           normalisation, columns ascending, p_cnt = e_v (Sec. 4.2.1)
+ */
+typedef struct bms_hop_view {
+    int64_t rows, nnz, ncols, pnnz;
+    const int64_t *mb_rowoff;  /* k+1   */
+    const int32_t *row_vertex; /* rows  */
+    const int64_t *rowptr;     /* rows+1 */
+    const int32_t *col;        /* nnz   */
+    const int64_t *mb_coloff;  /* k+1   */
+    const int32_t *col_vertex; /* ncols */
+    const int64_t *p_off;      /* k+1   */
+    const int32_t *p_col;      /* pnnz  */
+    const uint32_t *p_cnt;     /* pnnz  */
+} bms_hop_view;
+
+/*
+ * Adjacency matrix A (Sec. 4, input 1) as CSR: rowptr[n+1] int64, col[nnz] int32, each row strictly
+ * ascending, entries in [0,n).  Directed patterns and self-loops are accepted.  The structure is
+ * verified on the device; a violation returns BMS_EFORMAT.  `location` is one of BMS_HOST,
+ * BMS_DEVICE_BORROW, BMS_DEVICE_COPY.  The handle is released with bms_free.
+ */
+int bms_csr_load(const int64_t *rowptr, const int32_t *col, int64_t n, int64_t nnz, int location, bms_csr **out);
+
+/* n, nnz and the largest row length of a loaded matrix (any pointer may be NULL). */
+int bms_csr_info(const bms_csr *csr, int64_t *n, int64_t *nnz, int64_t *max_degree);
+
+/*
+ * Bulk node-wise (GraphSAGE) sampling, Sec. 4.1 with the stacking of Eq. 1.
+ *   batches : k*b seed vertices, row-major (minibatch i = batches[i*b .. (i+1)*b)), host or device;
+ *             distinct inside a minibatch, each in [0,n), else BMS_ERANGE.
+ *   fanouts : L host integers >= 1; fanouts[h] = s at hop h.  A row of degree <= s keeps every
+ *             neighbour; otherwise exactly s distinct neighbours are chosen uniformly (ITS without
+ *             replacement, Sec. 4.1.2).
+ * The next hop's rows are the distinct sampled vertices of the minibatch, ascending.
+ */
+int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *fanouts,
+                        int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out);
+
+/*
+ * Bulk layer-wise (LADIES) sampling, Sec. 4.2: per minibatch and hop, P = Q A over the whole
+ * frontier (p_cnt = number of frontier vertices adjacent to the column), s_per_layer[h] draws by ITS
+ * with replacement over the integer weights, duplicates removed (so ncols per minibatch <= s), then
+ * the frontier's rows restricted to the sampled columns (Q_R A Q_C, Sec. 4.2.3).
+ */
+int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *s_per_layer,
+                      int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out);
+
+/* k and L of a result (either pointer may be NULL). */
+int bms_result_info(const bms_result *res, int32_t *k, int32_t *L);
+
+/* Fill *view for hop 0 <= hop < L. */
+int bms_result_hop(const bms_result *res, int32_t hop, bms_hop_view *view);
+
+/*
+ * Per-stage device time of the call that produced `res` (only with BMS_PROFILE; measured with HIP
+ * events on the call's stream).  idx enumerates the recorded stages in launch order; returns
+ * BMS_EINVAL past the end.  *name points to a static string such as "nw_sample", *hop to the hop.
+ */
+int bms_result_stage(const bms_result *res, int32_t idx, const char **name, int32_t *hop, float *ms);
+
+/* Release a bms_csr or a bms_result (told apart by a tag in the handle); NULL is a no-op. */
+void bms_free(void *csr_or_result);
+
+/* Static description of an error code. */
+const char *bms_strerror(int code);
+
+/* Detail of the last error raised on the calling thread ("" if none). */
+const char *bms_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BMS_H */

@@ -1,0 +1,273 @@
+"""Thin binding over the C ABI of libbms.so (include/bms.h).
+
+Argument marshalling only: every step of the sampling path runs in the library's HIP
+kernels.  PyTorch supplies device memory for the inputs, the current stream, and
+zero-copy tensor views of the result buffers.  There is no CPU fallback: if the
+library has not been built, importing any entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbms.so")
+
+OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
+HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
+LADIES_SQUARED, PROFILE = 1, 2
+
+
+class BmsError(RuntimeError):
+    def __init__(self, code: int, detail: str):
+        super().__init__("bms error %d: %s" % (code, detail))
+        self.code = code
+
+
+class _Opts(C.Structure):
+    _fields_ = [("stream", C.c_void_p), ("mb_base", C.c_int32), ("flags", C.c_uint32),
+                ("recycle", C.c_void_p), ("scratch_limit", C.c_int64)]
+
+
+class _HopView(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("nnz", C.c_int64), ("ncols", C.c_int64), ("pnnz", C.c_int64),
+                ("mb_rowoff", C.c_void_p), ("row_vertex", C.c_void_p), ("rowptr", C.c_void_p), ("col", C.c_void_p),
+                ("mb_coloff", C.c_void_p), ("col_vertex", C.c_void_p), ("p_off", C.c_void_p), ("p_col", C.c_void_p),
+                ("p_cnt", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "or `python -m paper_2311_02909_amd.build` first" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        L.bms_csr_load.restype = C.c_int
+        L.bms_csr_load.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_void_p)]
+        L.bms_csr_info.restype = C.c_int
+        L.bms_csr_info.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        for fn in (L.bms_sample_nodewise, L.bms_sample_ladies):
+            fn.restype = C.c_int
+            fn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_uint64,
+                           C.POINTER(_Opts), C.POINTER(C.c_void_p)]
+        L.bms_result_info.restype = C.c_int
+        L.bms_result_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.bms_result_hop.restype = C.c_int
+        L.bms_result_hop.argtypes = [C.c_void_p, C.c_int32, C.POINTER(_HopView)]
+        L.bms_result_stage.restype = C.c_int
+        L.bms_result_stage.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_float)]
+        L.bms_free.restype = None
+        L.bms_free.argtypes = [C.c_void_p]
+        L.bms_strerror.restype = C.c_char_p
+        L.bms_strerror.argtypes = [C.c_int]
+        L.bms_last_error.restype = C.c_char_p
+        L.bms_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != OK:
+        detail = lib().bms_last_error().decode() or lib().bms_strerror(rc).decode()
+        raise BmsError(rc, detail)
+
+
+class _DevArray:
+    """A device buffer owned by a result, exposed through the CUDA array interface."""
+
+    def __init__(self, ptr: int, count: int, typestr: str, owner):
+        self.owner = owner
+        self.__cuda_array_interface__ = {"shape": (count,), "typestr": typestr, "data": (ptr, False), "version": 2}
+
+
+def _view(ptr, count: int, dtype: torch.dtype, owner) -> torch.Tensor:
+    if count == 0 or not ptr:
+        return torch.empty(0, dtype=dtype, device="cuda")
+    typestr = {torch.int32: "<i4", torch.int64: "<i8"}[dtype]
+    return torch.as_tensor(_DevArray(int(ptr), int(count), typestr, owner), device="cuda")
+
+
+@dataclass
+class Hop:
+    """One hop of a bulk sample (see bms_hop_view in include/bms.h). Tensors are views of
+    device memory owned by the result; p_cnt holds uint32 values in an int32 tensor."""
+    rows: int
+    nnz: int
+    ncols: int
+    pnnz: int
+    mb_rowoff: torch.Tensor
+    row_vertex: torch.Tensor
+    rowptr: torch.Tensor
+    col: torch.Tensor
+    mb_coloff: torch.Tensor
+    col_vertex: torch.Tensor
+    p_off: Optional[torch.Tensor]
+    p_col: Optional[torch.Tensor]
+    p_cnt: Optional[torch.Tensor]
+
+    def to_host(self) -> "HostHop":
+        def cp(t, dt=None):
+            if t is None:
+                return None
+            a = t.cpu().numpy()
+            return a.view(dt) if dt is not None else a
+        return HostHop(self.rows, self.nnz, self.ncols, cp(self.mb_rowoff), cp(self.row_vertex), cp(self.rowptr),
+                       cp(self.col), cp(self.mb_coloff), cp(self.col_vertex), cp(self.p_off), cp(self.p_col),
+                       cp(self.p_cnt, np.uint32))
+
+
+@dataclass
+class HostHop:
+    rows: int
+    nnz: int
+    ncols: int
+    mb_rowoff: np.ndarray
+    row_vertex: np.ndarray
+    rowptr: np.ndarray
+    col: np.ndarray
+    mb_coloff: np.ndarray
+    col_vertex: np.ndarray
+    p_off: Optional[np.ndarray] = None
+    p_col: Optional[np.ndarray] = None
+    p_cnt: Optional[np.ndarray] = None
+
+
+class Csr:
+    """Adjacency matrix resident on the device (bms_csr_load)."""
+
+    def __init__(self, rowptr: torch.Tensor, col: torch.Tensor):
+        if rowptr.dtype != torch.int64 or col.dtype != torch.int32:
+            raise TypeError("rowptr must be int64 and col int32")
+        rowptr, col = rowptr.contiguous(), col.contiguous()
+        n, nnz = rowptr.numel() - 1, col.numel()
+        if rowptr.is_cuda != col.is_cuda:
+            raise ValueError("rowptr and col must live on the same side")
+        self._keep = (rowptr, col)          # borrowed device arrays must stay alive
+        loc = DEVICE_BORROW if rowptr.is_cuda else HOST
+        h = C.c_void_p()
+        _check(lib().bms_csr_load(rowptr.data_ptr(), col.data_ptr() if nnz else None, n, nnz, loc, C.byref(h)))
+        self.handle = h
+        if loc == HOST:
+            self._keep = None
+        a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+        _check(lib().bms_csr_info(h, C.byref(a), C.byref(b), C.byref(c)))
+        self.n, self.nnz, self.max_degree = a.value, b.value, c.value
+
+    def free(self):
+        if getattr(self, "handle", None):
+            lib().bms_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class Result:
+    """Owner of the device buffers of one bulk sample (bms_result)."""
+
+    def __init__(self, handle):
+        self.handle = handle
+        k, L = C.c_int32(), C.c_int32()
+        _check(lib().bms_result_info(handle, C.byref(k), C.byref(L)))
+        self.k, self.L = k.value, L.value
+
+    def hop(self, h: int) -> Hop:
+        v = _HopView()
+        _check(lib().bms_result_hop(self.handle, h, C.byref(v)))
+        k = self.k
+        has_p = bool(v.p_off)
+        return Hop(
+            rows=v.rows, nnz=v.nnz, ncols=v.ncols, pnnz=v.pnnz,
+            mb_rowoff=_view(v.mb_rowoff, k + 1, torch.int64, self),
+            row_vertex=_view(v.row_vertex, v.rows, torch.int32, self),
+            rowptr=_view(v.rowptr, v.rows + 1, torch.int64, self),
+            col=_view(v.col, v.nnz, torch.int32, self),
+            mb_coloff=_view(v.mb_coloff, k + 1, torch.int64, self),
+            col_vertex=_view(v.col_vertex, v.ncols, torch.int32, self),
+            p_off=_view(v.p_off, k + 1, torch.int64, self) if has_p else None,
+            p_col=_view(v.p_col, v.pnnz, torch.int32, self) if has_p else None,
+            p_cnt=_view(v.p_cnt, v.pnnz, torch.int32, self) if has_p else None,
+        )
+
+    def hops(self) -> List[Hop]:
+        return [self.hop(h) for h in range(self.L)]
+
+    def sizes(self) -> List[Tuple[int, int, int]]:
+        """(rows, nnz, ncols) per hop without creating tensor views."""
+        out = []
+        v = _HopView()
+        for h in range(self.L):
+            _check(lib().bms_result_hop(self.handle, h, C.byref(v)))
+            out.append((v.rows, v.nnz, v.ncols))
+        return out
+
+    def stages(self) -> List[Tuple[str, int, float]]:
+        """(stage name, hop, milliseconds) in launch order; empty unless sampled with profile=True."""
+        out, i = [], 0
+        name, hop, ms = C.c_char_p(), C.c_int32(), C.c_float()
+        while lib().bms_result_stage(self.handle, i, C.byref(name), C.byref(hop), C.byref(ms)) == OK:
+            out.append((name.value.decode(), hop.value, ms.value))
+            i += 1
+        return out
+
+    def free(self):
+        if getattr(self, "handle", None):
+            lib().bms_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _sample(fn, csr: Csr, batches, params: Sequence[int], seed: int, mb_base, stream, recycle, flags, scratch_limit):
+    if isinstance(batches, np.ndarray):
+        batches = torch.from_numpy(np.ascontiguousarray(batches, dtype=np.int32))
+    if batches.dtype != torch.int32 or batches.dim() != 2:
+        raise TypeError("batches must be a k x b int32 tensor")
+    batches = batches.contiguous()
+    k, b = batches.shape
+    par = (C.c_int32 * len(params))(*[int(p) for p in params])
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    opts = _Opts(stream=stream, mb_base=mb_base, flags=flags,
+                 recycle=recycle.handle if recycle is not None else None, scratch_limit=scratch_limit)
+    out = C.c_void_p()
+    _check(fn(csr.handle, batches.data_ptr(), k, b, par, len(params), seed & 0xFFFFFFFFFFFFFFFF, C.byref(opts),
+              C.byref(out)))
+    if recycle is not None:
+        recycle.k, recycle.L = k, len(params)
+        return recycle
+    return Result(out)
+
+
+def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_base: int = 0, stream=None,
+                    recycle: Optional[Result] = None, profile: bool = False, scratch_limit: int = 0) -> Result:
+    """bms_sample_nodewise: bulk GraphSAGE sampling of the k x b seed batches."""
+    return _sample(lib().bms_sample_nodewise, csr, batches, fanouts, seed, mb_base, stream, recycle,
+                   PROFILE if profile else 0, scratch_limit)
+
+
+def sample_ladies(csr: Csr, batches, s_per_layer: Sequence[int], seed: int, *, mb_base: int = 0, squared: bool = False,
+                  stream=None, recycle: Optional[Result] = None, profile: bool = False,
+                  scratch_limit: int = 0) -> Result:
+    """bms_sample_ladies: bulk LADIES sampling of the k x b seed batches."""
+    flags = (PROFILE if profile else 0) | (LADIES_SQUARED if squared else 0)
+    return _sample(lib().bms_sample_ladies, csr, batches, s_per_layer, seed, mb_base, stream, recycle, flags,
+                   scratch_limit)

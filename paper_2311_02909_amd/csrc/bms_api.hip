@@ -1,0 +1,635 @@
+// C ABI of libbms.so: handle management and the per-hop orchestration of the kernels.
+#include "../../include/bms.h"
+#include "bms_device.h"
+#include "bms_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace bms;
+
+namespace {
+
+constexpr uint32_t kTagCsr = 0x31525343u;    // "CSR1"
+constexpr uint32_t kTagResult = 0x31534552u; // "RES1"
+constexpr int64_t kDefaultScratchLimit = 32LL << 30;
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                                                  \
+    do {                                                                                                               \
+        hipError_t e_ = (expr);                                                                                        \
+        if (e_ != hipSuccess)                                                                                          \
+            return fail(e_ == hipErrorOutOfMemory ? BMS_ENOMEM : BMS_EHIP, "%s failed: %s (%s:%d)", #expr,             \
+                        hipGetErrorString(e_), __FILE__, __LINE__);                                                    \
+    } while (0)
+
+#define BMS_TRY(expr)                                                                                                  \
+    do {                                                                                                               \
+        int rc_ = (expr);                                                                                              \
+        if (rc_ != BMS_OK)                                                                                             \
+            return rc_;                                                                                                \
+    } while (0)
+
+// Growable device buffer; contents are not preserved across growth.
+struct DevBuf {
+    void *p = nullptr;
+    size_t cap = 0;
+    bool grew = false; // set when the last ensure() reallocated
+    int ensure(size_t bytes)
+    {
+        grew = false;
+        if (bytes <= cap && p)
+            return BMS_OK;
+        if (p) {
+            (void)hipFree(p);
+            p = nullptr;
+            cap = 0;
+        }
+        if (bytes < 256)
+            bytes = 256;
+        HIP_TRY(hipMalloc(&p, bytes));
+        cap = bytes;
+        grew = true;
+        return BMS_OK;
+    }
+    void release()
+    {
+        if (p)
+            (void)hipFree(p);
+        p = nullptr;
+        cap = 0;
+    }
+    template <class T>
+    T *as() const
+    {
+        return static_cast<T *>(p);
+    }
+};
+
+struct StageTime {
+    const char *name;
+    int32_t hop;
+    hipEvent_t t0, t1;
+    float ms;
+};
+
+} // namespace
+
+struct bms_csr {
+    uint32_t tag = kTagCsr;
+    int device = 0;
+    int num_cu = 256;
+    int64_t n = 0, nnz = 0, max_degree = 0;
+    const int64_t *rowptr = nullptr;
+    const int32_t *col = nullptr;
+    DevBuf own_rowptr, own_col;
+    // scratch reused across calls
+    DevBuf vs_words, vs_prefix, vs_chunks;
+    bool vs_clean = false; // all words zero
+    DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars;
+    DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
+    bool ld_clean = false; // all dense counters zero
+    int64_t *host_pinned = nullptr; // 64 int64
+};
+
+struct HopBufs {
+    DevBuf mb_rowoff, row_vertex; // own storage only at hop 0; later hops alias the previous hop's columns
+    DevBuf rowptr, col, mb_coloff, col_vertex, p_off, p_col, p_cnt;
+    bms_hop_view view;
+};
+
+struct bms_result {
+    uint32_t tag = kTagResult;
+    int32_t k = 0, L = 0;
+    std::vector<HopBufs> hops;
+    std::vector<StageTime> stages;
+    std::vector<hipEvent_t> event_pool;
+    size_t events_used = 0;
+};
+
+namespace {
+
+void result_release(bms_result *r)
+{
+    for (auto &h : r->hops) {
+        h.mb_rowoff.release();
+        h.row_vertex.release();
+        h.rowptr.release();
+        h.col.release();
+        h.mb_coloff.release();
+        h.col_vertex.release();
+        h.p_off.release();
+        h.p_col.release();
+        h.p_cnt.release();
+    }
+    for (auto e : r->event_pool)
+        (void)hipEventDestroy(e);
+    r->event_pool.clear();
+}
+
+// Records one stage between two events when profiling is on.
+struct Profiler {
+    bms_result *res;
+    hipStream_t stream;
+    bool on;
+    int begin(const char *name, int32_t hop)
+    {
+        if (!on)
+            return BMS_OK;
+        while (res->event_pool.size() < res->events_used + 2) {
+            hipEvent_t e;
+            HIP_TRY(hipEventCreate(&e));
+            res->event_pool.push_back(e);
+        }
+        StageTime st{name, hop, res->event_pool[res->events_used], res->event_pool[res->events_used + 1], 0.f};
+        res->events_used += 2;
+        HIP_TRY(hipEventRecord(st.t0, stream));
+        res->stages.push_back(st);
+        return BMS_OK;
+    }
+    int end()
+    {
+        if (!on)
+            return BMS_OK;
+        HIP_TRY(hipEventRecord(res->stages.back().t1, stream));
+        return BMS_OK;
+    }
+    int finish()
+    {
+        if (!on)
+            return BMS_OK;
+        for (auto &st : res->stages)
+            HIP_TRY(hipEventElapsedTime(&st.ms, st.t0, st.t1));
+        return BMS_OK;
+    }
+};
+
+bool is_device_pointer(const void *p)
+{
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError(); // plain host memory reports an error: clear it
+        return false;
+    }
+    return attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged;
+}
+
+struct CallCtx {
+    bms_csr *csr;
+    bms_result *res;
+    bool fresh_result;
+    hipStream_t stream;
+    Launch launch;
+    int32_t k, b, L;
+    uint64_t seed;
+    uint32_t mb_base;
+    uint32_t flags;
+    int64_t scratch_limit;
+    VSet vs;
+};
+
+int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *params, int32_t L,
+                 const bms_opts *opts, bms_result **out)
+{
+    if (!csr || csr->tag != kTagCsr)
+        return fail(BMS_EINVAL, "csr is not a handle returned by bms_csr_load");
+    if (!batches || !params || !out)
+        return fail(BMS_EINVAL, "null argument");
+    if (k < 1 || b < 1 || L < 1)
+        return fail(BMS_EINVAL, "k, b and L must be >= 1 (k=%d b=%d L=%d)", k, b, L);
+    for (int32_t h = 0; h < L; ++h)
+        if (params[h] < 1)
+            return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
+    if (opts) {
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE))
+            return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
+        if (opts->recycle && opts->recycle->tag != kTagResult)
+            return fail(BMS_EINVAL, "opts->recycle is not a result handle");
+        if (opts->scratch_limit < 0)
+            return fail(BMS_EINVAL, "negative scratch_limit");
+    }
+    return BMS_OK;
+}
+
+// Sizes the per-minibatch vertex sets, allocates them inside the scratch limit and makes sure
+// they start all-zero.
+int setup_vset(CallCtx &c)
+{
+    bms_csr *csr = c.csr;
+    VSet &vs = c.vs;
+    vs.nl = (csr->n + kLineBits - 1) / kLineBits;
+    if (vs.nl < 1)
+        vs.nl = 1;
+    vs.nw = vs.nl * kLineWords;
+    vs.nc = (int32_t)((vs.nl + kChunkLines - 1) / kChunkLines);
+    const size_t wbytes = (size_t)c.k * vs.nw * sizeof(uint32_t);
+    const size_t pbytes = (size_t)c.k * vs.nl * sizeof(uint32_t);
+    const size_t cbytes = ((size_t)c.k * vs.nc + c.k) * sizeof(int64_t);
+    if ((int64_t)(wbytes + pbytes + cbytes) > c.scratch_limit)
+        return fail(BMS_ENOMEM,
+                    "vertex sets for k=%d minibatches over n=%lld vertices need %zu bytes of scratch, limit is %lld: "
+                    "raise bms_opts.scratch_limit or sample fewer minibatches per call",
+                    c.k, (long long)csr->n, wbytes + pbytes + cbytes, (long long)c.scratch_limit);
+    BMS_TRY(csr->vs_words.ensure(wbytes));
+    if (csr->vs_words.grew)
+        csr->vs_clean = false;
+    BMS_TRY(csr->vs_prefix.ensure(pbytes));
+    BMS_TRY(csr->vs_chunks.ensure(cbytes));
+    vs.words = csr->vs_words.as<uint32_t>();
+    vs.line_prefix = csr->vs_prefix.as<uint32_t>();
+    vs.chunk_off = csr->vs_chunks.as<int64_t>();
+    if (!csr->vs_clean)
+        HIP_TRY(hipMemsetAsync(vs.words, 0, csr->vs_words.cap, c.stream));
+    csr->vs_clean = false; // dirty until the call completes
+    return BMS_OK;
+}
+
+int begin_call(CallCtx &c, bms_csr *csr, int32_t k, int32_t b, int32_t L, uint64_t seed, const bms_opts *opts)
+{
+    c.csr = csr;
+    c.k = k;
+    c.b = b;
+    c.L = L;
+    c.seed = seed;
+    c.stream = opts ? (hipStream_t)opts->stream : nullptr;
+    c.mb_base = opts ? (uint32_t)opts->mb_base : 0u;
+    c.flags = opts ? opts->flags : 0u;
+    c.scratch_limit = (opts && opts->scratch_limit > 0) ? opts->scratch_limit : kDefaultScratchLimit;
+    c.launch = Launch{c.stream, csr->num_cu};
+    HIP_TRY(hipSetDevice(csr->device));
+    c.fresh_result = !(opts && opts->recycle);
+    if (c.fresh_result) {
+        c.res = new (std::nothrow) bms_result();
+        if (!c.res)
+            return fail(BMS_ENOMEM, "host allocation failed");
+    } else {
+        c.res = opts->recycle;
+    }
+    c.res->k = k;
+    c.res->L = L;
+    if ((int32_t)c.res->hops.size() < L)
+        c.res->hops.resize(L);
+    c.res->stages.clear();
+    c.res->events_used = 0;
+    if (!csr->host_pinned)
+        HIP_TRY(hipHostMalloc((void **)&csr->host_pinned, 64 * sizeof(int64_t), hipHostMallocDefault));
+    BMS_TRY(csr->scalars.ensure(64 * sizeof(int64_t)));
+    return BMS_OK;
+}
+
+int abort_call(CallCtx &c, int rc)
+{
+    (void)hipStreamSynchronize(c.stream);
+    if (c.fresh_result && c.res) {
+        result_release(c.res);
+        delete c.res;
+    }
+    c.res = nullptr;
+    return rc;
+}
+
+// Copies the seeds into hop 0's row_vertex, builds mb_rowoff = i*b and verifies the seeds.
+int stage_seeds(CallCtx &c, const int32_t *batches, Profiler &prof)
+{
+    HopBufs &h0 = c.res->hops[0];
+    const size_t nb = (size_t)c.k * c.b;
+    BMS_TRY(h0.row_vertex.ensure(nb * sizeof(int32_t)));
+    BMS_TRY(h0.mb_rowoff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+    BMS_TRY(prof.begin("seeds", 0));
+    HIP_TRY(hipMemcpyAsync(h0.row_vertex.p, batches, nb * sizeof(int32_t),
+                           is_device_pointer(batches) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c.stream));
+    launch_iota_offsets(c.launch, h0.mb_rowoff.as<int64_t>(), c.k, c.b);
+    int32_t *flag = reinterpret_cast<int32_t *>(c.csr->scalars.as<int64_t>() + 63);
+    HIP_TRY(hipMemsetAsync(c.csr->scalars.p, 0, 64 * sizeof(int64_t), c.stream));
+    launch_validate_seeds(c.launch, h0.row_vertex.as<int32_t>(), c.k, c.b, c.csr->n, c.vs, flag);
+    launch_clear_seed_bits(c.launch, h0.row_vertex.as<int32_t>(), c.k, c.b, c.csr->n, c.vs);
+    BMS_TRY(prof.end());
+    return BMS_OK;
+}
+
+// Device scalars -> pinned host copy, after draining the stream.
+int read_scalars(CallCtx &c)
+{
+    HIP_TRY(hipMemcpyAsync(c.csr->host_pinned, c.csr->scalars.p, 64 * sizeof(int64_t), hipMemcpyDeviceToHost,
+                           c.stream));
+    HIP_TRY(hipStreamSynchronize(c.stream));
+    return BMS_OK;
+}
+
+int seed_flag_error(CallCtx &c)
+{
+    const int32_t flag = (int32_t)(c.csr->host_pinned[63] & 0xFFFFFFFF);
+    if (flag & 1)
+        return fail(BMS_ERANGE, "a seed vertex lies outside [0, %lld)", (long long)c.csr->n);
+    if (flag & 2)
+        return fail(BMS_ERANGE, "a seed vertex is repeated inside one minibatch");
+    return BMS_OK;
+}
+
+// scalar slots: per hop 4 int64: [0] nnz, [1] ncols, [2] pnnz, [3] gathered D ; slot 63 = seed flag
+inline int64_t *slot(CallCtx &c, int32_t hop, int which) { return c.csr->scalars.as<int64_t>() + hop * 4 + which; }
+inline int64_t host_slot(CallCtx &c, int32_t hop, int which) { return c.csr->host_pinned[hop * 4 + which]; }
+
+constexpr int32_t kMaxHops = 15; // 4 scalar slots per hop in a 64-entry block
+
+int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fanouts)
+{
+    bms_csr *csr = c.csr;
+    Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
+    BMS_TRY(setup_vset(c));
+    BMS_TRY(stage_seeds(c, batches, prof));
+
+    int64_t rows_bound = (int64_t)c.k * c.b;
+    const int32_t *row_vertex = c.res->hops[0].row_vertex.as<int32_t>();
+    const int64_t *mb_rowoff = c.res->hops[0].mb_rowoff.as<int64_t>();
+    BMS_TRY(csr->mb_tileoff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+
+    for (int32_t h = 0; h < c.L; ++h) {
+        HopBufs &hb = c.res->hops[h];
+        const int64_t tiles_bound = rows_bound / kRowTile + c.k;
+        BMS_TRY(csr->row_beg.ensure((size_t)std::max<int64_t>(rows_bound, 1) * sizeof(int64_t)));
+        BMS_TRY(csr->row_deg.ensure((size_t)std::max<int64_t>(rows_bound, 1) * sizeof(int32_t)));
+        BMS_TRY(csr->tile_off.ensure((size_t)(tiles_bound + 2) * sizeof(int64_t)));
+        BMS_TRY(hb.rowptr.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
+        BMS_TRY(hb.mb_coloff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+
+        NwHop a{};
+        a.A_rowptr = csr->rowptr;
+        a.A_col = csr->col;
+        a.n = csr->n;
+        a.k = c.k;
+        a.s = fanouts[h];
+        a.hopkey = hop_key(c.seed, h);
+        a.mb_base = c.mb_base;
+        a.row_vertex = row_vertex;
+        a.mb_rowoff = mb_rowoff;
+        a.mb_tileoff = csr->mb_tileoff.as<int64_t>();
+        a.row_beg = csr->row_beg.as<int64_t>();
+        a.row_deg = csr->row_deg.as<int32_t>();
+        a.tile_off = csr->tile_off.as<int64_t>();
+        a.out_rowptr = hb.rowptr.as<int64_t>();
+        a.rows_bound = rows_bound;
+
+        BMS_TRY(prof.begin("nw_rows", h));
+        launch_plan_tiles(c.launch, mb_rowoff, c.k, kRowTile, a.mb_tileoff);
+        launch_nw_rows(c.launch, a);
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("scan_tiles", h));
+        launch_scan_i64(c.launch, a.tile_off, a.mb_tileoff + c.k, slot(c, h, 0), a.out_rowptr, mb_rowoff + c.k);
+        BMS_TRY(prof.end());
+
+        // the only host round trip of the hop: nnz sizes the column buffers
+        BMS_TRY(read_scalars(c));
+        if (h == 0)
+            BMS_TRY(seed_flag_error(c));
+        const int64_t nnz = host_slot(c, h, 0);
+        const int64_t ncols_bound = std::min<int64_t>(nnz, (int64_t)c.k * csr->n);
+        BMS_TRY(hb.col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
+        BMS_TRY(hb.col_vertex.ensure((size_t)std::max<int64_t>(ncols_bound, 1) * sizeof(int32_t)));
+        a.out_col = hb.col.as<int32_t>();
+
+        BMS_TRY(prof.begin("nw_sample", h));
+        launch_nw_sample(c.launch, a, c.vs);
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("vset_rank", h));
+        launch_vset_rank(c.launch, c.vs, c.k, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), slot(c, h, 1));
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("nw_relabel", h));
+        launch_nw_relabel(c.launch, a, c.vs);
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("vset_clear", h));
+        launch_vset_clear(c.launch, c.vs, c.k, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), ncols_bound);
+        BMS_TRY(prof.end());
+
+        hb.view = bms_hop_view{};
+        hb.view.nnz = nnz;
+        hb.view.mb_rowoff = mb_rowoff;
+        hb.view.row_vertex = row_vertex;
+        hb.view.rowptr = hb.rowptr.as<int64_t>();
+        hb.view.col = hb.col.as<int32_t>();
+        hb.view.mb_coloff = hb.mb_coloff.as<int64_t>();
+        hb.view.col_vertex = hb.col_vertex.as<int32_t>();
+
+        row_vertex = hb.col_vertex.as<int32_t>();
+        mb_rowoff = hb.mb_coloff.as<int64_t>();
+        rows_bound = ncols_bound;
+    }
+    BMS_TRY(read_scalars(c));
+    for (int32_t h = 0; h < c.L; ++h) {
+        bms_hop_view &v = c.res->hops[h].view;
+        v.ncols = host_slot(c, h, 1);
+        v.rows = h == 0 ? (int64_t)c.k * c.b : host_slot(c, h - 1, 1);
+    }
+    BMS_TRY(prof.finish());
+    csr->vs_clean = true;
+    return BMS_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int bms_csr_load(const int64_t *rowptr, const int32_t *col, int64_t n, int64_t nnz, int location, bms_csr **out)
+{
+    if (!rowptr || !out || (!col && nnz > 0))
+        return fail(BMS_EINVAL, "null argument");
+    if (n < 0 || nnz < 0 || n > 0x7FFFFFFFLL)
+        return fail(BMS_EINVAL, "n=%lld nnz=%lld out of range (vertex ids are int32)", (long long)n, (long long)nnz);
+    if (location != BMS_HOST && location != BMS_DEVICE_BORROW && location != BMS_DEVICE_COPY)
+        return fail(BMS_EINVAL, "unknown location %d", location);
+    bms_csr *c = new (std::nothrow) bms_csr();
+    if (!c)
+        return fail(BMS_ENOMEM, "host allocation failed");
+    auto bail = [&](int rc) {
+        bms_free(c);
+        return rc;
+    };
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess)
+        return bail(fail(BMS_EHIP, "hipGetDevice failed: %s", hipGetErrorString(e)));
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, c->device) == hipSuccess && prop.multiProcessorCount > 0)
+        c->num_cu = prop.multiProcessorCount;
+    c->n = n;
+    c->nnz = nnz;
+    if (location == BMS_DEVICE_BORROW) {
+        c->rowptr = rowptr;
+        c->col = col;
+    } else {
+        const hipMemcpyKind kind = location == BMS_HOST ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice;
+        int rc = c->own_rowptr.ensure((size_t)(n + 1) * sizeof(int64_t));
+        if (rc == BMS_OK)
+            rc = c->own_col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t));
+        if (rc != BMS_OK)
+            return bail(rc);
+        e = hipMemcpy(c->own_rowptr.p, rowptr, (size_t)(n + 1) * sizeof(int64_t), kind);
+        if (e == hipSuccess && nnz > 0)
+            e = hipMemcpy(c->own_col.p, col, (size_t)nnz * sizeof(int32_t), kind);
+        if (e != hipSuccess)
+            return bail(fail(BMS_EHIP, "copying the CSR arrays failed: %s", hipGetErrorString(e)));
+        c->rowptr = c->own_rowptr.as<int64_t>();
+        c->col = c->own_col.as<int32_t>();
+    }
+    // structure check on the device
+    int rc = c->scalars.ensure(64 * sizeof(int64_t));
+    if (rc != BMS_OK)
+        return bail(rc);
+    e = hipMemset(c->scalars.p, 0, 64 * sizeof(int64_t));
+    if (e != hipSuccess)
+        return bail(fail(BMS_EHIP, "hipMemset failed: %s", hipGetErrorString(e)));
+    Launch L{nullptr, c->num_cu};
+    int32_t *flag = reinterpret_cast<int32_t *>(c->scalars.as<int64_t>() + 1);
+    launch_csr_check(L, c->rowptr, c->col, n, nnz, flag, reinterpret_cast<unsigned long long *>(c->scalars.p));
+    int64_t host[2] = {0, 0};
+    e = hipMemcpy(host, c->scalars.p, sizeof(host), hipMemcpyDeviceToHost);
+    if (e != hipSuccess)
+        return bail(fail(BMS_EHIP, "CSR verification failed to run: %s", hipGetErrorString(e)));
+    const int32_t bad = (int32_t)(host[1] & 0xFFFFFFFF);
+    if (bad & 1)
+        return bail(fail(BMS_EFORMAT, "rowptr is not a monotone sequence from 0 to nnz"));
+    if (bad & 2)
+        return bail(fail(BMS_EFORMAT, "a column index lies outside [0, n)"));
+    if (bad & 4)
+        return bail(fail(BMS_EFORMAT, "a row is not strictly ascending (unsorted or duplicate column)"));
+    c->max_degree = host[0];
+    *out = c;
+    return BMS_OK;
+}
+
+int bms_csr_info(const bms_csr *csr, int64_t *n, int64_t *nnz, int64_t *max_degree)
+{
+    if (!csr || csr->tag != kTagCsr)
+        return fail(BMS_EINVAL, "not a csr handle");
+    if (n)
+        *n = csr->n;
+    if (nnz)
+        *nnz = csr->nnz;
+    if (max_degree)
+        *max_degree = csr->max_degree;
+    return BMS_OK;
+}
+
+int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *fanouts, int32_t L,
+                        uint64_t seed, const bms_opts *opts, bms_result **out)
+{
+    BMS_TRY(check_common(csr, batches, k, b, fanouts, L, opts, out));
+    if (L > kMaxHops)
+        return fail(BMS_EINVAL, "at most %d hops are supported", kMaxHops);
+    for (int32_t h = 0; h < L; ++h)
+        if (fanouts[h] > kMaxSampledFanout && (int64_t)fanouts[h] < csr->max_degree)
+            return fail(BMS_EINVAL,
+                        "fanout %d at hop %d: a fanout above %d must be >= the largest degree (%lld) so that no row "
+                        "needs sampling",
+                        fanouts[h], h, kMaxSampledFanout, (long long)csr->max_degree);
+    CallCtx c{};
+    int rc = begin_call(c, csr, k, b, L, seed, opts);
+    if (rc == BMS_OK)
+        rc = sample_nodewise_impl(c, batches, fanouts);
+    if (rc != BMS_OK)
+        return abort_call(c, rc);
+    *out = c.res;
+    return BMS_OK;
+}
+
+int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *s_per_layer,
+                      int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out)
+{
+    BMS_TRY(check_common(csr, batches, k, b, s_per_layer, L, opts, out));
+    (void)seed;
+    return fail(BMS_EINVAL, "layer-wise sampling is not available in this build");
+}
+
+int bms_result_info(const bms_result *res, int32_t *k, int32_t *L)
+{
+    if (!res || res->tag != kTagResult)
+        return fail(BMS_EINVAL, "not a result handle");
+    if (k)
+        *k = res->k;
+    if (L)
+        *L = res->L;
+    return BMS_OK;
+}
+
+int bms_result_hop(const bms_result *res, int32_t hop, bms_hop_view *view)
+{
+    if (!res || res->tag != kTagResult || !view)
+        return fail(BMS_EINVAL, "not a result handle, or null view");
+    if (hop < 0 || hop >= res->L)
+        return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
+    *view = res->hops[hop].view;
+    return BMS_OK;
+}
+
+int bms_result_stage(const bms_result *res, int32_t idx, const char **name, int32_t *hop, float *ms)
+{
+    if (!res || res->tag != kTagResult)
+        return fail(BMS_EINVAL, "not a result handle");
+    if (idx < 0 || idx >= (int32_t)res->stages.size())
+        return BMS_EINVAL; // past the end: not an error worth a message
+    const StageTime &st = res->stages[idx];
+    if (name)
+        *name = st.name;
+    if (hop)
+        *hop = st.hop;
+    if (ms)
+        *ms = st.ms;
+    return BMS_OK;
+}
+
+void bms_free(void *handle)
+{
+    if (!handle)
+        return;
+    const uint32_t tag = *static_cast<const uint32_t *>(handle);
+    if (tag == kTagCsr) {
+        bms_csr *c = static_cast<bms_csr *>(handle);
+        (void)hipSetDevice(c->device);
+        DevBuf *bufs[] = {&c->own_rowptr, &c->own_col,    &c->vs_words,   &c->vs_prefix,     &c->vs_chunks,
+                          &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars,
+                          &c->ld_counters, &c->ld_gather_off, &c->ld_row_mb, &c->ld_chunks, &c->ld_prefix,
+                          &c->ld_ptileoff, &c->ld_tilesum};
+        for (DevBuf *b : bufs)
+            b->release();
+        if (c->host_pinned)
+            (void)hipHostFree(c->host_pinned);
+        c->tag = 0;
+        delete c;
+    } else if (tag == kTagResult) {
+        bms_result *r = static_cast<bms_result *>(handle);
+        result_release(r);
+        r->tag = 0;
+        delete r;
+    }
+}
+
+const char *bms_strerror(int code)
+{
+    switch (code) {
+    case BMS_OK: return "success";
+    case BMS_EINVAL: return "invalid argument";
+    case BMS_ERANGE: return "seed vertex out of range or repeated inside a minibatch";
+    case BMS_EFORMAT: return "malformed CSR matrix";
+    case BMS_ENOMEM: return "out of memory or scratch limit too small";
+    case BMS_EHIP: return "HIP runtime error";
+    default: return "unknown error code";
+    }
+}
+
+const char *bms_last_error(void) { return g_err; }
+
+} // extern "C"

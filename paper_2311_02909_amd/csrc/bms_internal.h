@@ -1,0 +1,110 @@
+// Host-side declarations shared by the translation units of libbms.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bms {
+
+// Per-minibatch vertex set over [0,n): a bitmap in 64-byte lines plus, per line, the number of
+// set bits before it (the rank of the line's first vertex).  It serves as the dedup structure
+// ("remove empty columns", Sec. 4.1.3), as the ordered compaction that yields the next frontier,
+// and as the membership/rank lookup of column extraction (Sec. 4.2.3).
+// Invariant between calls: every word is zero.
+struct VSet {
+    uint32_t *words = nullptr;       // k * nw
+    uint32_t *line_prefix = nullptr; // k * nl
+    int64_t *chunk_off = nullptr;    // k * nc : set bits per chunk, then their exclusive scan
+    int64_t nw = 0, nl = 0;
+    int32_t nc = 0;
+};
+
+struct Launch {
+    hipStream_t stream;
+    int num_cu;
+};
+
+int grid_for(const Launch &L, int64_t blocks, int per_cu);
+
+// ---- common ----
+void launch_csr_check(const Launch &, const int64_t *rowptr, const int32_t *col, int64_t n, int64_t nnz,
+                      int32_t *flag /*device, zeroed*/, unsigned long long *maxdeg /*device, zeroed*/);
+void launch_validate_seeds(const Launch &, const int32_t *seeds, int32_t k, int32_t b, int64_t n, const VSet &,
+                           int32_t *flag);
+void launch_clear_seed_bits(const Launch &, const int32_t *seeds, int32_t k, int32_t b, int64_t n, const VSet &);
+void launch_iota_offsets(const Launch &, int64_t *off, int32_t k, int64_t step); // off[i] = i*step, i<=k
+void launch_plan_tiles(const Launch &, const int64_t *seg_off, int32_t k, int32_t tile, int64_t *seg_tileoff);
+// exclusive scan of vals[0..*count) in place, vals[*count] = total; total also stored to *total_out and,
+// when tail_ptr != nullptr, to tail_ptr[*tail_idx]
+void launch_scan_i64(const Launch &, int64_t *vals, const int64_t *count, int64_t *total_out, int64_t *tail_ptr,
+                     const int64_t *tail_idx);
+void launch_vset_rank(const Launch &, const VSet &, int32_t k, int64_t *mb_coloff /*k+1*/, int32_t *col_vertex,
+                      int64_t *ncols_out);
+void launch_vset_clear(const Launch &, const VSet &, int32_t k, const int64_t *mb_coloff, const int32_t *col_vertex,
+                       int64_t ncols_bound);
+
+// ---- node-wise ----
+struct NwHop {
+    const int64_t *A_rowptr;
+    const int32_t *A_col;
+    int64_t n;
+    int32_t k;
+    int32_t s;
+    uint64_t hopkey;
+    uint32_t mb_base;
+    const int32_t *row_vertex; // stacked frontier
+    const int64_t *mb_rowoff;  // k+1
+    int64_t *mb_tileoff;       // k+1
+    int64_t *row_beg;          // scratch, rows
+    int32_t *row_deg;          // scratch, rows
+    int64_t *tile_off;         // scratch, tiles+1
+    int64_t *out_rowptr;       // rows+1
+    int32_t *out_col;          // nnz
+    int64_t *nnz_out;          // device scalar
+    int64_t rows_bound;        // host-side upper bound of the row count
+    int32_t max_degree;
+};
+void launch_nw_rows(const Launch &, const NwHop &);
+void launch_nw_sample(const Launch &, const NwHop &, const VSet &);
+void launch_nw_relabel(const Launch &, const NwHop &, const VSet &);
+constexpr int32_t kMaxSampledFanout = 2048; // largest fanout that may be smaller than a row's degree
+
+// ---- LADIES ----
+struct LdHop {
+    const int64_t *A_rowptr;
+    const int32_t *A_col;
+    int64_t n;
+    int32_t k;
+    int32_t s;
+    int squared;
+    uint64_t hopkey;
+    uint32_t mb_base;
+    const int32_t *row_vertex;
+    const int64_t *mb_rowoff; // k+1
+    int64_t rows_bound;
+    // scratch
+    int64_t *row_beg;    // rows
+    int64_t *gather_off; // rows+1 : exclusive scan of degrees over the stacked rows
+    int32_t *row_mb;     // rows
+    int64_t *gather_total; // device scalar D
+    uint32_t *counters;  // k * n dense e_v
+};
+void launch_ld_rows(const Launch &, const LdHop &);
+void launch_ld_accumulate(const Launch &, const LdHop &, int64_t D);
+// P: count nonzero counters per (minibatch, chunk) -> p_off (k+1), total
+void launch_ld_p_count(const Launch &, const LdHop &, int64_t *chunk_off, int32_t nchunk, int64_t *p_off,
+                       int64_t *pnnz_out);
+void launch_ld_p_fill(const Launch &, const LdHop &, const int64_t *chunk_off, int32_t nchunk, const int64_t *p_off,
+                      int32_t *p_col, uint32_t *p_cnt);
+void launch_ld_prefix(const Launch &, const LdHop &, const int64_t *p_off, const uint32_t *p_cnt, int64_t pnnz,
+                      int64_t *p_tileoff, int64_t *tile_sum, uint64_t *prefix);
+void launch_ld_draw(const Launch &, const LdHop &, const int64_t *p_off, const int32_t *p_col, const uint64_t *prefix,
+                    const VSet &);
+void launch_ld_clear_counters(const Launch &, const LdHop &, const int64_t *p_off, const int32_t *p_col, int64_t pnnz);
+void launch_ld_extract_count(const Launch &, const LdHop &, const VSet &, int64_t D, int64_t *tile_sum,
+                             int64_t *out_rowptr);
+void launch_ld_extract_fill(const Launch &, const LdHop &, const VSet &, int64_t D, const int64_t *tile_off,
+                            int32_t *out_col);
+constexpr int kGatherTile = 4096; // gathered neighbours handled by one workgroup iteration
+constexpr int kPChunk = 4096;     // dense counters compacted by one workgroup
+
+} // namespace bms

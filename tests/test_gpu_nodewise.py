@@ -1,0 +1,156 @@
+"""Parity of the HIP node-wise sampler with the CPU oracle (bit-exact), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from conftest import random_batches, random_csr
+from parity import assert_hops_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mods():
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms, synth
+    assert torch.cuda.is_available()
+    return O, bms, synth
+
+
+def _run_both(mods, rowptr, col, batches, fanouts, seed, mb_base=0, device_csr=True):
+    O, bms, _ = mods
+    rp, cl = torch.from_numpy(rowptr), torch.from_numpy(col)
+    if device_csr:
+        rp, cl = rp.cuda(), cl.cuda()
+    csr = bms.Csr(rp, cl)
+    res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fanouts, seed, mb_base=mb_base)
+    ref = O.sample_nodewise(rowptr, col, batches, fanouts, seed, mb_base)
+    assert_hops_equal(res.hops(), ref, what="fanouts=%s seed=%d" % (fanouts, seed))
+    return csr, res, ref
+
+
+def test_tiny_workload(mods):
+    O, bms, synth = mods
+    g, batches, w = synth.make_workload("tiny_sage")
+    print("tiny_sage:", g.describe(), flush=True)
+    _run_both(mods, g.rowptr.numpy(), g.col.numpy(), batches.numpy(), w["params"], synth.SAMPLING_SEED)
+
+
+@pytest.mark.parametrize("fanouts", [(3,), (4, 4), (5, 5), (8, 3, 2), (15, 10, 5), (16, 2), (17, 3), (32, 2), (1, 1, 1)])
+def test_random_graph_all_lane_capacities(mods, fanouts):
+    # n and b chosen so that a minibatch spans several 256-row tiles with a ragged tail
+    rng = np.random.default_rng(sum(fanouts))
+    rowptr, col = random_csr(20000, 24.0, rng)
+    batches = random_batches(20000, 5, 300, rng)
+    _run_both(mods, rowptr, col, batches, fanouts, 7, mb_base=3)
+
+
+@pytest.mark.parametrize("fanouts", [(33, 2), (40, 40), (200, 3), (2048, 2)])
+def test_wide_fanouts_one_wave_per_row(mods, fanouts):
+    rng = np.random.default_rng(5)
+    rowptr, col = random_csr(6000, 60.0, rng)       # skewed: some rows have thousands of entries
+    assert np.diff(rowptr).max() > 2048
+    batches = random_batches(6000, 3, 70, rng)
+    _run_both(mods, rowptr, col, batches, fanouts, 11)
+
+
+def test_fanout_at_least_max_degree_is_exact(mods):
+    rng = np.random.default_rng(6)
+    rowptr, col = random_csr(3000, 10.0, rng)
+    maxdeg = int(np.diff(rowptr).max())
+    batches = random_batches(3000, 4, 33, rng)
+    for fan in ((maxdeg, maxdeg), (2**31 - 1, maxdeg + 7)):
+        _, res, ref = _run_both(mods, rowptr, col, batches, fan, 1)
+        # no randomness: a different seed gives the same result
+        _, res2, _ = _run_both(mods, rowptr, col, batches, fan, 2)
+        assert torch.equal(res.hop(1).col, res2.hop(1).col)
+
+
+def test_host_csr_host_batches_directed_with_loops(mods):
+    O, bms, _ = mods
+    rng = np.random.default_rng(8)
+    rowptr, col = random_csr(5000, 9.0, rng, symmetric=False, allow_loops=True)
+    batches = random_batches(5000, 6, 40, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr), torch.from_numpy(col))           # host arrays, copied
+    res = bms.sample_nodewise(csr, batches, (6, 4), 21)                       # host batches
+    assert_hops_equal(res.hops(), O.sample_nodewise(rowptr, col, batches, (6, 4), 21))
+
+
+def test_bulk_equals_stack_and_recycle(mods):
+    O, bms, _ = mods
+    rng = np.random.default_rng(9)
+    rowptr, col = random_csr(8000, 16.0, rng)
+    batches = random_batches(8000, 6, 100, rng)
+    csr, bulk, ref = _run_both(mods, rowptr, col, batches, (7, 5), 5, mb_base=40)
+    res = None
+    for i in range(6):        # k = 1 calls with the minibatch index advanced, reusing one result
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches[i:i + 1]).cuda(), (7, 5), 5, mb_base=40 + i,
+                                  recycle=res)
+        one = O.sample_nodewise(rowptr, col, batches[i:i + 1], (7, 5), 5, 40 + i)
+        assert_hops_equal(res.hops(), one, what="minibatch %d alone" % i)
+        for h in range(2):
+            r0, r1 = ref[h].mb_coloff[i], ref[h].mb_coloff[i + 1]
+            assert np.array_equal(res.hop(h).col_vertex.cpu().numpy(), ref[h].col_vertex[r0:r1])
+    # the same csr handle keeps working for a larger call afterwards (scratch regrown, sets clean)
+    res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (7, 5), 5, mb_base=40, recycle=res)
+    assert_hops_equal(res.hops(), ref)
+
+
+def test_degenerate_graphs_and_empty_frontiers(mods):
+    O, bms, _ = mods
+    # isolated vertices, a hop whose frontier becomes empty, a graph with no edges at all
+    rowptr = np.array([0, 0, 1, 1, 1], dtype=np.int64)
+    col = np.array([2], dtype=np.int32)
+    batches = np.array([[0, 1], [2, 0], [3, 2]], dtype=np.int32)
+    _run_both(mods, rowptr, col, batches, (3, 3, 3), 1)
+    rowptr0 = np.zeros(11, dtype=np.int64)
+    col0 = np.zeros(0, dtype=np.int32)
+    _run_both(mods, rowptr0, col0, np.array([[1, 2, 3]], dtype=np.int32), (2, 2), 1)
+    # one vertex, one self-loop
+    _run_both(mods, np.array([0, 1], dtype=np.int64), np.array([0], dtype=np.int32),
+              np.array([[0]], dtype=np.int32), (1, 1), 1)
+
+
+def test_error_codes(mods):
+    O, bms, _ = mods
+    rng = np.random.default_rng(10)
+    rowptr, col = random_csr(500, 8.0, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    good = random_batches(500, 2, 8, rng)
+    for bad, code in ((np.array([[1, 2, 1, 3]], dtype=np.int32), bms.ERANGE),
+                      (np.array([[1, 500]], dtype=np.int32), bms.ERANGE),
+                      (np.array([[-1, 4]], dtype=np.int32), bms.ERANGE)):
+        with pytest.raises(bms.BmsError) as e:
+            bms.sample_nodewise(csr, bad, (2,), 1)
+        assert e.value.code == code
+        # the handle is still usable and the vertex sets are clean again
+        res = bms.sample_nodewise(csr, good, (3, 2), 4)
+        assert_hops_equal(res.hops(), O.sample_nodewise(rowptr, col, good, (3, 2), 4))
+    with pytest.raises(bms.BmsError) as e:
+        bms.sample_nodewise(csr, good, (3, 0), 1)
+    assert e.value.code == bms.EINVAL
+    big = int(np.diff(rowptr).max())
+    # malformed matrices are refused at load time
+    unsorted = col.copy()
+    v = int(np.argmax(np.diff(rowptr)))
+    unsorted[rowptr[v]], unsorted[rowptr[v] + 1] = unsorted[rowptr[v] + 1], unsorted[rowptr[v]]
+    dup = col.copy()
+    dup[rowptr[v] + 1] = dup[rowptr[v]]
+    oob = col.copy()
+    oob[3] = 500
+    badptr = rowptr.copy()
+    badptr[5] = badptr[6] + 1
+    for rp, cl in ((rowptr, unsorted), (rowptr, dup), (rowptr, oob), (badptr, col)):
+        with pytest.raises(bms.BmsError) as e:
+            bms.Csr(torch.from_numpy(rp).cuda(), torch.from_numpy(cl).cuda())
+        assert e.value.code == bms.EFORMAT, big
+
+
+def test_profile_stages_are_reported(mods):
+    O, bms, _ = mods
+    rng = np.random.default_rng(12)
+    rowptr, col = random_csr(4000, 12.0, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    res = bms.sample_nodewise(csr, random_batches(4000, 4, 64, rng), (5, 5), 3, profile=True)
+    names = [s[0] for s in res.stages()]
+    assert names.count("nw_sample") == 2 and all(s[2] >= 0 for s in res.stages())
