@@ -440,6 +440,155 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     return BMS_OK;
 }
 
+int sample_ladies_impl(CallCtx &c, const int32_t *batches, const int32_t *s_per_layer)
+{
+    bms_csr *csr = c.csr;
+    Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
+    BMS_TRY(setup_vset(c));
+
+    // dense per-minibatch counters e_v, all zero between hops and between calls
+    const size_t cbytes = (size_t)c.k * (size_t)std::max<int64_t>(csr->n, 1) * sizeof(uint32_t);
+    const size_t vbytes = csr->vs_words.cap + csr->vs_prefix.cap + csr->vs_chunks.cap;
+    if ((int64_t)(cbytes + vbytes) > c.scratch_limit)
+        return fail(BMS_ENOMEM,
+                    "dense counters for k=%d minibatches over n=%lld vertices need %zu bytes of scratch (plus %zu for "
+                    "the vertex sets), limit is %lld: raise bms_opts.scratch_limit or sample fewer minibatches per call",
+                    c.k, (long long)csr->n, cbytes, vbytes, (long long)c.scratch_limit);
+    BMS_TRY(csr->ld_counters.ensure(cbytes));
+    if (csr->ld_counters.grew)
+        csr->ld_clean = false;
+    if (!csr->ld_clean)
+        HIP_TRY(hipMemsetAsync(csr->ld_counters.p, 0, csr->ld_counters.cap, c.stream));
+    csr->ld_clean = false;
+    const int32_t nchunk = (int32_t)((std::max<int64_t>(csr->n, 1) + kPChunk - 1) / kPChunk);
+    BMS_TRY(csr->ld_chunks.ensure(((size_t)c.k * nchunk + c.k) * sizeof(int64_t)));
+    BMS_TRY(csr->ld_ptileoff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+
+    BMS_TRY(stage_seeds(c, batches, prof));
+
+    int64_t rows_bound = (int64_t)c.k * c.b;
+    const int32_t *row_vertex = c.res->hops[0].row_vertex.as<int32_t>();
+    const int64_t *mb_rowoff = c.res->hops[0].mb_rowoff.as<int64_t>();
+
+    for (int32_t h = 0; h < c.L; ++h) {
+        HopBufs &hb = c.res->hops[h];
+        const int32_t s = s_per_layer[h];
+        const int64_t ncols_bound = (int64_t)c.k * std::min<int64_t>(s, std::max<int64_t>(csr->n, 1));
+        BMS_TRY(csr->row_beg.ensure((size_t)rows_bound * sizeof(int64_t)));
+        BMS_TRY(csr->ld_gather_off.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
+        BMS_TRY(csr->ld_row_mb.ensure((size_t)rows_bound * sizeof(int32_t)));
+        BMS_TRY(hb.rowptr.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
+        BMS_TRY(hb.mb_coloff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+        BMS_TRY(hb.col_vertex.ensure((size_t)ncols_bound * sizeof(int32_t)));
+        BMS_TRY(hb.p_off.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+
+        LdHop a{};
+        a.A_rowptr = csr->rowptr;
+        a.A_col = csr->col;
+        a.n = csr->n;
+        a.k = c.k;
+        a.s = s;
+        a.squared = (c.flags & BMS_LADIES_SQUARED) ? 1 : 0;
+        a.hopkey = hop_key(c.seed, h);
+        a.mb_base = c.mb_base;
+        a.row_vertex = row_vertex;
+        a.mb_rowoff = mb_rowoff;
+        a.rows_bound = rows_bound;
+        a.row_beg = csr->row_beg.as<int64_t>();
+        a.gather_off = csr->ld_gather_off.as<int64_t>();
+        a.row_mb = csr->ld_row_mb.as<int32_t>();
+        a.gather_tiles = csr->scalars.as<int64_t>() + 62;
+        a.counters = csr->ld_counters.as<uint32_t>();
+        a.p_chunks = csr->ld_chunks.as<int64_t>();
+        a.nchunk = nchunk;
+        a.p_off = hb.p_off.as<int64_t>();
+        a.p_tileoff = csr->ld_ptileoff.as<int64_t>();
+        a.out_rowptr = hb.rowptr.as<int64_t>();
+
+        // P = Q A
+        BMS_TRY(prof.begin("ld_rows", h));
+        launch_ld_rows(c.launch, a, slot(c, h, 3));
+        BMS_TRY(prof.end());
+        BMS_TRY(read_scalars(c)); // D sizes the tile arrays of the gathered order
+        if (h == 0)
+            BMS_TRY(seed_flag_error(c));
+        const int64_t D = host_slot(c, h, 3);
+        BMS_TRY(csr->tile_off.ensure((size_t)(D / kGatherTile + 3) * sizeof(int64_t)));
+        a.tile_off = csr->tile_off.as<int64_t>();
+        BMS_TRY(prof.begin("ld_accumulate", h));
+        launch_ld_accumulate(c.launch, a);
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("ld_p_count", h));
+        launch_ld_p_count(c.launch, a, slot(c, h, 2));
+        BMS_TRY(prof.end());
+        BMS_TRY(read_scalars(c)); // pnnz sizes P and its prefix sums
+        const int64_t pnnz = host_slot(c, h, 2);
+        BMS_TRY(hb.p_col.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(int32_t)));
+        BMS_TRY(hb.p_cnt.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(uint32_t)));
+        BMS_TRY(csr->ld_prefix.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(uint64_t)));
+        BMS_TRY(csr->ld_tilesum.ensure((size_t)(pnnz / kPTile + c.k + 1) * sizeof(uint64_t)));
+        a.p_col = hb.p_col.as<int32_t>();
+        a.p_cnt = hb.p_cnt.as<uint32_t>();
+        a.prefix = csr->ld_prefix.as<uint64_t>();
+        a.p_tilesum = csr->ld_tilesum.as<uint64_t>();
+        a.pnnz_bound = pnnz;
+        BMS_TRY(prof.begin("ld_p_fill", h));
+        launch_ld_p_fill(c.launch, a);
+        BMS_TRY(prof.end());
+        // NORM (implicit) + SAMPLE
+        BMS_TRY(prof.begin("ld_prefix", h));
+        launch_ld_prefix(c.launch, a);
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("ld_draw", h));
+        launch_ld_draw(c.launch, a, c.vs);
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("vset_rank", h));
+        launch_vset_rank(c.launch, c.vs, c.k, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), slot(c, h, 1));
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("ld_clear", h));
+        launch_ld_clear_counters(c.launch, a);
+        BMS_TRY(prof.end());
+        // EXTRACT
+        BMS_TRY(prof.begin("ld_extract_count", h));
+        launch_ld_extract_count(c.launch, a, c.vs, slot(c, h, 0));
+        BMS_TRY(prof.end());
+        BMS_TRY(read_scalars(c)); // nnz sizes the column buffer
+        const int64_t nnz = host_slot(c, h, 0);
+        BMS_TRY(hb.col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
+        a.out_col = hb.col.as<int32_t>();
+        BMS_TRY(prof.begin("ld_extract_fill", h));
+        launch_ld_extract_fill(c.launch, a, c.vs);
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("vset_clear", h));
+        launch_vset_clear(c.launch, c.vs, c.k, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), ncols_bound);
+        BMS_TRY(prof.end());
+
+        hb.view = bms_hop_view{};
+        hb.view.nnz = nnz;
+        hb.view.pnnz = pnnz;
+        hb.view.ncols = host_slot(c, h, 1); // written before the last read-back of this hop
+        hb.view.mb_rowoff = mb_rowoff;
+        hb.view.row_vertex = row_vertex;
+        hb.view.rowptr = hb.rowptr.as<int64_t>();
+        hb.view.col = hb.col.as<int32_t>();
+        hb.view.mb_coloff = hb.mb_coloff.as<int64_t>();
+        hb.view.col_vertex = hb.col_vertex.as<int32_t>();
+        hb.view.p_off = hb.p_off.as<int64_t>();
+        hb.view.p_col = hb.p_col.as<int32_t>();
+        hb.view.p_cnt = hb.p_cnt.as<uint32_t>();
+        hb.view.rows = h == 0 ? (int64_t)c.k * c.b : c.res->hops[h - 1].view.ncols;
+
+        row_vertex = hb.col_vertex.as<int32_t>();
+        mb_rowoff = hb.mb_coloff.as<int64_t>();
+        rows_bound = std::max<int64_t>(ncols_bound, 1);
+    }
+    HIP_TRY(hipStreamSynchronize(c.stream));
+    BMS_TRY(prof.finish());
+    csr->vs_clean = true;
+    csr->ld_clean = true;
+    return BMS_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -550,8 +699,16 @@ int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b
                       int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out)
 {
     BMS_TRY(check_common(csr, batches, k, b, s_per_layer, L, opts, out));
-    (void)seed;
-    return fail(BMS_EINVAL, "layer-wise sampling is not available in this build");
+    if (L > kMaxHops)
+        return fail(BMS_EINVAL, "at most %d hops are supported", kMaxHops);
+    CallCtx c{};
+    int rc = begin_call(c, csr, k, b, L, seed, opts);
+    if (rc == BMS_OK)
+        rc = sample_ladies_impl(c, batches, s_per_layer);
+    if (rc != BMS_OK)
+        return abort_call(c, rc);
+    *out = c.res;
+    return BMS_OK;
 }
 
 int bms_result_info(const bms_result *res, int32_t *k, int32_t *L)

@@ -126,4 +126,37 @@ __device__ inline int locate_segment(const int64_t *__restrict__ off, int k, int
     return lo;
 }
 
+// Rank of vertex g inside one minibatch's vertex set: set bits before it = line_prefix of its
+// 64-byte line + set bits before it inside the line.  `words`/`line_prefix` point at the
+// minibatch's own slice.
+__device__ inline int32_t vset_rank_of(const uint32_t *__restrict__ words, const uint32_t *__restrict__ line_prefix,
+                                       int32_t g)
+{
+    const int32_t line = g >> 9;
+    const int32_t w = (g >> 5) & (kLineWords - 1);
+    const uint4 *p = reinterpret_cast<const uint4 *>(words + (int64_t)line * kLineWords);
+    uint32_t rank = line_prefix[line];
+    const int nq = w >> 2; // whole 16-byte quarters before the word
+    for (int q = 0; q < nq; ++q) {
+        const uint4 x = p[q];
+        rank += __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w);
+    }
+    const uint4 x = p[nq];
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
+    const int rem = w & 3;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (q < rem)
+            rank += __popc(xs[q]);
+        else if (q == rem)
+            rank += __popc(xs[q] & ((1u << (g & 31)) - 1u));
+    }
+    return (int32_t)rank;
+}
+
+__device__ inline bool vset_test(const uint32_t *__restrict__ words, int32_t g)
+{
+    return (words[g >> 5] >> (g & 31)) & 1u;
+}
+
 } // namespace bms

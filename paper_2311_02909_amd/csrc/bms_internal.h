@@ -69,6 +69,10 @@ void launch_nw_relabel(const Launch &, const NwHop &, const VSet &);
 constexpr int32_t kMaxSampledFanout = 2048; // largest fanout that may be smaller than a row's degree
 
 // ---- LADIES ----
+constexpr int kGatherTile = 4096; // gathered neighbours handled by one workgroup iteration (16 per lane)
+constexpr int kPChunk = 4096;     // dense counters compacted by one workgroup (16 per lane)
+constexpr int kPTile = 1024;      // entries of P per prefix-sum tile
+
 struct LdHop {
     const int64_t *A_rowptr;
     const int32_t *A_col;
@@ -78,33 +82,39 @@ struct LdHop {
     int squared;
     uint64_t hopkey;
     uint32_t mb_base;
-    const int32_t *row_vertex;
-    const int64_t *mb_rowoff; // k+1
+    const int32_t *row_vertex; // stacked frontier
+    const int64_t *mb_rowoff;  // k+1
     int64_t rows_bound;
     // scratch
-    int64_t *row_beg;    // rows
-    int64_t *gather_off; // rows+1 : exclusive scan of degrees over the stacked rows
-    int32_t *row_mb;     // rows
-    int64_t *gather_total; // device scalar D
-    uint32_t *counters;  // k * n dense e_v
+    int64_t *row_beg;      // rows
+    int64_t *gather_off;   // rows+1 : exclusive scan of the frontier's degrees (the gathered order)
+    int32_t *row_mb;       // rows   : minibatch of each stacked row
+    int64_t *gather_tiles; // device scalar: ceil(D / kGatherTile)
+    uint32_t *counters;    // k * n  : dense e_v, all zero between hops
+    int64_t *p_chunks;     // k * nchunk + k
+    int32_t nchunk;        // ceil(n / kPChunk)
+    int64_t *tile_off;     // gather tiles + 1
+    // P (result buffers) and its prefix sums
+    int64_t *p_off;        // k+1
+    int32_t *p_col;
+    uint32_t *p_cnt;
+    int64_t *p_tileoff;    // k+1
+    uint64_t *p_tilesum;   // P tiles
+    uint64_t *prefix;      // pnnz, inclusive, restarts per minibatch
+    int64_t pnnz_bound;
+    // output
+    int64_t *out_rowptr;   // rows+1
+    int32_t *out_col;
 };
-void launch_ld_rows(const Launch &, const LdHop &);
-void launch_ld_accumulate(const Launch &, const LdHop &, int64_t D);
-// P: count nonzero counters per (minibatch, chunk) -> p_off (k+1), total
-void launch_ld_p_count(const Launch &, const LdHop &, int64_t *chunk_off, int32_t nchunk, int64_t *p_off,
-                       int64_t *pnnz_out);
-void launch_ld_p_fill(const Launch &, const LdHop &, const int64_t *chunk_off, int32_t nchunk, const int64_t *p_off,
-                      int32_t *p_col, uint32_t *p_cnt);
-void launch_ld_prefix(const Launch &, const LdHop &, const int64_t *p_off, const uint32_t *p_cnt, int64_t pnnz,
-                      int64_t *p_tileoff, int64_t *tile_sum, uint64_t *prefix);
-void launch_ld_draw(const Launch &, const LdHop &, const int64_t *p_off, const int32_t *p_col, const uint64_t *prefix,
-                    const VSet &);
-void launch_ld_clear_counters(const Launch &, const LdHop &, const int64_t *p_off, const int32_t *p_col, int64_t pnnz);
-void launch_ld_extract_count(const Launch &, const LdHop &, const VSet &, int64_t D, int64_t *tile_sum,
-                             int64_t *out_rowptr);
-void launch_ld_extract_fill(const Launch &, const LdHop &, const VSet &, int64_t D, const int64_t *tile_off,
-                            int32_t *out_col);
-constexpr int kGatherTile = 4096; // gathered neighbours handled by one workgroup iteration
-constexpr int kPChunk = 4096;     // dense counters compacted by one workgroup
+void launch_ld_rows(const Launch &, const LdHop &, int64_t *gather_total_out);
+void launch_ld_accumulate(const Launch &, const LdHop &);
+void launch_ld_p_count(const Launch &, const LdHop &, int64_t *pnnz_out);
+void launch_ld_p_fill(const Launch &, const LdHop &);
+void launch_ld_prefix(const Launch &, const LdHop &);
+void launch_ld_draw(const Launch &, const LdHop &, const VSet &);
+void launch_ld_clear_counters(const Launch &, const LdHop &);
+void launch_ld_extract_count(const Launch &, const LdHop &, const VSet &, int64_t *nnz_out);
+void launch_ld_extract_fill(const Launch &, const LdHop &, const VSet &);
+void launch_chunk_scan(const Launch &, int64_t *chunk_off, int32_t k, int32_t nc, int64_t *mb_off, int64_t *total_out);
 
 } // namespace bms

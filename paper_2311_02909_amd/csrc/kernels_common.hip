@@ -276,22 +276,22 @@ __global__ __launch_bounds__(256) void vset_count_kernel(VSet vs, int32_t k)
     }
 }
 
-// one workgroup per minibatch: exclusive scan of its chunk counts; mb_count[i] = total
-__global__ __launch_bounds__(1024) void vset_scan_kernel(VSet vs, int64_t *mb_count)
+// one workgroup per minibatch: exclusive scan of its nc chunk counts in place; mb_count[i] = total
+__global__ __launch_bounds__(1024) void chunk_scan_kernel(int64_t *chunk_off, int32_t nc, int64_t *mb_count)
 {
     __shared__ int64_t smem[16];
     __shared__ int64_t carry_s;
-    int64_t *c = vs.chunk_off + (int64_t)blockIdx.x * vs.nc;
+    int64_t *c = chunk_off + (int64_t)blockIdx.x * nc;
     if (threadIdx.x == 0)
         carry_s = 0;
     __syncthreads();
-    for (int32_t base = 0; base < vs.nc; base += 1024) {
+    for (int32_t base = 0; base < nc; base += 1024) {
         const int32_t q = base + threadIdx.x;
-        const int64_t v = q < vs.nc ? c[q] : 0;
+        const int64_t v = q < nc ? c[q] : 0;
         int64_t total;
         const int64_t ex = block_exclusive_scan<int64_t, 1024>(v, smem, total);
         const int64_t carry = carry_s;
-        if (q < vs.nc)
+        if (q < nc)
             c[q] = carry + ex;
         __syncthreads();
         if (threadIdx.x == 0)
@@ -367,15 +367,20 @@ __global__ __launch_bounds__(256) void vset_fill_kernel(VSet vs, int32_t k, cons
     }
 }
 
+void launch_chunk_scan(const Launch &L, int64_t *chunk_off, int32_t k, int32_t nc, int64_t *mb_off, int64_t *total_out)
+{
+    // per-minibatch totals are parked in the k entries after the k*nc chunk entries of chunk_off
+    int64_t *mb_count = chunk_off + (int64_t)k * nc;
+    hipLaunchKernelGGL(chunk_scan_kernel, dim3(k), dim3(1024), 0, L.stream, chunk_off, nc, mb_count);
+    hipLaunchKernelGGL(offsets_from_counts_kernel, dim3(1), dim3(1024), 0, L.stream, mb_count, k, mb_off, total_out);
+}
+
 void launch_vset_rank(const Launch &L, const VSet &vs, int32_t k, int64_t *mb_coloff, int32_t *col_vertex,
                       int64_t *ncols_out)
 {
     const int64_t nblocks = (int64_t)k * vs.nc;
     hipLaunchKernelGGL(vset_count_kernel, dim3(grid_for(L, nblocks, 16)), dim3(256), 0, L.stream, vs, k);
-    // per-minibatch totals are parked in the k entries after the k*nc chunk entries of chunk_off
-    int64_t *mb_count = vs.chunk_off + nblocks;
-    hipLaunchKernelGGL(vset_scan_kernel, dim3(k), dim3(1024), 0, L.stream, vs, mb_count);
-    hipLaunchKernelGGL(offsets_from_counts_kernel, dim3(1), dim3(1024), 0, L.stream, mb_count, k, mb_coloff, ncols_out);
+    launch_chunk_scan(L, vs.chunk_off, k, vs.nc, mb_coloff, ncols_out);
     hipLaunchKernelGGL(vset_fill_kernel, dim3(grid_for(L, nblocks, 16)), dim3(256), 0, L.stream, vs, k, mb_coloff,
                        col_vertex);
 }

@@ -240,31 +240,6 @@ void launch_nw_sample(const Launch &L, const NwHop &a, const VSet &vs)
 // ascending order, so a sampled vertex's local column is its rank in the vertex set:
 // line_prefix[line] + set bits before it inside its 64-byte line.
 // ---------------------------------------------------------------------------------------------
-__device__ inline int32_t vset_rank_of(const uint32_t *__restrict__ words, const uint32_t *__restrict__ line_prefix,
-                                       int32_t g)
-{
-    const int32_t line = g >> 9;
-    const int32_t w = (g >> 5) & (kLineWords - 1);
-    const uint4 *p = reinterpret_cast<const uint4 *>(words + (int64_t)line * kLineWords);
-    uint32_t rank = line_prefix[line];
-    const int nq = w >> 2; // whole 16-byte quarters before the word
-    for (int q = 0; q < nq; ++q) {
-        const uint4 x = p[q];
-        rank += __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w);
-    }
-    const uint4 x = p[nq];
-    const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
-    const int rem = w & 3;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        if (q < rem)
-            rank += __popc(xs[q]);
-        else if (q == rem)
-            rank += __popc(xs[q] & ((1u << (g & 31)) - 1u));
-    }
-    return (int32_t)rank;
-}
-
 __global__ __launch_bounds__(256) void nw_relabel_kernel(NwHop a, VSet vs)
 {
     const int64_t ntiles = a.mb_tileoff[a.k];

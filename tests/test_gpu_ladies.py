@@ -1,0 +1,107 @@
+"""Parity of the HIP layer-wise (LADIES) sampler with the CPU oracle (bit-exact), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from conftest import random_batches, random_csr
+from parity import assert_hops_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mods():
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms, synth
+    assert torch.cuda.is_available()
+    return O, bms, synth
+
+
+def _run_both(mods, rowptr, col, batches, s_per_layer, seed, mb_base=0, squared=False, csr=None):
+    O, bms, _ = mods
+    if csr is None:
+        csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    res = bms.sample_ladies(csr, torch.from_numpy(batches).cuda(), s_per_layer, seed, mb_base=mb_base, squared=squared)
+    ref = O.sample_ladies(rowptr, col, batches, s_per_layer, seed, mb_base, squared)
+    assert_hops_equal(res.hops(), ref, with_p=True, what="s=%s seed=%d squared=%s" % (s_per_layer, seed, squared))
+    return csr, res, ref
+
+
+def test_tiny_graph_layerwise(mods):
+    O, bms, synth = mods
+    g, batches, _ = synth.make_workload("tiny_sage")
+    _run_both(mods, g.rowptr.numpy(), g.col.numpy(), batches.numpy(), (64, 64), synth.SAMPLING_SEED)
+
+
+@pytest.mark.parametrize("s,squared", [((1,), False), ((16, 16), False), ((100, 50, 25), False), ((512, 512, 512), False),
+                                       ((64, 64), True), ((3000, 10), True)])
+def test_random_graph(mods, s, squared):
+    # gathered order spans many 4096-entry tiles with a ragged tail; P spans several chunks and tiles
+    rng = np.random.default_rng(len(s) * 100 + s[0])
+    rowptr, col = random_csr(30000, 30.0, rng)
+    batches = random_batches(30000, 5, 200, rng)
+    _run_both(mods, rowptr, col, batches, s, 17, mb_base=2, squared=squared)
+
+
+def test_directed_with_loops_and_host_inputs(mods):
+    O, bms, _ = mods
+    rng = np.random.default_rng(31)
+    rowptr, col = random_csr(5000, 9.0, rng, symmetric=False, allow_loops=True)
+    batches = random_batches(5000, 6, 40, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr), torch.from_numpy(col))
+    res = bms.sample_ladies(csr, batches, (30, 30), 21)
+    assert_hops_equal(res.hops(), O.sample_ladies(rowptr, col, batches, (30, 30), 21), with_p=True)
+
+
+def test_bulk_equals_stack_recycle_and_mixed_calls(mods):
+    O, bms, _ = mods
+    rng = np.random.default_rng(32)
+    rowptr, col = random_csr(8000, 16.0, rng)
+    batches = random_batches(8000, 4, 64, rng)
+    csr, bulk, ref = _run_both(mods, rowptr, col, batches, (40, 40), 5, mb_base=9)
+    res = None
+    for i in range(4):
+        res = bms.sample_ladies(csr, torch.from_numpy(batches[i:i + 1]).cuda(), (40, 40), 5, mb_base=9 + i, recycle=res)
+        assert_hops_equal(res.hops(), O.sample_ladies(rowptr, col, batches[i:i + 1], (40, 40), 5, 9 + i), with_p=True)
+    # node-wise and layer-wise calls share the handle's vertex sets: interleave them
+    nw = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (5, 5), 3)
+    assert_hops_equal(nw.hops(), O.sample_nodewise(rowptr, col, batches, (5, 5), 3))
+    _run_both(mods, rowptr, col, batches, (40, 40), 6, csr=csr)
+
+
+def test_degenerate_inputs_and_errors(mods):
+    O, bms, _ = mods
+    rowptr = np.array([0, 0, 0, 1, 2], dtype=np.int64)
+    col = np.array([3, 2], dtype=np.int32)
+    _run_both(mods, rowptr, col, np.array([[0, 1], [2, 0]], dtype=np.int32), (2, 2, 2), 1)
+    _run_both(mods, np.zeros(6, dtype=np.int64), np.zeros(0, dtype=np.int32), np.array([[1, 2]], dtype=np.int32),
+              (3, 3), 1)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    for bad in (np.array([[1, 1]], dtype=np.int32), np.array([[0, 4]], dtype=np.int32)):
+        with pytest.raises(bms.BmsError) as e:
+            bms.sample_ladies(csr, bad, (2,), 1)
+        assert e.value.code == bms.ERANGE
+    _run_both(mods, rowptr, col, np.array([[3, 2]], dtype=np.int32), (1,), 1, csr=csr)
+    with pytest.raises(bms.BmsError) as e:
+        bms.sample_ladies(csr, np.array([[3, 2]], dtype=np.int32), (1,), 1, scratch_limit=64)
+    assert e.value.code == bms.ENOMEM
+
+
+def test_paper_worked_example_on_the_gpu(mods):
+    # Sec. 2.2: batch {1,5}; e = [1,0,1,1,2,0]; with squared weights the array is [1,0,1,1,4,0]/7
+    O, bms, _ = mods
+    edges = [(0, 1), (2, 1), (3, 5), (4, 1), (4, 5)]
+    A = np.zeros((6, 6), dtype=np.int64)
+    for u, v in edges:
+        A[u, v] = A[v, u] = 1
+    rowptr = np.concatenate([[0], np.cumsum(A.sum(axis=1))]).astype(np.int64)
+    col = np.concatenate([np.nonzero(A[v])[0] for v in range(6)]).astype(np.int32)
+    batch = np.array([[1, 5]], dtype=np.int32)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    for seed in range(20):
+        res = bms.sample_ladies(csr, batch, (2,), seed, squared=True)
+        hop = res.hop(0).to_host()
+        e = np.zeros(6, dtype=np.int64)
+        e[hop.p_col] = hop.p_cnt
+        assert e.tolist() == [1, 0, 1, 1, 2, 0]
+        assert_hops_equal([hop], O.sample_ladies(rowptr, col, batch, (2,), seed, squared=True), with_p=True)
