@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the bulk minibatch sampler on one MI355X.
+
+A step is one bulk sampling call over one batch of synthetic input: all hops of the
+hot path (P = Q A, SAMPLE, EXTRACT) for k minibatches, with the CSR adjacency and the
+seed batches already resident in HBM.  Prints ONE JSON line:
+  value      sampled edges per second (sum of nnz over the hops / time per call)
+  roofline   the dominant kernel's algorithmic bytes / its measured duration vs 8 TB/s
+  cpu_baseline  the CPU oracle timed on this machine's host cores on the same workload
+The kernel durations come from HIP events that the library records on the call's own
+stream around each launch (BMS_PROFILE), during the timed steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of the dominant kernel, in bytes, scaled by the
+# factor a plain copy kernel of known size reads on the same counters (see profiles/); keyed by
+# (workload, kernel stage).  None = not measured for this build of the kernel.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0, gathered: int = 0) -> float:
+    """Bytes the method itself must move in one launch of `stage` for a hop of the given sizes.
+
+    Node-wise hop: 28 R + 16 E + 4 U in total (R stacked rows, E sampled edges, U distinct sampled
+    vertices): frontier id 4 R + two adjacent rowptr entries 16 R (nw_rows); output rowptr 8 R,
+    chosen neighbours read 4 E and staged 4 E (nw_sample); staged ids read 4 E, local columns
+    written 4 E (nw_relabel); next frontier written 4 U (vset_rank).
+    Layer-wise hop: 8 D + 8 C + 28 F + 4 nnz(A_S): frontier 4 F + rowptr 16 F (ld_rows); gathered
+    neighbours 4 D (ld_accumulate); P written 8 C (ld_p_fill); second pass over the rows 4 D
+    (ld_extract_count); output 8 F + 4 nnz (ld_extract_fill); sampled set 4 S (vset_rank).
+    Scratch traffic (degrees, vertex-set bitmaps, dense counters, tile sums) is not counted.
+    """
+    R, E, U = float(rows), float(nnz), float(ncols)
+    table = {
+        "nw_rows": 20 * R,
+        "nw_sample": 8 * R + 8 * E,
+        "nw_relabel": 8 * E,
+        "vset_rank": 4 * U,
+        "ld_rows": 20 * R,
+        "ld_accumulate": 4.0 * gathered,
+        "ld_p_fill": 8.0 * pnnz,
+        "ld_extract_count": 4.0 * gathered,
+        "ld_extract_fill": 8 * R + 4 * E,
+    }
+    return table.get(stage, 0.0)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large_sage",
+                    help="one of paper_2311_02909_amd.synth.WORKLOADS (default: the 111M-vertex node-wise config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run a plain device copy of MIB mebibytes 5 times "
+                         "(calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters against a known size)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2311_02909_amd import bms, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    if args.copy_probe:
+        src = torch.arange(args.copy_probe * (1 << 18), dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read_per_launch": src.numel() * 4,
+                          "copy_probe_bytes_written_per_launch": src.numel() * 4, "launches": 5}))
+        return 0
+    t0 = time.time()
+    g, batches, w = synth.make_workload(args.workload, device="cuda")
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    print("[bench] %s: %s (generated in %.1f s)" % (args.workload, g.describe(), gen_s), file=sys.stderr, flush=True)
+    csr = bms.Csr(g.rowptr, g.col)
+    nodewise = w["sampler"] == "nodewise"
+    fn = bms.sample_nodewise if nodewise else bms.sample_ladies
+    seed = synth.SAMPLING_SEED
+    stream = torch.cuda.current_stream()
+
+    res = None
+    for _ in range(args.warmup):
+        res = fn(csr, batches, w["params"], seed, recycle=res, profile=True)
+    torch.cuda.synchronize()
+    # timed region: exactly `steps` bulk calls, inputs resident in HBM
+    stage_ms, stage_n = {}, {}
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        res = fn(csr, batches, w["params"], seed, recycle=res, profile=True)
+        for name, hop, ms in res.stages():
+            stage_ms[(name, hop)] = stage_ms.get((name, hop), 0.0) + ms
+            stage_n[(name, hop)] = stage_n.get((name, hop), 0) + 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed / args.steps * 1e3
+
+    sizes = res.sizes()
+    edges = sum(nnz for _, nnz, _ in sizes)
+    k = w["k"]
+    value = edges / (ms_per_step * 1e-3)
+
+    # per-kernel totals over the hops (each stage is one kernel launch per hop, except the few
+    # multi-kernel stages named after their main kernel)
+    per_stage = {}
+    for (name, hop), ms in stage_ms.items():
+        d = per_stage.setdefault(name, {"ms": 0.0, "launches": 0, "bytes": 0.0})
+        d["ms"] += ms / stage_n[(name, hop)]
+        d["launches"] += 1
+        hv = res.hop(hop)
+        gathered = 0
+        if not nodewise:
+            deg = (g.rowptr[1:] - g.rowptr[:-1])
+            gathered = int(deg[hv.row_vertex.long()].sum().item())
+        d["bytes"] += algorithmic_bytes(name, hv.rows, hv.nnz, hv.ncols, hv.pnnz, gathered)
+    dominant = max(per_stage, key=lambda s: per_stage[s]["ms"])
+    dom = per_stage[dominant]
+    achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9 if dom["ms"] > 0 else 0.0
+    roofline = {
+        "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 5),
+        "traffic": MEASURED_TRAFFIC.get((args.workload, dominant)),
+        "avg_launch_ms": round(dom["ms"] / dom["launches"], 4), "launches_per_step": dom["launches"],
+        "algorithmic_bytes_per_step": int(dom["bytes"]),
+        "all_kernels_ms_per_step": {s: round(v["ms"], 4) for s, v in sorted(per_stage.items())},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import bms_oracle as O
+        rp, cl, bt = g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy()
+        cores = O.set_threads(0)
+        ofn = O.sample_nodewise if nodewise else O.sample_ladies
+        t1 = time.perf_counter()
+        ofn(rp, cl, bt, w["params"], seed, collect=False)
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": round(edges / cpu_s, 1), "unit": "edges/s", "cores": cores, "kind": "oracle",
+               "sample": "the same %d minibatches, one oracle call (%.2f s), OpenMP over minibatches" % (k, cpu_s)}
+
+    out = {
+        "metric": "sampled_edges_per_sec", "value": round(value, 1), "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "minibatches_per_sec": round(k / (ms_per_step * 1e-3), 1),
+        "config": {"workload": args.workload, "sampler": w["sampler"], "params": list(w["params"]),
+                   "batch": w["batch"], "k": k, "n": g.n, "nnz": g.nnz, "max_degree": g.max_degree,
+                   "rows_nnz_cols_per_hop": [list(s) for s in sizes]},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
