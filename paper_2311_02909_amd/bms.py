@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libbms.so")
 
 OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
-LADIES_SQUARED, PROFILE = 1, 2
+LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP = 1, 2, 4, 8
 
 
 class BmsError(RuntimeError):
@@ -258,10 +258,13 @@ def _sample(fn, csr: Csr, batches, params: Sequence[int], seed: int, mb_base, st
 
 
 def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_base: int = 0, stream=None,
-                    recycle: Optional[Result] = None, profile: bool = False, scratch_limit: int = 0) -> Result:
-    """bms_sample_nodewise: bulk GraphSAGE sampling of the k x b seed batches."""
-    return _sample(lib().bms_sample_nodewise, csr, batches, fanouts, seed, mb_base, stream, recycle,
-                   PROFILE if profile else 0, scratch_limit)
+                    recycle: Optional[Result] = None, profile: bool = False, scratch_limit: int = 0,
+                    extract: Optional[str] = None) -> Result:
+    """bms_sample_nodewise: bulk GraphSAGE sampling of the k x b seed batches.
+    extract: None (library's choice), "buckets" or "bitmap" -- which EXTRACT kernels run; same result."""
+    flags = (PROFILE if profile else 0) | {None: 0, "buckets": EXTRACT_BUCKETS, "bitmap": EXTRACT_BITMAP}[extract]
+    return _sample(lib().bms_sample_nodewise, csr, batches, fanouts, seed, mb_base, stream, recycle, flags,
+                   scratch_limit)
 
 
 def sample_ladies(csr: Csr, batches, s_per_layer: Sequence[int], seed: int, *, mb_base: int = 0, squared: bool = False,

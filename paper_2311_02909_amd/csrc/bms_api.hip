@@ -102,6 +102,7 @@ struct bms_csr {
     bool vs_clean = false; // all words zero
     DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars;
     DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
+    DevBuf dd_pairs, dd_uniq, dd_edgeoff, dd_count; // bucket EXTRACT
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
 };
@@ -216,7 +217,7 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
     if (opts) {
-        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE))
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP))
             return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
         if (opts->recycle && opts->recycle->tag != kTagResult)
             return fail(BMS_EINVAL, "opts->recycle is not a result handle");
@@ -304,7 +305,7 @@ int abort_call(CallCtx &c, int rc)
 }
 
 // Copies the seeds into hop 0's row_vertex, builds mb_rowoff = i*b and verifies the seeds.
-int stage_seeds(CallCtx &c, const int32_t *batches, Profiler &prof)
+int stage_seeds(CallCtx &c, const int32_t *batches, Profiler &prof, bool use_vset = true)
 {
     HopBufs &h0 = c.res->hops[0];
     const size_t nb = (size_t)c.k * c.b;
@@ -316,8 +317,12 @@ int stage_seeds(CallCtx &c, const int32_t *batches, Profiler &prof)
     launch_iota_offsets(c.launch, h0.mb_rowoff.as<int64_t>(), c.k, c.b);
     int32_t *flag = reinterpret_cast<int32_t *>(c.csr->scalars.as<int64_t>() + 63);
     HIP_TRY(hipMemsetAsync(c.csr->scalars.p, 0, 64 * sizeof(int64_t), c.stream));
-    launch_validate_seeds(c.launch, h0.row_vertex.as<int32_t>(), c.k, c.b, c.csr->n, c.vs, flag);
-    launch_clear_seed_bits(c.launch, h0.row_vertex.as<int32_t>(), c.k, c.b, c.csr->n, c.vs);
+    if (use_vset) {
+        launch_validate_seeds(c.launch, h0.row_vertex.as<int32_t>(), c.k, c.b, c.csr->n, c.vs, flag);
+        launch_clear_seed_bits(c.launch, h0.row_vertex.as<int32_t>(), c.k, c.b, c.csr->n, c.vs);
+    } else {
+        launch_validate_seeds_sorted(c.launch, h0.row_vertex.as<int32_t>(), c.k, c.b, c.csr->n, flag);
+    }
     BMS_TRY(prof.end());
     return BMS_OK;
 }
@@ -351,8 +356,24 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
 {
     bms_csr *csr = c.csr;
     Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
-    BMS_TRY(setup_vset(c));
-    BMS_TRY(stage_seeds(c, batches, prof));
+    // EXTRACT strategy: per-minibatch bitmaps over [0,n) in HBM pay off while a bitmap stays cache
+    // sized; beyond that the id-range bucket kernel (one workgroup per minibatch, bitmap in LDS) wins.
+    const int64_t nbuckets = (csr->n + (1LL << kBucketBits) - 1) >> kBucketBits;
+    bool buckets = csr->n > (1LL << 24);
+    if (c.flags & BMS_EXTRACT_BUCKETS)
+        buckets = true;
+    if (c.flags & BMS_EXTRACT_BITMAP)
+        buckets = false;
+    if (nbuckets > kMaxBuckets)
+        buckets = false;
+    const bool seeds_by_sort = buckets && c.b <= kMaxSortedSeeds;
+    if (!buckets || !seeds_by_sort)
+        BMS_TRY(setup_vset(c));
+    BMS_TRY(stage_seeds(c, batches, prof, !seeds_by_sort));
+    if (buckets) {
+        BMS_TRY(csr->dd_edgeoff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+        BMS_TRY(csr->dd_count.ensure((size_t)c.k * sizeof(int64_t)));
+    }
 
     int64_t rows_bound = (int64_t)c.k * c.b;
     const int32_t *row_vertex = c.res->hops[0].row_vertex.as<int32_t>();
@@ -404,17 +425,36 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         a.out_col = hb.col.as<int32_t>();
 
         BMS_TRY(prof.begin("nw_sample", h));
-        launch_nw_sample(c.launch, a, c.vs);
+        launch_nw_sample(c.launch, a, c.vs, !buckets);
         BMS_TRY(prof.end());
-        BMS_TRY(prof.begin("vset_rank", h));
-        launch_vset_rank(c.launch, c.vs, c.k, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), slot(c, h, 1));
-        BMS_TRY(prof.end());
-        BMS_TRY(prof.begin("nw_relabel", h));
-        launch_nw_relabel(c.launch, a, c.vs);
-        BMS_TRY(prof.end());
-        BMS_TRY(prof.begin("vset_clear", h));
-        launch_vset_clear(c.launch, c.vs, c.k, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), ncols_bound);
-        BMS_TRY(prof.end());
+        if (buckets) {
+            BMS_TRY(csr->dd_pairs.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
+            BMS_TRY(csr->dd_uniq.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
+            DedupArgs d{};
+            d.k = c.k;
+            d.nbuckets = (int32_t)nbuckets;
+            d.mb_edgeoff = csr->dd_edgeoff.as<int64_t>();
+            d.col = a.out_col;
+            d.pairs = csr->dd_pairs.as<uint64_t>();
+            d.uniq = csr->dd_uniq.as<int32_t>();
+            d.mb_count = csr->dd_count.as<int64_t>();
+            BMS_TRY(prof.begin("nw_dedup_bucket", h));
+            launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
+                                   hb.col_vertex.as<int32_t>(), slot(c, h, 1), ncols_bound);
+            BMS_TRY(prof.end());
+        } else {
+            BMS_TRY(prof.begin("vset_rank", h));
+            launch_vset_rank(c.launch, c.vs, c.k, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(),
+                             slot(c, h, 1));
+            BMS_TRY(prof.end());
+            BMS_TRY(prof.begin("nw_relabel", h));
+            launch_nw_relabel(c.launch, a, c.vs);
+            BMS_TRY(prof.end());
+            BMS_TRY(prof.begin("vset_clear", h));
+            launch_vset_clear(c.launch, c.vs, c.k, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(),
+                              ncols_bound);
+            BMS_TRY(prof.end());
+        }
 
         hb.view = bms_hop_view{};
         hb.view.nnz = nnz;
@@ -436,7 +476,8 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         v.rows = h == 0 ? (int64_t)c.k * c.b : host_slot(c, h - 1, 1);
     }
     BMS_TRY(prof.finish());
-    csr->vs_clean = true;
+    if (!buckets || !seeds_by_sort)
+        csr->vs_clean = true;
     return BMS_OK;
 }
 
@@ -759,7 +800,7 @@ void bms_free(void *handle)
         DevBuf *bufs[] = {&c->own_rowptr, &c->own_col,    &c->vs_words,   &c->vs_prefix,     &c->vs_chunks,
                           &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars,
                           &c->ld_counters, &c->ld_gather_off, &c->ld_row_mb, &c->ld_chunks, &c->ld_prefix,
-                          &c->ld_ptileoff, &c->ld_tilesum};
+                          &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count};
         for (DevBuf *b : bufs)
             b->release();
         if (c->host_pinned)

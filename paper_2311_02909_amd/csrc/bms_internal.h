@@ -64,8 +64,29 @@ struct NwHop {
     int32_t max_degree;
 };
 void launch_nw_rows(const Launch &, const NwHop &);
-void launch_nw_sample(const Launch &, const NwHop &, const VSet &);
+// set_bits: also mark every sampled vertex in the minibatch's vertex set (bitmap EXTRACT path)
+void launch_nw_sample(const Launch &, const NwHop &, const VSet &, bool set_bits);
 void launch_nw_relabel(const Launch &, const NwHop &, const VSet &);
+
+// EXTRACT by id-range buckets, one workgroup per minibatch (large vertex ranges)
+constexpr int kBucketBits = 18;     // ids per bucket = 2^18 (a 32 KB bitmap in LDS)
+constexpr int kMaxBuckets = 3968;   // bucket cursors that fit beside the bitmap in 64 KB of LDS
+struct DedupArgs {
+    int32_t k;
+    int32_t nbuckets;    // ceil(n / 2^kBucketBits) <= kMaxBuckets
+    int64_t *mb_edgeoff; // k+1, scratch
+    int32_t *col;        // in: sampled global ids (stacked), out: local column indices
+    uint64_t *pairs;     // nnz, scratch: (id << 32 | position in minibatch), partitioned by bucket
+    int32_t *uniq;       // nnz, scratch: distinct ids of minibatch i ascending, from mb_edgeoff[i]
+    int64_t *mb_count;   // k, scratch: distinct ids per minibatch
+};
+void launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,
+                            int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t ncols_bound);
+void launch_offsets_from_counts(const Launch &, const int64_t *mb_count, int32_t k, int64_t *mb_off,
+                                int64_t *total_out);
+// seed check without a vertex set: range test + per-minibatch sort in LDS (b <= kMaxSortedSeeds)
+constexpr int32_t kMaxSortedSeeds = 8192;
+void launch_validate_seeds_sorted(const Launch &, const int32_t *seeds, int32_t k, int32_t b, int64_t n, int32_t *flag);
 constexpr int32_t kMaxSampledFanout = 2048; // largest fanout that may be smaller than a row's degree
 
 // ---- LADIES ----

@@ -367,6 +367,67 @@ __global__ __launch_bounds__(256) void vset_fill_kernel(VSet vs, int32_t k, cons
     }
 }
 
+void launch_offsets_from_counts(const Launch &L, const int64_t *mb_count, int32_t k, int64_t *mb_off, int64_t *total_out)
+{
+    hipLaunchKernelGGL(offsets_from_counts_kernel, dim3(1), dim3(1024), 0, L.stream, mb_count, k, mb_off, total_out);
+}
+
+// Seed verification without a vertex set: one workgroup sorts a minibatch's b seeds in LDS
+// (bitonic network over the next power of two, padded with distinct values above every id) and
+// looks for equal neighbours.  flag bit 0: out of range, bit 1: repeated.
+__global__ __launch_bounds__(1024) void validate_seeds_sorted_kernel(const int32_t *__restrict__ seeds, int32_t k,
+                                                                     int32_t b, int32_t m /*pow2 >= b*/, int64_t n,
+                                                                     int32_t *flag)
+{
+    __shared__ uint32_t key[kMaxSortedSeeds];
+    for (int32_t i = blockIdx.x; i < k; i += gridDim.x) {
+        int bad = 0;
+        for (int32_t j = threadIdx.x; j < m; j += 1024) {
+            uint32_t v = 0x80000000u + (uint32_t)j; // padding: distinct, above every valid id
+            if (j < b) {
+                const int32_t sv = seeds[(int64_t)i * b + j];
+                if (sv < 0 || (int64_t)sv >= n)
+                    bad |= 1; // keeps its padding value so that it cannot fake a repeat
+                else
+                    v = (uint32_t)sv;
+            }
+            key[j] = v;
+        }
+        __syncthreads();
+        for (int32_t size = 2; size <= m; size <<= 1) {
+            for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                for (int32_t j = threadIdx.x; j < m; j += 1024) {
+                    const int32_t partner = j ^ stride;
+                    if (partner > j) {
+                        const bool up = (j & size) == 0;
+                        const uint32_t x = key[j], y = key[partner];
+                        if ((x > y) == up) {
+                            key[j] = y;
+                            key[partner] = x;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        for (int32_t j = threadIdx.x; j + 1 < m; j += 1024)
+            if (key[j] == key[j + 1])
+                bad |= 2;
+        if (bad)
+            atomicOr(flag, bad);
+        __syncthreads();
+    }
+}
+
+void launch_validate_seeds_sorted(const Launch &L, const int32_t *seeds, int32_t k, int32_t b, int64_t n, int32_t *flag)
+{
+    int32_t m = 2;
+    while (m < b)
+        m <<= 1;
+    hipLaunchKernelGGL(validate_seeds_sorted_kernel, dim3(grid_for(L, k, 2)), dim3(1024), 0, L.stream, seeds, k, b, m, n,
+                       flag);
+}
+
 void launch_chunk_scan(const Launch &L, int64_t *chunk_off, int32_t k, int32_t nc, int64_t *mb_off, int64_t *total_out)
 {
     // per-minibatch totals are parked in the k entries after the k*nc chunk entries of chunk_off

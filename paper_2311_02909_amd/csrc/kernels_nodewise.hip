@@ -65,7 +65,7 @@ void launch_nw_rows(const Launch &L, const NwHop &a)
 // ascending order, turns it into the position; the list is kept sorted by one bubble pass,
 // which also leaves the row's output in ascending column order.
 // ---------------------------------------------------------------------------------------------
-template <int S>
+template <int S, bool SET>
 __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
 {
     __shared__ int32_t stage[kRowTile * S];
@@ -126,7 +126,8 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
         for (int32_t e = tid; e < tot; e += kRowTile) {
             const int32_t g = stage[e];
             a.out_col[base + e] = g;
-            atomicOr(&words[g >> 5], 1u << (g & 31));
+            if (SET)
+                atomicOr(&words[g >> 5], 1u << (g & 31));
         }
         __syncthreads();
     }
@@ -138,6 +139,7 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
 // positions that the pick steps over is the count of list entries p_t with p_t - t <= x
 // (p_t - t = unchosen positions before p_t, non-decreasing in t), found by binary search.
 // ---------------------------------------------------------------------------------------------
+template <bool SET>
 __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet vs)
 {
     __shared__ uint32_t chosen_all[(kRowTile / kWave) * kMaxSampledFanout];
@@ -177,7 +179,8 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
                 for (int32_t e = lane; e < deg; e += kWave) {
                     const int32_t g = src[e];
                     dst[e] = g;
-                    atomicOr(&words[g >> 5], 1u << (g & 31));
+                    if (SET)
+                        atomicOr(&words[g >> 5], 1u << (g & 31));
                 }
                 continue;
             }
@@ -212,7 +215,8 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
             for (int32_t e = lane; e < s; e += kWave) {
                 const int32_t g = src[chosen[e]];
                 dst[e] = g;
-                atomicOr(&words[g >> 5], 1u << (g & 31));
+                if (SET)
+                    atomicOr(&words[g >> 5], 1u << (g & 31));
             }
             __builtin_amdgcn_wave_barrier();
         }
@@ -220,19 +224,28 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
     }
 }
 
-void launch_nw_sample(const Launch &L, const NwHop &a, const VSet &vs)
+template <bool SET>
+static void launch_nw_sample_impl(const Launch &L, const NwHop &a, const VSet &vs)
 {
     const int64_t tiles = a.rows_bound / kRowTile + a.k;
     if (a.s <= 4)
-        hipLaunchKernelGGL(nw_sample_kernel<4>, dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_kernel<4, SET>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
     else if (a.s <= 8)
-        hipLaunchKernelGGL(nw_sample_kernel<8>, dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_kernel<8, SET>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
     else if (a.s <= 16)
-        hipLaunchKernelGGL(nw_sample_kernel<16>, dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_kernel<16, SET>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
     else if (a.s <= 32)
-        hipLaunchKernelGGL(nw_sample_kernel<32>, dim3(grid_for(L, tiles, 4)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_kernel<32, SET>), dim3(grid_for(L, tiles, 4)), dim3(kRowTile), 0, L.stream, a, vs);
     else
-        hipLaunchKernelGGL(nw_sample_wide_kernel, dim3(grid_for(L, tiles, 2)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_wide_kernel<SET>), dim3(grid_for(L, tiles, 2)), dim3(kRowTile), 0, L.stream, a, vs);
+}
+
+void launch_nw_sample(const Launch &L, const NwHop &a, const VSet &vs, bool set_bits)
+{
+    if (set_bits)
+        launch_nw_sample_impl<true>(L, a, vs);
+    else
+        launch_nw_sample_impl<false>(L, a, vs);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -18,14 +18,17 @@ def mods():
 
 
 def _run_both(mods, rowptr, col, batches, fanouts, seed, mb_base=0, device_csr=True):
+    """Runs both EXTRACT kernel paths of the library and compares each with the oracle."""
     O, bms, _ = mods
     rp, cl = torch.from_numpy(rowptr), torch.from_numpy(col)
     if device_csr:
         rp, cl = rp.cuda(), cl.cuda()
     csr = bms.Csr(rp, cl)
-    res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fanouts, seed, mb_base=mb_base)
     ref = O.sample_nodewise(rowptr, col, batches, fanouts, seed, mb_base)
-    assert_hops_equal(res.hops(), ref, what="fanouts=%s seed=%d" % (fanouts, seed))
+    for extract in ("buckets", "bitmap"):
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fanouts, seed, mb_base=mb_base,
+                                  extract=extract)
+        assert_hops_equal(res.hops(), ref, what="extract=%s fanouts=%s seed=%d" % (extract, fanouts, seed))
     return csr, res, ref
 
 
@@ -154,3 +157,39 @@ def test_profile_stages_are_reported(mods):
     res = bms.sample_nodewise(csr, random_batches(4000, 4, 64, rng), (5, 5), 3, profile=True)
     names = [s[0] for s in res.stages()]
     assert names.count("nw_sample") == 2 and all(s[2] >= 0 for s in res.stages())
+
+
+def test_bucket_extract_many_buckets_and_large_batches(mods):
+    # vertex range spanning many 2^18-id buckets, sparse so that most buckets hold a few ids;
+    # b above the LDS seed-sort limit exercises the vertex-set seed check next to bucket EXTRACT
+    O, bms, _ = mods
+    rng = np.random.default_rng(44)
+    n = 3_000_000
+    src = rng.integers(0, n, size=400_000)
+    dst = rng.integers(0, n, size=400_000)
+    keep = src != dst
+    key = np.unique(np.concatenate([src[keep] * n + dst[keep], dst[keep] * n + src[keep]]))
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rowptr, key // n + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    col = (key % n).astype(np.int32)
+    nonisolated = np.nonzero(np.diff(rowptr))[0]
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    for k, b in ((3, 9000), (7, 500)):
+        batches = random_batches(n, k, b, rng, candidates=nonisolated)
+        ref = O.sample_nodewise(rowptr, col, batches, (3, 3, 2), 5)
+        for extract in ("buckets", "bitmap", None):
+            res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 3, 2), 5, extract=extract)
+            assert_hops_equal(res.hops(), ref, what="extract=%s k=%d b=%d" % (extract, k, b))
+    # repeated seed found by the LDS sort check (b <= 8192) and by the vertex-set check (b > 8192)
+    for b in (500, 9000):
+        bad = random_batches(n, 2, b, rng)
+        bad[1, b - 1] = bad[1, 0]
+        with pytest.raises(bms.BmsError) as e:
+            bms.sample_nodewise(csr, bad, (2,), 1, extract="buckets")
+        assert e.value.code == bms.ERANGE
+    bad = random_batches(n, 2, 100, rng)
+    bad[0, 7] = n
+    with pytest.raises(bms.BmsError) as e:
+        bms.sample_nodewise(csr, bad, (2,), 1, extract="buckets")
+    assert e.value.code == bms.ERANGE
