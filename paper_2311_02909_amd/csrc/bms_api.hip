@@ -102,7 +102,7 @@ struct bms_csr {
     bool vs_clean = false; // all words zero
     DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars;
     DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
-    DevBuf dd_pairs, dd_uniq, dd_edgeoff, dd_count; // bucket EXTRACT
+    DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count; // bucket EXTRACT
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
 };
@@ -429,6 +429,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         BMS_TRY(prof.end());
         if (buckets) {
             BMS_TRY(csr->dd_pairs.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
+            BMS_TRY(csr->dd_utmp.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
             BMS_TRY(csr->dd_uniq.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
             DedupArgs d{};
             d.k = c.k;
@@ -436,11 +437,13 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.mb_edgeoff = csr->dd_edgeoff.as<int64_t>();
             d.col = a.out_col;
             d.pairs = csr->dd_pairs.as<uint64_t>();
+            d.utmp = csr->dd_utmp.as<uint64_t>();
             d.uniq = csr->dd_uniq.as<int32_t>();
             d.mb_count = csr->dd_count.as<int64_t>();
             BMS_TRY(prof.begin("nw_dedup_bucket", h));
-            launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
-                                   hb.col_vertex.as<int32_t>(), slot(c, h, 1), ncols_bound);
+            if (launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
+                                       hb.col_vertex.as<int32_t>(), slot(c, h, 1), ncols_bound) != 0)
+                return fail(BMS_EHIP, "launch of the bucket EXTRACT kernel was refused");
             BMS_TRY(prof.end());
         } else {
             BMS_TRY(prof.begin("vset_rank", h));
@@ -800,7 +803,7 @@ void bms_free(void *handle)
         DevBuf *bufs[] = {&c->own_rowptr, &c->own_col,    &c->vs_words,   &c->vs_prefix,     &c->vs_chunks,
                           &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars,
                           &c->ld_counters, &c->ld_gather_off, &c->ld_row_mb, &c->ld_chunks, &c->ld_prefix,
-                          &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count};
+                          &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_utmp, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count};
         for (DevBuf *b : bufs)
             b->release();
         if (c->host_pinned)

@@ -69,18 +69,20 @@ void launch_nw_sample(const Launch &, const NwHop &, const VSet &, bool set_bits
 void launch_nw_relabel(const Launch &, const NwHop &, const VSet &);
 
 // EXTRACT by id-range buckets, one workgroup per minibatch (large vertex ranges)
-constexpr int kBucketBits = 18;     // ids per bucket = 2^18 (a 32 KB bitmap in LDS)
-constexpr int kMaxBuckets = 3968;   // bucket cursors that fit beside the bitmap in 64 KB of LDS
+constexpr int kBucketBits = 15;     // ids per bucket = 2^15 (a 4 KB bitmap per wave in LDS)
+constexpr int kMaxBuckets = 8000;   // two uint32 per bucket must fit beside 16 wave bitmaps in 160 KB of LDS
 struct DedupArgs {
     int32_t k;
     int32_t nbuckets;    // ceil(n / 2^kBucketBits) <= kMaxBuckets
     int64_t *mb_edgeoff; // k+1, scratch
     int32_t *col;        // in: sampled global ids (stacked), out: local column indices
-    uint64_t *pairs;     // nnz, scratch: (id << 32 | position in minibatch), partitioned by bucket
+    uint64_t *pairs;     // nnz, scratch: (id << 32 | position in minibatch) partitioned by bin, then (bin, rank, position)
+    uint64_t *utmp;      // nnz, scratch: (bin, rank, id) of every distinct id, at its group's slots
     int32_t *uniq;       // nnz, scratch: distinct ids of minibatch i ascending, from mb_edgeoff[i]
     int64_t *mb_count;   // k, scratch: distinct ids per minibatch
 };
-void launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,
+// returns 0, or -1 when the launch was refused (then nothing ran)
+int launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,
                             int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t ncols_bound);
 void launch_offsets_from_counts(const Launch &, const int64_t *mb_count, int32_t k, int64_t *mb_off,
                                 int64_t *total_out);

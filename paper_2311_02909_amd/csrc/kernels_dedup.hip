@@ -1,21 +1,37 @@
 // EXTRACT for the node-wise sampler on large vertex ranges (Sec. 4.1.3: "remove empty columns"):
 // one workgroup per minibatch turns the minibatch's sampled global ids into local column indices
 // and the ascending list of distinct ids, without any per-minibatch structure of size n in HBM.
+// Work is proportional to the number of sampled edges of the minibatch, not to n.
 //
-//   A  partition the minibatch's (id, position) pairs by id range into buckets of 2^18 ids
+//   A  partition the minibatch's (id, position) pairs by id range into bins of 2^15 ids
 //      (LDS histogram, LDS scan, one scattered 8-byte store per sampled edge);
-//   B  per bucket, a 2^18-bit bitmap held in LDS: set the bits, popcount-scan the words, emit the
-//      set ids in ascending order, and give every pair its rank = distinct ids before it.
+//   B  every wave owns a contiguous run of bins (balanced by element count) and walks it in
+//      groups: consecutive bins holding <= 64 pairs together are sorted in registers (one pair per
+//      lane, 64-lane bitonic network on id-within-group << 6 | lane), a bin holding more than 64
+//      pairs is ranked with a 2^15-bit bitmap in LDS.  Either way every pair learns its rank among
+//      the distinct ids of its group, every distinct id is noted once, and the group's distinct
+//      count is recorded;
+//      a workgroup scan turns the counts into "distinct ids before the group";
+//   C  one streaming pass adds that base: local column = base + rank, distinct id list.
 //
-// Buckets are visited in ascending id order and the bitmap orders ids inside a bucket, so the
+// Bins are ascending id ranges, groups are runs of bins, and ids are ordered inside a group, so the
 // result is the ascending order whatever order the pairs landed in (the partition need not be
-// stable).  All synchronisation is workgroup-local.
+// stable).  All synchronisation is workgroup-local; no wave ever waits on another except at
+// workgroup barriers.
 #include "bms_device.h"
 #include "bms_internal.h"
 
 namespace bms {
 
-constexpr int kBucketWords = 1 << (kBucketBits - 5); // 8192 words = 32 KB
+constexpr int kBinWords = 1 << (kBucketBits - 5);  // 1024 words = 4 KB: a bin's bitmap, per wave
+constexpr int kWordsPerLane = kBinWords / kWave;   // 16
+constexpr uint32_t kBinMask = (1u << kBucketBits) - 1u;
+constexpr int kDedupWaves = 16;
+constexpr int kWindow = 512;                       // pairs a wave stages in LDS at a time (aliases the bitmap)
+constexpr uint64_t kNoEntry = ~0ULL;
+constexpr int kWaveLdsWords = kBinWords + kBinWords / 2; // bitmap (or pair window) + uint16 prefix per word
+
+size_t dedup_lds_bytes(int32_t nbins) { return (size_t)nbins * 8 + (size_t)kDedupWaves * kWaveLdsWords * 4; }
 
 // mb_edgeoff[i] = first entry of minibatch i in the stacked column array
 __global__ void mb_edge_offsets_kernel(const int64_t *__restrict__ out_rowptr, const int64_t *__restrict__ mb_rowoff,
@@ -25,36 +41,136 @@ __global__ void mb_edge_offsets_kernel(const int64_t *__restrict__ out_rowptr, c
         mb_edgeoff[i] = out_rowptr[mb_rowoff[i]];
 }
 
-__global__ __launch_bounds__(1024) void nw_dedup_bucket_kernel(DedupArgs a)
+// entry written for every pair / every distinct id: low 32 bits payload, then rank in group, then bin
+__device__ inline uint64_t pack_entry(uint32_t payload, uint32_t rank, uint32_t bin)
 {
-    __shared__ uint32_t bm[kBucketWords];      // bitmap of the current bucket
-    __shared__ uint32_t pre[kBucketWords / 2]; // set bits before each pair of words
-    __shared__ uint32_t cur[kMaxBuckets];      // bucket counts -> starts -> ends
-    __shared__ uint32_t smem[16];
+    return (uint64_t)payload | ((uint64_t)rank << 32) | ((uint64_t)bin << 48);
+}
+
+// LDS layout of a wave's bitmap.  Lane l owns the 16 logical words [16 l, 16 l + 16) (ascending
+// ids), stored as four 16-byte quarters; quarter q4 of lane l sits at uint4 index q4*64 + l, so the
+// per-lane 16-byte accesses of a wave hit consecutive addresses (no bank conflicts).
+__device__ inline uint32_t bm_word_index(uint32_t W) { return ((((W >> 2) & 3u) << 6) + (W >> 4)) * 4u + (W & 3u); }
+// per-word prefix (uint16): word q of lane l at halfword index q*64 + l
+__device__ inline uint32_t pre_index(uint32_t W) { return ((W & 15u) << 6) + (W >> 4); }
+
+// 64-lane bitonic sorting network, ascending by lane
+__device__ inline uint32_t wave_sort_u32(uint32_t c, int lane)
+{
+#pragma unroll
+    for (int kk = 2; kk <= kWave; kk <<= 1) {
+#pragma unroll
+        for (int j = kk >> 1; j > 0; j >>= 1) {
+            const uint32_t o = __shfl_xor(c, j, kWave);
+            const bool keep_min = ((lane & j) == 0) == ((lane & kk) == 0);
+            c = keep_min ? min(c, o) : max(c, o);
+        }
+    }
+    return c;
+}
+
+// A bin with more than 64 pairs: bitmap over its 2^15 ids in the wave's LDS.
+__device__ inline uint32_t rank_big_bin(uint32_t *wbm, uint16_t *wpre, uint64_t *__restrict__ pairs,
+                                        uint64_t *__restrict__ utmp, uint32_t bin, uint32_t s, uint32_t e, int lane)
+{
+    uint4 *bm4 = reinterpret_cast<uint4 *>(wbm) + lane;
+#pragma unroll
+    for (int q = 0; q < kWordsPerLane / 4; ++q)
+        bm4[q * kWave] = make_uint4(0, 0, 0, 0);
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t j = s + lane; j < e; j += kWave) {
+        const uint32_t l = (uint32_t)(pairs[j] >> 32) & kBinMask;
+        atomicOr(&wbm[bm_word_index(l >> 5)], 1u << (l & 31));
+    }
+    __builtin_amdgcn_wave_barrier();
+    uint32_t w[kWordsPerLane];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < kWordsPerLane / 4; ++q) {
+        const uint4 x = bm4[q * kWave];
+        w[4 * q] = x.x;
+        w[4 * q + 1] = x.y;
+        w[4 * q + 2] = x.z;
+        w[4 * q + 3] = x.w;
+        mine += __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w);
+    }
+    const uint32_t inc = wave_inclusive_scan(mine);
+    const uint32_t cnt = __shfl(inc, kWave - 1, kWave);
+    uint32_t run = inc - mine;
+    const uint32_t id0 = (bin << kBucketBits) + (uint32_t)lane * (kWordsPerLane * 32);
+#pragma unroll
+    for (int q = 0; q < kWordsPerLane; ++q) {
+        wpre[q * kWave + lane] = (uint16_t)run;
+        uint32_t x = w[q];
+        while (x) {
+            const int bit = __ffs(x) - 1;
+            x &= x - 1;
+            utmp[s + run] = pack_entry(id0 + q * 32 + bit, run, bin);
+            ++run;
+        }
+    }
+    for (uint32_t j = s + cnt + lane; j < e; j += kWave)
+        utmp[j] = kNoEntry;
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t j = s + lane; j < e; j += kWave) {
+        const uint64_t p = pairs[j];
+        const uint32_t l = (uint32_t)(p >> 32) & kBinMask;
+        const uint32_t wi = l >> 5;
+        const uint32_t r = wpre[pre_index(wi)] + __popc(wbm[bm_word_index(wi)] & ((1u << (l & 31)) - 1u));
+        pairs[j] = pack_entry((uint32_t)p, r, bin);
+    }
+    __builtin_amdgcn_wave_barrier();
+    return cnt;
+}
+
+__global__ __launch_bounds__(kDedupWaves *kWave) void nw_dedup_bucket_kernel(DedupArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    __shared__ uint32_t smem[kDedupWaves];
     __shared__ uint32_t carry_s;
-    const int tid = threadIdx.x;
+    constexpr int NT = kDedupWaves * kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int32_t nb = a.nbuckets;
+    uint32_t *cur = lds;        // bin counts -> starts -> ends
+    uint32_t *ubase = lds + nb; // distinct ids of a group (at its last bin) -> distinct ids before the bin's group
+    uint32_t *wbm = lds + 2 * nb + wave * kWaveLdsWords;
+    uint16_t *wpre = reinterpret_cast<uint16_t *>(wbm + kBinWords);
+    uint64_t *win = reinterpret_cast<uint64_t *>(wbm); // pair window, aliases the bitmap
+
     for (int32_t i = blockIdx.x; i < a.k; i += gridDim.x) {
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
-        int32_t *__restrict__ col = a.col + e0;        // in: global ids, out: local column indices
+        int32_t *__restrict__ col = a.col + e0; // in: global ids, out: local column indices
         uint64_t *__restrict__ pairs = a.pairs + e0;
+        uint64_t *__restrict__ utmp = a.utmp + e0;
         int32_t *__restrict__ uniq = a.uniq + e0;
 
         // ---- A: partition by id range ----
-        for (int32_t b = tid; b < nb; b += 1024)
+        for (int32_t b = tid; b < nb; b += NT) {
             cur[b] = 0;
+            ubase[b] = 0;
+        }
         if (tid == 0)
             carry_s = 0;
         __syncthreads();
-        for (uint32_t j = tid; j < N; j += 1024)
-            atomicAdd(&cur[(uint32_t)col[j] >> kBucketBits], 1u);
+        for (uint32_t j0 = 0; j0 < N; j0 += 4 * NT) {
+            uint32_t g[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t j = j0 + q * NT + tid;
+                g[q] = j < N ? (uint32_t)col[j] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (g[q] != 0xFFFFFFFFu)
+                    atomicAdd(&cur[g[q] >> kBucketBits], 1u);
+        }
         __syncthreads();
-        for (int32_t base = 0; base < nb; base += 1024) {
+        for (int32_t base = 0; base < nb; base += NT) {
             const int32_t b = base + tid;
             const uint32_t v = b < nb ? cur[b] : 0u;
             uint32_t total;
-            const uint32_t ex = block_exclusive_scan<uint32_t, 1024>(v, smem, total);
+            const uint32_t ex = block_exclusive_scan<uint32_t, NT>(v, smem, total);
             const uint32_t carry = carry_s;
             if (b < nb)
                 cur[b] = carry + ex;
@@ -63,72 +179,145 @@ __global__ __launch_bounds__(1024) void nw_dedup_bucket_kernel(DedupArgs a)
                 carry_s = carry + total;
             __syncthreads();
         }
-        for (uint32_t j = tid; j < N; j += 1024) {
-            const uint32_t g = (uint32_t)col[j];
-            const uint32_t pos = atomicAdd(&cur[g >> kBucketBits], 1u);
-            pairs[pos] = ((uint64_t)g << 32) | (uint64_t)j;
-        }
-        __syncthreads(); // cur[b] is now the end of bucket b; its start is cur[b-1]
-
-        // ---- B: per bucket, bitmap in LDS ----
-        uint32_t ubase = 0; // distinct ids in the buckets before this one (same value in every lane)
-        for (int32_t b = 0; b < nb; ++b) {
-            const uint32_t s = b ? cur[b - 1] : 0u;
-            const uint32_t e = cur[b];
-            if (s == e)
-                continue;
-            uint4 *bm4 = reinterpret_cast<uint4 *>(bm);
-            bm4[2 * tid] = make_uint4(0, 0, 0, 0);
-            bm4[2 * tid + 1] = make_uint4(0, 0, 0, 0);
-            __syncthreads();
-            for (uint32_t j = s + tid; j < e; j += 1024) {
-                const uint32_t l = (uint32_t)(pairs[j] >> 32) & ((1u << kBucketBits) - 1u);
-                atomicOr(&bm[l >> 5], 1u << (l & 31));
+        for (uint32_t j0 = 0; j0 < N; j0 += 4 * NT) {
+            uint32_t g[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t j = j0 + q * NT + tid;
+                g[q] = j < N ? (uint32_t)col[j] : 0xFFFFFFFFu;
             }
-            __syncthreads();
-            // lane t owns words [8t, 8t+8)
-            const uint4 w0 = bm4[2 * tid], w1 = bm4[2 * tid + 1];
-            const uint32_t w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-            uint32_t mine = 0;
 #pragma unroll
-            for (int q = 0; q < 8; ++q)
-                mine += __popc(w[q]);
-            uint32_t total;
-            const uint32_t ex = block_exclusive_scan<uint32_t, 1024>(mine, smem, total);
-            uint32_t run = ex;
-#pragma unroll
-            for (int q = 0; q < 8; q += 2) {
-                pre[4 * tid + (q >> 1)] = run;
-                run += __popc(w[q]) + __popc(w[q + 1]);
-            }
-            if (mine) {
-                int32_t *dst = uniq + ubase + ex;
-                const uint32_t id0 = ((uint32_t)b << kBucketBits) + (uint32_t)tid * 256u;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    uint32_t x = w[q];
-                    while (x) {
-                        const int bit = __ffs(x) - 1;
-                        x &= x - 1;
-                        *dst++ = (int32_t)(id0 + q * 32 + bit);
-                    }
+            for (int q = 0; q < 4; ++q)
+                if (g[q] != 0xFFFFFFFFu) {
+                    const uint32_t pos = atomicAdd(&cur[g[q] >> kBucketBits], 1u);
+                    pairs[pos] = ((uint64_t)g[q] << 32) | (uint64_t)(j0 + q * NT + tid);
                 }
+        }
+        __syncthreads(); // cur[b] is now the end of bin b; its start is cur[b-1]
+
+        // ---- B: ranks inside groups of bins ----
+        // wave w owns the bins whose first pair lies in [w*per, (w+1)*per)
+        const uint32_t per = (N + kDedupWaves - 1) / kDedupWaves;
+        int32_t b_lo, b_hi;
+        {
+            // smallest bin b with start(b) >= pos, start(b) = b ? cur[b-1] : 0
+            auto first_bin_from = [&](uint32_t pos) -> int32_t {
+                if (pos == 0)
+                    return 0;
+                int32_t lo = 0, hi = nb;
+                while (lo < hi) {
+                    const int32_t mid = (lo + hi) >> 1;
+                    if (cur[mid] < pos)
+                        lo = mid + 1;
+                    else
+                        hi = mid;
+                }
+                return lo + 1 < nb ? lo + 1 : nb;
+            };
+            b_lo = first_bin_from((uint32_t)wave * per);
+            b_hi = first_bin_from((uint32_t)(wave + 1) * per);
+        }
+        const uint32_t lim = b_hi > 0 ? cur[b_hi - 1] : 0u; // end of this wave's pairs
+        uint32_t win_base = 0, win_end = 0;                  // pairs [win_base, win_end) are staged in `win`
+        int32_t bin = b_lo;
+        while (bin < b_hi) {
+            const uint32_t start = bin ? cur[bin - 1] : 0u;
+            const int32_t span = (b_hi - bin) < kWave ? (b_hi - bin) : kWave;
+            const uint32_t end_l = lane < span ? cur[bin + lane] : 0xFFFFFFFFu; // ends of the next 64 bins
+            const unsigned long long fits = __ballot(lane < span && end_l - start <= (uint32_t)kWave);
+            const int nbins = fits == ~0ULL ? kWave : __ffsll((unsigned long long)~fits) - 1;
+            if (nbins == 0) {
+                // more than 64 pairs in this bin alone
+                const uint32_t e = __shfl(end_l, 0, kWave);
+                const uint32_t cnt = rank_big_bin(wbm, wpre, pairs, utmp, (uint32_t)bin, start, e, lane);
+                if (lane == 0)
+                    ubase[bin] = cnt;
+                win_base = win_end = 0; // the bitmap overwrote the window
+                bin += 1;
+                continue;
             }
+            const uint32_t m = __shfl(end_l, nbins - 1, kWave) - start; // pairs in bins [bin, bin + nbins)
+            if (m > 0) {
+                if (start + m > win_end || start < win_base) {
+                    // stage the next kWindow pairs: 8 independent loads per lane, then LDS
+                    uint64_t v[kWindow / kWave];
+#pragma unroll
+                    for (int u = 0; u < kWindow / kWave; ++u) {
+                        const uint32_t j = start + u * kWave + lane;
+                        v[u] = j < lim ? pairs[j] : kNoEntry;
+                    }
+#pragma unroll
+                    for (int u = 0; u < kWindow / kWave; ++u)
+                        win[u * kWave + lane] = v[u];
+                    win_base = start;
+                    win_end = (start + kWindow < lim) ? start + kWindow : lim;
+                    __builtin_amdgcn_wave_barrier();
+                }
+                uint64_t p = kNoEntry;
+                if ((uint32_t)lane < m)
+                    p = win[start - win_base + lane];
+                const uint32_t idx = (uint32_t)p;
+                const uint32_t id0 = (uint32_t)bin << kBucketBits;
+                uint32_t c = 0xFFFFFFFFu;
+                if ((uint32_t)lane < m)
+                    c = ((((uint32_t)(p >> 32)) - id0) << 6) | (uint32_t)lane; // < 64 bins * 2^15 ids * 64
+                c = wave_sort_u32(c, lane);
+                const bool valid = (uint32_t)lane < m; // the m real entries sort to the front
+                const uint32_t rel = c >> 6;
+                const uint32_t prev = __shfl_up(rel, 1, kWave);
+                const bool head = valid && (lane == 0 || rel != prev);
+                const unsigned long long heads = __ballot(head);
+                const uint32_t r = (uint32_t)__popcll(heads & ((2ULL << lane) - 1ULL)) - 1u;
+                const uint32_t cnt = (uint32_t)__popcll(heads);
+                const uint32_t oidx = __shfl(idx, (int)(c & 63u), kWave);
+                if (valid)
+                    pairs[start + lane] = pack_entry(oidx, r, (uint32_t)bin);
+                if (head)
+                    utmp[start + r] = pack_entry(id0 + rel, r, (uint32_t)bin);
+                if (valid && (uint32_t)lane >= cnt)
+                    utmp[start + lane] = kNoEntry; // slots [cnt, m) of the group hold no distinct id
+                if (lane == 0)
+                    ubase[bin + nbins - 1] = cnt;
+            }
+            bin += nbins;
+        }
+        if (tid == 0)
+            carry_s = 0;
+        __syncthreads();
+        for (int32_t base = 0; base < nb; base += NT) {
+            const int32_t b = base + tid;
+            const uint32_t v = b < nb ? ubase[b] : 0u;
+            uint32_t total;
+            const uint32_t ex = block_exclusive_scan<uint32_t, NT>(v, smem, total);
+            const uint32_t carry = carry_s;
+            if (b < nb)
+                ubase[b] = carry + ex;
             __syncthreads();
-            for (uint32_t j = s + tid; j < e; j += 1024) {
-                const uint64_t p = pairs[j];
-                const uint32_t l = (uint32_t)(p >> 32) & ((1u << kBucketBits) - 1u);
-                const uint32_t wi = l >> 5;
-                uint32_t r = ubase + pre[wi >> 1] + __popc(bm[wi] & ((1u << (l & 31)) - 1u));
-                if (wi & 1)
-                    r += __popc(bm[wi - 1]);
-                col[(uint32_t)p] = (int32_t)r;
-            }
-            ubase += total;
+            if (tid == 0)
+                carry_s = carry + total;
             __syncthreads();
         }
         if (tid == 0)
-            a.mb_count[i] = ubase;
+            a.mb_count[i] = carry_s;
+
+        // ---- C: add the group bases ----
+        for (uint32_t j0 = 0; j0 < N; j0 += 4 * NT) {
+            uint64_t t[4], u[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t j = j0 + q * NT + tid;
+                t[q] = j < N ? pairs[j] : kNoEntry;
+                u[q] = j < N ? utmp[j] : kNoEntry;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (t[q] != kNoEntry)
+                    col[(uint32_t)t[q]] = (int32_t)(ubase[t[q] >> 48] + (uint32_t)((t[q] >> 32) & 0xFFFFu));
+                if (u[q] != kNoEntry)
+                    uniq[ubase[u[q] >> 48] + (uint32_t)((u[q] >> 32) & 0xFFFFu)] = (int32_t)(uint32_t)u[q];
+            }
+        }
+        __syncthreads(); // the next minibatch reuses cur / ubase
     }
 }
 
@@ -143,15 +332,26 @@ __global__ __launch_bounds__(256) void compact_unique_kernel(DedupArgs a, const 
     }
 }
 
-void launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                            int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t ncols_bound)
+int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *out_rowptr, const int64_t *mb_rowoff,
+                           int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t ncols_bound)
 {
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nw_dedup_bucket_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 128) != hipSuccess)
+            (void)hipGetLastError(); // not required on every runtime; the launch below reports real failures
+        attr_set = true;
+    }
     hipLaunchKernelGGL(mb_edge_offsets_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, out_rowptr, mb_rowoff,
                        a.k, a.mb_edgeoff);
-    hipLaunchKernelGGL(nw_dedup_bucket_kernel, dim3(a.k), dim3(1024), 0, L.stream, a);
+    hipLaunchKernelGGL(nw_dedup_bucket_kernel, dim3(a.k), dim3(kDedupWaves * kWave), dedup_lds_bytes(a.nbuckets),
+                       L.stream, a);
+    if (hipGetLastError() != hipSuccess)
+        return -1;
     launch_offsets_from_counts(L, a.mb_count, a.k, mb_coloff, ncols_out);
     hipLaunchKernelGGL(compact_unique_kernel, dim3(grid_for(L, (ncols_bound + 255) / 256, 8)), dim3(256), 0, L.stream,
                        a, mb_coloff, col_vertex);
+    return 0;
 }
 
 } // namespace bms
