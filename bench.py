@@ -47,6 +47,7 @@ def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0
         "nw_sample": 8 * R + 8 * E,
         "nw_relabel": 8 * E,
         "vset_rank": 4 * U,
+        "nw_dedup_bucket": 8 * E + 4 * U,   # the bucket EXTRACT stage does relabel and frontier in one
         "ld_rows": 20 * R,
         "ld_accumulate": 4.0 * gathered,
         "ld_p_fill": 8.0 * pnnz,

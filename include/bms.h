@@ -52,9 +52,10 @@ extern "C" {
 /* bms_opts.flags */
 #define BMS_LADIES_SQUARED 1u /* LADIES column weight e_v^2 (definition in Sec. 2.2) instead of e_v   */
 #define BMS_PROFILE 2u        /* record per-stage device times, see bms_result_stage                  */
-#define BMS_EXTRACT_BUCKETS 4u /* node-wise EXTRACT by id-range buckets (default when n > 2^24)         */
-#define BMS_EXTRACT_BITMAP 8u  /* node-wise EXTRACT by per-minibatch bitmaps in HBM (default otherwise) */
-                               /* both give identical results; the flags only pick the kernel path      */
+#define BMS_EXTRACT_BUCKETS 4u /* node-wise EXTRACT by one workgroup per minibatch over id-range bins      */
+#define BMS_EXTRACT_BITMAP 8u  /* node-wise EXTRACT by per-minibatch bitmaps in HBM (default above 2.6e8 vertices) */
+#define BMS_EXTRACT_SORT 16u   /* node-wise EXTRACT by LDS sorts of id-range segments (default)              */
+                               /* all give identical results; the flags only pick the kernel path          */
 
 typedef struct bms_csr bms_csr;       /* adjacency matrix on the device + reusable scratch            */
 typedef struct bms_result bms_result; /* owns every device buffer its hop views point to              */

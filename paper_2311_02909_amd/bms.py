@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libbms.so")
 
 OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
-LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP = 1, 2, 4, 8
+LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT = 1, 2, 4, 8, 16
 
 
 class BmsError(RuntimeError):
@@ -261,8 +261,9 @@ def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_
                     recycle: Optional[Result] = None, profile: bool = False, scratch_limit: int = 0,
                     extract: Optional[str] = None) -> Result:
     """bms_sample_nodewise: bulk GraphSAGE sampling of the k x b seed batches.
-    extract: None (library's choice), "buckets" or "bitmap" -- which EXTRACT kernels run; same result."""
-    flags = (PROFILE if profile else 0) | {None: 0, "buckets": EXTRACT_BUCKETS, "bitmap": EXTRACT_BITMAP}[extract]
+    extract: None (library's choice), "sort", "buckets" or "bitmap" -- which EXTRACT kernels run; same result."""
+    flags = (PROFILE if profile else 0) | {None: 0, "buckets": EXTRACT_BUCKETS, "bitmap": EXTRACT_BITMAP,
+                                           "sort": EXTRACT_SORT}[extract]
     return _sample(lib().bms_sample_nodewise, csr, batches, fanouts, seed, mb_base, stream, recycle, flags,
                    scratch_limit)
 

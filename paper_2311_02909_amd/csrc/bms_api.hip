@@ -102,7 +102,7 @@ struct bms_csr {
     bool vs_clean = false; // all words zero
     DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars;
     DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
-    DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count; // bucket EXTRACT
+    DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count, dd_back, dd_tileoff, dd_cursor, dd_seg; // bucket EXTRACT
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
 };
@@ -217,7 +217,7 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
     if (opts) {
-        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP))
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT))
             return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
         if (opts->recycle && opts->recycle->tag != kTagResult)
             return fail(BMS_EINVAL, "opts->recycle is not a result handle");
@@ -356,12 +356,18 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
 {
     bms_csr *csr = c.csr;
     Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
-    // EXTRACT strategy: per-minibatch bitmaps over [0,n) in HBM pay off while a bitmap stays cache
-    // sized; beyond that the id-range bucket kernel (one workgroup per minibatch, bitmap in LDS) wins.
+    // EXTRACT strategy: LDS sorts of id-range segments (with the per-minibatch bin kernel as the
+    // fallback for crowded id ranges) whenever the bin table of that fallback fits in LDS; the
+    // per-minibatch bitmaps over [0,n) in HBM otherwise.
     const int64_t nbuckets = (csr->n + (1LL << kBucketBits) - 1) >> kBucketBits;
-    bool buckets = csr->n > (1LL << 24);
-    if (c.flags & BMS_EXTRACT_BUCKETS)
+    bool buckets = true;
+    bool seg_sort = true; // with buckets: sort id-range segments in LDS, per-minibatch kernel as fallback
+    if (c.flags & BMS_EXTRACT_SORT)
         buckets = true;
+    if (c.flags & BMS_EXTRACT_BUCKETS) {
+        buckets = true;
+        seg_sort = false;
+    }
     if (c.flags & BMS_EXTRACT_BITMAP)
         buckets = false;
     if (nbuckets > kMaxBuckets)
@@ -430,7 +436,24 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         if (buckets) {
             BMS_TRY(csr->dd_pairs.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
             BMS_TRY(csr->dd_utmp.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
-            BMS_TRY(csr->dd_uniq.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
+            // segments = id ranges of 2^cshift ids: about 500 sampled ids each on average (uniform ids),
+            // at most kMaxSegments of them, at most 2^20 ids wide (the sort key has 32 bits)
+            int32_t C = 0, cshift = 0;
+            if (seg_sort) {
+                const double per_mb = (double)nnz / c.k + 1.0;
+                cshift = 0;
+                while (cshift < 20 && (double)(2LL << cshift) * per_mb <= 700.0 * (double)csr->n)
+                    ++cshift;
+                while (((csr->n + (1LL << cshift) - 1) >> cshift) > kMaxSegments)
+                    ++cshift;
+                C = (int32_t)std::max<int64_t>((csr->n + (1LL << cshift) - 1) >> cshift, 1);
+                if (cshift > 20)
+                    C = 0; // vertex range too wide for the segment sort: per-minibatch kernel only
+            }
+            const size_t stride = (size_t)std::max<int64_t>(nbuckets, C);
+            BMS_TRY(csr->dd_uniq.ensure((size_t)c.k * stride * sizeof(uint32_t)));
+            BMS_TRY(csr->dd_seg.ensure(((size_t)c.k * (4 * (size_t)kMaxSegments + 1) + 16) * sizeof(uint32_t)));
+            BMS_TRY(csr->dd_tileoff.ensure(3 * ((size_t)c.k + 1) * sizeof(int64_t)));
             DedupArgs d{};
             d.k = c.k;
             d.nbuckets = (int32_t)nbuckets;
@@ -438,12 +461,31 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.col = a.out_col;
             d.pairs = csr->dd_pairs.as<uint64_t>();
             d.utmp = csr->dd_utmp.as<uint64_t>();
-            d.uniq = csr->dd_uniq.as<int32_t>();
+            d.bin_base = csr->dd_uniq.as<uint32_t>();
+            BMS_TRY(csr->dd_back.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
+            BMS_TRY(csr->dd_cursor.ensure((size_t)(nnz / kDedupPlaceTile + c.k + 1) * sizeof(uint32_t)));
+            d.back = csr->dd_back.as<uint64_t>();
+            d.split_tileoff = csr->dd_tileoff.as<int64_t>();
+            d.place_tileoff = csr->dd_tileoff.as<int64_t>() + c.k + 1;
+            d.place_cursor = csr->dd_cursor.as<uint32_t>();
+            d.stride = (int32_t)stride;
+            d.C = C;
+            d.cshift = cshift;
+            d.fwd_tileoff = csr->dd_tileoff.as<int64_t>() + 2 * (c.k + 1);
+            d.fallback = C ? reinterpret_cast<int32_t *>(csr->dd_seg.as<uint32_t>()) : nullptr;
+            d.seg_cnt = csr->dd_seg.as<uint32_t>() + 16;
+            d.seg_off = d.seg_cnt + (size_t)c.k * kMaxSegments;
+            d.seg_cursor = d.seg_off + (size_t)c.k * (kMaxSegments + 1);
+            d.big_list = d.seg_cursor + (size_t)c.k * kMaxSegments;
+            d.big_count = csr->dd_seg.as<uint32_t>() + 1;
             d.mb_count = csr->dd_count.as<int64_t>();
-            BMS_TRY(prof.begin("nw_dedup_bucket", h));
+            BMS_TRY(prof.begin("nw_dedup_rank", h));
             if (launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
-                                       hb.col_vertex.as<int32_t>(), slot(c, h, 1), ncols_bound) != 0)
+                                       slot(c, h, 1), nnz) != 0)
                 return fail(BMS_EHIP, "launch of the bucket EXTRACT kernel was refused");
+            BMS_TRY(prof.end());
+            BMS_TRY(prof.begin("nw_dedup_fixup", h));
+            launch_nw_dedup_fixup(c.launch, d, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), nnz);
             BMS_TRY(prof.end());
         } else {
             BMS_TRY(prof.begin("vset_rank", h));
@@ -803,7 +845,7 @@ void bms_free(void *handle)
         DevBuf *bufs[] = {&c->own_rowptr, &c->own_col,    &c->vs_words,   &c->vs_prefix,     &c->vs_chunks,
                           &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars,
                           &c->ld_counters, &c->ld_gather_off, &c->ld_row_mb, &c->ld_chunks, &c->ld_prefix,
-                          &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_utmp, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count};
+                          &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_utmp, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count, &c->dd_back, &c->dd_tileoff, &c->dd_cursor, &c->dd_seg};
         for (DevBuf *b : bufs)
             b->release();
         if (c->host_pinned)

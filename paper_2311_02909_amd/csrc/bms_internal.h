@@ -78,12 +78,33 @@ struct DedupArgs {
     int32_t *col;        // in: sampled global ids (stacked), out: local column indices
     uint64_t *pairs;     // nnz, scratch: (id << 32 | position in minibatch) partitioned by bin, then (bin, rank, position)
     uint64_t *utmp;      // nnz, scratch: (bin, rank, id) of every distinct id, at its group's slots
-    int32_t *uniq;       // nnz, scratch: distinct ids of minibatch i ascending, from mb_edgeoff[i]
+    uint32_t *bin_base;  // k * nbuckets, scratch: distinct ids of the minibatch before each bin's group
+    uint64_t *back;      // nnz, scratch: (local column << 32 | position) grouped by destination range
+    int64_t *split_tileoff, *place_tileoff; // k+1 each, scratch
+    uint32_t *place_cursor;                 // one per destination range, scratch
     int64_t *mb_count;   // k, scratch: distinct ids per minibatch
+    int32_t stride;      // entries of bin_base per minibatch (>= nbuckets and >= C)
+    // segment-sort path (C == 0: not used)
+    int32_t C;           // id-range segments per minibatch = ceil(n / 2^cshift) <= kMaxSegments
+    int32_t cshift;      // segment of an id = id >> cshift
+    uint32_t *seg_cnt;   // k * C: pairs per segment, later distinct ids per segment
+    uint32_t *seg_off;   // k * (C+1): exclusive scan of the pair counts
+    uint32_t *seg_cursor; // k * C
+    int64_t *fwd_tileoff; // k+1
+    uint32_t *big_list;  // k * C: segments of 1025..kSegCap pairs
+    uint32_t *big_count; // device counter of big_list (the word after `fallback`)
+    int32_t *fallback;   // device flag: a segment does not fit in LDS, the per-minibatch kernel takes the hop
 };
+constexpr int kFwdTile = 4096;      // sampled ids per tile of the count / split kernels
+constexpr int kSegCap = 4096;       // pairs of one segment that are sorted in LDS (32 KB)
+constexpr int kMaxSegments = 2048;
+void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz);
 // returns 0, or -1 when the launch was refused (then nothing ran)
 int launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                            int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t ncols_bound);
+                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz);
+void launch_nw_dedup_fixup(const Launch &, const DedupArgs &, const int64_t *mb_coloff, int32_t *col_vertex,
+                           int64_t nnz);
+constexpr int kDedupPlaceTile = 8192; // must equal kPlaceTile in kernels_dedup.hip (sizes the cursor array)
 void launch_offsets_from_counts(const Launch &, const int64_t *mb_count, int32_t k, int64_t *mb_off,
                                 int64_t *total_out);
 // seed check without a vertex set: range test + per-minibatch sort in LDS (b <= kMaxSortedSeeds)

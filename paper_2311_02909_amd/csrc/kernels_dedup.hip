@@ -12,7 +12,8 @@
 //      the distinct ids of its group, every distinct id is noted once, and the group's distinct
 //      count is recorded;
 //      a workgroup scan turns the counts into "distinct ids before the group";
-//   C  one streaming pass adds that base: local column = base + rank, distinct id list.
+//   C  (second kernel, all compute units) adds that base: local column = base + rank, and writes
+//      the distinct ids to their final place in the next frontier.
 //
 // Bins are ascending id ranges, groups are runs of bins, and ids are ordered inside a group, so the
 // result is the ascending order whatever order the pairs landed in (the partition need not be
@@ -29,6 +30,7 @@ constexpr uint32_t kBinMask = (1u << kBucketBits) - 1u;
 constexpr int kDedupWaves = 16;
 constexpr int kWindow = 512;                       // pairs a wave stages in LDS at a time (aliases the bitmap)
 constexpr uint64_t kNoEntry = ~0ULL;
+constexpr int kUnroll = 8;                         // independent loads a lane keeps in flight while streaming
 constexpr int kWaveLdsWords = kBinWords + kBinWords / 2; // bitmap (or pair window) + uint16 prefix per word
 
 size_t dedup_lds_bytes(int32_t nbins) { return (size_t)nbins * 8 + (size_t)kDedupWaves * kWaveLdsWords * 4; }
@@ -137,13 +139,14 @@ __global__ __launch_bounds__(kDedupWaves *kWave) void nw_dedup_bucket_kernel(Ded
     uint16_t *wpre = reinterpret_cast<uint16_t *>(wbm + kBinWords);
     uint64_t *win = reinterpret_cast<uint64_t *>(wbm); // pair window, aliases the bitmap
 
+    if (a.fallback && !*a.fallback)
+        return; // the segment-sort kernels handled this hop
     for (int32_t i = blockIdx.x; i < a.k; i += gridDim.x) {
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
         int32_t *__restrict__ col = a.col + e0; // in: global ids, out: local column indices
         uint64_t *__restrict__ pairs = a.pairs + e0;
         uint64_t *__restrict__ utmp = a.utmp + e0;
-        int32_t *__restrict__ uniq = a.uniq + e0;
 
         // ---- A: partition by id range ----
         for (int32_t b = tid; b < nb; b += NT) {
@@ -153,15 +156,15 @@ __global__ __launch_bounds__(kDedupWaves *kWave) void nw_dedup_bucket_kernel(Ded
         if (tid == 0)
             carry_s = 0;
         __syncthreads();
-        for (uint32_t j0 = 0; j0 < N; j0 += 4 * NT) {
-            uint32_t g[4];
+        for (uint32_t j0 = 0; j0 < N; j0 += kUnroll * NT) {
+            uint32_t g[kUnroll];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kUnroll; ++q) {
                 const uint32_t j = j0 + q * NT + tid;
                 g[q] = j < N ? (uint32_t)col[j] : 0xFFFFFFFFu;
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < kUnroll; ++q)
                 if (g[q] != 0xFFFFFFFFu)
                     atomicAdd(&cur[g[q] >> kBucketBits], 1u);
         }
@@ -179,15 +182,15 @@ __global__ __launch_bounds__(kDedupWaves *kWave) void nw_dedup_bucket_kernel(Ded
                 carry_s = carry + total;
             __syncthreads();
         }
-        for (uint32_t j0 = 0; j0 < N; j0 += 4 * NT) {
-            uint32_t g[4];
+        for (uint32_t j0 = 0; j0 < N; j0 += kUnroll * NT) {
+            uint32_t g[kUnroll];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kUnroll; ++q) {
                 const uint32_t j = j0 + q * NT + tid;
                 g[q] = j < N ? (uint32_t)col[j] : 0xFFFFFFFFu;
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < kUnroll; ++q)
                 if (g[q] != 0xFFFFFFFFu) {
                     const uint32_t pos = atomicAdd(&cur[g[q] >> kBucketBits], 1u);
                     pairs[pos] = ((uint64_t)g[q] << 32) | (uint64_t)(j0 + q * NT + tid);
@@ -299,41 +302,155 @@ __global__ __launch_bounds__(kDedupWaves *kWave) void nw_dedup_bucket_kernel(Ded
         }
         if (tid == 0)
             a.mb_count[i] = carry_s;
-
-        // ---- C: add the group bases ----
-        for (uint32_t j0 = 0; j0 < N; j0 += 4 * NT) {
-            uint64_t t[4], u[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t j = j0 + q * NT + tid;
-                t[q] = j < N ? pairs[j] : kNoEntry;
-                u[q] = j < N ? utmp[j] : kNoEntry;
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (t[q] != kNoEntry)
-                    col[(uint32_t)t[q]] = (int32_t)(ubase[t[q] >> 48] + (uint32_t)((t[q] >> 32) & 0xFFFFu));
-                if (u[q] != kNoEntry)
-                    uniq[ubase[u[q] >> 48] + (uint32_t)((u[q] >> 32) & 0xFFFFu)] = (int32_t)(uint32_t)u[q];
-            }
-        }
+        // the bases go to global memory for the fix-up kernel
+        for (int32_t b = tid; b < nb; b += NT)
+            a.bin_base[(int64_t)i * a.stride + b] = ubase[b];
         __syncthreads(); // the next minibatch reuses cur / ubase
     }
 }
 
-// col_vertex[mb_coloff[i] + c] = uniq[mb_edgeoff[i] + c]
-__global__ __launch_bounds__(256) void compact_unique_kernel(DedupArgs a, const int64_t *__restrict__ mb_coloff,
+// ---------------------------------------------------------------------------------------------
+// Fix-up (all compute units).  The entries left by the ranking kernel carry (bin, rank in group,
+// position in the minibatch); local column = base[bin] + rank has to land at that position.
+// Positions are random, and one scattered 4-byte store per sampled edge is bound by the request
+// rate of the memory pipeline, so the values travel in two coalesced steps instead:
+//   split  a tile of 2048 entries is counting-sorted in LDS by destination range (8192 positions)
+//          and every range's run is appended to that range's slot list with wide stores;
+//   place  one workgroup per range reads its slot list, scatters the values inside a 32 KB LDS
+//          tile and writes the tile out contiguously.
+// Minibatches with more than 256 ranges (2 M sampled edges) store directly.
+// ---------------------------------------------------------------------------------------------
+constexpr int kPlaceTile = 8192;
+constexpr int kPlaceShift = 13;
+constexpr int kSplitTile = 2048;
+constexpr int kMaxPlaceTiles = 256;
+static_assert(kPlaceTile == kDedupPlaceTile && (1 << kPlaceShift) == kPlaceTile, "tile constants out of step");
+
+__global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a)
+{
+    __shared__ uint64_t stage[kSplitTile];
+    __shared__ uint32_t cnt[kMaxPlaceTiles], off[kMaxPlaceTiles], gpos[kMaxPlaceTiles];
+    __shared__ uint32_t smem[4];
+    const int tid = threadIdx.x;
+    const int64_t ntiles = a.split_tileoff[a.k];
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int i = locate_segment(a.split_tileoff, a.k, t);
+        const int64_t e0 = a.mb_edgeoff[i];
+        const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
+        const uint32_t j0 = (uint32_t)(t - a.split_tileoff[i]) * kSplitTile;
+        const uint32_t jend = (j0 + kSplitTile < N) ? j0 + kSplitTile : N;
+        const uint32_t Q = (N + kPlaceTile - 1) >> kPlaceShift;
+        const uint64_t *__restrict__ pairs = a.pairs + e0;
+        const uint32_t *__restrict__ base = a.bin_base + (int64_t)i * a.stride;
+        uint64_t ent[kSplitTile / 256];
+#pragma unroll
+        for (int q = 0; q < kSplitTile / 256; ++q) {
+            const uint32_t j = j0 + q * 256 + tid;
+            ent[q] = kNoEntry;
+            if (j < jend) {
+                const uint64_t p = pairs[j];
+                const uint32_t val = base[p >> 48] + (uint32_t)((p >> 32) & 0xFFFFu);
+                ent[q] = ((uint64_t)val << 32) | (uint64_t)(uint32_t)p; // (local column, position)
+            }
+        }
+        if (Q > kMaxPlaceTiles) { // uniform for the workgroup
+            int32_t *__restrict__ col = a.col + e0;
+#pragma unroll
+            for (int q = 0; q < kSplitTile / 256; ++q)
+                if (ent[q] != kNoEntry)
+                    col[(uint32_t)ent[q]] = (int32_t)(ent[q] >> 32);
+            continue;
+        }
+        cnt[tid] = 0;
+        __syncthreads();
+        uint32_t lpos[kSplitTile / 256];
+#pragma unroll
+        for (int q = 0; q < kSplitTile / 256; ++q)
+            if (ent[q] != kNoEntry)
+                lpos[q] = atomicAdd(&cnt[(uint32_t)ent[q] >> kPlaceShift], 1u);
+        __syncthreads();
+        const uint32_t mine = cnt[tid];
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan<uint32_t, 256>(mine, smem, total);
+        off[tid] = ex;
+        if (mine)
+            gpos[tid] = atomicAdd(&a.place_cursor[a.place_tileoff[i] + tid], mine);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < kSplitTile / 256; ++q)
+            if (ent[q] != kNoEntry)
+                stage[off[(uint32_t)ent[q] >> kPlaceShift] + lpos[q]] = ent[q];
+        __syncthreads();
+        uint64_t *__restrict__ back = a.back + e0;
+        for (uint32_t sidx = tid; sidx < jend - j0; sidx += 256) {
+            const uint64_t e = stage[sidx];
+            const uint32_t r = (uint32_t)e >> kPlaceShift;
+            back[r * kPlaceTile + gpos[r] + (sidx - off[r])] = e;
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void nw_dedup_place_kernel(DedupArgs a)
+{
+    __shared__ int32_t tile[kPlaceTile];
+    const int tid = threadIdx.x;
+    const int64_t ntiles = a.place_tileoff[a.k];
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int i = locate_segment(a.place_tileoff, a.k, t);
+        const int64_t e0 = a.mb_edgeoff[i];
+        const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
+        if (((N + kPlaceTile - 1) >> kPlaceShift) > (uint32_t)kMaxPlaceTiles)
+            continue; // stored directly by the split kernel
+        const uint32_t p0 = (uint32_t)(t - a.place_tileoff[i]) * kPlaceTile;
+        const uint32_t n = (p0 + kPlaceTile < N) ? kPlaceTile : N - p0;
+        const uint64_t *__restrict__ back = a.back + e0 + p0;
+        for (uint32_t s0 = 0; s0 < n; s0 += 8 * 256) {
+            uint64_t e[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t sidx = s0 + q * 256 + tid;
+                e[q] = sidx < n ? back[sidx] : kNoEntry;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (e[q] != kNoEntry)
+                    tile[(uint32_t)e[q] & (kPlaceTile - 1)] = (int32_t)(e[q] >> 32);
+        }
+        __syncthreads();
+        int32_t *__restrict__ col = a.col + e0 + p0;
+        for (uint32_t sidx = tid; sidx < n; sidx += 256)
+            col[sidx] = tile[sidx];
+        __syncthreads();
+    }
+}
+
+// distinct ids to their final place in the next frontier (blockIdx.y = minibatch)
+__global__ __launch_bounds__(256) void nw_dedup_front_kernel(DedupArgs a, const int64_t *__restrict__ mb_coloff,
                                                              int32_t *__restrict__ col_vertex)
 {
-    const int64_t total = mb_coloff[a.k];
-    for (int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; x < total; x += (int64_t)gridDim.x * blockDim.x) {
-        const int i = locate_segment(mb_coloff, a.k, x);
-        col_vertex[x] = a.uniq[a.mb_edgeoff[i] + (x - mb_coloff[i])];
+    const int32_t i = blockIdx.y;
+    const int64_t e0 = a.mb_edgeoff[i];
+    const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
+    const uint64_t *__restrict__ utmp = a.utmp + e0;
+    const uint32_t *__restrict__ base = a.bin_base + (int64_t)i * a.stride;
+    int32_t *__restrict__ front = col_vertex + mb_coloff[i];
+    for (uint32_t j0 = blockIdx.x * (8 * 256); j0 < N; j0 += gridDim.x * (8 * 256)) {
+        uint64_t u[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t j = j0 + q * 256 + threadIdx.x;
+            u[q] = j < N ? utmp[j] : kNoEntry;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (u[q] != kNoEntry)
+                front[base[u[q] >> 48] + (uint32_t)((u[q] >> 32) & 0xFFFFu)] = (int32_t)(uint32_t)u[q];
     }
 }
 
 int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                           int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t ncols_bound)
+                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz)
 {
     static bool attr_set = false;
     if (!attr_set) {
@@ -344,14 +461,28 @@ int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *o
     }
     hipLaunchKernelGGL(mb_edge_offsets_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, out_rowptr, mb_rowoff,
                        a.k, a.mb_edgeoff);
+    if (a.C > 0)
+        launch_nw_dedup_sorted(L, a, nnz);
     hipLaunchKernelGGL(nw_dedup_bucket_kernel, dim3(a.k), dim3(kDedupWaves * kWave), dedup_lds_bytes(a.nbuckets),
                        L.stream, a);
     if (hipGetLastError() != hipSuccess)
         return -1;
     launch_offsets_from_counts(L, a.mb_count, a.k, mb_coloff, ncols_out);
-    hipLaunchKernelGGL(compact_unique_kernel, dim3(grid_for(L, (ncols_bound + 255) / 256, 8)), dim3(256), 0, L.stream,
-                       a, mb_coloff, col_vertex);
     return 0;
+}
+
+void launch_nw_dedup_fixup(const Launch &L, const DedupArgs &a, const int64_t *mb_coloff, int32_t *col_vertex,
+                           int64_t nnz)
+{
+    int gx = (int)((nnz / a.k + 2047) / 2048) + 1; // about one workgroup per 2048 entries of a minibatch
+    if (gx > 64)
+        gx = 64;
+    hipLaunchKernelGGL(nw_dedup_front_kernel, dim3(gx, a.k), dim3(256), 0, L.stream, a, mb_coloff, col_vertex);
+    launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile, a.split_tileoff);
+    launch_plan_tiles(L, a.mb_edgeoff, a.k, kPlaceTile, a.place_tileoff);
+    (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
+    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(nw_dedup_place_kernel, dim3(grid_for(L, nnz / kPlaceTile + a.k, 4)), dim3(256), 0, L.stream, a);
 }
 
 } // namespace bms

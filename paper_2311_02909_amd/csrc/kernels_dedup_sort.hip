@@ -1,0 +1,409 @@
+// EXTRACT for the node-wise sampler, fast path (Sec. 4.1.3: "remove empty columns"): every
+// minibatch's sampled ids are cut into C id ranges ("segments") small enough to be sorted inside
+// LDS, so that all random accesses of the dedup happen in LDS and global memory only sees
+// coalesced traffic.  All kernels run on every compute unit, whatever the number of minibatches.
+//
+//   count  per tile of 4096 sampled ids: LDS histogram over the C segments -> global counts
+//   scan   per minibatch: segment offsets; raises the fallback flag when a segment would not
+//          fit in LDS (ids crowded into a narrow range) -- then these kernels do nothing and the
+//          per-minibatch kernel of kernels_dedup.hip does the hop instead
+//   split  per tile: counting sort by segment in LDS, every segment's run appended with wide stores
+//   sort   per (minibatch, segment): the pairs are sorted by id -- up to 1024 pairs by one wave in
+//          registers, up to 4096 by a workgroup in LDS (bitonic networks); head flags + scan give
+//          the rank among the segment's distinct ids; every pair becomes (segment, rank,
+//          position), every distinct id is noted once
+//   base   per minibatch: scan of the segments' distinct counts
+// The fix-up kernels of kernels_dedup.hip then add the bases and put everything in place.
+#include "bms_device.h"
+#include "bms_internal.h"
+
+namespace bms {
+
+constexpr uint64_t kNoEntry = ~0ULL;
+
+__device__ inline uint64_t pack_entry(uint32_t payload, uint32_t rank, uint32_t seg)
+{
+    return (uint64_t)payload | ((uint64_t)rank << 32) | ((uint64_t)seg << 48);
+}
+
+__global__ __launch_bounds__(256) void dd_count_kernel(DedupArgs a)
+{
+    __shared__ uint32_t hist[kMaxSegments];
+    const int tid = threadIdx.x;
+    const int64_t ntiles = a.fwd_tileoff[a.k];
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int i = locate_segment(a.fwd_tileoff, a.k, t);
+        const int64_t e0 = a.mb_edgeoff[i];
+        const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
+        const uint32_t j0 = (uint32_t)(t - a.fwd_tileoff[i]) * kFwdTile;
+        const int32_t *__restrict__ col = a.col + e0;
+        for (int c = tid; c < a.C; c += 256)
+            hist[c] = 0;
+        __syncthreads();
+        uint32_t g[kFwdTile / 256];
+#pragma unroll
+        for (int q = 0; q < kFwdTile / 256; ++q) {
+            const uint32_t j = j0 + q * 256 + tid;
+            g[q] = (j < N && j < j0 + kFwdTile) ? (uint32_t)col[j] : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int q = 0; q < kFwdTile / 256; ++q)
+            if (g[q] != 0xFFFFFFFFu)
+                atomicAdd(&hist[g[q] >> a.cshift], 1u);
+        __syncthreads();
+        for (int c = tid; c < a.C; c += 256)
+            if (hist[c])
+                atomicAdd(&a.seg_cnt[(int64_t)i * a.C + c], hist[c]);
+        __syncthreads();
+    }
+}
+
+// one workgroup per minibatch: seg_off = exclusive scan of the counts (C+1 entries), cursors zeroed
+__global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
+{
+    __shared__ uint32_t smem[4];
+    __shared__ uint32_t carry_s;
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *__restrict__ cnt = a.seg_cnt + (int64_t)i * a.C;
+    uint32_t *__restrict__ off = a.seg_off + (int64_t)i * (a.C + 1);
+    if (tid == 0)
+        carry_s = 0;
+    __syncthreads();
+    bool too_big = false;
+    for (int base = 0; base < a.C; base += 256) {
+        const int c = base + tid;
+        const uint32_t v = c < a.C ? cnt[c] : 0u;
+        too_big |= v > (uint32_t)kSegCap;
+        if (v > 1024u && v <= (uint32_t)kSegCap) // too many pairs for one wave: listed for the workgroup sort
+            a.big_list[atomicAdd(a.big_count, 1u)] = (uint32_t)(i * a.C + c);
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan<uint32_t, 256>(v, smem, total);
+        const uint32_t carry = carry_s;
+        if (c < a.C) {
+            off[c] = carry + ex;
+            a.seg_cursor[(int64_t)i * a.C + c] = 0;
+        }
+        __syncthreads();
+        if (tid == 0)
+            carry_s = carry + total;
+        __syncthreads();
+    }
+    if (tid == 0)
+        off[a.C] = carry_s;
+    if (too_big)
+        atomicOr(a.fallback, 1);
+}
+
+__global__ __launch_bounds__(256) void dd_split_kernel(DedupArgs a)
+{
+    __shared__ uint64_t stage[kFwdTile];
+    __shared__ uint32_t cnt[kMaxSegments], off[kMaxSegments], gpos[kMaxSegments];
+    __shared__ uint32_t smem[4];
+    __shared__ uint32_t carry_s;
+    if (*a.fallback)
+        return;
+    const int tid = threadIdx.x;
+    const int64_t ntiles = a.fwd_tileoff[a.k];
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int i = locate_segment(a.fwd_tileoff, a.k, t);
+        const int64_t e0 = a.mb_edgeoff[i];
+        const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
+        const uint32_t j0 = (uint32_t)(t - a.fwd_tileoff[i]) * kFwdTile;
+        const uint32_t jend = (j0 + kFwdTile < N) ? j0 + kFwdTile : N;
+        const int32_t *__restrict__ col = a.col + e0;
+        for (int c = tid; c < a.C; c += 256)
+            cnt[c] = 0;
+        if (tid == 0)
+            carry_s = 0;
+        __syncthreads();
+        uint64_t ent[kFwdTile / 256];
+        uint32_t lpos[kFwdTile / 256];
+#pragma unroll
+        for (int q = 0; q < kFwdTile / 256; ++q) {
+            const uint32_t j = j0 + q * 256 + tid;
+            ent[q] = j < jend ? (((uint64_t)(uint32_t)col[j] << 32) | (uint64_t)j) : kNoEntry;
+        }
+#pragma unroll
+        for (int q = 0; q < kFwdTile / 256; ++q)
+            if (ent[q] != kNoEntry)
+                lpos[q] = atomicAdd(&cnt[(uint32_t)(ent[q] >> 32) >> a.cshift], 1u);
+        __syncthreads();
+        for (int base = 0; base < a.C; base += 256) {
+            const int c = base + tid;
+            const uint32_t v = c < a.C ? cnt[c] : 0u;
+            uint32_t total;
+            const uint32_t ex = block_exclusive_scan<uint32_t, 256>(v, smem, total);
+            const uint32_t carry = carry_s;
+            if (c < a.C) {
+                off[c] = carry + ex;
+                if (v)
+                    gpos[c] = a.seg_off[(int64_t)i * (a.C + 1) + c] + atomicAdd(&a.seg_cursor[(int64_t)i * a.C + c], v);
+            }
+            __syncthreads();
+            if (tid == 0)
+                carry_s = carry + total;
+            __syncthreads();
+        }
+#pragma unroll
+        for (int q = 0; q < kFwdTile / 256; ++q)
+            if (ent[q] != kNoEntry)
+                stage[off[(uint32_t)(ent[q] >> 32) >> a.cshift] + lpos[q]] = ent[q];
+        __syncthreads();
+        uint64_t *__restrict__ pairs = a.pairs + e0;
+        for (uint32_t sidx = tid; sidx < jend - j0; sidx += 256) {
+            const uint64_t e = stage[sidx];
+            const uint32_t c = (uint32_t)(e >> 32) >> a.cshift;
+            pairs[gpos[c] + (sidx - off[c])] = e;
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// One wave per (minibatch, segment) of at most 1024 pairs: the sort runs in registers.
+// Sort key = (id - first id of the segment) << 12 | slot, 32 bits (segments span <= 2^20 ids).
+// Lane l holds sorted positions [16 l, 16 l + 16): compare-exchanges at distance < 16 stay inside
+// a lane, larger distances pair the same register of two lanes (one cross-lane move each).
+// ---------------------------------------------------------------------------------------------
+constexpr int kWaveSeg = 1024; // pairs per segment handled by one wave
+// LDS staging index: lanes that hold neighbouring runs of slots would all hit the same banks
+__device__ inline uint32_t swz(uint32_t x) { return x ^ ((x >> 5) & 31u); }
+
+// Bitonic network over 64*R values, R per lane; lane l ends up with sorted positions [R l, R l + R).
+template <int R>
+__device__ inline void wave_sort(uint32_t (&c)[R], int lane)
+{
+#pragma unroll
+    for (int size = 2; size <= kWave * R; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            if (stride >= R) {
+                const int lmask = stride / R;
+                const bool lower = (lane & lmask) == 0;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const uint32_t o = __shfl_xor(c[r], lmask, kWave);
+                    const bool asc = ((lane * R + r) & size) == 0; // always true in the last merge
+                    c[r] = (lower == asc) ? min(c[r], o) : max(c[r], o);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if ((r & stride) == 0) {
+                        const uint32_t x = c[r], y = c[r | stride];
+                        const uint32_t lo = min(x, y), hi = max(x, y);
+                        const bool asc = ((lane * R + r) & size) == 0;
+                        c[r] = asc ? lo : hi;
+                        c[r | stride] = asc ? hi : lo;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Sorts one segment of m <= 64 R pairs and writes its entries; returns the number of distinct ids.
+template <int R>
+__device__ inline uint32_t rank_segment_wave(uint64_t *__restrict__ pairs, uint64_t *__restrict__ utmp, uint32_t m,
+                                             uint32_t id0, uint32_t cseg, uint32_t *idx_l, uint64_t *out_l, int lane)
+{
+    uint32_t c[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t j = r * kWave + lane;
+        c[r] = 0xFFFFFFFFu;
+        if (j < m) {
+            const uint64_t p = pairs[j];
+            idx_l[j] = (uint32_t)p;
+            c[r] = (((uint32_t)(p >> 32) - id0) << 12) | j;
+        }
+    }
+    wave_sort<R>(c, lane);
+    __builtin_amdgcn_wave_barrier();
+    // sorted position e = R lane + r; heads = first occurrence of an id
+    const uint32_t last_below = __shfl_up(c[R - 1], 1, kWave);
+    uint32_t heads = 0;
+    bool head[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t prev = r ? c[r - 1] : last_below;
+        const bool first = (r == 0 && lane == 0);
+        head[r] = c[r] != 0xFFFFFFFFu && (first || (c[r] >> 12) != (prev >> 12));
+        heads += head[r] ? 1u : 0u;
+    }
+    const uint32_t inc = wave_inclusive_scan(heads);
+    const uint32_t cnt = __shfl(inc, kWave - 1, kWave);
+    uint32_t rank = inc - heads; // heads before this lane
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        rank += head[r] ? 1u : 0u;
+        if (c[r] != 0xFFFFFFFFu) // back to the slot the pair came from: the order of the pairs is free
+            out_l[swz(c[r] & 0xFFFu)] = pack_entry(idx_l[c[r] & 0xFFFu], rank - 1u, cseg);
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t j = r * kWave + lane;
+        if (j < m)
+            pairs[j] = out_l[swz(j)];
+    }
+    __builtin_amdgcn_wave_barrier();
+    rank = inc - heads;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        rank += head[r] ? 1u : 0u;
+        if (head[r])
+            out_l[swz(rank - 1u)] = pack_entry(id0 + (c[r] >> 12), rank - 1u, cseg);
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t j = r * kWave + lane;
+        if (j < m)
+            utmp[j] = j < cnt ? out_l[swz(j)] : kNoEntry;
+    }
+    __builtin_amdgcn_wave_barrier();
+    return cnt;
+}
+
+__global__ __launch_bounds__(256) void dd_sort_wave_kernel(DedupArgs a)
+{
+    __shared__ uint32_t idx_all[4 * kWaveSeg];  // position of every pair of the segment
+    __shared__ uint64_t out_all[4 * kWaveSeg];  // staging for coalesced stores
+    if (*a.fallback)
+        return;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    uint32_t *idx_l = idx_all + wave * kWaveSeg;
+    uint64_t *out_l = out_all + wave * kWaveSeg;
+    const int64_t nseg = (int64_t)a.k * a.C;
+    for (int64_t sg = (int64_t)blockIdx.x * 4 + wave; sg < nseg; sg += (int64_t)gridDim.x * 4) {
+        const int64_t i = sg / a.C;
+        const uint32_t cseg = (uint32_t)(sg % a.C);
+        const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
+        const uint32_t s0 = soff[cseg], m = soff[cseg + 1] - s0;
+        if (m > (uint32_t)kWaveSeg)
+            continue; // sorted by a whole workgroup in dd_sort_kernel
+        uint32_t cnt = 0;
+        if (m > 0) {
+            const int64_t e0 = a.mb_edgeoff[i];
+            uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
+            uint64_t *__restrict__ utmp = a.utmp + e0 + s0;
+            const uint32_t id0 = cseg << a.cshift;
+            if (m <= 64)
+                cnt = rank_segment_wave<1>(pairs, utmp, m, id0, cseg, idx_l, out_l, lane);
+            else if (m <= 256)
+                cnt = rank_segment_wave<4>(pairs, utmp, m, id0, cseg, idx_l, out_l, lane);
+            else
+                cnt = rank_segment_wave<16>(pairs, utmp, m, id0, cseg, idx_l, out_l, lane);
+        }
+        if (lane == 0)
+            a.seg_cnt[sg] = cnt;
+    }
+}
+
+// One workgroup per (minibatch, segment) of 1025..4096 pairs: sort in LDS.
+__global__ __launch_bounds__(256) void dd_sort_kernel(DedupArgs a)
+{
+    __shared__ uint64_t key[kSegCap];
+    __shared__ uint32_t smem[4];
+    if (*a.fallback)
+        return;
+    const int tid = threadIdx.x;
+    const uint32_t nbig = *a.big_count;
+    for (uint32_t x = blockIdx.x; x < nbig; x += gridDim.x) {
+        const int64_t sg = a.big_list[x];
+        const int64_t i = sg / a.C;
+        const uint32_t c = (uint32_t)(sg % a.C);
+        const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
+        const uint32_t s0 = soff[c], m = soff[c + 1] - s0;
+        const int64_t e0 = a.mb_edgeoff[i];
+        uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
+        uint64_t *__restrict__ utmp = a.utmp + e0 + s0;
+        uint32_t M = 256; // sorted size: power of two >= m, at least one element per lane
+        while (M < m)
+            M <<= 1;
+        for (uint32_t j = tid; j < M; j += 256)
+            key[j] = j < m ? pairs[j] : kNoEntry;
+        __syncthreads();
+        for (uint32_t size = 2; size <= M; size <<= 1) {
+            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                for (uint32_t t = tid; t < (M >> 1); t += 256) {
+                    const uint32_t lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
+                    const uint32_t hi = lo | stride;
+                    const uint64_t x = key[lo], y = key[hi];
+                    if ((x > y) == ((lo & size) == 0)) {
+                        key[lo] = y;
+                        key[hi] = x;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        // lane t owns sorted slots [t*per, (t+1)*per)
+        const uint32_t per = M >> 8;
+        const uint32_t j_lo = tid * per;
+        uint32_t heads = 0;
+        for (uint32_t j = j_lo; j < j_lo + per && j < m; ++j)
+            heads += (j == 0 || (uint32_t)(key[j] >> 32) != (uint32_t)(key[j - 1] >> 32)) ? 1u : 0u;
+        uint32_t cnt;
+        uint32_t rank = block_exclusive_scan<uint32_t, 256>(heads, smem, cnt); // heads before my slots
+        for (uint32_t j = j_lo; j < j_lo + per && j < m; ++j) {
+            const uint64_t e = key[j];
+            const uint32_t id = (uint32_t)(e >> 32);
+            const bool head = j == 0 || id != (uint32_t)(key[j - 1] >> 32);
+            rank += head ? 1u : 0u; // inclusive count of heads
+            pairs[j] = pack_entry((uint32_t)e, rank - 1u, c);
+            if (head)
+                utmp[rank - 1u] = pack_entry(id, rank - 1u, c);
+        }
+        for (uint32_t j = cnt + tid; j < m; j += 256)
+            utmp[j] = kNoEntry;
+        if (tid == 0)
+            a.seg_cnt[sg] = cnt;
+        __syncthreads();
+    }
+}
+
+// one workgroup per minibatch: distinct ids before each segment; distinct ids of the minibatch
+__global__ __launch_bounds__(256) void dd_base_scan_kernel(DedupArgs a)
+{
+    __shared__ uint32_t smem[4];
+    __shared__ uint32_t carry_s;
+    if (*a.fallback)
+        return;
+    const int i = blockIdx.x, tid = threadIdx.x;
+    if (tid == 0)
+        carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < a.C; base += 256) {
+        const int c = base + tid;
+        const uint32_t v = c < a.C ? a.seg_cnt[(int64_t)i * a.C + c] : 0u;
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan<uint32_t, 256>(v, smem, total);
+        const uint32_t carry = carry_s;
+        if (c < a.C)
+            a.bin_base[(int64_t)i * a.stride + c] = carry + ex;
+        __syncthreads();
+        if (tid == 0)
+            carry_s = carry + total;
+        __syncthreads();
+    }
+    if (tid == 0)
+        a.mb_count[i] = carry_s;
+}
+
+void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz)
+{
+    (void)hipMemsetAsync(a.seg_cnt, 0, (size_t)a.k * a.C * sizeof(uint32_t), L.stream);
+    (void)hipMemsetAsync(a.fallback, 0, 2 * sizeof(int32_t), L.stream); // flag and big_count
+    launch_plan_tiles(L, a.mb_edgeoff, a.k, kFwdTile, a.fwd_tileoff);
+    const int64_t tiles = nnz / kFwdTile + a.k;
+    hipLaunchKernelGGL(dd_count_kernel, dim3(grid_for(L, tiles, 8)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(dd_split_kernel, dim3(grid_for(L, tiles, 3)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(dd_sort_wave_kernel, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 3)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 4)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(dd_base_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
+}
+
+} // namespace bms

@@ -18,14 +18,14 @@ def mods():
 
 
 def _run_both(mods, rowptr, col, batches, fanouts, seed, mb_base=0, device_csr=True):
-    """Runs both EXTRACT kernel paths of the library and compares each with the oracle."""
+    """Runs every EXTRACT kernel path of the library and compares each with the oracle."""
     O, bms, _ = mods
     rp, cl = torch.from_numpy(rowptr), torch.from_numpy(col)
     if device_csr:
         rp, cl = rp.cuda(), cl.cuda()
     csr = bms.Csr(rp, cl)
     ref = O.sample_nodewise(rowptr, col, batches, fanouts, seed, mb_base)
-    for extract in ("buckets", "bitmap"):
+    for extract in ("sort", "buckets", "bitmap"):
         res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fanouts, seed, mb_base=mb_base,
                                   extract=extract)
         assert_hops_equal(res.hops(), ref, what="extract=%s fanouts=%s seed=%d" % (extract, fanouts, seed))
@@ -178,7 +178,7 @@ def test_bucket_extract_many_buckets_and_large_batches(mods):
     for k, b in ((3, 9000), (7, 500)):
         batches = random_batches(n, k, b, rng, candidates=nonisolated)
         ref = O.sample_nodewise(rowptr, col, batches, (3, 3, 2), 5)
-        for extract in ("buckets", "bitmap", None):
+        for extract in ("sort", "buckets", "bitmap", None):
             res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 3, 2), 5, extract=extract)
             assert_hops_equal(res.hops(), ref, what="extract=%s k=%d b=%d" % (extract, k, b))
     # repeated seed found by the LDS sort check (b <= 8192) and by the vertex-set check (b > 8192)
@@ -193,3 +193,26 @@ def test_bucket_extract_many_buckets_and_large_batches(mods):
     with pytest.raises(bms.BmsError) as e:
         bms.sample_nodewise(csr, bad, (2,), 1, extract="buckets")
     assert e.value.code == bms.ERANGE
+
+
+def test_sort_extract_falls_back_when_ids_crowd_one_segment(mods):
+    # directed graph whose edges all point into a narrow id range: every sampled id of a minibatch
+    # lands in one id-range segment, which cannot be sorted in LDS -> the per-minibatch kernel runs
+    O, bms, _ = mods
+    rng = np.random.default_rng(45)
+    n, m = 3_000_000, 600_000
+    src = rng.integers(0, n, size=m)
+    dst = rng.integers(1000, 60_000, size=m)
+    key = np.unique(src * n + dst)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rowptr, key // n + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    col = (key % n).astype(np.int32)
+    sources = np.nonzero(np.diff(rowptr))[0]
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    batches = random_batches(n, 3, 8000, rng, candidates=sources)
+    ref = O.sample_nodewise(rowptr, col, batches, (3, 2), 9)
+    assert ref[0].nnz > 3 * 4096      # more pairs per minibatch than one LDS segment holds
+    for extract in ("sort", "buckets", "bitmap"):
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 2), 9, extract=extract)
+        assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
