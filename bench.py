@@ -47,7 +47,13 @@ def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0
         "nw_sample": 8 * R + 8 * E,
         "nw_relabel": 8 * E,
         "vset_rank": 4 * U,
-        "nw_dedup_bucket": 8 * E + 4 * U,   # the bucket EXTRACT stage does relabel and frontier in one
+        # EXTRACT by segment sorts: the staged ids are read once (4 E, charged to dd_split), the local
+        # columns written once (4 E, dd_place), the next frontier written once (4 U, dd_front); the
+        # other kernels of the path (dd_count, dd_sort, dd_back_split) move scratch only
+        "dd_split": 4 * E,
+        "dd_place": 4 * E,
+        "dd_front": 4 * U,
+        "dd_bins": 8 * E + 4 * U,
         "ld_rows": 20 * R,
         "ld_accumulate": 4.0 * gathered,
         "ld_p_fill": 8.0 * pnnz,

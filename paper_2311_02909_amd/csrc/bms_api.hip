@@ -147,10 +147,12 @@ struct Profiler {
     bms_result *res;
     hipStream_t stream;
     bool on;
+    bool open = false;
     int begin(const char *name, int32_t hop)
     {
         if (!on)
             return BMS_OK;
+        open = true;
         while (res->event_pool.size() < res->events_used + 2) {
             hipEvent_t e;
             HIP_TRY(hipEventCreate(&e));
@@ -164,10 +166,17 @@ struct Profiler {
     }
     int end()
     {
-        if (!on)
+        if (!on || !open)
             return BMS_OK;
+        open = false;
         HIP_TRY(hipEventRecord(res->stages.back().t1, stream));
         return BMS_OK;
+    }
+    // closes the running stage, if any, and opens the next one
+    int mark(const char *name, int32_t hop)
+    {
+        BMS_TRY(end());
+        return begin(name, hop);
     }
     int finish()
     {
@@ -479,13 +488,11 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.big_list = d.seg_cursor + (size_t)c.k * kMaxSegments;
             d.big_count = csr->dd_seg.as<uint32_t>() + 1;
             d.mb_count = csr->dd_count.as<int64_t>();
-            BMS_TRY(prof.begin("nw_dedup_rank", h));
+            const StageMark mark = [&](const char *name) { (void)prof.mark(name, h); };
             if (launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
-                                       slot(c, h, 1), nnz) != 0)
+                                       slot(c, h, 1), nnz, mark) != 0)
                 return fail(BMS_EHIP, "launch of the bucket EXTRACT kernel was refused");
-            BMS_TRY(prof.end());
-            BMS_TRY(prof.begin("nw_dedup_fixup", h));
-            launch_nw_dedup_fixup(c.launch, d, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), nnz);
+            launch_nw_dedup_fixup(c.launch, d, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), nnz, mark);
             BMS_TRY(prof.end());
         } else {
             BMS_TRY(prof.begin("vset_rank", h));

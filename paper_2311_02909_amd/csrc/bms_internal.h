@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <functional>
 
 namespace bms {
 
@@ -24,6 +25,8 @@ struct Launch {
 };
 
 int grid_for(const Launch &L, int64_t blocks, int per_cu);
+// called by multi-kernel launchers before each kernel (group) so that it can be timed on its own
+using StageMark = std::function<void(const char *)>;
 
 // ---- common ----
 void launch_csr_check(const Launch &, const int64_t *rowptr, const int32_t *col, int64_t n, int64_t nnz,
@@ -98,12 +101,12 @@ struct DedupArgs {
 constexpr int kFwdTile = 4096;      // sampled ids per tile of the count / split kernels
 constexpr int kSegCap = 4096;       // pairs of one segment that are sorted in LDS (32 KB)
 constexpr int kMaxSegments = 2048;
-void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz);
+void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz, const StageMark &mark);
 // returns 0, or -1 when the launch was refused (then nothing ran)
 int launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz);
+                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz, const StageMark &mark);
 void launch_nw_dedup_fixup(const Launch &, const DedupArgs &, const int64_t *mb_coloff, int32_t *col_vertex,
-                           int64_t nnz);
+                           int64_t nnz, const StageMark &mark);
 constexpr int kDedupPlaceTile = 8192; // must equal kPlaceTile in kernels_dedup.hip (sizes the cursor array)
 void launch_offsets_from_counts(const Launch &, const int64_t *mb_count, int32_t k, int64_t *mb_off,
                                 int64_t *total_out);

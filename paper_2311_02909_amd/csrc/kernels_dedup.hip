@@ -431,10 +431,23 @@ __global__ __launch_bounds__(256) void nw_dedup_front_kernel(DedupArgs a, const 
 {
     const int32_t i = blockIdx.y;
     const int64_t e0 = a.mb_edgeoff[i];
-    const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
-    const uint64_t *__restrict__ utmp = a.utmp + e0;
     const uint32_t *__restrict__ base = a.bin_base + (int64_t)i * a.stride;
     int32_t *__restrict__ front = col_vertex + mb_coloff[i];
+    if (a.fallback && !*a.fallback) {
+        // segment sorts: segment c left its distinct ids, in rank order, at the head of its slots
+        const uint32_t *__restrict__ uids = reinterpret_cast<const uint32_t *>(a.utmp) + e0;
+        const uint32_t *__restrict__ soff = a.seg_off + (int64_t)i * (a.C + 1);
+        const uint32_t *__restrict__ scnt = a.seg_cnt + (int64_t)i * a.C;
+        const int lane = threadIdx.x & (kWave - 1);
+        for (int32_t c = blockIdx.x * 4 + threadIdx.x / kWave; c < a.C; c += gridDim.x * 4) {
+            const uint32_t cnt = scnt[c], s0 = soff[c], b0 = base[c];
+            for (uint32_t r = lane; r < cnt; r += kWave)
+                front[b0 + r] = (int32_t)uids[s0 + r];
+        }
+        return;
+    }
+    const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
+    const uint64_t *__restrict__ utmp = a.utmp + e0;
     for (uint32_t j0 = blockIdx.x * (8 * 256); j0 < N; j0 += gridDim.x * (8 * 256)) {
         uint64_t u[8];
 #pragma unroll
@@ -450,7 +463,7 @@ __global__ __launch_bounds__(256) void nw_dedup_front_kernel(DedupArgs a, const 
 }
 
 int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz)
+                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz, const StageMark &mark)
 {
     static bool attr_set = false;
     if (!attr_set) {
@@ -462,7 +475,9 @@ int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *o
     hipLaunchKernelGGL(mb_edge_offsets_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, out_rowptr, mb_rowoff,
                        a.k, a.mb_edgeoff);
     if (a.C > 0)
-        launch_nw_dedup_sorted(L, a, nnz);
+        launch_nw_dedup_sorted(L, a, nnz, mark);
+    else
+        mark("dd_bins");
     hipLaunchKernelGGL(nw_dedup_bucket_kernel, dim3(a.k), dim3(kDedupWaves * kWave), dedup_lds_bytes(a.nbuckets),
                        L.stream, a);
     if (hipGetLastError() != hipSuccess)
@@ -472,16 +487,19 @@ int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *o
 }
 
 void launch_nw_dedup_fixup(const Launch &L, const DedupArgs &a, const int64_t *mb_coloff, int32_t *col_vertex,
-                           int64_t nnz)
+                           int64_t nnz, const StageMark &mark)
 {
+    mark("dd_front");
     int gx = (int)((nnz / a.k + 2047) / 2048) + 1; // about one workgroup per 2048 entries of a minibatch
     if (gx > 64)
         gx = 64;
     hipLaunchKernelGGL(nw_dedup_front_kernel, dim3(gx, a.k), dim3(256), 0, L.stream, a, mb_coloff, col_vertex);
+    mark("dd_back_split");
     launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile, a.split_tileoff);
     launch_plan_tiles(L, a.mb_edgeoff, a.k, kPlaceTile, a.place_tileoff);
     (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
     hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a);
+    mark("dd_place");
     hipLaunchKernelGGL(nw_dedup_place_kernel, dim3(grid_for(L, nnz / kPlaceTile + a.k, 4)), dim3(256), 0, L.stream, a);
 }
 

@@ -11,7 +11,7 @@
 //   sort   per (minibatch, segment): the pairs are sorted by id -- up to 1024 pairs by one wave in
 //          registers, up to 4096 by a workgroup in LDS (bitonic networks); head flags + scan give
 //          the rank among the segment's distinct ids; every pair becomes (segment, rank,
-//          position), every distinct id is noted once
+//          position), the distinct ids are written in rank order at the head of the segment's slots
 //   base   per minibatch: scan of the segments' distinct counts
 // The fix-up kernels of kernels_dedup.hip then add the bases and put everything in place.
 #include "bms_device.h"
@@ -204,7 +204,7 @@ __device__ inline void wave_sort(uint32_t (&c)[R], int lane)
 
 // Sorts one segment of m <= 64 R pairs and writes its entries; returns the number of distinct ids.
 template <int R>
-__device__ inline uint32_t rank_segment_wave(uint64_t *__restrict__ pairs, uint64_t *__restrict__ utmp, uint32_t m,
+__device__ inline uint32_t rank_segment_wave(uint64_t *__restrict__ pairs, uint32_t *__restrict__ uids, uint32_t m,
                                              uint32_t id0, uint32_t cseg, uint32_t *idx_l, uint64_t *out_l, int lane)
 {
     uint32_t c[R];
@@ -249,18 +249,19 @@ __device__ inline uint32_t rank_segment_wave(uint64_t *__restrict__ pairs, uint6
     }
     __builtin_amdgcn_wave_barrier();
     rank = inc - heads;
+    uint32_t *ids_l = reinterpret_cast<uint32_t *>(out_l); // the distinct ids in rank order, staged for wide stores
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         rank += head[r] ? 1u : 0u;
         if (head[r])
-            out_l[swz(rank - 1u)] = pack_entry(id0 + (c[r] >> 12), rank - 1u, cseg);
+            ids_l[swz(rank - 1u)] = id0 + (c[r] >> 12);
     }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t j = r * kWave + lane;
-        if (j < m)
-            utmp[j] = j < cnt ? out_l[swz(j)] : kNoEntry;
+        if (j < cnt)
+            uids[j] = ids_l[swz(j)];
     }
     __builtin_amdgcn_wave_barrier();
     return cnt;
@@ -287,14 +288,14 @@ __global__ __launch_bounds__(256) void dd_sort_wave_kernel(DedupArgs a)
         if (m > 0) {
             const int64_t e0 = a.mb_edgeoff[i];
             uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
-            uint64_t *__restrict__ utmp = a.utmp + e0 + s0;
+            uint32_t *__restrict__ uids = reinterpret_cast<uint32_t *>(a.utmp) + e0 + s0;
             const uint32_t id0 = cseg << a.cshift;
             if (m <= 64)
-                cnt = rank_segment_wave<1>(pairs, utmp, m, id0, cseg, idx_l, out_l, lane);
+                cnt = rank_segment_wave<1>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
             else if (m <= 256)
-                cnt = rank_segment_wave<4>(pairs, utmp, m, id0, cseg, idx_l, out_l, lane);
+                cnt = rank_segment_wave<4>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
             else
-                cnt = rank_segment_wave<16>(pairs, utmp, m, id0, cseg, idx_l, out_l, lane);
+                cnt = rank_segment_wave<16>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
         }
         if (lane == 0)
             a.seg_cnt[sg] = cnt;
@@ -318,7 +319,7 @@ __global__ __launch_bounds__(256) void dd_sort_kernel(DedupArgs a)
         const uint32_t s0 = soff[c], m = soff[c + 1] - s0;
         const int64_t e0 = a.mb_edgeoff[i];
         uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
-        uint64_t *__restrict__ utmp = a.utmp + e0 + s0;
+        uint32_t *__restrict__ uids = reinterpret_cast<uint32_t *>(a.utmp) + e0 + s0;
         uint32_t M = 256; // sorted size: power of two >= m, at least one element per lane
         while (M < m)
             M <<= 1;
@@ -354,10 +355,8 @@ __global__ __launch_bounds__(256) void dd_sort_kernel(DedupArgs a)
             rank += head ? 1u : 0u; // inclusive count of heads
             pairs[j] = pack_entry((uint32_t)e, rank - 1u, c);
             if (head)
-                utmp[rank - 1u] = pack_entry(id, rank - 1u, c);
+                uids[rank - 1u] = id;
         }
-        for (uint32_t j = cnt + tid; j < m; j += 256)
-            utmp[j] = kNoEntry;
         if (tid == 0)
             a.seg_cnt[sg] = cnt;
         __syncthreads();
@@ -392,15 +391,18 @@ __global__ __launch_bounds__(256) void dd_base_scan_kernel(DedupArgs a)
         a.mb_count[i] = carry_s;
 }
 
-void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz)
+void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, const StageMark &mark)
 {
+    mark("dd_count");
     (void)hipMemsetAsync(a.seg_cnt, 0, (size_t)a.k * a.C * sizeof(uint32_t), L.stream);
     (void)hipMemsetAsync(a.fallback, 0, 2 * sizeof(int32_t), L.stream); // flag and big_count
     launch_plan_tiles(L, a.mb_edgeoff, a.k, kFwdTile, a.fwd_tileoff);
     const int64_t tiles = nnz / kFwdTile + a.k;
     hipLaunchKernelGGL(dd_count_kernel, dim3(grid_for(L, tiles, 8)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
+    mark("dd_split");
     hipLaunchKernelGGL(dd_split_kernel, dim3(grid_for(L, tiles, 3)), dim3(256), 0, L.stream, a);
+    mark("dd_sort");
     hipLaunchKernelGGL(dd_sort_wave_kernel, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 3)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 4)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_base_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
