@@ -26,7 +26,10 @@ HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of the dominant kernel, in bytes, scaled by the
 # factor a plain copy kernel of known size reads on the same counters (see profiles/); keyed by
 # (workload, kernel stage).  None = not measured for this build of the kernel.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/large_sage_hbm_traffic.txt: nw_sample_kernel<8> + <16>, read + write, bytes per step (3 launches)
+    ("large_sage", "nw_sample"): {"bytes_per_step": 5_914_800_000, "launches": 3},
+}
 
 
 def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0, gathered: int = 0) -> float:
@@ -146,7 +149,11 @@ def main() -> int:
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 5),
-        "traffic": MEASURED_TRAFFIC.get((args.workload, dominant)),
+        # measured HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated), average over the launches
+        "traffic": (MEASURED_TRAFFIC[(args.workload, dominant)]["bytes_per_step"]
+                    // MEASURED_TRAFFIC[(args.workload, dominant)]["launches"])
+        if (args.workload, dominant) in MEASURED_TRAFFIC else None,
+        "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"]),
         "avg_launch_ms": round(dom["ms"] / dom["launches"], 4), "launches_per_step": dom["launches"],
         "algorithmic_bytes_per_step": int(dom["bytes"]),
         "all_kernels_ms_per_step": {s: round(v["ms"], 4) for s, v in sorted(per_stage.items())},

@@ -441,8 +441,20 @@ __global__ __launch_bounds__(256) void nw_dedup_front_kernel(DedupArgs a, const 
         const int lane = threadIdx.x & (kWave - 1);
         for (int32_t c = blockIdx.x * 4 + threadIdx.x / kWave; c < a.C; c += gridDim.x * 4) {
             const uint32_t cnt = scnt[c], s0 = soff[c], b0 = base[c];
-            for (uint32_t r = lane; r < cnt; r += kWave)
-                front[b0 + r] = (int32_t)uids[s0 + r];
+            for (uint32_t r0 = 0; r0 < cnt; r0 += 8 * kWave) { // 8 independent loads in flight per lane
+                uint32_t v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t r = r0 + u * kWave + lane;
+                    v[u] = r < cnt ? uids[s0 + r] : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t r = r0 + u * kWave + lane;
+                    if (r < cnt)
+                        front[b0 + r] = (int32_t)v[u];
+                }
+            }
         }
         return;
     }

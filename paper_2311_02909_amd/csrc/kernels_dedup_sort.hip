@@ -97,11 +97,12 @@ __global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
 __global__ __launch_bounds__(256) void dd_split_kernel(DedupArgs a)
 {
     __shared__ uint64_t stage[kFwdTile];
-    __shared__ uint32_t cnt[kMaxSegments], off[kMaxSegments], gpos[kMaxSegments];
+    extern __shared__ uint32_t seg_lds[]; // 3 C words: per-segment count, start in the tile, start in global
     __shared__ uint32_t smem[4];
     __shared__ uint32_t carry_s;
     if (*a.fallback)
         return;
+    uint32_t *cnt = seg_lds, *off = seg_lds + a.C, *gpos = seg_lds + 2 * a.C;
     const int tid = threadIdx.x;
     const int64_t ntiles = a.fwd_tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
@@ -292,8 +293,12 @@ __global__ __launch_bounds__(256) void dd_sort_wave_kernel(DedupArgs a)
             const uint32_t id0 = cseg << a.cshift;
             if (m <= 64)
                 cnt = rank_segment_wave<1>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
+            else if (m <= 128)
+                cnt = rank_segment_wave<2>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
             else if (m <= 256)
                 cnt = rank_segment_wave<4>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
+            else if (m <= 512)
+                cnt = rank_segment_wave<8>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
             else
                 cnt = rank_segment_wave<16>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
         }
@@ -401,7 +406,7 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
     hipLaunchKernelGGL(dd_count_kernel, dim3(grid_for(L, tiles, 8)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
     mark("dd_split");
-    hipLaunchKernelGGL(dd_split_kernel, dim3(grid_for(L, tiles, 3)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(dd_split_kernel, dim3(grid_for(L, tiles, 4)), dim3(256), 3 * (size_t)a.C * sizeof(uint32_t), L.stream, a);
     mark("dd_sort");
     hipLaunchKernelGGL(dd_sort_wave_kernel, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 3)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 4)), dim3(256), 0, L.stream, a);
