@@ -216,3 +216,31 @@ def test_sort_extract_falls_back_when_ids_crowd_one_segment(mods):
     for extract in ("sort", "buckets", "bitmap"):
         res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 2), 9, extract=extract)
         assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
+
+
+def test_recycled_calls_without_host_round_trips(mods):
+    # a recycled result of the same call shape lets the library enqueue all hops without reading sizes
+    # back; the second call here samples far more edges than the first (high-degree seeds), a third
+    # far fewer, so buffers must be sized by upper bounds and not by the remembered sizes
+    O, bms, _ = mods
+    rng = np.random.default_rng(46)
+    rowptr, col = random_csr(40000, 40.0, rng)
+    deg = np.diff(rowptr)
+    order = np.argsort(deg)
+    low, high = order[:8000], order[-8000:]
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    res = None
+    for pool, seed in ((low, 1), (high, 2), (low, 3), (high, 3)):
+        batches = random_batches(40000, 6, 256, rng, candidates=pool)
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (10, 5, 3), seed, recycle=res)
+        ref = O.sample_nodewise(rowptr, col, batches, (10, 5, 3), seed)
+        assert_hops_equal(res.hops(), ref, what="recycled, seed %d" % seed)
+    # an invalid batch on the no-round-trip path is still reported, and the handle recovers
+    bad = random_batches(40000, 6, 256, rng)
+    bad[2, 5] = bad[2, 6]
+    with pytest.raises(bms.BmsError) as e:
+        bms.sample_nodewise(csr, torch.from_numpy(bad).cuda(), (10, 5, 3), 4, recycle=res)
+    assert e.value.code == bms.ERANGE
+    good = random_batches(40000, 6, 256, rng)
+    res = bms.sample_nodewise(csr, torch.from_numpy(good).cuda(), (10, 5, 3), 5, recycle=res)
+    assert_hops_equal(res.hops(), O.sample_nodewise(rowptr, col, good, (10, 5, 3), 5))
