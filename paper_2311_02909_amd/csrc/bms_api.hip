@@ -492,7 +492,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             }
             const size_t stride = (size_t)std::max<int64_t>(nbuckets, C);
             BMS_TRY(csr->dd_uniq.ensure((size_t)c.k * stride * sizeof(uint32_t)));
-            BMS_TRY(csr->dd_seg.ensure(((size_t)c.k * (4 * (size_t)kMaxSegments + 1) + 16) * sizeof(uint32_t)));
+            BMS_TRY(csr->dd_seg.ensure(((size_t)c.k * (5 * (size_t)kMaxSegments + 1) + 16) * sizeof(uint32_t)));
             BMS_TRY(csr->dd_tileoff.ensure(3 * ((size_t)c.k + 1) * sizeof(int64_t)));
             DedupArgs d{};
             d.k = c.k;
@@ -511,6 +511,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.stride = (int32_t)stride;
             d.C = C;
             d.cshift = cshift;
+            d.fuse_back = C ? 1 : 0;
             d.fwd_tileoff = csr->dd_tileoff.as<int64_t>() + 2 * (c.k + 1);
             d.fallback = C ? reinterpret_cast<int32_t *>(csr->dd_seg.as<uint32_t>()) : nullptr;
             d.seg_cnt = csr->dd_seg.as<uint32_t>() + 16;
@@ -518,6 +519,8 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.seg_cursor = d.seg_off + (size_t)c.k * (kMaxSegments + 1);
             d.big_list = d.seg_cursor + (size_t)c.k * kMaxSegments;
             d.big_count = csr->dd_seg.as<uint32_t>() + 1;
+            d.wide_list = d.big_list + (size_t)c.k * kMaxSegments;
+            d.wide_count = csr->dd_seg.as<uint32_t>() + 2;
             d.mb_count = csr->dd_count.as<int64_t>();
             const StageMark mark = [&](const char *name) { (void)prof.mark(name, h); };
             if (launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),

@@ -96,6 +96,9 @@ struct DedupArgs {
     int64_t *fwd_tileoff; // k+1
     uint32_t *big_list;  // k * C: segments of 1025..kSegCap pairs
     uint32_t *big_count; // device counter of big_list (the word after `fallback`)
+    uint32_t *wide_list; // k * C: segments of 513..1024 pairs (one wave each, in a kernel of their own)
+    uint32_t *wide_count; // device counter of wide_list (the word after big_count)
+    int32_t fuse_back;   // 1: the sorting waves append their entries to the slot lists themselves (no split pass)
     int32_t *fallback;   // device flag: a segment does not fit in LDS, the per-minibatch kernel takes the hop
 };
 constexpr int kFwdTile = 4096;      // sampled ids per tile of the count / split kernels

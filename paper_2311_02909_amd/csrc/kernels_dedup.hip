@@ -326,39 +326,67 @@ constexpr int kSplitTile = 2048;
 constexpr int kMaxPlaceTiles = 256;
 static_assert(kPlaceTile == kDedupPlaceTile && (1 << kPlaceShift) == kPlaceTile, "tile constants out of step");
 
-__global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a)
+// big_segments == 0: walks all tiles of `pairs`.  After the per-minibatch kernel (fallback) that is
+// every entry; after the segment sorts only minibatches of more than 256 ranges still have their
+// entries in `pairs` (they are stored directly), the others were split by the sorting waves.
+// big_segments == 1 (segment sorts only): walks the segments sorted by whole workgroups.
+__global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a, int big_segments)
 {
     __shared__ uint64_t stage[kSplitTile];
     __shared__ uint32_t cnt[kMaxPlaceTiles], off[kMaxPlaceTiles], gpos[kMaxPlaceTiles];
     __shared__ uint32_t smem[4];
     const int tid = threadIdx.x;
-    const int64_t ntiles = a.split_tileoff[a.k];
+    const bool sorted = a.fuse_back && a.fallback && !*a.fallback; // the waves have split their segments
+    if (big_segments && !sorted)
+        return;
+    if (sorted && !big_segments) { // nothing to do unless some minibatch is stored directly
+        bool any = false;
+        for (int i = tid; i < a.k; i += 256)
+            any |= a.mb_edgeoff[i + 1] - a.mb_edgeoff[i] > (int64_t)kMaxPlaceTiles * kPlaceTile;
+        if (!__syncthreads_or(any))
+            return;
+    }
+    const int64_t ntiles = big_segments ? 2 * (int64_t)*a.big_count : a.split_tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int i = locate_segment(a.split_tileoff, a.k, t);
+        int i;
+        uint32_t j0, jend;
+        if (big_segments) { // a listed segment holds at most 2 tiles of entries
+            const int64_t sg = a.big_list[t >> 1];
+            i = (int)(sg / a.C);
+            const uint32_t *__restrict__ soff = a.seg_off + (int64_t)i * (a.C + 1);
+            const uint32_t s0 = soff[sg % a.C], s1 = soff[sg % a.C + 1];
+            j0 = s0 + (uint32_t)(t & 1) * kSplitTile;
+            jend = (j0 + kSplitTile < s1) ? j0 + kSplitTile : s1;
+            if (j0 >= s1)
+                continue;
+        } else {
+            i = locate_segment(a.split_tileoff, a.k, t);
+            j0 = (uint32_t)(t - a.split_tileoff[i]) * kSplitTile;
+        }
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
-        const uint32_t j0 = (uint32_t)(t - a.split_tileoff[i]) * kSplitTile;
-        const uint32_t jend = (j0 + kSplitTile < N) ? j0 + kSplitTile : N;
         const uint32_t Q = (N + kPlaceTile - 1) >> kPlaceShift;
+        if (!big_segments) {
+            jend = (j0 + kSplitTile < N) ? j0 + kSplitTile : N;
+            if (sorted && Q <= kMaxPlaceTiles)
+                continue; // already split by the sorting waves (and by the big_segments pass)
+        } else if (Q > kMaxPlaceTiles) {
+            continue; // stored directly by the pass over all tiles
+        }
         const uint64_t *__restrict__ pairs = a.pairs + e0;
-        const uint32_t *__restrict__ base = a.bin_base + (int64_t)i * a.stride;
         uint64_t ent[kSplitTile / 256];
 #pragma unroll
         for (int q = 0; q < kSplitTile / 256; ++q) {
             const uint32_t j = j0 + q * 256 + tid;
-            ent[q] = kNoEntry;
-            if (j < jend) {
-                const uint64_t p = pairs[j];
-                const uint32_t val = base[p >> 48] + (uint32_t)((p >> 32) & 0xFFFFu);
-                ent[q] = ((uint64_t)val << 32) | (uint64_t)(uint32_t)p; // (local column, position)
-            }
+            ent[q] = j < jend ? pairs[j] : kNoEntry; // (bin or segment, rank, position)
         }
         if (Q > kMaxPlaceTiles) { // uniform for the workgroup
             int32_t *__restrict__ col = a.col + e0;
+            const uint32_t *__restrict__ base = a.bin_base + (int64_t)i * a.stride;
 #pragma unroll
             for (int q = 0; q < kSplitTile / 256; ++q)
                 if (ent[q] != kNoEntry)
-                    col[(uint32_t)ent[q]] = (int32_t)(ent[q] >> 32);
+                    col[(uint32_t)ent[q]] = (int32_t)(base[ent[q] >> 48] + (uint32_t)((ent[q] >> 32) & 0xFFFFu));
             continue;
         }
         cnt[tid] = 0;
@@ -404,6 +432,7 @@ __global__ __launch_bounds__(256) void nw_dedup_place_kernel(DedupArgs a)
             continue; // stored directly by the split kernel
         const uint32_t p0 = (uint32_t)(t - a.place_tileoff[i]) * kPlaceTile;
         const uint32_t n = (p0 + kPlaceTile < N) ? kPlaceTile : N - p0;
+        const uint32_t *__restrict__ base = a.bin_base + (int64_t)i * a.stride;
         const uint64_t *__restrict__ back = a.back + e0 + p0;
         for (uint32_t s0 = 0; s0 < n; s0 += 8 * 256) {
             uint64_t e[8];
@@ -414,8 +443,9 @@ __global__ __launch_bounds__(256) void nw_dedup_place_kernel(DedupArgs a)
             }
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                if (e[q] != kNoEntry)
-                    tile[(uint32_t)e[q] & (kPlaceTile - 1)] = (int32_t)(e[q] >> 32);
+                if (e[q] != kNoEntry) // local column = distinct ids before the entry's bin or segment + its rank there
+                    tile[(uint32_t)e[q] & (kPlaceTile - 1)] =
+                        (int32_t)(base[e[q] >> 48] + (uint32_t)((e[q] >> 32) & 0xFFFFu));
         }
         __syncthreads();
         int32_t *__restrict__ col = a.col + e0 + p0;
@@ -508,9 +538,14 @@ void launch_nw_dedup_fixup(const Launch &L, const DedupArgs &a, const int64_t *m
     hipLaunchKernelGGL(nw_dedup_front_kernel, dim3(gx, a.k), dim3(256), 0, L.stream, a, mb_coloff, col_vertex);
     mark("dd_back_split");
     launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile, a.split_tileoff);
-    launch_plan_tiles(L, a.mb_edgeoff, a.k, kPlaceTile, a.place_tileoff);
-    (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
-    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a);
+    if (a.C == 0) { // the segment-sort launcher has done this already (its waves append to the slot lists)
+        launch_plan_tiles(L, a.mb_edgeoff, a.k, kPlaceTile, a.place_tileoff);
+        (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
+    }
+    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a, 0);
+    if (a.C > 0 && a.fuse_back)
+        hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a,
+                           1);
     mark("dd_place");
     hipLaunchKernelGGL(nw_dedup_place_kernel, dim3(grid_for(L, nnz / kPlaceTile + a.k, 4)), dim3(256), 0, L.stream, a);
 }

@@ -58,6 +58,22 @@ __global__ __launch_bounds__(256) void dd_count_kernel(DedupArgs a)
     }
 }
 
+// appends `value` of every lane with `flag` to a list in global memory: one atomic per wave
+__device__ inline void wave_append(uint32_t *__restrict__ list, uint32_t *__restrict__ count, bool flag, uint32_t value)
+{
+    const unsigned long long mask = __ballot(flag);
+    if (mask == 0)
+        return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int leader = __ffsll((long long)mask) - 1;
+    uint32_t base = 0;
+    if (lane == leader)
+        base = atomicAdd(count, (uint32_t)__popcll(mask));
+    base = __shfl(base, leader, kWave);
+    if (flag)
+        list[base + __popcll(mask & ((1ull << lane) - 1ull))] = value;
+}
+
 // one workgroup per minibatch: seg_off = exclusive scan of the counts (C+1 entries), cursors zeroed
 __global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
 {
@@ -74,8 +90,9 @@ __global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
         const int c = base + tid;
         const uint32_t v = c < a.C ? cnt[c] : 0u;
         too_big |= v > (uint32_t)kSegCap;
-        if (v > 1024u && v <= (uint32_t)kSegCap) // too many pairs for one wave: listed for the workgroup sort
-            a.big_list[atomicAdd(a.big_count, 1u)] = (uint32_t)(i * a.C + c);
+        // too many pairs for one wave: listed for the workgroup sort; 513..1024: listed for the wide wave sort
+        wave_append(a.big_list, a.big_count, v > 1024u && v <= (uint32_t)kSegCap, (uint32_t)(i * a.C + c));
+        wave_append(a.wide_list, a.wide_count, v > 512u && v <= 1024u, (uint32_t)(i * a.C + c));
         uint32_t total;
         const uint32_t ex = block_exclusive_scan<uint32_t, 256>(v, smem, total);
         const uint32_t carry = carry_s;
@@ -167,6 +184,10 @@ __global__ __launch_bounds__(256) void dd_split_kernel(DedupArgs a)
 // a lane, larger distances pair the same register of two lanes (one cross-lane move each).
 // ---------------------------------------------------------------------------------------------
 constexpr int kWaveSeg = 1024; // pairs per segment handled by one wave
+constexpr int kRanges = 256;    // destination ranges per minibatch the fused back-split handles (kMaxPlaceTiles)
+constexpr int kRangeShift = 13; // 8192 positions per destination range (kDedupPlaceTile)
+constexpr int kRangeSize = 1 << kRangeShift;
+static_assert(kRangeSize == kDedupPlaceTile && 3 * kRanges <= kWaveSeg, "range constants out of step");
 // LDS staging index: lanes that hold neighbouring runs of slots would all hit the same banks
 __device__ inline uint32_t swz(uint32_t x) { return x ^ ((x >> 5) & 31u); }
 
@@ -204,9 +225,13 @@ __device__ inline void wave_sort(uint32_t (&c)[R], int lane)
 }
 
 // Sorts one segment of m <= 64 R pairs and writes its entries; returns the number of distinct ids.
+// When `back` is not null the entries go straight to the slot lists of their destination ranges
+// (the wave counting-sorts them by range in LDS and appends every run with wide stores, see the
+// fix-up kernels); otherwise they return to `pairs` for the stand-alone split kernel.
 template <int R>
 __device__ inline uint32_t rank_segment_wave(uint64_t *__restrict__ pairs, uint32_t *__restrict__ uids, uint32_t m,
-                                             uint32_t id0, uint32_t cseg, uint32_t *idx_l, uint64_t *out_l, int lane)
+                                             uint32_t id0, uint32_t cseg, uint32_t *idx_l, uint64_t *out_l, int lane,
+                                             uint64_t *__restrict__ back, uint32_t *__restrict__ range_cursor, int nq)
 {
     uint32_t c[R];
 #pragma unroll
@@ -235,18 +260,64 @@ __device__ inline uint32_t rank_segment_wave(uint64_t *__restrict__ pairs, uint3
     const uint32_t inc = wave_inclusive_scan(heads);
     const uint32_t cnt = __shfl(inc, kWave - 1, kWave);
     uint32_t rank = inc - heads; // heads before this lane
+    if (back == nullptr) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        rank += head[r] ? 1u : 0u;
-        if (c[r] != 0xFFFFFFFFu) // back to the slot the pair came from: the order of the pairs is free
-            out_l[swz(c[r] & 0xFFFu)] = pack_entry(idx_l[c[r] & 0xFFFu], rank - 1u, cseg);
-    }
-    __builtin_amdgcn_wave_barrier();
+        for (int r = 0; r < R; ++r) {
+            rank += head[r] ? 1u : 0u;
+            if (c[r] != 0xFFFFFFFFu) // back to the slot the pair came from: the order of the pairs is free
+                out_l[swz(c[r] & 0xFFFu)] = pack_entry(idx_l[c[r] & 0xFFFu], rank - 1u, cseg);
+        }
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint32_t j = r * kWave + lane;
-        if (j < m)
-            pairs[j] = out_l[swz(j)];
+        for (int r = 0; r < R; ++r) {
+            const uint32_t j = r * kWave + lane;
+            if (j < m)
+                pairs[j] = out_l[swz(j)];
+        }
+    } else {
+        uint32_t pidx[R]; // position of the pair in its minibatch; its destination range is pidx >> 13
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            pidx[r] = c[r] != 0xFFFFFFFFu ? idx_l[c[r] & 0xFFFu] : 0xFFFFFFFFu;
+        __builtin_amdgcn_wave_barrier();
+        // the position table is no longer needed: its LDS now holds, per destination range, the entry
+        // count, the start inside this wave's staging and (start in the slot list - start in the staging)
+        uint32_t *cntq = idx_l, *offq = idx_l + kRanges, *gdelta = idx_l + 2 * kRanges;
+        for (int u = 0; u < nq; ++u)
+            cntq[u * kWave + lane] = 0;
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int r = 0; r < R; ++r) // the slot number in the key's low bits gives way to the place within the range
+            if (pidx[r] != 0xFFFFFFFFu)
+                c[r] = (c[r] & ~0xFFFu) | atomicAdd(&cntq[pidx[r] >> kRangeShift], 1u);
+        __builtin_amdgcn_wave_barrier();
+        uint32_t carry = 0;
+        for (int u = 0; u < nq; ++u) { // lane owns range 64 u + lane
+            const uint32_t q = u * kWave + lane;
+            const uint32_t mine = cntq[q];
+            const uint32_t inc_q = wave_inclusive_scan(mine);
+            const uint32_t start = carry + inc_q - mine;
+            offq[q] = start;
+            if (mine)
+                gdelta[q] = q * kRangeSize + atomicAdd(&range_cursor[q], mine) - start;
+            carry += __shfl(inc_q, kWave - 1, kWave);
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            rank += head[r] ? 1u : 0u;
+            if (pidx[r] != 0xFFFFFFFFu)
+                out_l[swz(offq[pidx[r] >> kRangeShift] + (c[r] & 0xFFFu))] = pack_entry(pidx[r], rank - 1u, cseg);
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t t = r * kWave + lane;
+            if (t < m) {
+                const uint64_t e = out_l[swz(t)];
+                back[gdelta[(uint32_t)e >> kRangeShift] + t] = e;
+            }
+        }
     }
     __builtin_amdgcn_wave_barrier();
     rank = inc - heads;
@@ -268,44 +339,76 @@ __device__ inline uint32_t rank_segment_wave(uint64_t *__restrict__ pairs, uint3
     return cnt;
 }
 
+// WIDE = false: segments of at most 512 pairs; WIDE = true: those of 513..1024 pairs, whose sorting
+// network needs twice the registers (two kernels, so that the common small segments run at the
+// higher occupancy)
+template <bool WIDE>
 __global__ __launch_bounds__(256) void dd_sort_wave_kernel(DedupArgs a)
 {
-    __shared__ uint32_t idx_all[4 * kWaveSeg];  // position of every pair of the segment
-    __shared__ uint64_t out_all[4 * kWaveSeg];  // staging for coalesced stores
+    constexpr int kIdxWords = WIDE ? kWaveSeg : 3 * kRanges; // per wave; also holds the three range tables
+    constexpr int kOutSlots = WIDE ? kWaveSeg : kWaveSeg / 2;
+    __shared__ uint32_t idx_all[4 * kIdxWords];  // position of every pair of the segment
+    __shared__ uint64_t out_all[4 * kOutSlots];  // staging for coalesced stores
     if (*a.fallback)
         return;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    uint32_t *idx_l = idx_all + wave * kWaveSeg;
-    uint64_t *out_l = out_all + wave * kWaveSeg;
-    const int64_t nseg = (int64_t)a.k * a.C;
-    for (int64_t sg = (int64_t)blockIdx.x * 4 + wave; sg < nseg; sg += (int64_t)gridDim.x * 4) {
-        const int64_t i = sg / a.C;
-        const uint32_t cseg = (uint32_t)(sg % a.C);
+    uint32_t *idx_l = idx_all + wave * kIdxWords;
+    uint64_t *out_l = out_all + wave * kOutSlots;
+    const int64_t nseg = WIDE ? (int64_t)*a.wide_count : (int64_t)a.k * ((a.C + 3) & ~3);
+    for (int64_t w = (int64_t)blockIdx.x * 4 + wave; w < nseg; w += (int64_t)gridDim.x * 4) {
+        int64_t i, sg;
+        uint32_t cseg;
+        if (WIDE) {
+            sg = a.wide_list[w];
+            i = sg / a.C;
+            cseg = (uint32_t)(sg % a.C);
+        } else {
+            // workgroups that run at the same time take segments of different minibatches, so that their
+            // appends to the slot lists do not queue up on the cursors of one minibatch; the 4 waves of a
+            // workgroup take neighbouring segments of one minibatch
+            const int64_t grp = w >> 2;
+            i = grp % a.k;
+            cseg = (uint32_t)((grp / a.k) * 4 + (w & 3));
+            if (cseg >= (uint32_t)a.C)
+                continue;
+            sg = i * a.C + cseg;
+        }
         const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
         const uint32_t s0 = soff[cseg], m = soff[cseg + 1] - s0;
         if (m > (uint32_t)kWaveSeg)
             continue; // sorted by a whole workgroup in dd_sort_kernel
+        if ((m > 512u) != WIDE)
+            continue;
         uint32_t cnt = 0;
         if (m > 0) {
             const int64_t e0 = a.mb_edgeoff[i];
             uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
             uint32_t *__restrict__ uids = reinterpret_cast<uint32_t *>(a.utmp) + e0 + s0;
             const uint32_t id0 = cseg << a.cshift;
-            if (m <= 64)
-                cnt = rank_segment_wave<1>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
+            // minibatches of at most 256 destination ranges take the fused back-split
+            const uint32_t Ni = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
+            const uint32_t Q = (Ni + kRangeSize - 1) >> kRangeShift;
+            const bool fused = a.fuse_back && Q <= (uint32_t)kRanges;
+            const int nq = (int)((Q + kWave - 1) / kWave); // groups of 64 ranges in use
+            uint64_t *back = fused ? a.back + e0 : nullptr;
+            uint32_t *cursor = a.place_cursor + a.place_tileoff[i];
+            if (WIDE)
+                cnt = rank_segment_wave<16>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
+            else if (m <= 64)
+                cnt = rank_segment_wave<1>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
             else if (m <= 128)
-                cnt = rank_segment_wave<2>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
+                cnt = rank_segment_wave<2>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
             else if (m <= 256)
-                cnt = rank_segment_wave<4>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
-            else if (m <= 512)
-                cnt = rank_segment_wave<8>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
+                cnt = rank_segment_wave<4>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
             else
-                cnt = rank_segment_wave<16>(pairs, uids, m, id0, cseg, idx_l, out_l, lane);
+                cnt = rank_segment_wave<8>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
         }
         if (lane == 0)
             a.seg_cnt[sg] = cnt;
     }
 }
+template __global__ void dd_sort_wave_kernel<false>(DedupArgs);
+template __global__ void dd_sort_wave_kernel<true>(DedupArgs);
 
 // One workgroup per (minibatch, segment) of 1025..4096 pairs: sort in LDS.
 __global__ __launch_bounds__(256) void dd_sort_kernel(DedupArgs a)
@@ -400,7 +503,7 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
 {
     mark("dd_count");
     (void)hipMemsetAsync(a.seg_cnt, 0, (size_t)a.k * a.C * sizeof(uint32_t), L.stream);
-    (void)hipMemsetAsync(a.fallback, 0, 2 * sizeof(int32_t), L.stream); // flag and big_count
+    (void)hipMemsetAsync(a.fallback, 0, 3 * sizeof(int32_t), L.stream); // flag, big_count, wide_count
     launch_plan_tiles(L, a.mb_edgeoff, a.k, kFwdTile, a.fwd_tileoff);
     const int64_t tiles = nnz / kFwdTile + a.k;
     hipLaunchKernelGGL(dd_count_kernel, dim3(grid_for(L, tiles, 8)), dim3(256), 0, L.stream, a);
@@ -408,7 +511,10 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
     mark("dd_split");
     hipLaunchKernelGGL(dd_split_kernel, dim3(grid_for(L, tiles, 4)), dim3(256), 3 * (size_t)a.C * sizeof(uint32_t), L.stream, a);
     mark("dd_sort");
-    hipLaunchKernelGGL(dd_sort_wave_kernel, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 3)), dim3(256), 0, L.stream, a);
+    launch_plan_tiles(L, a.mb_edgeoff, a.k, kDedupPlaceTile, a.place_tileoff);
+    (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kDedupPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
+    hipLaunchKernelGGL(dd_sort_wave_kernel<false>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 4)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(dd_sort_wave_kernel<true>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 2)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 4)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_base_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
 }

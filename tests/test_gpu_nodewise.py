@@ -244,3 +244,49 @@ def test_recycled_calls_without_host_round_trips(mods):
     good = random_batches(40000, 6, 256, rng)
     res = bms.sample_nodewise(csr, torch.from_numpy(good).cuda(), (10, 5, 3), 5, recycle=res)
     assert_hops_equal(res.hops(), O.sample_nodewise(rowptr, col, good, (10, 5, 3), 5))
+
+
+def test_sort_extract_segments_sorted_by_whole_workgroups(mods):
+    # most edges point into a few id-range segments, each of which then holds more pairs than one wave
+    # sorts (but few enough for one workgroup); the rest spread over the whole id range, so that waves
+    # and workgroups both feed the slot lists of the same minibatch
+    O, bms, _ = mods
+    rng = np.random.default_rng(47)
+    n, m = 3_000_000, 900_000
+    src = rng.integers(0, n, size=m)
+    dst = np.where(rng.random(m) < 0.7, rng.integers(1 << 16, 4 << 16, size=m), rng.integers(0, n, size=m))
+    key = np.unique(src * n + dst)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rowptr, key // n + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    col = (key % n).astype(np.int32)
+    sources = np.nonzero(np.diff(rowptr))[0]
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    batches = random_batches(n, 5, 8000, rng, candidates=sources)
+    ref = O.sample_nodewise(rowptr, col, batches, (3, 2), 11)
+    # sampled ids of minibatch 0 per range of 2^16 ids (the segment width the library picks for this shape)
+    e1 = ref[0].rowptr[ref[0].mb_rowoff[1]]
+    per_segment = np.bincount(ref[0].col_vertex[ref[0].col[:e1]] >> 16)
+    assert 1024 < per_segment.max() <= 4096, per_segment.max()
+    for extract in ("sort", None):
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 2), 11, extract=extract)
+        assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
+
+
+def test_minibatch_with_more_sampled_edges_than_the_slot_lists_cover(mods):
+    # one minibatch whose last hop samples more than 256 * 8192 edges: its local columns are stored
+    # directly instead of through the per-range slot lists
+    O, bms, synth = mods
+    g = synth.rmat_graph(1 << 21, 24_000_000, 0.45, 0.22, 0.22, seed=5, device="cuda")
+    rowptr, col = g.rowptr.cpu().numpy(), g.col.cpu().numpy()
+    rng = np.random.default_rng(48)
+    deg = np.diff(rowptr)
+    batches = random_batches(g.n, 2, 8000, rng, candidates=np.nonzero(deg >= 8)[0])
+    csr = bms.Csr(g.rowptr, g.col)
+    ref = O.sample_nodewise(rowptr, col, batches, (15, 10, 5), 3)
+    per_mb = np.diff(ref[2].rowptr[ref[2].mb_rowoff])
+    assert per_mb.max() > 256 * 8192, per_mb
+    res = None
+    for extract in ("sort", "buckets", "sort"):
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (15, 10, 5), 3, extract=extract, recycle=res)
+        assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
