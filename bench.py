@@ -28,8 +28,10 @@ HBM_PEAK_GBS = 8000.0
 # (workload, kernel stage).  None = not measured for this build of the kernel.
 MEASURED_TRAFFIC = {
     # profiles/large_sage_hbm_traffic.txt: nw_sample_kernel<8> + <16>, read + write, bytes per step (3 launches)
-    ("large_sage", "nw_sample"): {"bytes_per_step": 5_914_800_000, "launches": 3},
+    ("large_sage", "nw_sample"): {"bytes_per_step": 5_898_797_296, "launches": 3},
 }
+# the same counters summed over every kernel of one bulk call (bytes per step)
+MEASURED_CALL_TRAFFIC = {"large_sage": 11_217_423_514}
 
 
 def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0, gathered: int = 0) -> float:
@@ -157,6 +159,19 @@ def main() -> int:
         "avg_launch_ms": round(dom["ms"] / dom["launches"], 4), "launches_per_step": dom["launches"],
         "algorithmic_bytes_per_step": int(dom["bytes"]),
         "all_kernels_ms_per_step": {s: round(v["ms"], 4) for s, v in sorted(per_stage.items())},
+    }
+    # whole call: algorithmic bytes of all stages ("effective") and the profiled HBM bytes ("achieved"),
+    # both over the sum of the kernel times measured in this run
+    kernels_ms = sum(v["ms"] for v in per_stage.values())
+    call_alg = sum(v["bytes"] for v in per_stage.values())
+    roofline["call"] = {
+        "kernels_ms_per_step": round(kernels_ms, 4),
+        "effective_GBps": round(call_alg / (kernels_ms * 1e-3) / 1e9, 1),
+        "effective_frac": round(call_alg / (kernels_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "achieved_GBps": round(MEASURED_CALL_TRAFFIC[args.workload] / (kernels_ms * 1e-3) / 1e9, 1)
+        if args.workload in MEASURED_CALL_TRAFFIC else None,
+        "achieved_frac": round(MEASURED_CALL_TRAFFIC[args.workload] / (kernels_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        if args.workload in MEASURED_CALL_TRAFFIC else None,
     }
 
     cpu = None
