@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libbms.so")
 
 OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
-LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT = 1, 2, 4, 8, 16
+LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT, LADIES_DENSE = 1, 2, 4, 8, 16, 32
 
 
 class BmsError(RuntimeError):
@@ -270,8 +270,10 @@ def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_
 
 def sample_ladies(csr: Csr, batches, s_per_layer: Sequence[int], seed: int, *, mb_base: int = 0, squared: bool = False,
                   stream=None, recycle: Optional[Result] = None, profile: bool = False,
-                  scratch_limit: int = 0) -> Result:
-    """bms_sample_ladies: bulk LADIES sampling of the k x b seed batches."""
-    flags = (PROFILE if profile else 0) | (LADIES_SQUARED if squared else 0)
+                  scratch_limit: int = 0, dense: bool = False) -> Result:
+    """bms_sample_ladies: bulk LADIES sampling of the k x b seed batches.
+
+    dense=True picks the kernel path with per-minibatch counters in HBM (same results)."""
+    flags = (PROFILE if profile else 0) | (LADIES_SQUARED if squared else 0) | (LADIES_DENSE if dense else 0)
     return _sample(lib().bms_sample_ladies, csr, batches, s_per_layer, seed, mb_base, stream, recycle, flags,
                    scratch_limit)

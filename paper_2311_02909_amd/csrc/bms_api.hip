@@ -103,6 +103,7 @@ struct bms_csr {
     DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars;
     DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
     DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count, dd_back, dd_tileoff, dd_cursor, dd_seg; // bucket EXTRACT
+    DevBuf lw_bounds, lw_win, lw_tmpcol, lw_tmpcnt, lw_sel, lw_xtmp, lw_count; // LADIES by LDS windows
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
 };
@@ -231,7 +232,7 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
     if (opts) {
-        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT))
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE))
             return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
         if (opts->recycle && opts->recycle->tag != kTagResult)
             return fail(BMS_EINVAL, "opts->recycle is not a result handle");
@@ -574,8 +575,183 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     return BMS_OK;
 }
 
+// LADIES with the column counts of P accumulated in LDS, one window of 2^16 vertex ids at a time.
+bool ladies_windows_apply(const CallCtx &c, const int32_t *s_per_layer)
+{
+    if (c.flags & BMS_LADIES_DENSE)
+        return false;
+    if (c.b > kMaxSortedSeeds || c.b > kMaxWinRows)
+        return false;
+    for (int32_t h = 0; h < c.L; ++h)
+        if (s_per_layer[h] > kMaxWinSampled)
+            return false;
+    return true;
+}
+
+int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t *s_per_layer)
+{
+    bms_csr *csr = c.csr;
+    Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
+    const int64_t n1 = std::max<int64_t>(csr->n, 1);
+    const int32_t nwin = (int32_t)((n1 + (1LL << kWinShift) - 1) >> kWinShift);
+    const size_t nw = (size_t)c.k * nwin;
+    BMS_TRY(csr->lw_win.ensure(nw * (sizeof(uint32_t) + 4 * sizeof(int64_t)) + 64));
+    BMS_TRY(csr->lw_count.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+    BMS_TRY(stage_seeds(c, batches, prof, false));
+
+    int64_t rows_bound = (int64_t)c.k * c.b;
+    const int32_t *row_vertex = c.res->hops[0].row_vertex.as<int32_t>();
+    const int64_t *mb_rowoff = c.res->hops[0].mb_rowoff.as<int64_t>();
+
+    for (int32_t h = 0; h < c.L; ++h) {
+        HopBufs &hb = c.res->hops[h];
+        const int32_t s = s_per_layer[h];
+        const int64_t ncols_bound = (int64_t)c.k * std::min<int64_t>(s, n1);
+        const size_t bbytes = (size_t)(nwin + 1) * (size_t)rows_bound * sizeof(uint32_t);
+        if ((int64_t)bbytes > c.scratch_limit)
+            return fail(BMS_ENOMEM, "window boundaries of %lld rows need %zu bytes of scratch, limit is %lld: raise "
+                                    "bms_opts.scratch_limit or sample fewer minibatches per call",
+                        (long long)rows_bound, bbytes, (long long)c.scratch_limit);
+        BMS_TRY(csr->row_beg.ensure((size_t)rows_bound * sizeof(int64_t)));
+        BMS_TRY(csr->ld_gather_off.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
+        BMS_TRY(csr->ld_row_mb.ensure((size_t)rows_bound * sizeof(int32_t)));
+        BMS_TRY(csr->lw_bounds.ensure(bbytes));
+        BMS_TRY(csr->lw_sel.ensure((size_t)c.k * (size_t)s * sizeof(int32_t)));
+        BMS_TRY(hb.rowptr.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
+        BMS_TRY(hb.mb_coloff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+        BMS_TRY(hb.col_vertex.ensure((size_t)ncols_bound * sizeof(int32_t)));
+        BMS_TRY(hb.p_off.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+
+        LdHop a{};
+        a.A_rowptr = csr->rowptr;
+        a.A_col = csr->col;
+        a.n = csr->n;
+        a.k = c.k;
+        a.s = s;
+        a.row_vertex = row_vertex;
+        a.mb_rowoff = mb_rowoff;
+        a.rows_bound = rows_bound;
+        a.row_beg = csr->row_beg.as<int64_t>();
+        a.gather_off = csr->ld_gather_off.as<int64_t>();
+        a.row_mb = csr->ld_row_mb.as<int32_t>();
+        a.gather_tiles = csr->scalars.as<int64_t>() + 62;
+        a.out_rowptr = hb.rowptr.as<int64_t>();
+
+        LwHop w{};
+        w.A_rowptr = csr->rowptr;
+        w.A_col = csr->col;
+        w.n = csr->n;
+        w.k = c.k;
+        w.s = s;
+        w.squared = (c.flags & BMS_LADIES_SQUARED) ? 1 : 0;
+        w.hopkey = hop_key(c.seed, h);
+        w.mb_base = c.mb_base;
+        w.row_vertex = row_vertex;
+        w.mb_rowoff = mb_rowoff;
+        w.rows_bound = rows_bound;
+        w.row_beg = a.row_beg;
+        w.gather_off = a.gather_off;
+        w.nwin = nwin;
+        w.bounds = csr->lw_bounds.as<uint32_t>();
+        w.win_wt = csr->lw_win.as<uint64_t>();
+        w.win_woff = w.win_wt + nw;
+        w.win_base = reinterpret_cast<int64_t *>(w.win_woff + nw);
+        w.win_poff = w.win_base + nw;
+        w.win_cnt = reinterpret_cast<uint32_t *>(w.win_poff + nw);
+        w.cursor = reinterpret_cast<unsigned long long *>(csr->scalars.as<int64_t>() + 61);
+        w.mb_count = csr->lw_count.as<int64_t>();
+        w.p_off = hb.p_off.as<int64_t>();
+        w.sel_tmp = csr->lw_sel.as<int32_t>();
+        w.mb_coloff = hb.mb_coloff.as<int64_t>();
+        w.col_vertex = hb.col_vertex.as<int32_t>();
+        w.out_rowptr = hb.rowptr.as<int64_t>();
+
+        // P = Q A
+        BMS_TRY(prof.begin("ld_rows", h));
+        launch_ld_rows(c.launch, a, slot(c, h, 3));
+        BMS_TRY(prof.end());
+        BMS_TRY(read_scalars(c)); // D sizes the staging of P and of the kept neighbours
+        if (h == 0)
+            BMS_TRY(seed_flag_error(c));
+        const int64_t D = host_slot(c, h, 3);
+        const int64_t tmp_cap = std::max<int64_t>(std::min<int64_t>(D, (int64_t)c.k * n1), 1);
+        const size_t tbytes = (size_t)tmp_cap * 8 + (size_t)std::max<int64_t>(D, 1) * 4;
+        if ((int64_t)(tbytes + bbytes) > c.scratch_limit)
+            return fail(BMS_ENOMEM, "%lld gathered neighbours need %zu bytes of scratch, limit is %lld: raise "
+                                    "bms_opts.scratch_limit or sample fewer minibatches per call",
+                        (long long)D, tbytes + bbytes, (long long)c.scratch_limit);
+        BMS_TRY(csr->lw_tmpcol.ensure((size_t)tmp_cap * sizeof(int32_t)));
+        BMS_TRY(csr->lw_tmpcnt.ensure((size_t)tmp_cap * sizeof(uint32_t)));
+        BMS_TRY(csr->lw_xtmp.ensure((size_t)std::max<int64_t>(D, 1) * sizeof(int32_t)));
+        w.tmp_col = csr->lw_tmpcol.as<int32_t>();
+        w.tmp_cnt = csr->lw_tmpcnt.as<uint32_t>();
+        w.xtmp = csr->lw_xtmp.as<int32_t>();
+        BMS_TRY(prof.begin("ldw_bounds", h));
+        launch_ldw_bounds(c.launch, w);
+        BMS_TRY(prof.end());
+        BMS_TRY(prof.begin("ldw_accumulate", h));
+        if (launch_ldw_accumulate(c.launch, w) != 0)
+            return fail(BMS_EHIP, "launch of the LDS accumulation kernel was refused");
+        launch_offsets_from_counts(c.launch, w.mb_count, c.k, w.p_off, slot(c, h, 2));
+        BMS_TRY(prof.end());
+        BMS_TRY(read_scalars(c)); // pnnz sizes P and its prefix sums
+        const int64_t pnnz = host_slot(c, h, 2);
+        BMS_TRY(hb.p_col.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(int32_t)));
+        BMS_TRY(hb.p_cnt.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(uint32_t)));
+        BMS_TRY(csr->ld_prefix.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(uint64_t)));
+        w.p_col = hb.p_col.as<int32_t>();
+        w.p_cnt = hb.p_cnt.as<uint32_t>();
+        w.prefix = csr->ld_prefix.as<uint64_t>();
+        BMS_TRY(prof.begin("ldw_p_copy", h));
+        launch_ldw_p_copy(c.launch, w);
+        BMS_TRY(prof.end());
+        // NORM (implicit) + SAMPLE
+        BMS_TRY(prof.begin("ldw_draw", h));
+        launch_ldw_draw(c.launch, w);
+        launch_offsets_from_counts(c.launch, w.mb_count, c.k, w.mb_coloff, slot(c, h, 1));
+        launch_ldw_sel_copy(c.launch, w);
+        BMS_TRY(prof.end());
+        // EXTRACT
+        BMS_TRY(prof.begin("ldw_extract", h));
+        launch_ldw_extract(c.launch, w);
+        launch_scan_i64(c.launch, w.out_rowptr, mb_rowoff + c.k, slot(c, h, 0), nullptr, nullptr);
+        BMS_TRY(prof.end());
+        BMS_TRY(read_scalars(c)); // nnz sizes the column buffer
+        const int64_t nnz = host_slot(c, h, 0);
+        BMS_TRY(hb.col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
+        w.out_col = hb.col.as<int32_t>();
+        BMS_TRY(prof.begin("ldw_extract_copy", h));
+        launch_ldw_extract_copy(c.launch, w);
+        BMS_TRY(prof.end());
+
+        hb.view = bms_hop_view{};
+        hb.view.nnz = nnz;
+        hb.view.pnnz = pnnz;
+        hb.view.ncols = host_slot(c, h, 1);
+        hb.view.mb_rowoff = mb_rowoff;
+        hb.view.row_vertex = row_vertex;
+        hb.view.rowptr = hb.rowptr.as<int64_t>();
+        hb.view.col = hb.col.as<int32_t>();
+        hb.view.mb_coloff = hb.mb_coloff.as<int64_t>();
+        hb.view.col_vertex = hb.col_vertex.as<int32_t>();
+        hb.view.p_off = hb.p_off.as<int64_t>();
+        hb.view.p_col = hb.p_col.as<int32_t>();
+        hb.view.p_cnt = hb.p_cnt.as<uint32_t>();
+        hb.view.rows = h == 0 ? (int64_t)c.k * c.b : c.res->hops[h - 1].view.ncols;
+
+        row_vertex = hb.col_vertex.as<int32_t>();
+        mb_rowoff = hb.mb_coloff.as<int64_t>();
+        rows_bound = std::max<int64_t>(ncols_bound, 1);
+    }
+    HIP_TRY(hipStreamSynchronize(c.stream));
+    BMS_TRY(prof.finish());
+    return BMS_OK;
+}
+
 int sample_ladies_impl(CallCtx &c, const int32_t *batches, const int32_t *s_per_layer)
 {
+    if (ladies_windows_apply(c, s_per_layer))
+        return sample_ladies_windows_impl(c, batches, s_per_layer);
     bms_csr *csr = c.csr;
     Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
     BMS_TRY(setup_vset(c));
@@ -893,7 +1069,8 @@ void bms_free(void *handle)
         DevBuf *bufs[] = {&c->own_rowptr, &c->own_col,    &c->vs_words,   &c->vs_prefix,     &c->vs_chunks,
                           &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars,
                           &c->ld_counters, &c->ld_gather_off, &c->ld_row_mb, &c->ld_chunks, &c->ld_prefix,
-                          &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_utmp, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count, &c->dd_back, &c->dd_tileoff, &c->dd_cursor, &c->dd_seg};
+                          &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_utmp, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count, &c->dd_back, &c->dd_tileoff, &c->dd_cursor, &c->dd_seg,
+                          &c->lw_bounds, &c->lw_win, &c->lw_tmpcol, &c->lw_tmpcnt, &c->lw_sel, &c->lw_xtmp, &c->lw_count};
         for (DevBuf *b : bufs)
             b->release();
         if (c->host_pinned)

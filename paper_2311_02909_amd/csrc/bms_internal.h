@@ -167,4 +167,52 @@ void launch_ld_extract_count(const Launch &, const LdHop &, const VSet &, int64_
 void launch_ld_extract_fill(const Launch &, const LdHop &, const VSet &);
 void launch_chunk_scan(const Launch &, int64_t *chunk_off, int32_t k, int32_t nc, int64_t *mb_off, int64_t *total_out);
 
+// ---- LADIES with the column counts accumulated in LDS, window by window ----
+constexpr int kWinShift = 16;            // a window = 2^16 vertex ids = 2^16 16-bit counters = 128 KB of LDS
+constexpr int32_t kMaxWinRows = 65535;   // frontier rows per minibatch (a 16-bit counter cannot overflow)
+constexpr int32_t kMaxWinSampled = 4096; // columns sampled per minibatch (sorted, then hashed, in LDS)
+struct LwHop {
+    const int64_t *A_rowptr;
+    const int32_t *A_col;
+    int64_t n;
+    int32_t k;
+    int32_t s;
+    int squared;
+    uint64_t hopkey;
+    uint32_t mb_base;
+    const int32_t *row_vertex; // stacked frontier
+    const int64_t *mb_rowoff;  // k+1
+    int64_t rows_bound;
+    const int64_t *row_beg;    // rows   (from launch_ld_rows)
+    const int64_t *gather_off; // rows+1 (from launch_ld_rows)
+    int32_t nwin;              // ceil(n / 2^kWinShift)
+    uint32_t *bounds;          // (nwin+1) * rows_bound, window-major
+    uint32_t *win_cnt;         // k * nwin: columns of P inside the window
+    uint64_t *win_wt;          // k * nwin: their weight
+    int64_t *win_base;         // k * nwin: where the window's entries start in tmp_*
+    int64_t *win_poff;         // k * nwin: columns of the minibatch before the window
+    uint64_t *win_woff;        // k * nwin: weight of the minibatch before the window
+    unsigned long long *cursor; // device scalar: entries of tmp_* in use
+    int32_t *tmp_col;          // min(D, k n) entries
+    uint32_t *tmp_cnt;
+    int64_t *mb_count;         // k
+    int64_t *p_off;            // k+1
+    int32_t *p_col;
+    uint32_t *p_cnt;
+    uint64_t *prefix;          // pnnz, inclusive, restarts per minibatch
+    int32_t *sel_tmp;          // k * s
+    int64_t *mb_coloff;        // k+1
+    int32_t *col_vertex;
+    int32_t *xtmp;             // D entries: the kept neighbours of row r start at gather_off[r]
+    int64_t *out_rowptr;       // rows+1
+    int32_t *out_col;
+};
+void launch_ldw_bounds(const Launch &, const LwHop &);
+int launch_ldw_accumulate(const Launch &, const LwHop &); // also scans the windows; -1: launch refused
+void launch_ldw_p_copy(const Launch &, const LwHop &);
+void launch_ldw_draw(const Launch &, const LwHop &);
+void launch_ldw_sel_copy(const Launch &, const LwHop &);
+void launch_ldw_extract(const Launch &, const LwHop &);
+void launch_ldw_extract_copy(const Launch &, const LwHop &);
+
 } // namespace bms

@@ -21,9 +21,12 @@ def _run_both(mods, rowptr, col, batches, s_per_layer, seed, mb_base=0, squared=
     O, bms, _ = mods
     if csr is None:
         csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
-    res = bms.sample_ladies(csr, torch.from_numpy(batches).cuda(), s_per_layer, seed, mb_base=mb_base, squared=squared)
     ref = O.sample_ladies(rowptr, col, batches, s_per_layer, seed, mb_base, squared)
-    assert_hops_equal(res.hops(), ref, with_p=True, what="s=%s seed=%d squared=%s" % (s_per_layer, seed, squared))
+    for dense in (True, False):  # both kernel paths: counters in HBM, counters in LDS windows
+        res = bms.sample_ladies(csr, torch.from_numpy(batches).cuda(), s_per_layer, seed, mb_base=mb_base,
+                                squared=squared, dense=dense)
+        assert_hops_equal(res.hops(), ref, with_p=True,
+                          what="s=%s seed=%d squared=%s dense=%s" % (s_per_layer, seed, squared, dense))
     return csr, res, ref
 
 
@@ -34,13 +37,25 @@ def test_tiny_graph_layerwise(mods):
 
 
 @pytest.mark.parametrize("s,squared", [((1,), False), ((16, 16), False), ((100, 50, 25), False), ((512, 512, 512), False),
-                                       ((64, 64), True), ((3000, 10), True)])
+                                       ((64, 64), True), ((3000, 10), True), ((4096, 4097, 5), False)])
 def test_random_graph(mods, s, squared):
     # gathered order spans many 4096-entry tiles with a ragged tail; P spans several chunks and tiles
     rng = np.random.default_rng(len(s) * 100 + s[0])
     rowptr, col = random_csr(30000, 30.0, rng)
     batches = random_batches(30000, 5, 200, rng)
     _run_both(mods, rowptr, col, batches, s, 17, mb_base=2, squared=squared)
+
+
+@pytest.mark.parametrize("s,squared", [((400, 300, 200), False), ((2000, 50), True)])
+def test_many_id_windows(mods, s, squared):
+    # vertex ids span several 2^16-id windows; a skewed graph, so hub rows cross every window and
+    # leaf rows cross none
+    O, bms, synth = mods
+    g = synth.rmat_graph(300_000, 2_000_000, 0.55, 0.2, 0.2, seed=9, device="cuda")
+    rowptr, col = g.rowptr.cpu().numpy(), g.col.cpu().numpy()
+    rng = np.random.default_rng(s[0])
+    batches = random_batches(g.n, 6, 300, rng)
+    _run_both(mods, rowptr, col, batches, s, 23, mb_base=1, squared=squared, csr=bms.Csr(g.rowptr, g.col))
 
 
 def test_directed_with_loops_and_host_inputs(mods):
@@ -83,7 +98,7 @@ def test_degenerate_inputs_and_errors(mods):
         assert e.value.code == bms.ERANGE
     _run_both(mods, rowptr, col, np.array([[3, 2]], dtype=np.int32), (1,), 1, csr=csr)
     with pytest.raises(bms.BmsError) as e:
-        bms.sample_ladies(csr, np.array([[3, 2]], dtype=np.int32), (1,), 1, scratch_limit=64)
+        bms.sample_ladies(csr, np.array([[3, 2]], dtype=np.int32), (1,), 1, scratch_limit=8)
     assert e.value.code == bms.ENOMEM
 
 
