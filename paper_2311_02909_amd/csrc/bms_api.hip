@@ -103,7 +103,7 @@ struct bms_csr {
     DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars;
     DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
     DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count, dd_back, dd_tileoff, dd_cursor, dd_seg; // bucket EXTRACT
-    DevBuf lw_bounds, lw_win, lw_tmpcol, lw_tmpcnt, lw_sel, lw_xtmp, lw_count; // LADIES by LDS windows
+    DevBuf lw_bounds, lw_win, lw_tmpcol, lw_tmpcnt, lw_sel, lw_xtmp, lw_count, lw_tiles, lw_rowcnt; // LADIES by LDS windows
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
 };
@@ -596,7 +596,7 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
     const int32_t nwin = (int32_t)((n1 + (1LL << kWinShift) - 1) >> kWinShift);
     const size_t nw = (size_t)c.k * nwin;
     BMS_TRY(csr->lw_win.ensure(nw * (sizeof(uint32_t) + 4 * sizeof(int64_t)) + 64));
-    BMS_TRY(csr->lw_count.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+    BMS_TRY(csr->lw_count.ensure((3 * (size_t)c.k + 3) * sizeof(int64_t)));
     BMS_TRY(stage_seeds(c, batches, prof, false));
 
     int64_t rows_bound = (int64_t)c.k * c.b;
@@ -660,6 +660,9 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         w.win_cnt = reinterpret_cast<uint32_t *>(w.win_poff + nw);
         w.cursor = reinterpret_cast<unsigned long long *>(csr->scalars.as<int64_t>() + 61);
         w.mb_count = csr->lw_count.as<int64_t>();
+        w.mb_goff = w.mb_count + c.k + 1;
+        w.mb_gtileoff = w.mb_goff + c.k + 1;
+        w.row_mb = a.row_mb;
         w.p_off = hb.p_off.as<int64_t>();
         w.sel_tmp = csr->lw_sel.as<int32_t>();
         w.mb_coloff = hb.mb_coloff.as<int64_t>();
@@ -686,6 +689,12 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         w.tmp_col = csr->lw_tmpcol.as<int32_t>();
         w.tmp_cnt = csr->lw_tmpcnt.as<uint32_t>();
         w.xtmp = csr->lw_xtmp.as<int32_t>();
+        w.tiles_bound = D / kLwTile + c.k;
+        BMS_TRY(csr->lw_tiles.ensure((size_t)w.tiles_bound * (sizeof(int64_t) + sizeof(uint32_t)) + 64));
+        BMS_TRY(csr->lw_rowcnt.ensure((size_t)rows_bound * sizeof(uint32_t)));
+        w.tile_row = csr->lw_tiles.as<int64_t>();
+        w.tile_cnt = reinterpret_cast<uint32_t *>(w.tile_row + w.tiles_bound);
+        w.first_cnt = csr->lw_rowcnt.as<uint32_t>();
         BMS_TRY(prof.begin("ldw_bounds", h));
         launch_ldw_bounds(c.launch, w);
         BMS_TRY(prof.end());
@@ -1070,7 +1079,7 @@ void bms_free(void *handle)
                           &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars,
                           &c->ld_counters, &c->ld_gather_off, &c->ld_row_mb, &c->ld_chunks, &c->ld_prefix,
                           &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_utmp, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count, &c->dd_back, &c->dd_tileoff, &c->dd_cursor, &c->dd_seg,
-                          &c->lw_bounds, &c->lw_win, &c->lw_tmpcol, &c->lw_tmpcnt, &c->lw_sel, &c->lw_xtmp, &c->lw_count};
+                          &c->lw_bounds, &c->lw_win, &c->lw_tmpcol, &c->lw_tmpcnt, &c->lw_sel, &c->lw_xtmp, &c->lw_count, &c->lw_tiles, &c->lw_rowcnt};
         for (DevBuf *b : bufs)
             b->release();
         if (c->host_pinned)

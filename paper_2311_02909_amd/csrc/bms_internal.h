@@ -171,6 +171,7 @@ void launch_chunk_scan(const Launch &, int64_t *chunk_off, int32_t k, int32_t nc
 constexpr int kWinShift = 16;            // a window = 2^16 vertex ids = 2^16 16-bit counters = 128 KB of LDS
 constexpr int32_t kMaxWinRows = 65535;   // frontier rows per minibatch (a 16-bit counter cannot overflow)
 constexpr int32_t kMaxWinSampled = 4096; // columns sampled per minibatch (sorted, then hashed, in LDS)
+constexpr int kLwTile = 4096;            // positions of the gathered order streamed by one wave at a time
 struct LwHop {
     const int64_t *A_rowptr;
     const int32_t *A_col;
@@ -185,6 +186,13 @@ struct LwHop {
     int64_t rows_bound;
     const int64_t *row_beg;    // rows   (from launch_ld_rows)
     const int64_t *gather_off; // rows+1 (from launch_ld_rows)
+    const int32_t *row_mb;     // rows   (from launch_ld_rows)
+    int64_t *mb_goff;          // k+1: gathered position where each minibatch starts
+    int64_t *mb_gtileoff;      // k+1: tiles before each minibatch
+    int64_t *tile_row;         // tiles: row holding the tile's first position
+    uint32_t *tile_cnt;        // tiles: neighbours kept from the piece the tile starts with (row begun earlier)
+    uint32_t *first_cnt;       // rows: neighbours kept from the piece the row starts with
+    int64_t tiles_bound;       // host-side upper bound of the number of tiles
     int32_t nwin;              // ceil(n / 2^kWinShift)
     uint32_t *bounds;          // (nwin+1) * rows_bound, window-major
     uint32_t *win_cnt;         // k * nwin: columns of P inside the window

@@ -3,9 +3,12 @@
 //
 // The rows of A are sorted by column, so the neighbours of a frontier row that fall into a window
 // of 2^16 vertex ids form one contiguous piece of its adjacency list.  One hop, all k minibatches:
-//   ldw_bounds      one wave per frontier row streams the row once and records where it crosses
-//                   every window boundary (lower bounds, kept window-major so that the next
-//                   kernel reads them coalesced)
+//   ldw_tiles       the gathered order (the neighbour lists of the stacked frontier laid end to
+//                   end) cut into tiles of 4096 positions that never straddle minibatches; the
+//                   row each tile starts in
+//   ldw_bounds      one wave per tile streams its pieces of rows once and records where every
+//                   row crosses every window boundary (lower bounds, kept window-major so that
+//                   the next kernel reads them coalesced)
 //   ldw_accumulate  one workgroup per (minibatch, window): 2^16 packed 16-bit counters in LDS
 //                   (128 KB); every row's piece of the window adds 1 per neighbour (e_v cannot
 //                   exceed the number of frontier rows, which this path keeps below 2^16); the
@@ -18,11 +21,13 @@
 //   ldw_draw        SAMPLE (Sec. 4.2.2): one workgroup per minibatch: s draws, each the smallest t
 //                   with prefix[t] > r, sorted in LDS, duplicates dropped -> sampled columns
 //   ldw_extract     EXTRACT (Sec. 4.2.3): the sampled columns of the minibatch sit in an LDS hash
-//                   table (column -> local index); one wave per frontier row streams the row a
+//                   table (column -> local index); one wave per tile streams the gathered order a
 //                   second time and keeps the neighbours found in the table ((Q_R A) Q_C), in
-//                   row order; rows are then sized by a scan and copied to their place
+//                   row order, piece by piece; rows are then sized by a scan and their pieces
+//                   copied to their place
 #include "bms_device.h"
 #include "bms_internal.h"
+#include <algorithm>
 
 namespace bms {
 
@@ -32,6 +37,10 @@ constexpr int kAccThreads = 1024;
 constexpr int kAccWaves = kAccThreads / kWave;
 constexpr int kWaveWords = kWinWords / kAccWaves; // counter words compacted by one wave
 constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;
+constexpr int kExtThreads = 1024; // the waves of a workgroup share one hash table
+constexpr int kExtWaves = kExtThreads / kWave;
+constexpr int kAccUnroll = 16;
+constexpr int kStreamUnroll = 8; // neighbours per lane in flight in the two streaming passes // neighbours per lane in flight while accumulating
 constexpr int kHashSlots = 2 * kMaxWinSampled;    // load factor <= 1/2
 
 __device__ inline uint64_t ldw_weight(uint32_t cnt, int squared)
@@ -40,37 +49,86 @@ __device__ inline uint64_t ldw_weight(uint32_t cnt, int squared)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Tiles of the gathered order
+// ---------------------------------------------------------------------------------------------
+__global__ void ldw_mb_goff_kernel(LwHop a)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= a.k)
+        a.mb_goff[i] = a.gather_off[a.mb_rowoff[i]];
+}
+
+// tile_row[x] = the row that holds the first position of tile x (the last row starting at or before it)
+__global__ __launch_bounds__(256) void ldw_tile_rows_kernel(LwHop a)
+{
+    const int64_t ntiles = a.mb_gtileoff[a.k];
+    for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < ntiles; x += (int64_t)gridDim.x * 256) {
+        const int i = locate_segment(a.mb_gtileoff, a.k, x);
+        const int64_t g0 = a.mb_goff[i] + (x - a.mb_gtileoff[i]) * kLwTile;
+        int64_t lo = a.mb_rowoff[i], hi = a.mb_rowoff[i + 1];
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (a.gather_off[mid] <= g0)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        a.tile_row[x] = lo;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // bounds[w * rows_bound + r] = number of neighbours of row r with id < w * 2^16, w = 0..nwin
+// (rows without neighbours are skipped: their entries are never read)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t R = a.mb_rowoff[a.k];
-    const int64_t nwaves = (int64_t)gridDim.x * 4;
-    for (int64_t r = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave; r < R; r += nwaves) {
-        const uint32_t deg = (uint32_t)(a.gather_off[r + 1] - a.gather_off[r]);
-        const int32_t *__restrict__ src = a.A_col + a.row_beg[r];
-        uint32_t *__restrict__ out = a.bounds + r;
-        // position deg acts as one more entry that lies in window nwin: it closes every window left
-        int32_t carry = -1; // window of the entry before the ones in flight
-        for (uint32_t j0 = 0; j0 <= deg; j0 += 4 * kWave) {
-            int32_t wv[4];
+    const int64_t ntiles = a.mb_gtileoff[a.k];
+    for (int64_t x = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave; x < ntiles; x += (int64_t)gridDim.x * 4) {
+        const int i = locate_segment(a.mb_gtileoff, a.k, x);
+        int64_t g = a.mb_goff[i] + (x - a.mb_gtileoff[i]) * kLwTile;
+        const int64_t g1 = min(g + kLwTile, a.mb_goff[i + 1]);
+        int64_t r = a.tile_row[x];
+        while (g < g1) {
+            int64_t re = a.gather_off[r + 1];
+            while (re <= g)
+                re = a.gather_off[++r + 1];
+            const int64_t rs = a.gather_off[r];
+            const int64_t pe = min(re, g1);
+            const int64_t shift = a.row_beg[r] - rs; // A_col[shift + p] = neighbour at gathered position p
+            uint32_t *__restrict__ out = a.bounds + r;
+            // when the row ends inside the tile, position `re` acts as one more entry that lies in
+            // window nwin: it closes every window left
+            const int64_t last = pe == re ? pe : pe - 1;
+            int32_t carry = g == rs ? -1 : (a.A_col[shift + g - 1] >> kWinShift); // window of the entry before
+            for (int64_t p0 = g; p0 <= last; p0 += kStreamUnroll * kWave) {
+                // 32-bit slot numbers from here on: slot x of the step is gathered position p0 + x
+                const int32_t *__restrict__ from = a.A_col + (shift + p0);
+                const int32_t nreal = (int32_t)min<int64_t>(re - p0, kStreamUnroll * kWave); // slots that hold a neighbour
+                const int32_t xlast = (int32_t)min<int64_t>(last - p0, kStreamUnroll * kWave - 1);
+                const uint32_t pos0 = (uint32_t)(p0 - rs);
+                int32_t wv[kStreamUnroll];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t j = j0 + u * kWave + lane;
-                wv[u] = j < deg ? (src[j] >> kWinShift) : a.nwin;
-            }
+                for (int u = 0; u < kStreamUnroll; ++u) {
+                    const int32_t x = u * kWave + lane;
+                    wv[u] = x < nreal && x <= xlast ? (from[x] >> kWinShift) : a.nwin;
+                }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t j = j0 + u * kWave + lane;
-                int32_t pw = __shfl_up(wv[u], 1, kWave);
-                if (lane == 0)
-                    pw = carry;
-                if (j <= deg)
-                    for (int32_t w = pw + 1; w <= wv[u]; ++w)
-                        out[(int64_t)w * a.rows_bound] = j;
-                carry = __shfl(wv[u], kWave - 1, kWave);
+                for (int u = 0; u < kStreamUnroll; ++u) {
+                    const int32_t x = u * kWave + lane;
+                    int32_t pw = __shfl_up(wv[u], 1, kWave);
+                    if (lane == 0)
+                        pw = carry;
+                    if (x <= xlast)
+                        for (int32_t w = pw + 1; w <= wv[u]; ++w)
+                            out[(int64_t)w * a.rows_bound] = pos0 + (uint32_t)x;
+                    carry = __shfl(wv[u], kWave - 1, kWave);
+                }
             }
+            g = pe;
+            if (pe == re)
+                ++r;
         }
     }
 }
@@ -86,6 +144,10 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
     uint32_t *wave_nz = lds + kWinWords + 2 * kAccWaves;               // kAccWaves
     uint64_t *base_s = reinterpret_cast<uint64_t *>(lds + kWinWords + 3 * kAccWaves); // 1
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    // per wave: address origins of its nonempty pieces (64) and the start bits of one span of positions
+    int64_t *origin_of = reinterpret_cast<int64_t *>(lds + kWinWords + 3 * kAccWaves + 4) + wave * (kWave + kAccUnroll);
+    uint64_t *starts = reinterpret_cast<uint64_t *>(origin_of + kWave);
+    const uint64_t below = (1ull << lane) - 1ull, below_incl = below | (1ull << lane);
     const int64_t nblk = (int64_t)a.k * a.nwin;
     for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
         const int i = (int)(blk / a.nwin), w = (int)(blk % a.nwin);
@@ -96,28 +158,65 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         const uint32_t *__restrict__ lo_b = a.bounds + (int64_t)w * a.rows_bound;
         const uint32_t *__restrict__ hi_b = lo_b + a.rows_bound;
         const int32_t id0 = w << kWinShift;
-        const int sub = lane & 15, gbase = lane & 48;
-        for (int64_t base = r0 + (int64_t)wave * kWave; base < r1; base += (int64_t)kAccWaves * kWave) {
-            const int64_t r = base + lane;
-            uint32_t len = 0;
-            int64_t addr = 0;
+        // the piece of this window in row r: (length, address of its first neighbour); rows without
+        // neighbours have no boundaries on record: whatever is read there is dropped
+        auto piece_of = [&](int64_t r, uint32_t &len, int64_t &addr) {
+            len = 0;
+            addr = 0;
             if (r < r1) {
                 const uint32_t b0 = lo_b[r];
-                len = hi_b[r] - b0;
+                const uint32_t b1 = hi_b[r];
+                const bool empty = a.gather_off[r + 1] == a.gather_off[r];
+                len = empty ? 0u : b1 - b0;
                 addr = a.row_beg[r] + b0;
             }
-            if (__ballot(len != 0) == 0)
-                continue;
-            // four groups of 16 lanes; group g walks the pieces held by lanes 16 g .. 16 g + 15
-#pragma unroll 4
-            for (int t = 0; t < 16; ++t) {
-                const uint32_t l = __shfl(len, gbase + t, kWave);
-                const int64_t ad = __shfl(addr, gbase + t, kWave);
-                for (uint32_t e = sub; e < l; e += 16) {
-                    const uint32_t v = (uint32_t)(a.A_col[ad + e] - id0);
-                    atomicAdd(&cnt[v >> 1], 1u << ((v & 1u) * 16));
+        };
+        uint32_t len, next_len;
+        int64_t addr, next_addr;
+        piece_of(r0 + (int64_t)wave * kWave + lane, len, addr);
+        for (int64_t base = r0 + (int64_t)wave * kWave; base < r1; base += (int64_t)kAccWaves * kWave) {
+            // the next 64 pieces are on their way while these are walked
+            piece_of(base + (int64_t)kAccWaves * kWave + lane, next_len, next_addr);
+            // the 64 pieces of the wave laid end to end: lane f of a step takes position f of that order.
+            // Which piece that is follows from counting piece starts up to f: the starts inside the
+            // current span of positions are bits in LDS, the address origins of the nonempty pieces a
+            // small table in LDS indexed by their rank
+            const uint32_t inc = wave_inclusive_scan(len);
+            const uint32_t total = __shfl(inc, kWave - 1, kWave);
+            const uint32_t start = inc - len;
+            const bool nonempty = len != 0;
+            const uint64_t ne_mask = __ballot(nonempty);
+            __builtin_amdgcn_wave_barrier();
+            if (nonempty) // address of the piece's first neighbour - its position
+                origin_of[__popcll(ne_mask & below)] = addr - (int64_t)start;
+            for (uint32_t f0 = 0; f0 < total; f0 += kAccUnroll * kWave) {
+                __builtin_amdgcn_wave_barrier();
+                if (lane < kAccUnroll)
+                    starts[lane] = 0;
+                __builtin_amdgcn_wave_barrier();
+                const uint32_t rel = start - f0; // wraps for pieces that start before the span
+                if (nonempty && rel < (uint32_t)(kAccUnroll * kWave))
+                    atomicOr(reinterpret_cast<uint32_t *>(starts) + (rel >> 5), 1u << (rel & 31u));
+                __builtin_amdgcn_wave_barrier();
+                int rank = __popcll(__ballot(nonempty && start < f0)) - 1; // piece that holds position f0 - 1
+                uint32_t v[kAccUnroll];
+#pragma unroll
+                for (int u = 0; u < kAccUnroll; ++u) {
+                    const uint32_t f = f0 + u * kWave + lane;
+                    const uint64_t m = starts[u];
+                    const int mine = rank + __popcll(m & below_incl);
+                    rank += __popcll(m);
+                    v[u] = kEmptySlot;
+                    if (f < total)
+                        v[u] = (uint32_t)(a.A_col[origin_of[mine] + f] - id0);
                 }
+#pragma unroll
+                for (int u = 0; u < kAccUnroll; ++u)
+                    if (v[u] != kEmptySlot)
+                        atomicAdd(&cnt[v[u] >> 1], 1u << ((v[u] & 1u) * 16));
             }
+            len = next_len;
+            addr = next_addr;
         }
         __syncthreads();
         // each wave compacts kWaveWords consecutive words: first how many, then where, then the entries
@@ -155,7 +254,6 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         __syncthreads();
         if (nz) { // uniform per wave
             int64_t run = (int64_t)*base_s + wave_nz[wave];
-            const uint64_t below = (1ull << lane) - 1ull;
             for (int it = 0; it < kWaveWords / kWave; ++it) {
                 const int word = wave * kWaveWords + it * kWave + lane;
                 const uint32_t x = cnt[word];
@@ -336,19 +434,20 @@ __global__ __launch_bounds__(256) void ldw_sel_copy_kernel(LwHop a)
 __device__ inline uint32_t ldw_hash(uint32_t v) { return (v * 0x9E3779B1u) >> (32 - 13); }
 static_assert(kHashSlots == 1 << 13, "hash width out of step");
 
-__global__ __launch_bounds__(256) void ldw_extract_kernel(LwHop a)
+__global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
 {
     __shared__ uint32_t hkey[kHashSlots];
     __shared__ uint16_t hval[kHashSlots];
     const int i = blockIdx.y, tid = threadIdx.x, lane = tid & (kWave - 1);
     const int64_t c0 = a.mb_coloff[i];
     const int32_t ns = (int32_t)(a.mb_coloff[i + 1] - c0);
-    const int64_t r0 = a.mb_rowoff[i], r1 = a.mb_rowoff[i + 1];
-    const int64_t wave0 = (int64_t)blockIdx.x * 4 + tid / kWave, nwaves = (int64_t)gridDim.x * 4;
-    for (int x = tid; x < kHashSlots; x += 256)
+    const int64_t x0 = a.mb_gtileoff[i], ntiles = a.mb_gtileoff[i + 1] - x0;
+    if (ns == 0 || (int64_t)blockIdx.x * kExtWaves >= ntiles)
+        return; // nothing sampled: every row stays empty (the counters start at zero)
+    for (int x = tid; x < kHashSlots; x += kExtThreads)
         hkey[x] = kEmptySlot;
     __syncthreads();
-    for (int j = tid; j < ns; j += 256) {
+    for (int j = tid; j < ns; j += kExtThreads) {
         const uint32_t v = (uint32_t)a.col_vertex[c0 + j];
         uint32_t slot = ldw_hash(v);
         while (atomicCAS(&hkey[slot], kEmptySlot, v) != kEmptySlot)
@@ -357,22 +456,31 @@ __global__ __launch_bounds__(256) void ldw_extract_kernel(LwHop a)
     }
     __syncthreads();
     const uint64_t below = (1ull << lane) - 1ull;
-    for (int64_t r = r0 + wave0; r < r1; r += nwaves) {
-        const int64_t g0 = a.gather_off[r];
-        const uint32_t deg = (uint32_t)(a.gather_off[r + 1] - g0);
-        const int32_t *__restrict__ src = a.A_col + a.row_beg[r];
-        int32_t *__restrict__ out = a.xtmp + g0;
-        uint32_t kept = 0;
-        if (ns > 0) {
-            for (uint32_t j0 = 0; j0 < deg; j0 += 4 * kWave) {
-                uint32_t v[4];
+    unsigned long long *rowcnt = reinterpret_cast<unsigned long long *>(a.out_rowptr);
+    for (int64_t t = (int64_t)blockIdx.x * kExtWaves + tid / kWave; t < ntiles; t += (int64_t)gridDim.x * kExtWaves) {
+        int64_t g = a.mb_goff[i] + t * kLwTile;
+        const int64_t g1 = min(g + kLwTile, a.mb_goff[i + 1]);
+        int64_t r = a.tile_row[x0 + t];
+        while (g < g1) {
+            int64_t re = a.gather_off[r + 1];
+            while (re <= g)
+                re = a.gather_off[++r + 1];
+            const int64_t rs = a.gather_off[r];
+            const int64_t pe = min(re, g1);
+            const int64_t shift = a.row_beg[r] - rs; // A_col[shift + p] = neighbour at gathered position p
+            int32_t *__restrict__ out = a.xtmp + g; // the kept neighbours of a piece start where the piece starts
+            uint32_t kept = 0;
+            for (int64_t p0 = g; p0 < pe; p0 += kStreamUnroll * kWave) {
+                const int32_t *__restrict__ from = a.A_col + (shift + p0); // slot x of the step is position p0 + x
+                const int32_t nslots = (int32_t)min<int64_t>(pe - p0, kStreamUnroll * kWave);
+                uint32_t v[kStreamUnroll];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint32_t j = j0 + u * kWave + lane;
-                    v[u] = j < deg ? (uint32_t)src[j] : kEmptySlot;
+                for (int u = 0; u < kStreamUnroll; ++u) {
+                    const int32_t x = u * kWave + lane;
+                    v[u] = x < nslots ? (uint32_t)from[x] : kEmptySlot;
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < kStreamUnroll; ++u) {
                     int32_t local = -1;
                     if (v[u] != kEmptySlot) {
                         uint32_t slot = ldw_hash(v[u]);
@@ -391,34 +499,65 @@ __global__ __launch_bounds__(256) void ldw_extract_kernel(LwHop a)
                     kept += __popcll(m);
                 }
             }
+            if (lane == 0) {
+                if (g == rs)
+                    a.first_cnt[r] = kept; // the piece a row starts with
+                else
+                    a.tile_cnt[x0 + t] = kept; // the piece a tile starts with, of a row begun earlier
+                if (kept)
+                    atomicAdd(&rowcnt[r], (unsigned long long)kept);
+            }
+            g = pe;
+            if (pe == re)
+                ++r;
         }
-        if (lane == 0)
-            a.out_rowptr[r] = kept;
     }
 }
 
-// rows to their place: 16 lanes per row
+// rows to their place, piece by piece: 16 lanes per row
 __global__ __launch_bounds__(256) void ldw_extract_copy_kernel(LwHop a)
 {
     const int64_t R = a.mb_rowoff[a.k];
     const int sub = threadIdx.x & 15;
     const int64_t groups = (int64_t)gridDim.x * 16;
     for (int64_t r = (int64_t)blockIdx.x * 16 + threadIdx.x / 16; r < R; r += groups) {
-        const int64_t o0 = a.out_rowptr[r], cnt = a.out_rowptr[r + 1] - o0;
-        const int32_t *__restrict__ src = a.xtmp + a.gather_off[r];
-        for (int64_t j = sub; j < cnt; j += 16)
-            a.out_col[o0 + j] = src[j];
+        int64_t o = a.out_rowptr[r];
+        const int64_t total = a.out_rowptr[r + 1] - o;
+        if (total == 0)
+            continue;
+        const int i = a.row_mb[r];
+        const int64_t rs = a.gather_off[r], re = a.gather_off[r + 1];
+        const int64_t gm = a.mb_goff[i], xm = a.mb_gtileoff[i];
+        int64_t g = rs;
+        int64_t cnt = a.first_cnt[r];
+        int64_t t = (rs - gm) / kLwTile;
+        while (true) {
+            for (int64_t j = sub; j < cnt; j += 16)
+                a.out_col[o + j] = a.xtmp[g + j];
+            o += cnt;
+            ++t;
+            g = gm + t * kLwTile;
+            if (g >= re)
+                break;
+            cnt = a.tile_cnt[xm + t];
+        }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-size_t ldw_accumulate_lds_bytes() { return (size_t)(kWinWords + 3 * kAccWaves + 4) * sizeof(uint32_t); }
+size_t ldw_accumulate_lds_bytes()
+{
+    return (size_t)(kWinWords + 3 * kAccWaves + 4) * sizeof(uint32_t) + (size_t)kAccWaves * (kWave + kAccUnroll) * sizeof(uint64_t);
+}
 
 void launch_ldw_bounds(const Launch &L, const LwHop &a)
 {
-    hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.rows_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(ldw_mb_goff_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, a);
+    launch_plan_tiles(L, a.mb_goff, a.k, kLwTile, a.mb_gtileoff);
+    hipLaunchKernelGGL(ldw_tile_rows_kernel, dim3(grid_for(L, (a.tiles_bound + 255) / 256, 8)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.tiles_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
 }
 
 int launch_ldw_accumulate(const Launch &L, const LwHop &a)
@@ -456,10 +595,10 @@ void launch_ldw_sel_copy(const Launch &L, const LwHop &a)
 
 void launch_ldw_extract(const Launch &L, const LwHop &a)
 {
-    int per_mb = (L.num_cu * 8 + a.k - 1) / a.k; // workgroups per minibatch: about 8 per compute unit in all
-    if (per_mb > 64)
-        per_mb = 64;
-    hipLaunchKernelGGL(ldw_extract_kernel, dim3(per_mb, a.k), dim3(256), 0, L.stream, a);
+    int64_t per_mb = (L.num_cu * 2 + a.k - 1) / a.k; // workgroups per minibatch: about 2 per compute unit in all
+    per_mb = std::min<int64_t>(per_mb, (a.tiles_bound + kExtWaves - 1) / kExtWaves); // never more than there are tiles
+    per_mb = std::max<int64_t>(per_mb, 1);
+    hipLaunchKernelGGL(ldw_extract_kernel, dim3((unsigned)per_mb, a.k), dim3(kExtThreads), 0, L.stream, a);
 }
 
 void launch_ldw_extract_copy(const Launch &L, const LwHop &a)
