@@ -41,9 +41,9 @@ def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0
     vertices): frontier id 4 R + two adjacent rowptr entries 16 R (nw_rows); output rowptr 8 R,
     chosen neighbours read 4 E and staged 4 E (nw_sample); staged ids read 4 E, local columns
     written 4 E (nw_relabel); next frontier written 4 U (vset_rank).
-    Layer-wise hop: 8 D + 8 C + 28 F + 4 nnz(A_S): frontier 4 F + rowptr 16 F (ld_rows); gathered
-    neighbours 4 D (ld_accumulate); P written 8 C (ld_p_fill); second pass over the rows 4 D
-    (ld_extract_count); output 8 F + 4 nnz (ld_extract_fill); sampled set 4 S (vset_rank).
+    Layer-wise hop: 8 D + 8 C + 28 F + 4 nnz(A_S) + 4 S: frontier 4 F + rowptr 16 F (ld_rows); gathered
+    neighbours 4 D (ldw_accumulate); P written 8 C (ldw_p_copy); sampled set 4 S (ldw_draw); second pass
+    over the rows 4 D (ldw_extract); output 8 F + 4 nnz (ldw_extract_copy).
     Scratch traffic (degrees, vertex-set bitmaps, dense counters, tile sums) is not counted.
     """
     R, E, U = float(rows), float(nnz), float(ncols)
@@ -60,6 +60,14 @@ def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0
         "dd_front": 4 * U,
         "dd_bins": 8 * E + 4 * U,
         "ld_rows": 20 * R,
+        # LADIES by LDS windows (default): the neighbours are read once to build P (ldw_accumulate) and once
+        # to extract (ldw_extract); ldw_bounds is a third pass that moves scratch only
+        "ldw_accumulate": 4.0 * gathered,
+        "ldw_p_copy": 8.0 * pnnz,
+        "ldw_draw": 4 * U,
+        "ldw_extract": 4.0 * gathered,
+        "ldw_extract_copy": 8 * R + 4 * E,
+        # LADIES with dense counters in HBM (BMS_LADIES_DENSE)
         "ld_accumulate": 4.0 * gathered,
         "ld_p_fill": 8.0 * pnnz,
         "ld_extract_count": 4.0 * gathered,
@@ -135,15 +143,17 @@ def main() -> int:
     # per-kernel totals over the hops (each stage is one kernel launch per hop, except the few
     # multi-kernel stages named after their main kernel)
     per_stage = {}
+    gathered_of_hop = {}
+    if not nodewise:  # D_h = sum of the degrees of hop h's frontier rows (what LADIES has to read)
+        deg = (g.rowptr[1:] - g.rowptr[:-1])
+        for hop in range(len(sizes)):
+            gathered_of_hop[hop] = int(deg[res.hop(hop).row_vertex.long()].sum().item())
     for (name, hop), ms in stage_ms.items():
         d = per_stage.setdefault(name, {"ms": 0.0, "launches": 0, "bytes": 0.0})
         d["ms"] += ms / stage_n[(name, hop)]
         d["launches"] += 1
         hv = res.hop(hop)
-        gathered = 0
-        if not nodewise:
-            deg = (g.rowptr[1:] - g.rowptr[:-1])
-            gathered = int(deg[hv.row_vertex.long()].sum().item())
+        gathered = gathered_of_hop.get(hop, 0)
         d["bytes"] += algorithmic_bytes(name, hv.rows, hv.nnz, hv.ncols, hv.pnnz, gathered)
     dominant = max(per_stage, key=lambda s: per_stage[s]["ms"])
     dom = per_stage[dominant]
@@ -196,6 +206,9 @@ def main() -> int:
                    "rows_nnz_cols_per_hop": [list(s) for s in sizes]},
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if not nodewise:
+        out["gathered_neighbours_per_sec"] = round(sum(gathered_of_hop.values()) / (ms_per_step * 1e-3), 1)
+        out["config"]["gathered_per_hop"] = [gathered_of_hop[h] for h in sorted(gathered_of_hop)]
     print(json.dumps(out), flush=True)
     return 0
 
