@@ -561,3 +561,25 @@ int orc_set_threads(int nthreads)
     return 1;
 #endif
 }
+
+/*
+ * Feature fetching, the part one GPU does (Sec. 6.2): H_i holds the rows of the feature matrix H that
+ * belong to the vertices of a minibatch's last frontier, in frontier order.  H is n x f, row-major.
+ * Returns 0, or -2 when an id lies outside [0, n) (such rows are written as zeros).
+ */
+int orc_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids, int64_t m, float *out)
+{
+    int rc = 0;
+    for (int64_t j = 0; j < m; ++j) {
+        const int64_t v = ids[j];
+        for (int32_t x = 0; x < f; ++x) {
+            if (v < 0 || v >= n) {
+                out[j * f + x] = 0.0f;
+                rc = -2;
+            } else {
+                out[j * f + x] = H[v * f + x];
+            }
+        }
+    }
+    return rc;
+}

@@ -84,6 +84,8 @@ def lib() -> C.CDLL:
         L.orc_result_hop.argtypes = [C.c_void_p, C.c_int32]
         L.orc_result_free.restype = None
         L.orc_result_free.argtypes = [C.c_void_p]
+        L.orc_fetch_features.restype = C.c_int
+        L.orc_fetch_features.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
         L.orc_set_threads.restype = C.c_int
         L.orc_set_threads.argtypes = [C.c_int]
         _lib = L
@@ -128,6 +130,18 @@ def its_distinct(key: int, deg: int, s: int) -> List[int]:
 def set_threads(nthreads: int = 0) -> int:
     """Set (if > 0) and return the number of threads of the loop over minibatches."""
     return int(lib().orc_set_threads(nthreads))
+
+
+def fetch_features(H: np.ndarray, ids: np.ndarray) -> np.ndarray:
+    """Rows of the n x f fp32 feature matrix H for the listed vertex ids (Sec. 6.2); raises on an id outside [0, n)."""
+    H = np.ascontiguousarray(H, dtype=np.float32)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    n, f = H.shape
+    out = np.empty((ids.shape[0], f), dtype=np.float32)
+    rc = lib().orc_fetch_features(H.ctypes.data, n, f, ids.ctypes.data, ids.shape[0], out.ctypes.data)
+    if rc != 0:
+        raise ValueError("vertex id outside [0, %d)" % n)
+    return out
 
 
 NOVERTEX = 0xFFFFFFFF
