@@ -84,6 +84,8 @@ def main() -> int:
     ap.add_argument("--workload", default="large_sage",
                     help="one of paper_2311_02909_amd.synth.WORKLOADS (default: the 111M-vertex node-wise config)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--no-feature-fetch", action="store_true",
+                    help="skip the feature fetch of the last frontier that is timed after the sampling steps")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB mebibytes 5 times "
                          "(calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters against a known size)")
@@ -184,6 +186,39 @@ def main() -> int:
         if args.workload in MEASURED_CALL_TRAFFIC else None,
     }
 
+    # The step after sampling (not part of `value`): fetch the feature rows of the last frontier of all k
+    # minibatches, H n x f fp32 resident in HBM.  Timed with HIP events on the stream the copy runs on.
+    fetch = None
+    if not args.no_feature_fetch:
+        f = w["features"]
+        last = res.hop(len(sizes) - 1)
+        m = int(last.ncols)
+        free_b = torch.cuda.mem_get_info()[0]
+        need = (g.n + m) * f * 4
+        if need < 0.8 * free_b and m > 0:
+            H = torch.empty((g.n, f), dtype=torch.float32, device="cuda")
+            H.view(-1)[:] = 1.0  # contents do not matter for a copy; avoid reading never-written pages
+            out_rows = torch.empty((m, f), dtype=torch.float32, device="cuda")
+            ids = last.col_vertex
+            for _ in range(2):
+                bms.fetch_features(H, ids, out=out_rows)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 5
+            e0.record(stream)
+            for _ in range(reps):
+                bms.fetch_features(H, ids, out=out_rows)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            fetch_ms = e0.elapsed_time(e1) / reps
+            fetch_bytes = m * (4 + 8 * f)  # ids read, rows read, rows written
+            fetch = {"rows": m, "f": f, "ms": round(fetch_ms, 4), "bound": "hbm",
+                     "achieved": round(fetch_bytes / (fetch_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(fetch_bytes / (fetch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "algorithmic_bytes": fetch_bytes}
+            del H, out_rows
+        else:
+            fetch = {"skipped": "feature matrix of %d bytes does not fit beside the graph" % need}
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import bms_oracle as O
@@ -204,7 +239,7 @@ def main() -> int:
         "config": {"workload": args.workload, "sampler": w["sampler"], "params": list(w["params"]),
                    "batch": w["batch"], "k": k, "n": g.n, "nnz": g.nnz, "max_degree": g.max_degree,
                    "rows_nnz_cols_per_hop": [list(s) for s in sizes]},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "feature_fetch": fetch,
     }
     if not nodewise:
         out["gathered_neighbours_per_sec"] = round(sum(gathered_of_hop.values()) / (ms_per_step * 1e-3), 1)

@@ -136,6 +136,20 @@ int bms_result_info(const bms_result *res, int32_t *k, int32_t *L);
 int bms_result_hop(const bms_result *res, int32_t hop, bms_hop_view *view);
 
 /*
+ * Feature fetching, the part one GPU does (Sec. 6.2): H_i = the rows of the feature matrix H that belong to
+ * the vertices of the last frontier.  out[j * f + x] = H[ids[j] * f + x] for j in [0, m), x in [0, f).
+ *   H    device, n x f fp32, row-major, caller-owned, read only
+ *   ids  device, m vertex ids, e.g. bms_hop_view.col_vertex of the last hop (all minibatches stacked:
+ *        minibatch i owns rows [mb_coloff[i], mb_coloff[i+1]) of out)
+ *   out  device, m x f fp32, caller-owned, overwritten
+ * The copy is enqueued on `stream` (hipStream_t, NULL = the null stream); the call returns after it has
+ * completed.  Rows are copied bit for bit.  An id outside [0, n) gives BMS_ERANGE (its row is written as
+ * zeros, the other rows are valid); n < 0, f < 1, m < 0, or a null pointer while m > 0, give BMS_EINVAL.
+ */
+int bms_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids, int64_t m, float *out,
+                       void *stream);
+
+/*
  * Per-stage device time of the call that produced `res` (only with BMS_PROFILE; measured with HIP
  * events on the call's stream).  idx enumerates the recorded stages in launch order; returns
  * BMS_EINVAL past the end.  *name points to a static string such as "nw_sample", *hop to the hop.

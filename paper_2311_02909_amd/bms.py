@@ -69,6 +69,8 @@ def lib() -> C.CDLL:
                                        C.POINTER(C.c_float)]
         L.bms_free.restype = None
         L.bms_free.argtypes = [C.c_void_p]
+        L.bms_fetch_features.restype = C.c_int
+        L.bms_fetch_features.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.bms_strerror.restype = C.c_char_p
         L.bms_strerror.argtypes = [C.c_int]
         L.bms_last_error.restype = C.c_char_p
@@ -277,3 +279,21 @@ def sample_ladies(csr: Csr, batches, s_per_layer: Sequence[int], seed: int, *, m
     flags = (PROFILE if profile else 0) | (LADIES_SQUARED if squared else 0) | (LADIES_DENSE if dense else 0)
     return _sample(lib().bms_sample_ladies, csr, batches, s_per_layer, seed, mb_base, stream, recycle, flags,
                    scratch_limit)
+
+
+def fetch_features(H: torch.Tensor, ids: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """bms_fetch_features: out[j, :] = H[ids[j], :] (device tensors; H n x f fp32, ids int32)."""
+    if H.dtype != torch.float32 or H.dim() != 2 or not H.is_cuda or not H.is_contiguous():
+        raise TypeError("H must be a contiguous n x f float32 device tensor")
+    if ids.dtype != torch.int32 or ids.dim() != 1 or not ids.is_cuda or not ids.is_contiguous():
+        raise TypeError("ids must be a contiguous int32 device vector")
+    n, f = H.shape
+    m = ids.shape[0]
+    if out is None:
+        out = torch.empty((m, f), dtype=torch.float32, device=H.device)
+    elif out.dtype != torch.float32 or tuple(out.shape) != (m, f) or not out.is_cuda or not out.is_contiguous():
+        raise TypeError("out must be a contiguous m x f float32 device tensor")
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().bms_fetch_features(H.data_ptr(), n, f, ids.data_ptr(), m, out.data_ptr(), stream))
+    return out

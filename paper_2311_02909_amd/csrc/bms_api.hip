@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1094,12 +1095,52 @@ void bms_free(void *handle)
     }
 }
 
+int bms_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids, int64_t m, float *out, void *stream)
+{
+    if (n < 0 || f < 1 || m < 0)
+        return fail(BMS_EINVAL, "n=%lld f=%d m=%lld out of range", (long long)n, f, (long long)m);
+    if (m == 0)
+        return BMS_OK; // nothing to fetch: the pointers are not looked at
+    if (!H || !out || !ids)
+        return fail(BMS_EINVAL, "null argument");
+    int device = 0;
+    HIP_TRY(hipGetDevice(&device));
+    // one error flag per device in host memory that the kernel can write: nothing to allocate per call
+    static int32_t *flags[64] = {nullptr};
+    static std::mutex flags_lock;
+    int32_t *flag = nullptr;
+    {
+        std::lock_guard<std::mutex> guard(flags_lock);
+        if (device < 0 || device >= 64)
+            return fail(BMS_EINVAL, "device ordinal %d not supported", device);
+        if (!flags[device])
+            HIP_TRY(hipHostMalloc((void **)&flags[device], 64, hipHostMallocMapped));
+        flag = flags[device];
+    }
+    int32_t *flag_dev = nullptr;
+    HIP_TRY(hipHostGetDevicePointer((void **)&flag_dev, flag, 0));
+    hipDeviceProp_t prop;
+    int num_cu = 256;
+    static int cached_cu[64] = {0};
+    if (!cached_cu[device] && hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
+        cached_cu[device] = prop.multiProcessorCount;
+    if (cached_cu[device])
+        num_cu = cached_cu[device];
+    *flag = 0;
+    launch_feature_fetch(Launch{(hipStream_t)stream, num_cu}, H, n, f, ids, m, out, flag_dev);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    if (*flag)
+        return fail(BMS_ERANGE, "a vertex id lies outside [0, %lld)", (long long)n);
+    return BMS_OK;
+}
+
 const char *bms_strerror(int code)
 {
     switch (code) {
     case BMS_OK: return "success";
     case BMS_EINVAL: return "invalid argument";
-    case BMS_ERANGE: return "seed vertex out of range or repeated inside a minibatch";
+    case BMS_ERANGE: return "vertex id out of range, or seed repeated inside a minibatch";
     case BMS_EFORMAT: return "malformed CSR matrix";
     case BMS_ENOMEM: return "out of memory or scratch limit too small";
     case BMS_EHIP: return "HIP runtime error";

@@ -223,4 +223,9 @@ void launch_ldw_sel_copy(const Launch &, const LwHop &);
 void launch_ldw_extract(const Launch &, const LwHop &);
 void launch_ldw_extract_copy(const Launch &, const LwHop &);
 
+// ---- feature fetching ----
+// out[j, :] = H[ids[j], :]; *flag (device-visible, zeroed by the caller) is set when an id lies outside [0, n)
+void launch_feature_fetch(const Launch &, const float *H, int64_t n, int32_t f, const int32_t *ids, int64_t m,
+                          float *out, int32_t *flag);
+
 } // namespace bms

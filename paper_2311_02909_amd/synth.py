@@ -168,24 +168,25 @@ def train_batches(n: int, frac: float, k: int, b: int, seed: int, device="cpu", 
 
 # The five workloads (graph recipe + sampler parameters).  `pairs` is the only tuned
 # number: how many R-MAT pairs to generate so that nnz lands near the target.
+# `features` = length f of a vertex's feature vector in the dataset the workload stands in for (Table 3)
 WORKLOADS = {
     # Tiny node-wise
     "tiny_sage": dict(graph=dict(n=10_000, pairs=148_000, a=0.57, b=0.19, c=0.19, seed=1),
-                      sampler="nodewise", params=(5, 5), batch=64, k=4, frac=0.10),
+                      sampler="nodewise", params=(5, 5), batch=64, k=4, frac=0.10, features=16),
     # Mid node-wise: stands in for the Products-sized row of Table 3
     "mid_sage": dict(graph=dict(n=2_450_000, pairs=94_000_000, a=0.50, b=0.17, c=0.17, seed=1),
-                     sampler="nodewise", params=(15, 10, 5), batch=1024, k=64, frac=0.08),
+                     sampler="nodewise", params=(15, 10, 5), batch=1024, k=64, frac=0.08, features=100),
     # Layer-wise on the same graph
     "mid_ladies": dict(graph=dict(n=2_450_000, pairs=94_000_000, a=0.50, b=0.17, c=0.17, seed=1),
-                       sampler="ladies", params=(512, 512, 512), batch=512, k=32, frac=0.08),
+                       sampler="ladies", params=(512, 512, 512), batch=512, k=32, frac=0.08, features=100),
     # Large node-wise: stands in for the Papers-sized row of Table 3
     "large_sage": dict(graph=dict(n=111_000_000, pairs=861_000_000, a=0.52, b=0.18, c=0.18, seed=1),
-                       sampler="nodewise", params=(15, 10, 5), batch=1024, k=256, frac=0.011),
+                       sampler="nodewise", params=(15, 10, 5), batch=1024, k=256, frac=0.011, features=128),
     # Dense-ish large: stands in for the Protein-sized row of Table 3
     "dense_sage": dict(graph=dict(n=8_700_000, pairs=1_280_000_000, a=0.45, b=0.22, c=0.22, seed=1),
-                       sampler="nodewise", params=(15, 10, 5), batch=1024, k=128, frac=0.12),
+                       sampler="nodewise", params=(15, 10, 5), batch=1024, k=128, frac=0.12, features=128),
     "dense_ladies": dict(graph=dict(n=8_700_000, pairs=1_280_000_000, a=0.45, b=0.22, c=0.22, seed=1),
-                         sampler="ladies", params=(2048, 2048, 2048), batch=1024, k=64, frac=0.12),
+                         sampler="ladies", params=(2048, 2048, 2048), batch=1024, k=64, frac=0.12, features=128),
 }
 
 SPLIT_SEED = 2
