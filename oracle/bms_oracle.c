@@ -583,3 +583,29 @@ int orc_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids,
     }
     return rc;
 }
+
+/*
+ * Forward neighbourhood aggregation of one hop (Sec. 6.2: an SpMM between a minibatch's sampled adjacency
+ * matrix A_i and the feature rows H_i of its columns), written for the stacked result: row r of minibatch i
+ * has entries e in [rowptr[r], rowptr[r+1]) whose local columns col[e] index the minibatch's own block of
+ * X, which starts at row mb_coloff[i].  out[r, :] = sum over e of X[mb_coloff[i] + col[e], :], divided by
+ * the number of entries when mean != 0 (all entries of A_i are 1).  Accumulated in double in entry order and
+ * rounded to float once; a row without entries gives zeros.
+ */
+void orc_aggregate(const int64_t *mb_rowoff, int32_t k, const int64_t *rowptr, const int32_t *col,
+                   const int64_t *mb_coloff, const float *X, int32_t f, int mean, float *out)
+{
+    for (int32_t i = 0; i < k; ++i) {
+        for (int64_t r = mb_rowoff[i]; r < mb_rowoff[i + 1]; ++r) {
+            const int64_t len = rowptr[r + 1] - rowptr[r];
+            for (int32_t x = 0; x < f; ++x) {
+                double acc = 0.0;
+                for (int64_t e = rowptr[r]; e < rowptr[r + 1]; ++e)
+                    acc += (double)X[(mb_coloff[i] + col[e]) * f + x];
+                if (mean && len > 0)
+                    acc /= (double)len;
+                out[r * f + x] = (float)acc;
+            }
+        }
+    }
+}

@@ -86,6 +86,9 @@ def lib() -> C.CDLL:
         L.orc_result_free.argtypes = [C.c_void_p]
         L.orc_fetch_features.restype = C.c_int
         L.orc_fetch_features.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+        L.orc_aggregate.restype = None
+        L.orc_aggregate.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                    C.c_int, C.c_void_p]
         L.orc_set_threads.restype = C.c_int
         L.orc_set_threads.argtypes = [C.c_int]
         _lib = L
@@ -141,6 +144,23 @@ def fetch_features(H: np.ndarray, ids: np.ndarray) -> np.ndarray:
     rc = lib().orc_fetch_features(H.ctypes.data, n, f, ids.ctypes.data, ids.shape[0], out.ctypes.data)
     if rc != 0:
         raise ValueError("vertex id outside [0, %d)" % n)
+    return out
+
+
+def aggregate(hop, X: np.ndarray, mean: bool = True) -> np.ndarray:
+    """Forward aggregation of one hop (Sec. 6.2): out[r] = mean (or sum) of X over row r's sampled columns.
+
+    `hop` is a Hop of a bulk sample; X has one fp32 row per stacked column (hop.ncols x f)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    assert X.shape[0] == hop.ncols
+    f = X.shape[1]
+    mb_rowoff = np.ascontiguousarray(hop.mb_rowoff, dtype=np.int64)
+    rowptr = np.ascontiguousarray(hop.rowptr, dtype=np.int64)
+    col = np.ascontiguousarray(hop.col, dtype=np.int32)
+    mb_coloff = np.ascontiguousarray(hop.mb_coloff, dtype=np.int64)
+    out = np.empty((hop.rows, f), dtype=np.float32)
+    lib().orc_aggregate(mb_rowoff.ctypes.data, mb_rowoff.shape[0] - 1, rowptr.ctypes.data, col.ctypes.data,
+                        mb_coloff.ctypes.data, X.ctypes.data, f, 1 if mean else 0, out.ctypes.data)
     return out
 
 
