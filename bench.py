@@ -215,7 +215,24 @@ def main() -> int:
                      "achieved": round(fetch_bytes / (fetch_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(fetch_bytes / (fetch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "algorithmic_bytes": fetch_bytes}
-            del H, out_rows
+            # ... and the first propagation step on it: mean aggregation over the last hop's sampled adjacency
+            last_h = len(sizes) - 1
+            agg_out = torch.empty((int(last.rows), f), dtype=torch.float32, device="cuda")
+            for _ in range(2):
+                bms.aggregate_hop(res, last_h, out_rows, out=agg_out)
+            e0.record(stream)
+            for _ in range(reps):
+                bms.aggregate_hop(res, last_h, out_rows, out=agg_out)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            agg_ms = e0.elapsed_time(e1) / reps
+            # every sampled edge reads one feature row, every row writes one; plus the CSR itself
+            agg_bytes = int(last.nnz) * (4 * f + 4) + int(last.rows) * (4 * f + 8)
+            fetch["aggregate_last_hop"] = {
+                "rows": int(last.rows), "edges": int(last.nnz), "ms": round(agg_ms, 4), "bound": "hbm",
+                "achieved": round(agg_bytes / (agg_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(agg_bytes / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "algorithmic_bytes": agg_bytes}
+            del H, out_rows, agg_out
         else:
             fetch = {"skipped": "feature matrix of %d bytes does not fit beside the graph" % need}
 

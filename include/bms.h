@@ -150,6 +150,21 @@ int bms_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids,
                        void *stream);
 
 /*
+ * Forward neighbourhood aggregation of one hop (Sec. 6.2: the SpMM between a minibatch's sampled adjacency
+ * matrix A_i and the feature rows H_i of its columns), for all k minibatches of the stacked result at once.
+ * For stacked row r of minibatch i:  out[r, :] = sum over the row's entries e of X[mb_coloff[i] + col[e], :],
+ * divided by the number of entries when mean != 0 (every entry of A_i is 1); a row without entries gives zeros.
+ *   res, hop  a completed bulk sample and the hop whose adjacency is used
+ *   X         device, ncols x f fp32 row-major: one row per stacked column of the hop (for the last hop the
+ *             output of bms_fetch_features on col_vertex; for earlier hops the previous aggregation's output)
+ *   out       device, rows x f fp32, caller-owned, overwritten
+ * fp32 arithmetic, entries added in ascending order (the result does not depend on the launch shape).
+ * Enqueued on `stream`; returns without waiting.  BMS_EINVAL for a bad handle, hop, f < 1 or null pointers.
+ */
+int bms_aggregate_hop(const bms_result *res, int32_t hop, const float *X, int32_t f, int mean, float *out,
+                      void *stream);
+
+/*
  * Per-stage device time of the call that produced `res` (only with BMS_PROFILE; measured with HIP
  * events on the call's stream).  idx enumerates the recorded stages in launch order; returns
  * BMS_EINVAL past the end.  *name points to a static string such as "nw_sample", *hop to the hop.

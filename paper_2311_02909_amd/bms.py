@@ -69,6 +69,8 @@ def lib() -> C.CDLL:
                                        C.POINTER(C.c_float)]
         L.bms_free.restype = None
         L.bms_free.argtypes = [C.c_void_p]
+        L.bms_aggregate_hop.restype = C.c_int
+        L.bms_aggregate_hop.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int, C.c_void_p, C.c_void_p]
         L.bms_fetch_features.restype = C.c_int
         L.bms_fetch_features.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.bms_strerror.restype = C.c_char_p
@@ -296,4 +298,23 @@ def fetch_features(H: torch.Tensor, ids: torch.Tensor, out: Optional[torch.Tenso
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
     _check(lib().bms_fetch_features(H.data_ptr(), n, f, ids.data_ptr(), m, out.data_ptr(), stream))
+    return out
+
+
+def aggregate_hop(res: "Result", hop: int, X: torch.Tensor, mean: bool = True, out: Optional[torch.Tensor] = None,
+                  stream=None) -> torch.Tensor:
+    """bms_aggregate_hop: out[r, :] = mean (or sum) of X over the sampled columns of stacked row r of `hop`."""
+    if X.dtype != torch.float32 or X.dim() != 2 or not X.is_cuda or not X.is_contiguous():
+        raise TypeError("X must be a contiguous ncols x f float32 device tensor")
+    rows, _, ncols = res.sizes()[hop]
+    if X.shape[0] != ncols:
+        raise ValueError("X has %d rows, the hop has %d columns" % (X.shape[0], ncols))
+    f = X.shape[1]
+    if out is None:
+        out = torch.empty((rows, f), dtype=torch.float32, device=X.device)
+    elif out.dtype != torch.float32 or tuple(out.shape) != (rows, f) or not out.is_cuda or not out.is_contiguous():
+        raise TypeError("out must be a contiguous rows x f float32 device tensor")
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().bms_aggregate_hop(res.handle, hop, X.data_ptr(), f, 1 if mean else 0, out.data_ptr(), stream))
     return out

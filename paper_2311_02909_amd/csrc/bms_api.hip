@@ -1135,6 +1135,38 @@ int bms_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids,
     return BMS_OK;
 }
 
+int bms_aggregate_hop(const bms_result *res, int32_t hop, const float *X, int32_t f, int mean, float *out, void *stream)
+{
+    if (!res || res->tag != kTagResult)
+        return fail(BMS_EINVAL, "not a result handle");
+    if (hop < 0 || hop >= res->L)
+        return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
+    if (f < 1)
+        return fail(BMS_EINVAL, "f=%d must be >= 1", f);
+    const bms_hop_view &v = res->hops[hop].view;
+    if (v.rows == 0)
+        return BMS_OK;
+    if (!out || (!X && v.nnz > 0))
+        return fail(BMS_EINVAL, "null argument");
+    AggArgs a{};
+    a.rows = v.rows;
+    a.k = res->k;
+    a.f = f;
+    a.mean = mean;
+    a.mb_rowoff = v.mb_rowoff;
+    a.rowptr = v.rowptr;
+    a.col = v.col;
+    a.mb_coloff = v.mb_coloff;
+    a.X = X;
+    a.out = out;
+    int device = 0, num_cu = 256;
+    HIP_TRY(hipGetDevice(&device));
+    HIP_TRY(hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, device));
+    launch_aggregate(Launch{(hipStream_t)stream, num_cu > 0 ? num_cu : 256}, a);
+    HIP_TRY(hipGetLastError());
+    return BMS_OK;
+}
+
 const char *bms_strerror(int code)
 {
     switch (code) {

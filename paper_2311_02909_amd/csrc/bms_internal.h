@@ -228,4 +228,19 @@ void launch_ldw_extract_copy(const Launch &, const LwHop &);
 void launch_feature_fetch(const Launch &, const float *H, int64_t n, int32_t f, const int32_t *ids, int64_t m,
                           float *out, int32_t *flag);
 
+// ---- forward aggregation of one hop ----
+struct AggArgs {
+    int64_t rows;
+    int32_t k;
+    int32_t f;
+    int mean;
+    const int64_t *mb_rowoff; // k+1
+    const int64_t *rowptr;    // rows+1
+    const int32_t *col;       // local columns
+    const int64_t *mb_coloff; // k+1
+    const float *X;           // ncols x f
+    float *out;               // rows x f
+};
+void launch_aggregate(const Launch &, const AggArgs &);
+
 } // namespace bms

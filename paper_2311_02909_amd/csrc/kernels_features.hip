@@ -72,3 +72,71 @@ void launch_feature_fetch(const Launch &L, const float *H, int64_t n, int32_t f,
 }
 
 } // namespace bms
+
+namespace bms {
+
+// Forward neighbourhood aggregation of one hop (Sec. 6.2): the SpMM between the stacked sampled adjacency
+// (all entries 1) and the feature rows of its columns.  2^lanes_log2 lanes share an output row and hold
+// VEC features each per access; the row's entries are added in ascending order in fp32, four gathered
+// rows in flight.  mean != 0 divides by the number of entries (rows without entries give zeros).
+template <int VEC>
+__global__ __launch_bounds__(256) void aggregate_kernel(AggArgs a, int lanes_log2)
+{
+    struct alignas(4 * VEC) Vec {
+        float x[VEC];
+    };
+    const int per_row = a.f / VEC;
+    const int lanes = 1 << lanes_log2;
+    const int sub = threadIdx.x & (lanes - 1);
+    const int64_t rows_per_block = 256 >> lanes_log2;
+    for (int64_t r = (int64_t)blockIdx.x * rows_per_block + (threadIdx.x >> lanes_log2); r < a.rows;
+         r += (int64_t)gridDim.x * rows_per_block) {
+        const int64_t e0 = a.rowptr[r], e1 = a.rowptr[r + 1];
+        const int64_t c0 = a.mb_coloff[locate_segment(a.mb_rowoff, a.k, r)];
+        const float len = (float)(e1 - e0);
+        for (int x = sub; x < per_row; x += lanes) {
+            Vec acc = Vec{};
+            for (int64_t e = e0; e < e1; e += 4) {
+                Vec v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    v[u] = Vec{};
+                    if (e + u < e1)
+                        v[u] = reinterpret_cast<const Vec *>(a.X + (c0 + a.col[e + u]) * a.f)[x];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (e + u < e1) { // entry order
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q)
+                            acc.x[q] += v[u].x[q];
+                    }
+            }
+            if (a.mean && e1 > e0) {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q)
+                    acc.x[q] = acc.x[q] / len;
+            }
+            reinterpret_cast<Vec *>(a.out + r * a.f)[x] = acc;
+        }
+    }
+}
+
+void launch_aggregate(const Launch &L, const AggArgs &a)
+{
+    if (a.rows <= 0)
+        return;
+    const bool wide = a.f % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & 15) == 0 && (reinterpret_cast<uintptr_t>(a.out) & 15) == 0;
+    const int per_row = wide ? a.f / 4 : a.f;
+    int lanes_log2 = 0;
+    while ((1 << lanes_log2) < per_row && lanes_log2 < 6)
+        ++lanes_log2;
+    const int64_t rows_per_block = 256 >> lanes_log2;
+    const int grid = grid_for(L, (a.rows + rows_per_block - 1) / rows_per_block, 8);
+    if (wide)
+        hipLaunchKernelGGL(aggregate_kernel<4>, dim3(grid), dim3(256), 0, L.stream, a, lanes_log2);
+    else
+        hipLaunchKernelGGL(aggregate_kernel<1>, dim3(grid), dim3(256), 0, L.stream, a, lanes_log2);
+}
+
+} // namespace bms
