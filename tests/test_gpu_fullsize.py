@@ -40,3 +40,47 @@ def test_workload_matches_oracle(name):
         assert hop.rows <= w["k"] * w["batch"] * (1 if h == 0 else max(w["params"][:h]) ** h * 10**6)
         if not nodewise:
             assert ((hop.mb_coloff[1:] - hop.mb_coloff[:-1]) <= w["params"][h]).all()
+
+
+def test_fetch_and_aggregate_at_full_size_on_sampled_outputs():
+    """The two consumer steps on the mid-size node-wise workload at its real shape (f = 100 as in Table 3),
+    in the launch configuration bench.py times; checked on outputs the oracle computes one by one:
+    100 000 random fetched rows, and every aggregated row of three whole minibatches."""
+    import numpy as np
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms, synth
+    g, batches, w = synth.make_workload("mid_sage", device="cuda")
+    f = w["features"]
+    csr = bms.Csr(g.rowptr, g.col)
+    res = bms.sample_nodewise(csr, batches, w["params"], synth.SAMPLING_SEED)
+    last_h = len(w["params"]) - 1
+    last = res.hop(last_h)
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    H = torch.randn((g.n, f), dtype=torch.float32, device="cuda", generator=gen)
+    X = bms.fetch_features(H, last.col_vertex)
+    assert X.shape == (last.ncols, f)
+    # every expected value below comes from the oracle's own sample of the same workload
+    ref_last = O.sample_nodewise(g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy(), w["params"],
+                                 synth.SAMPLING_SEED)[last_h]
+    rng = np.random.default_rng(1)
+    sel = np.sort(rng.integers(0, ref_last.ncols, size=100_000))
+    Hh = H.cpu().numpy()
+    got = X[torch.from_numpy(sel).cuda()].cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), O.fetch_features(Hh, ref_last.col_vertex[sel]).view(np.uint32))
+    out = bms.aggregate_hop(res, last_h, X, mean=True)
+    assert out.shape == (ref_last.rows, f)
+    hop = ref_last
+    u = 2.0 ** -24
+    for i in (0, w["k"] // 2, w["k"] - 1):
+        r0, r1 = int(hop.mb_rowoff[i]), int(hop.mb_rowoff[i + 1])
+        c0, c1 = int(hop.mb_coloff[i]), int(hop.mb_coloff[i + 1])
+        e0, e1 = int(hop.rowptr[r0]), int(hop.rowptr[r1])
+        sub = O.Hop(rows=r1 - r0, nnz=e1 - e0, ncols=c1 - c0, mb_rowoff=np.array([0, r1 - r0], dtype=np.int64),
+                    row_vertex=hop.row_vertex[r0:r1], rowptr=hop.rowptr[r0:r1 + 1] - e0, col=hop.col[e0:e1],
+                    mb_coloff=np.array([0, c1 - c0], dtype=np.int64), col_vertex=hop.col_vertex[c0:c1])
+        Xi = O.fetch_features(Hh, hop.col_vertex[c0:c1])
+        ref = O.aggregate(sub, Xi, mean=True).astype(np.float64)
+        m = np.diff(sub.rowptr).astype(np.float64)[:, None]
+        bound = (m + 2) * u * O.aggregate(sub, np.abs(Xi), mean=False).astype(np.float64) / np.maximum(m, 1.0) * 1.0001
+        err = np.abs(out[r0:r1].cpu().numpy().astype(np.float64) - ref)
+        assert np.all(err <= bound), (i, float(err.max()))
