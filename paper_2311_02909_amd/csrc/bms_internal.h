@@ -194,7 +194,7 @@ struct LwHop {
     uint32_t *first_cnt;       // rows: neighbours kept from the piece the row starts with
     int64_t tiles_bound;       // host-side upper bound of the number of tiles
     int32_t nwin;              // ceil(n / 2^kWinShift)
-    uint32_t *bounds;          // (nwin+1) * rows_bound, window-major
+    uint32_t *bounds;          // rows_bound * (nwin+1), one list per row
     uint32_t *win_cnt;         // k * nwin: columns of P inside the window
     uint64_t *win_wt;          // k * nwin: their weight
     int64_t *win_base;         // k * nwin: where the window's entries start in tmp_*

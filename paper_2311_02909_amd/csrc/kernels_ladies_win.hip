@@ -7,8 +7,7 @@
 //                   end) cut into tiles of 4096 positions that never straddle minibatches; the
 //                   row each tile starts in
 //   ldw_bounds      one wave per tile streams its pieces of rows once and records where every
-//                   row crosses every window boundary (lower bounds, kept window-major so that
-//                   the next kernel reads them coalesced)
+//                   row crosses every window boundary (lower bounds, one list per row)
 //   ldw_accumulate  one workgroup per (minibatch, window): 2^16 packed 16-bit counters in LDS
 //                   (128 KB); every row's piece of the window adds 1 per neighbour (e_v cannot
 //                   exceed the number of frontier rows, which this path keeps below 2^16); the
@@ -78,7 +77,8 @@ __global__ __launch_bounds__(256) void ldw_tile_rows_kernel(LwHop a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// bounds[w * rows_bound + r] = number of neighbours of row r with id < w * 2^16, w = 0..nwin
+// bounds[r * (nwin + 1) + w] = number of neighbours of row r with id < w * 2^16, w = 0..nwin (row-major:
+// the wave that streams a row writes its boundaries next to each other)
 // (rows without neighbours are skipped: their entries are never read)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
             const int64_t rs = a.gather_off[r];
             const int64_t pe = min(re, g1);
             const int64_t shift = a.row_beg[r] - rs; // A_col[shift + p] = neighbour at gathered position p
-            uint32_t *__restrict__ out = a.bounds + r;
+            uint32_t *__restrict__ out = a.bounds + r * (a.nwin + 1);
             // when the row ends inside the tile, position `re` acts as one more entry that lies in
             // window nwin: it closes every window left
             const int64_t last = pe == re ? pe : pe - 1;
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
                         pw = carry;
                     if (x <= xlast)
                         for (int32_t w = pw + 1; w <= wv[u]; ++w)
-                            out[(int64_t)w * a.rows_bound] = pos0 + (uint32_t)x;
+                            out[w] = pos0 + (uint32_t)x;
                     carry = __shfl(wv[u], kWave - 1, kWave);
                 }
             }
@@ -155,8 +155,8 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         for (int x = tid; x < kWinWords; x += kAccThreads)
             cnt[x] = 0;
         __syncthreads();
-        const uint32_t *__restrict__ lo_b = a.bounds + (int64_t)w * a.rows_bound;
-        const uint32_t *__restrict__ hi_b = lo_b + a.rows_bound;
+        const uint32_t *__restrict__ win_b = a.bounds + w; // entry w of every row's boundary list
+        const int64_t row_stride = a.nwin + 1;
         const int32_t id0 = w << kWinShift;
         // the piece of this window in row r: (length, address of its first neighbour); rows without
         // neighbours have no boundaries on record: whatever is read there is dropped
@@ -164,8 +164,8 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
             len = 0;
             addr = 0;
             if (r < r1) {
-                const uint32_t b0 = lo_b[r];
-                const uint32_t b1 = hi_b[r];
+                const uint32_t b0 = win_b[r * row_stride];
+                const uint32_t b1 = win_b[r * row_stride + 1];
                 const bool empty = a.gather_off[r + 1] == a.gather_off[r];
                 len = empty ? 0u : b1 - b0;
                 addr = a.row_beg[r] + b0;
