@@ -597,7 +597,7 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
     const int32_t nwin = (int32_t)((n1 + (1LL << kWinShift) - 1) >> kWinShift);
     const size_t nw = (size_t)c.k * nwin;
     BMS_TRY(csr->lw_win.ensure(nw * (sizeof(uint32_t) + 4 * sizeof(int64_t)) + 64));
-    BMS_TRY(csr->lw_count.ensure((3 * (size_t)c.k + 3) * sizeof(int64_t)));
+    BMS_TRY(csr->lw_count.ensure((4 * (size_t)c.k + 4) * sizeof(int64_t)));
     BMS_TRY(stage_seeds(c, batches, prof, false));
 
     int64_t rows_bound = (int64_t)c.k * c.b;
@@ -663,6 +663,7 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         w.mb_count = csr->lw_count.as<int64_t>();
         w.mb_goff = w.mb_count + c.k + 1;
         w.mb_gtileoff = w.mb_goff + c.k + 1;
+        w.tile_queue = reinterpret_cast<unsigned long long *>(w.mb_gtileoff + c.k + 1);
         w.row_mb = a.row_mb;
         w.p_off = hb.p_off.as<int64_t>();
         w.sel_tmp = csr->lw_sel.as<int32_t>();

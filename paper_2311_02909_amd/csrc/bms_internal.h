@@ -193,6 +193,7 @@ struct LwHop {
     uint32_t *tile_cnt;        // tiles: neighbours kept from the piece the tile starts with (row begun earlier)
     uint32_t *first_cnt;       // rows: neighbours kept from the piece the row starts with
     int64_t tiles_bound;       // host-side upper bound of the number of tiles
+    unsigned long long *tile_queue; // k+1 counters, zeroed per hop: next tile of each minibatch (extraction), of the hop (boundaries)
     int32_t nwin;              // ceil(n / 2^kWinShift)
     uint32_t *bounds;          // rows_bound * (nwin+1), one list per row
     uint32_t *win_cnt;         // k * nwin: columns of P inside the window

@@ -39,7 +39,7 @@ constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;
 constexpr int kExtThreads = 1024; // the waves of a workgroup share one hash table
 constexpr int kExtWaves = kExtThreads / kWave;
 constexpr int kAccUnroll = 16;
-constexpr int kStreamUnroll = 8; // neighbours per lane in flight in the two streaming passes // neighbours per lane in flight while accumulating
+constexpr int kStreamUnroll = 8; // neighbours per lane in flight in the two streaming passes
 constexpr int kHashSlots = 2 * kMaxWinSampled;    // load factor <= 1/2
 
 __device__ inline uint64_t ldw_weight(uint32_t cnt, int squared)
@@ -117,13 +117,13 @@ __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
 #pragma unroll
                 for (int u = 0; u < kStreamUnroll; ++u) {
                     const int32_t x = u * kWave + lane;
-                    int32_t pw = __shfl_up(wv[u], 1, kWave);
-                    if (lane == 0)
-                        pw = carry;
-                    if (x <= xlast)
+                    // window of the entry one lane below (lane 0: of the entry before the step): a lane shift in
+                    // the vector unit, not a trip through LDS
+                    const int32_t pw = __builtin_amdgcn_update_dpp(carry, wv[u], 0x138 /* wave_shr:1 */, 0xF, 0xF, false);
+                    if (x <= xlast) // this entry is the first at or past the boundaries pw+1 .. wv
                         for (int32_t w = pw + 1; w <= wv[u]; ++w)
                             out[w] = pos0 + (uint32_t)x;
-                    carry = __shfl(wv[u], kWave - 1, kWave);
+                    carry = __builtin_amdgcn_readlane(wv[u], kWave - 1);
                 }
             }
             g = pe;
@@ -431,13 +431,16 @@ __global__ __launch_bounds__(256) void ldw_sel_copy_kernel(LwHop a)
 // ---------------------------------------------------------------------------------------------
 // EXTRACT: blockIdx.y = minibatch; the workgroups of a minibatch share its rows wave by wave
 // ---------------------------------------------------------------------------------------------
-__device__ inline uint32_t ldw_hash(uint32_t v) { return (v * 0x9E3779B1u) >> (32 - 13); }
+// 16 hash bits: all of them index the filter bitmap, the low 13 the table
+__device__ inline uint32_t ldw_hash(uint32_t v) { return (v * 0x9E3779B1u) >> 16; }
 static_assert(kHashSlots == 1 << 13, "hash width out of step");
+constexpr int kFilterWords = 65536 / 32;
 
 __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
 {
     __shared__ uint32_t hkey[kHashSlots];
     __shared__ uint16_t hval[kHashSlots];
+    __shared__ uint32_t maybe[kFilterWords]; // bit h set: some sampled column hashes to h
     const int i = blockIdx.y, tid = threadIdx.x, lane = tid & (kWave - 1);
     const int64_t c0 = a.mb_coloff[i];
     const int32_t ns = (int32_t)(a.mb_coloff[i + 1] - c0);
@@ -446,10 +449,13 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
         return; // nothing sampled: every row stays empty (the counters start at zero)
     for (int x = tid; x < kHashSlots; x += kExtThreads)
         hkey[x] = kEmptySlot;
+    for (int x = tid; x < kFilterWords; x += kExtThreads)
+        maybe[x] = 0;
     __syncthreads();
     for (int j = tid; j < ns; j += kExtThreads) {
         const uint32_t v = (uint32_t)a.col_vertex[c0 + j];
-        uint32_t slot = ldw_hash(v);
+        atomicOr(&maybe[ldw_hash(v) >> 5], 1u << (ldw_hash(v) & 31u));
+        uint32_t slot = ldw_hash(v) & (kHashSlots - 1);
         while (atomicCAS(&hkey[slot], kEmptySlot, v) != kEmptySlot)
             slot = (slot + 1) & (kHashSlots - 1);
         hval[slot] = (uint16_t)j;
@@ -457,7 +463,15 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
     __syncthreads();
     const uint64_t below = (1ull << lane) - 1ull;
     unsigned long long *rowcnt = reinterpret_cast<unsigned long long *>(a.out_rowptr);
-    for (int64_t t = (int64_t)blockIdx.x * kExtWaves + tid / kWave; t < ntiles; t += (int64_t)gridDim.x * kExtWaves) {
+    // tiles cost very different amounts (one long piece, or many short rows): the minibatch's tiles go to
+    // whichever of its waves is free, off a shared counter, until none is left
+    while (true) {
+        int64_t t = 0;
+        if (lane == 0)
+            t = (int64_t)atomicAdd(a.tile_queue + i, 1ull);
+        t = __shfl(t, 0, kWave);
+        if (t >= ntiles)
+            break;
         int64_t g = a.mb_goff[i] + t * kLwTile;
         const int64_t g1 = min(g + kLwTile, a.mb_goff[i + 1]);
         int64_t r = a.tile_row[x0 + t];
@@ -479,11 +493,21 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
                     const int32_t x = u * kWave + lane;
                     v[u] = x < nslots ? (uint32_t)from[x] : kEmptySlot;
                 }
+                // almost no neighbour is a sampled column: one bit per hash value answers "certainly not" for
+                // nearly all of them with a single LDS read each (all of a step's reads in flight together);
+                // the table is searched only for the few that pass
+                uint32_t word[kStreamUnroll];
+#pragma unroll
+                for (int u = 0; u < kStreamUnroll; ++u)
+                    word[u] = maybe[ldw_hash(v[u]) >> 5];
 #pragma unroll
                 for (int u = 0; u < kStreamUnroll; ++u) {
+                    const bool pass = v[u] != kEmptySlot && ((word[u] >> (ldw_hash(v[u]) & 31u)) & 1u);
+                    if (__ballot(pass) == 0)
+                        continue;
                     int32_t local = -1;
-                    if (v[u] != kEmptySlot) {
-                        uint32_t slot = ldw_hash(v[u]);
+                    if (pass) {
+                        uint32_t slot = ldw_hash(v[u]) & (kHashSlots - 1);
                         uint32_t kx;
                         while ((kx = hkey[slot]) != kEmptySlot) {
                             if (kx == v[u]) {
@@ -556,6 +580,7 @@ void launch_ldw_bounds(const Launch &L, const LwHop &a)
 {
     hipLaunchKernelGGL(ldw_mb_goff_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, a);
     launch_plan_tiles(L, a.mb_goff, a.k, kLwTile, a.mb_gtileoff);
+    (void)hipMemsetAsync(a.tile_queue, 0, ((size_t)a.k + 1) * sizeof(unsigned long long), L.stream);
     hipLaunchKernelGGL(ldw_tile_rows_kernel, dim3(grid_for(L, (a.tiles_bound + 255) / 256, 8)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.tiles_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
 }
