@@ -609,14 +609,14 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         const int32_t s = s_per_layer[h];
         const int64_t ncols_bound = (int64_t)c.k * std::min<int64_t>(s, n1);
         const size_t bbytes = (size_t)(nwin + 1) * (size_t)rows_bound * sizeof(uint32_t);
-        if ((int64_t)bbytes > c.scratch_limit)
+        if ((int64_t)(2 * bbytes) > c.scratch_limit)
             return fail(BMS_ENOMEM, "window boundaries of %lld rows need %zu bytes of scratch, limit is %lld: raise "
                                     "bms_opts.scratch_limit or sample fewer minibatches per call",
-                        (long long)rows_bound, bbytes, (long long)c.scratch_limit);
+                        (long long)rows_bound, 2 * bbytes, (long long)c.scratch_limit);
         BMS_TRY(csr->row_beg.ensure((size_t)rows_bound * sizeof(int64_t)));
         BMS_TRY(csr->ld_gather_off.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
         BMS_TRY(csr->ld_row_mb.ensure((size_t)rows_bound * sizeof(int32_t)));
-        BMS_TRY(csr->lw_bounds.ensure(bbytes));
+        BMS_TRY(csr->lw_bounds.ensure(2 * bbytes));
         BMS_TRY(csr->lw_sel.ensure((size_t)c.k * (size_t)s * sizeof(int32_t)));
         BMS_TRY(hb.rowptr.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
         BMS_TRY(hb.mb_coloff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
@@ -654,6 +654,7 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         w.gather_off = a.gather_off;
         w.nwin = nwin;
         w.bounds = csr->lw_bounds.as<uint32_t>();
+        w.bounds_t = w.bounds + (size_t)(nwin + 1) * (size_t)rows_bound;
         w.win_wt = csr->lw_win.as<uint64_t>();
         w.win_woff = w.win_wt + nw;
         w.win_base = reinterpret_cast<int64_t *>(w.win_woff + nw);
@@ -681,10 +682,10 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         const int64_t D = host_slot(c, h, 3);
         const int64_t tmp_cap = std::max<int64_t>(std::min<int64_t>(D, (int64_t)c.k * n1), 1);
         const size_t tbytes = (size_t)tmp_cap * 8 + (size_t)std::max<int64_t>(D, 1) * 4;
-        if ((int64_t)(tbytes + bbytes) > c.scratch_limit)
+        if ((int64_t)(tbytes + 2 * bbytes) > c.scratch_limit)
             return fail(BMS_ENOMEM, "%lld gathered neighbours need %zu bytes of scratch, limit is %lld: raise "
                                     "bms_opts.scratch_limit or sample fewer minibatches per call",
-                        (long long)D, tbytes + bbytes, (long long)c.scratch_limit);
+                        (long long)D, tbytes + 2 * bbytes, (long long)c.scratch_limit);
         BMS_TRY(csr->lw_tmpcol.ensure((size_t)tmp_cap * sizeof(int32_t)));
         BMS_TRY(csr->lw_tmpcnt.ensure((size_t)tmp_cap * sizeof(uint32_t)));
         BMS_TRY(csr->lw_xtmp.ensure((size_t)std::max<int64_t>(D, 1) * sizeof(int32_t)));

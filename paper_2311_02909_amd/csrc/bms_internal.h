@@ -196,6 +196,7 @@ struct LwHop {
     unsigned long long *tile_queue; // k+1 counters, zeroed per hop: next tile of each minibatch (extraction), of the hop (boundaries)
     int32_t nwin;              // ceil(n / 2^kWinShift)
     uint32_t *bounds;          // rows_bound * (nwin+1), one list per row
+    uint32_t *bounds_t;        // (nwin+1) * rows_bound, the same window-major
     uint32_t *win_cnt;         // k * nwin: columns of P inside the window
     uint64_t *win_wt;          // k * nwin: their weight
     int64_t *win_base;         // k * nwin: where the window's entries start in tmp_*

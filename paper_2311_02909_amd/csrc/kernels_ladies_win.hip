@@ -7,7 +7,8 @@
 //                   end) cut into tiles of 4096 positions that never straddle minibatches; the
 //                   row each tile starts in
 //   ldw_bounds      one wave per tile streams its pieces of rows once and records where every
-//                   row crosses every window boundary (lower bounds, one list per row)
+//                   row crosses every window boundary (lower bounds, one list per row; a transpose then makes
+//                   them window-major for the next kernel)
 //   ldw_accumulate  one workgroup per (minibatch, window): 2^16 packed 16-bit counters in LDS
 //                   (128 KB); every row's piece of the window adds 1 per neighbour (e_v cannot
 //                   exceed the number of frontier rows, which this path keeps below 2^16); the
@@ -133,6 +134,27 @@ __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
     }
 }
 
+// The boundary lists turned window-major (bounds_t[w * rows_bound + r]): the accumulation reads one window of
+// all rows at a time.  64 x 64 tiles through LDS, both sides coalesced.
+__global__ __launch_bounds__(256) void ldw_bounds_transpose_kernel(LwHop a)
+{
+    __shared__ uint32_t tile[64][65];
+    const int64_t ncols = a.nwin + 1;
+    const int64_t tiles_c = (ncols + 63) / 64, tiles_r = (a.rows_bound + 63) / 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int64_t t = blockIdx.x; t < tiles_c * tiles_r; t += gridDim.x) {
+        const int64_t r0 = (t / tiles_c) * 64, c0 = (t % tiles_c) * 64;
+        for (int y = ty; y < 64; y += 4)
+            if (r0 + y < a.rows_bound && c0 + tx < ncols)
+                tile[y][tx] = a.bounds[(r0 + y) * ncols + c0 + tx];
+        __syncthreads();
+        for (int y = ty; y < 64; y += 4)
+            if (c0 + y < ncols && r0 + tx < a.rows_bound)
+                a.bounds_t[(c0 + y) * a.rows_bound + r0 + tx] = tile[tx][y];
+        __syncthreads();
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // P = Q A for one (minibatch, window) per workgroup
 // ---------------------------------------------------------------------------------------------
@@ -155,8 +177,8 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         for (int x = tid; x < kWinWords; x += kAccThreads)
             cnt[x] = 0;
         __syncthreads();
-        const uint32_t *__restrict__ win_b = a.bounds + w; // entry w of every row's boundary list
-        const int64_t row_stride = a.nwin + 1;
+        const uint32_t *__restrict__ lo_b = a.bounds_t + (int64_t)w * a.rows_bound; // boundary w of every row
+        const uint32_t *__restrict__ hi_b = lo_b + a.rows_bound;
         const int32_t id0 = w << kWinShift;
         // the piece of this window in row r: (length, address of its first neighbour); rows without
         // neighbours have no boundaries on record: whatever is read there is dropped
@@ -164,8 +186,8 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
             len = 0;
             addr = 0;
             if (r < r1) {
-                const uint32_t b0 = win_b[r * row_stride];
-                const uint32_t b1 = win_b[r * row_stride + 1];
+                const uint32_t b0 = lo_b[r];
+                const uint32_t b1 = hi_b[r];
                 const bool empty = a.gather_off[r + 1] == a.gather_off[r];
                 len = empty ? 0u : b1 - b0;
                 addr = a.row_beg[r] + b0;
@@ -583,6 +605,8 @@ void launch_ldw_bounds(const Launch &L, const LwHop &a)
     (void)hipMemsetAsync(a.tile_queue, 0, ((size_t)a.k + 1) * sizeof(unsigned long long), L.stream);
     hipLaunchKernelGGL(ldw_tile_rows_kernel, dim3(grid_for(L, (a.tiles_bound + 255) / 256, 8)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.tiles_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
+    const int64_t ttiles = ((a.nwin + 1 + 63) / 64) * ((a.rows_bound + 63) / 64);
+    hipLaunchKernelGGL(ldw_bounds_transpose_kernel, dim3(grid_for(L, ttiles, 8)), dim3(256), 0, L.stream, a);
 }
 
 int launch_ldw_accumulate(const Launch &L, const LwHop &a)
