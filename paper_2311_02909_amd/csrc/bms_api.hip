@@ -18,6 +18,7 @@ namespace {
 constexpr uint32_t kTagCsr = 0x31525343u;    // "CSR1"
 constexpr uint32_t kTagResult = 0x31534552u; // "RES1"
 constexpr int64_t kDefaultScratchLimit = 32LL << 30;
+constexpr int64_t kScanTmpLen = 1 << 17; // partial sums of multi-workgroup scans: arrays up to 2^29 values
 
 thread_local char g_err[512] = "";
 
@@ -101,7 +102,7 @@ struct bms_csr {
     // scratch reused across calls
     DevBuf vs_words, vs_prefix, vs_chunks;
     bool vs_clean = false; // all words zero
-    DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars;
+    DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars, scan_tmp;
     DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
     DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count, dd_back, dd_tileoff, dd_cursor, dd_seg; // bucket EXTRACT
     DevBuf lw_bounds, lw_win, lw_tmpcol, lw_tmpcnt, lw_sel, lw_xtmp, lw_count, lw_tiles, lw_rowcnt; // LADIES by LDS windows
@@ -287,8 +288,9 @@ int begin_call(CallCtx &c, bms_csr *csr, int32_t k, int32_t b, int32_t L, uint64
     c.mb_base = opts ? (uint32_t)opts->mb_base : 0u;
     c.flags = opts ? opts->flags : 0u;
     c.scratch_limit = (opts && opts->scratch_limit > 0) ? opts->scratch_limit : kDefaultScratchLimit;
-    c.launch = Launch{c.stream, csr->num_cu};
     HIP_TRY(hipSetDevice(csr->device));
+    BMS_TRY(csr->scan_tmp.ensure(kScanTmpLen * sizeof(int64_t)));
+    c.launch = Launch{c.stream, csr->num_cu, csr->scan_tmp.as<int64_t>(), kScanTmpLen};
     c.fresh_result = !(opts && opts->recycle);
     if (c.fresh_result) {
         c.res = new (std::nothrow) bms_result();
@@ -451,7 +453,8 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         launch_nw_rows(c.launch, a);
         BMS_TRY(prof.end());
         BMS_TRY(prof.begin("scan_tiles", h));
-        launch_scan_i64(c.launch, a.tile_off, a.mb_tileoff + c.k, slot(c, h, 0), a.out_rowptr, mb_rowoff + c.k);
+        launch_scan_i64(c.launch, a.tile_off, a.mb_tileoff + c.k, slot(c, h, 0), a.out_rowptr, mb_rowoff + c.k,
+                        rows_bound / kRowTile + c.k);
         BMS_TRY(prof.end());
 
         // nnz sizes the column buffers: read back (the only host round trip of the hop), or in the
@@ -726,7 +729,7 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         // EXTRACT
         BMS_TRY(prof.begin("ldw_extract", h));
         launch_ldw_extract(c.launch, w);
-        launch_scan_i64(c.launch, w.out_rowptr, mb_rowoff + c.k, slot(c, h, 0), nullptr, nullptr);
+        launch_scan_i64(c.launch, w.out_rowptr, mb_rowoff + c.k, slot(c, h, 0), nullptr, nullptr, rows_bound);
         BMS_TRY(prof.end());
         BMS_TRY(read_scalars(c)); // nnz sizes the column buffer
         const int64_t nnz = host_slot(c, h, 0);
@@ -1079,7 +1082,7 @@ void bms_free(void *handle)
         bms_csr *c = static_cast<bms_csr *>(handle);
         (void)hipSetDevice(c->device);
         DevBuf *bufs[] = {&c->own_rowptr, &c->own_col,    &c->vs_words,   &c->vs_prefix,     &c->vs_chunks,
-                          &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars,
+                          &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars, &c->scan_tmp,
                           &c->ld_counters, &c->ld_gather_off, &c->ld_row_mb, &c->ld_chunks, &c->ld_prefix,
                           &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_utmp, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count, &c->dd_back, &c->dd_tileoff, &c->dd_cursor, &c->dd_seg,
                           &c->lw_bounds, &c->lw_win, &c->lw_tmpcol, &c->lw_tmpcnt, &c->lw_sel, &c->lw_xtmp, &c->lw_count, &c->lw_tiles, &c->lw_rowcnt};

@@ -22,6 +22,8 @@ struct VSet {
 struct Launch {
     hipStream_t stream;
     int num_cu;
+    int64_t *scan_tmp = nullptr; // scratch for scans that span several workgroups: one value per 4096 inputs
+    int64_t scan_tmp_len = 0;
 };
 
 int grid_for(const Launch &L, int64_t blocks, int per_cu);
@@ -37,9 +39,10 @@ void launch_clear_seed_bits(const Launch &, const int32_t *seeds, int32_t k, int
 void launch_iota_offsets(const Launch &, int64_t *off, int32_t k, int64_t step); // off[i] = i*step, i<=k
 void launch_plan_tiles(const Launch &, const int64_t *seg_off, int32_t k, int32_t tile, int64_t *seg_tileoff);
 // exclusive scan of vals[0..*count) in place, vals[*count] = total; total also stored to *total_out and,
-// when tail_ptr != nullptr, to tail_ptr[*tail_idx]
+// when tail_ptr != nullptr, to tail_ptr[*tail_idx].  count_bound = host-side upper bound of *count (0: unknown);
+// long arrays are scanned by many workgroups when the launch context carries scratch for it
 void launch_scan_i64(const Launch &, int64_t *vals, const int64_t *count, int64_t *total_out, int64_t *tail_ptr,
-                     const int64_t *tail_idx);
+                     const int64_t *tail_idx, int64_t count_bound = 0);
 void launch_vset_rank(const Launch &, const VSet &, int32_t k, int64_t *mb_coloff /*k+1*/, int32_t *col_vertex,
                       int64_t *ncols_out);
 void launch_vset_clear(const Launch &, const VSet &, int32_t k, const int64_t *mb_coloff, const int32_t *col_vertex,

@@ -188,7 +188,7 @@ void launch_plan_tiles(const Launch &L, const int64_t *seg_off, int32_t k, int32
 
 // ---------------------------------------------------------------------------------------------
 // In-place exclusive scan of an int64 array whose length lives on the device.  One workgroup,
-// 4 values per lane per step; the arrays scanned here are per-tile sums (tens of thousands).
+// The arrays scanned here are per-tile sums and per-row counts (up to a few hundred thousand).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void scan_i64_kernel(int64_t *vals, const int64_t *__restrict__ count,
                                                         int64_t *total_out, int64_t *tail_ptr,
@@ -200,12 +200,19 @@ __global__ __launch_bounds__(1024) void scan_i64_kernel(int64_t *vals, const int
     if (threadIdx.x == 0)
         carry_s = 0;
     __syncthreads();
+    // 4 values per lane per step; the next step's values are on their way while this step is scanned
+    int64_t nxt[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        nxt[q] = ((int64_t)threadIdx.x * 4 + q < m) ? vals[(int64_t)threadIdx.x * 4 + q] : 0;
     for (int64_t base = 0; base < m; base += 4096) {
         const int64_t i0 = base + (int64_t)threadIdx.x * 4;
         int64_t v[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            v[q] = (i0 + q < m) ? vals[i0 + q] : 0;
+        for (int q = 0; q < 4; ++q) {
+            v[q] = nxt[q];
+            nxt[q] = (i0 + 4096 + q < m) ? vals[i0 + 4096 + q] : 0;
+        }
         const int64_t mine = v[0] + v[1] + v[2] + v[3];
         int64_t total;
         int64_t ex = block_exclusive_scan<int64_t, 1024>(mine, smem, total) + carry_s;
@@ -229,9 +236,82 @@ __global__ __launch_bounds__(1024) void scan_i64_kernel(int64_t *vals, const int
     }
 }
 
-void launch_scan_i64(const Launch &L, int64_t *vals, const int64_t *count, int64_t *total_out, int64_t *tail_ptr,
-                     const int64_t *tail_idx)
+// Long arrays, three steps: every workgroup scans its 4096 values in place and leaves their sum; one workgroup
+// scans the sums; every workgroup adds what lies before it.
+__global__ __launch_bounds__(1024) void scan_i64_chunks_kernel(int64_t *vals, const int64_t *__restrict__ count,
+                                                               int64_t *__restrict__ sums)
 {
+    __shared__ int64_t smem[16];
+    const int64_t m = *count;
+    const int64_t nchunks = (m + 4095) / 4096;
+    for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const int64_t i0 = c * 4096 + (int64_t)threadIdx.x * 4;
+        int64_t v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            v[q] = (i0 + q < m) ? vals[i0 + q] : 0;
+        int64_t total;
+        int64_t ex = block_exclusive_scan<int64_t, 1024>(v[0] + v[1] + v[2] + v[3], smem, total);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (i0 + q < m)
+                vals[i0 + q] = ex;
+            ex += v[q];
+        }
+        if (threadIdx.x == 0)
+            sums[c] = total;
+        __syncthreads();
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        sums[nchunks] = 0; // scanned along: becomes the grand total
+}
+
+__global__ __launch_bounds__(1024) void scan_i64_add_kernel(int64_t *vals, const int64_t *__restrict__ count,
+                                                            const int64_t *__restrict__ sums, int64_t *total_out,
+                                                            int64_t *tail_ptr, const int64_t *__restrict__ tail_idx)
+{
+    const int64_t m = *count;
+    const int64_t nchunks = (m + 4095) / 4096;
+    for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const int64_t before = sums[c];
+        const int64_t i0 = c * 4096 + (int64_t)threadIdx.x * 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (i0 + q < m)
+                vals[i0 + q] += before;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const int64_t total = sums[nchunks];
+        vals[m] = total;
+        if (total_out)
+            *total_out = total;
+        if (tail_ptr)
+            tail_ptr[*tail_idx] = total;
+    }
+}
+
+__global__ void scan_i64_count_kernel(const int64_t *__restrict__ count, int64_t *nchunks_plus_one)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        *nchunks_plus_one = (*count + 4095) / 4096 + 1;
+}
+
+void launch_scan_i64(const Launch &L, int64_t *vals, const int64_t *count, int64_t *total_out, int64_t *tail_ptr,
+                     const int64_t *tail_idx, int64_t count_bound)
+{
+    const int64_t chunks_bound = (count_bound + 4095) / 4096;
+    if (count_bound > 32768 && L.scan_tmp && chunks_bound + 3 <= L.scan_tmp_len) {
+        int64_t *sums = L.scan_tmp;                 // chunks_bound + 1 values
+        int64_t *nsums = L.scan_tmp + chunks_bound + 2; // device-side length of `sums` for the middle scan
+        const int grid = grid_for(L, chunks_bound, 2);
+        hipLaunchKernelGGL(scan_i64_chunks_kernel, dim3(grid), dim3(1024), 0, L.stream, vals, count, sums);
+        hipLaunchKernelGGL(scan_i64_count_kernel, dim3(1), dim3(64), 0, L.stream, count, nsums);
+        // scans sums[0 .. nchunks] (the extra trailing zero turns into the grand total) and writes one value past it
+        hipLaunchKernelGGL(scan_i64_kernel, dim3(1), dim3(1024), 0, L.stream, sums, nsums, nullptr, nullptr, nullptr);
+        hipLaunchKernelGGL(scan_i64_add_kernel, dim3(grid), dim3(1024), 0, L.stream, vals, count, sums, total_out, tail_ptr,
+                           tail_idx);
+        return;
+    }
     hipLaunchKernelGGL(scan_i64_kernel, dim3(1), dim3(1024), 0, L.stream, vals, count, total_out, tail_ptr, tail_idx);
 }
 

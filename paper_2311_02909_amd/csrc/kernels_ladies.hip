@@ -49,7 +49,7 @@ __global__ void ld_tiles_kernel(const int64_t *__restrict__ gather_off, const in
 void launch_ld_rows(const Launch &L, const LdHop &a, int64_t *gather_total_out)
 {
     hipLaunchKernelGGL(ld_rows_kernel, dim3(grid_for(L, (a.rows_bound + 255) / 256, 8)), dim3(256), 0, L.stream, a);
-    launch_scan_i64(L, a.gather_off, a.mb_rowoff + a.k, gather_total_out, nullptr, nullptr);
+    launch_scan_i64(L, a.gather_off, a.mb_rowoff + a.k, gather_total_out, nullptr, nullptr, a.rows_bound);
     hipLaunchKernelGGL(ld_tiles_kernel, dim3(1), dim3(64), 0, L.stream, a.gather_off, a.mb_rowoff + a.k,
                        a.gather_tiles, a.out_rowptr);
 }
