@@ -335,10 +335,16 @@ __global__ __launch_bounds__(256) void ldw_win_scan_kernel(LwHop a)
         a.mb_count[i] = (int64_t)carry_c;
 }
 
-// windows to their place in P, with the inclusive prefix sums of the weights
-__global__ __launch_bounds__(256) void ldw_p_copy_kernel(LwHop a)
+// windows to their place in P, with the inclusive prefix sums of the weights.  Global accesses are
+// coalesced (lane t of a step takes entries t, t + 512, ...); the running sums need consecutive entries per
+// lane, so weights and sums change layout through LDS.
+constexpr int kCopyThreads = 512;
+constexpr int kCopyStep = 4 * kCopyThreads;
+__global__ __launch_bounds__(kCopyThreads) void ldw_p_copy_kernel(LwHop a)
 {
-    __shared__ uint64_t smem[4];
+    __shared__ uint64_t smem[kCopyThreads / kWave];
+    __shared__ uint32_t wgt[kCopyStep];  // e_v^2 < 2^32 as well: e_v < 2^16 on this path
+    __shared__ uint64_t sums[kCopyStep];
     const int tid = threadIdx.x;
     const int64_t nblk = (int64_t)a.k * a.nwin;
     for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
@@ -346,37 +352,46 @@ __global__ __launch_bounds__(256) void ldw_p_copy_kernel(LwHop a)
         if (cw == 0)
             continue;
         const int i = (int)(blk / a.nwin);
-        const int64_t src = a.win_base[blk];
+        const int32_t *__restrict__ src_col = a.tmp_col + a.win_base[blk];
+        const uint32_t *__restrict__ src_cnt = a.tmp_cnt + a.win_base[blk];
         const int64_t dst = a.p_off[i] + a.win_poff[blk];
         uint64_t carry = a.win_woff[blk];
-        for (uint32_t x0 = 0; x0 < cw; x0 += 1024) {
-            uint32_t c[4];
-            int32_t col[4];
+        for (uint32_t x0 = 0; x0 < cw; x0 += kCopyStep) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t x = x0 + q * kCopyThreads + tid;
+                uint32_t c = 0;
+                if (x < cw) {
+                    c = src_cnt[x];
+                    a.p_col[dst + x] = src_col[x];
+                    a.p_cnt[dst + x] = c;
+                }
+                wgt[q * kCopyThreads + tid] = (uint32_t)ldw_weight(c, a.squared);
+            }
+            __syncthreads();
+            uint32_t w[4];
             uint64_t mine = 0;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint32_t x = x0 + tid * 4 + q;
-                c[q] = 0;
-                col[q] = 0;
-                if (x < cw) {
-                    c[q] = a.tmp_cnt[src + x];
-                    col[q] = a.tmp_col[src + x];
-                }
-                mine += ldw_weight(c[q], a.squared);
+                w[q] = wgt[tid * 4 + q];
+                mine += w[q];
             }
             uint64_t total;
-            uint64_t run = carry + block_exclusive_scan<uint64_t, 256>(mine, smem, total);
+            uint64_t run = carry + block_exclusive_scan<uint64_t, kCopyThreads>(mine, smem, total);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint32_t x = x0 + tid * 4 + q;
-                run += ldw_weight(c[q], a.squared);
-                if (x < cw) {
-                    a.p_col[dst + x] = col[q];
-                    a.p_cnt[dst + x] = c[q];
-                    a.prefix[dst + x] = run;
-                }
+                run += w[q];
+                sums[tid * 4 + q] = run;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t x = x0 + q * kCopyThreads + tid;
+                if (x < cw)
+                    a.prefix[dst + x] = sums[q * kCopyThreads + tid];
             }
             carry += total;
+            __syncthreads();
         }
     }
 }
@@ -629,7 +644,7 @@ int launch_ldw_accumulate(const Launch &L, const LwHop &a)
 
 void launch_ldw_p_copy(const Launch &L, const LwHop &a)
 {
-    hipLaunchKernelGGL(ldw_p_copy_kernel, dim3(grid_for(L, (int64_t)a.k * a.nwin, 8)), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(ldw_p_copy_kernel, dim3(grid_for(L, (int64_t)a.k * a.nwin, 4)), dim3(kCopyThreads), 0, L.stream, a);
 }
 
 void launch_ldw_draw(const Launch &L, const LwHop &a)
