@@ -84,3 +84,19 @@ def test_fetch_and_aggregate_at_full_size_on_sampled_outputs():
         bound = (m + 2) * u * O.aggregate(sub, np.abs(Xi), mean=False).astype(np.float64) / np.maximum(m, 1.0) * 1.0001
         err = np.abs(out[r0:r1].cpu().numpy().astype(np.float64) - ref)
         assert np.all(err <= bound), (i, float(err.max()))
+
+
+def test_layerwise_on_the_largest_graph():
+    """LADIES on the 111 M-vertex graph (1 694 id windows per minibatch, most of them empty; dense per-minibatch
+    counters would not fit in the scratch limit there), against the complete oracle result."""
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms, synth
+    g, batches, w = synth.make_workload("large_sage", device="cuda")
+    batches = batches[:16, :512].contiguous()
+    csr = bms.Csr(g.rowptr, g.col)
+    s = (512, 256, 128)
+    res = bms.sample_ladies(csr, batches, s, synth.SAMPLING_SEED, mb_base=3)
+    res = bms.sample_ladies(csr, batches, s, synth.SAMPLING_SEED, mb_base=3, recycle=res)
+    print("\n  sizes", res.sizes(), flush=True)
+    ref = O.sample_ladies(g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy(), s, synth.SAMPLING_SEED, 3)
+    assert_hops_equal(res.hops(), ref, with_p=True, what="ladies on the largest graph")
