@@ -695,7 +695,10 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         w.tmp_col = csr->lw_tmpcol.as<int32_t>();
         w.tmp_cnt = csr->lw_tmpcnt.as<uint32_t>();
         w.xtmp = csr->lw_xtmp.as<int32_t>();
-        w.tiles_bound = D / kLwTile + c.k;
+        w.tile = kLwTileMax; // about four tiles per wave slot of the chip, within the limits
+        while (w.tile > kLwTileMin && D / w.tile < (int64_t)csr->num_cu * 128)
+            w.tile >>= 1;
+        w.tiles_bound = D / w.tile + c.k;
         BMS_TRY(csr->lw_tiles.ensure((size_t)w.tiles_bound * (sizeof(int64_t) + sizeof(uint32_t)) + 64));
         BMS_TRY(csr->lw_rowcnt.ensure((size_t)rows_bound * sizeof(uint32_t)));
         w.tile_row = csr->lw_tiles.as<int64_t>();

@@ -174,7 +174,8 @@ void launch_chunk_scan(const Launch &, int64_t *chunk_off, int32_t k, int32_t nc
 constexpr int kWinShift = 16;            // a window = 2^16 vertex ids = 2^16 16-bit counters = 128 KB of LDS
 constexpr int32_t kMaxWinRows = 65535;   // frontier rows per minibatch (a 16-bit counter cannot overflow)
 constexpr int32_t kMaxWinSampled = 4096; // columns sampled per minibatch (sorted, then hashed, in LDS)
-constexpr int kLwTile = 4096;            // positions of the gathered order streamed by one wave at a time
+constexpr int kLwTileMax = 4096;         // positions of the gathered order streamed by one wave at a time: at most
+constexpr int kLwTileMin = 1024;         // ... and at least (hops that gather little use small tiles to fill the chip)
 struct LwHop {
     const int64_t *A_rowptr;
     const int32_t *A_col;
@@ -196,6 +197,7 @@ struct LwHop {
     uint32_t *tile_cnt;        // tiles: neighbours kept from the piece the tile starts with (row begun earlier)
     uint32_t *first_cnt;       // rows: neighbours kept from the piece the row starts with
     int64_t tiles_bound;       // host-side upper bound of the number of tiles
+    int32_t tile;              // positions per tile of this hop (power of two in [kLwTileMin, kLwTileMax])
     unsigned long long *tile_queue; // k+1 counters, zeroed per hop: next tile of each minibatch (extraction), of the hop (boundaries)
     int32_t nwin;              // ceil(n / 2^kWinShift)
     uint32_t *bounds;          // rows_bound * (nwin+1), one list per row

@@ -4,7 +4,8 @@
 // The rows of A are sorted by column, so the neighbours of a frontier row that fall into a window
 // of 2^16 vertex ids form one contiguous piece of its adjacency list.  One hop, all k minibatches:
 //   ldw_tiles       the gathered order (the neighbour lists of the stacked frontier laid end to
-//                   end) cut into tiles of 4096 positions that never straddle minibatches; the
+//                   end) cut into tiles of 1024..4096 positions (few gathered neighbours: small tiles, so that every
+//                   wave still gets some) that never straddle minibatches; the
 //                   row each tile starts in
 //   ldw_bounds      one wave per tile streams its pieces of rows once and records where every
 //                   row crosses every window boundary (lower bounds, one list per row; a transpose then makes
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256) void ldw_tile_rows_kernel(LwHop a)
     const int64_t ntiles = a.mb_gtileoff[a.k];
     for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < ntiles; x += (int64_t)gridDim.x * 256) {
         const int i = locate_segment(a.mb_gtileoff, a.k, x);
-        const int64_t g0 = a.mb_goff[i] + (x - a.mb_gtileoff[i]) * kLwTile;
+        const int64_t g0 = a.mb_goff[i] + (x - a.mb_gtileoff[i]) * a.tile;
         int64_t lo = a.mb_rowoff[i], hi = a.mb_rowoff[i + 1];
         while (hi - lo > 1) {
             const int64_t mid = (lo + hi) >> 1;
@@ -77,6 +78,36 @@ __global__ __launch_bounds__(256) void ldw_tile_rows_kernel(LwHop a)
     }
 }
 
+// Walks the pieces of rows inside tile [g0, g1) of the gathered order, starting in row r0 (the row that holds
+// g0), and calls body(r, rs, re, shift, g, pe) for each: row r spans gathered positions [rs, re), the piece is
+// [g, pe), and A_col[shift + p] is the neighbour at position p.  The extent of the following row is fetched
+// while a piece is being worked on, so a new piece does not start with a chain of dependent loads.
+template <class Body>
+__device__ inline void ldw_walk_tile(const LwHop &a, int64_t g0, int64_t g1, int64_t r0, int64_t nrows, Body body)
+{
+    int64_t g = g0, r = r0;
+    int64_t rs = a.gather_off[r], re = a.gather_off[r + 1], beg = a.row_beg[r];
+    while (g < g1) {
+        const int64_t rn = r + 1 < nrows ? r + 1 : r;
+        const int64_t next_re = a.gather_off[rn + 1], next_beg = a.row_beg[rn];
+        const int64_t pe = min(re, g1);
+        body(r, rs, re, beg - rs, g, pe);
+        g = pe;
+        if (pe == re) {
+            ++r;
+            rs = re;
+            re = next_re;
+            beg = next_beg;
+            while (re <= g && g < g1) { // rows without neighbours
+                ++r;
+                rs = re;
+                re = a.gather_off[r + 1];
+                beg = a.row_beg[r];
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // bounds[r * (nwin + 1) + w] = number of neighbours of row r with id < w * 2^16, w = 0..nwin (row-major:
 // the wave that streams a row writes its boundaries next to each other)
@@ -86,18 +117,13 @@ __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t ntiles = a.mb_gtileoff[a.k];
+    const int64_t nrows = a.mb_rowoff[a.k];
     for (int64_t x = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave; x < ntiles; x += (int64_t)gridDim.x * 4) {
         const int i = locate_segment(a.mb_gtileoff, a.k, x);
-        int64_t g = a.mb_goff[i] + (x - a.mb_gtileoff[i]) * kLwTile;
-        const int64_t g1 = min(g + kLwTile, a.mb_goff[i + 1]);
-        int64_t r = a.tile_row[x];
-        while (g < g1) {
-            int64_t re = a.gather_off[r + 1];
-            while (re <= g)
-                re = a.gather_off[++r + 1];
-            const int64_t rs = a.gather_off[r];
-            const int64_t pe = min(re, g1);
-            const int64_t shift = a.row_beg[r] - rs; // A_col[shift + p] = neighbour at gathered position p
+        const int64_t g0 = a.mb_goff[i] + (x - a.mb_gtileoff[i]) * a.tile;
+        const int64_t g1 = min(g0 + a.tile, a.mb_goff[i + 1]);
+        ldw_walk_tile(a, g0, g1, a.tile_row[x], nrows,
+                      [&](int64_t r, int64_t rs, int64_t re, int64_t shift, int64_t g, int64_t pe) {
             uint32_t *__restrict__ out = a.bounds + r * (a.nwin + 1);
             // when the row ends inside the tile, position `re` acts as one more entry that lies in
             // window nwin: it closes every window left
@@ -127,10 +153,7 @@ __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
                     carry = __builtin_amdgcn_readlane(wv[u], kWave - 1);
                 }
             }
-            g = pe;
-            if (pe == re)
-                ++r;
-        }
+        });
     }
 }
 
@@ -500,6 +523,7 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
     __syncthreads();
     const uint64_t below = (1ull << lane) - 1ull;
     unsigned long long *rowcnt = reinterpret_cast<unsigned long long *>(a.out_rowptr);
+    const int64_t nrows = a.mb_rowoff[a.k];
     // tiles cost very different amounts (one long piece, or many short rows): the minibatch's tiles go to
     // whichever of its waves is free, off a shared counter, until none is left
     while (true) {
@@ -509,16 +533,11 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
         t = __shfl(t, 0, kWave);
         if (t >= ntiles)
             break;
-        int64_t g = a.mb_goff[i] + t * kLwTile;
-        const int64_t g1 = min(g + kLwTile, a.mb_goff[i + 1]);
-        int64_t r = a.tile_row[x0 + t];
-        while (g < g1) {
-            int64_t re = a.gather_off[r + 1];
-            while (re <= g)
-                re = a.gather_off[++r + 1];
-            const int64_t rs = a.gather_off[r];
-            const int64_t pe = min(re, g1);
-            const int64_t shift = a.row_beg[r] - rs; // A_col[shift + p] = neighbour at gathered position p
+        const int64_t g0 = a.mb_goff[i] + t * a.tile;
+        const int64_t g1 = min(g0 + a.tile, a.mb_goff[i + 1]);
+        ldw_walk_tile(a, g0, g1, a.tile_row[x0 + t], nrows,
+                      [&](int64_t r, int64_t rs, int64_t re, int64_t shift, int64_t g, int64_t pe) {
+            (void)re;
             int32_t *__restrict__ out = a.xtmp + g; // the kept neighbours of a piece start where the piece starts
             uint32_t kept = 0;
             for (int64_t p0 = g; p0 < pe; p0 += kStreamUnroll * kWave) {
@@ -568,10 +587,7 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
                 if (kept)
                     atomicAdd(&rowcnt[r], (unsigned long long)kept);
             }
-            g = pe;
-            if (pe == re)
-                ++r;
-        }
+        });
     }
 }
 
@@ -591,13 +607,13 @@ __global__ __launch_bounds__(256) void ldw_extract_copy_kernel(LwHop a)
         const int64_t gm = a.mb_goff[i], xm = a.mb_gtileoff[i];
         int64_t g = rs;
         int64_t cnt = a.first_cnt[r];
-        int64_t t = (rs - gm) / kLwTile;
+        int64_t t = (rs - gm) / a.tile;
         while (true) {
             for (int64_t j = sub; j < cnt; j += 16)
                 a.out_col[o + j] = a.xtmp[g + j];
             o += cnt;
             ++t;
-            g = gm + t * kLwTile;
+            g = gm + t * a.tile;
             if (g >= re)
                 break;
             cnt = a.tile_cnt[xm + t];
@@ -616,7 +632,7 @@ size_t ldw_accumulate_lds_bytes()
 void launch_ldw_bounds(const Launch &L, const LwHop &a)
 {
     hipLaunchKernelGGL(ldw_mb_goff_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, a);
-    launch_plan_tiles(L, a.mb_goff, a.k, kLwTile, a.mb_gtileoff);
+    launch_plan_tiles(L, a.mb_goff, a.k, a.tile, a.mb_gtileoff);
     (void)hipMemsetAsync(a.tile_queue, 0, ((size_t)a.k + 1) * sizeof(unsigned long long), L.stream);
     hipLaunchKernelGGL(ldw_tile_rows_kernel, dim3(grid_for(L, (a.tiles_bound + 255) / 256, 8)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.tiles_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
