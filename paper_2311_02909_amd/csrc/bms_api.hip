@@ -18,6 +18,7 @@ namespace {
 constexpr uint32_t kTagCsr = 0x31525343u;    // "CSR1"
 constexpr uint32_t kTagResult = 0x31534552u; // "RES1"
 constexpr int64_t kDefaultScratchLimit = 32LL << 30;
+constexpr int64_t kNoWaitEntries = 32LL << 20; // result buffers up to this many entries may be sized by a bound
 constexpr int64_t kScanTmpLen = 1 << 17; // partial sums of multi-workgroup scans: arrays up to 2^29 values
 
 thread_local char g_err[512] = "";
@@ -712,8 +713,13 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
             return fail(BMS_EHIP, "launch of the LDS accumulation kernel was refused");
         launch_offsets_from_counts(c.launch, w.mb_count, c.k, w.p_off, slot(c, h, 2));
         BMS_TRY(prof.end());
-        BMS_TRY(read_scalars(c)); // pnnz sizes P and its prefix sums
-        const int64_t pnnz = host_slot(c, h, 2);
+        // nnz(P) sizes P and its prefix sums.  When its bound min(D, k n) is modest the buffers take the bound
+        // and the size is read back with everything else at the end of the call; else it is read back now.
+        int64_t pnnz = tmp_cap;
+        if (pnnz > kNoWaitEntries) {
+            BMS_TRY(read_scalars(c));
+            pnnz = host_slot(c, h, 2);
+        }
         BMS_TRY(hb.p_col.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(int32_t)));
         BMS_TRY(hb.p_cnt.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(uint32_t)));
         BMS_TRY(csr->ld_prefix.ensure((size_t)std::max<int64_t>(pnnz, 1) * sizeof(uint64_t)));
@@ -734,18 +740,19 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         launch_ldw_extract(c.launch, w);
         launch_scan_i64(c.launch, w.out_rowptr, mb_rowoff + c.k, slot(c, h, 0), nullptr, nullptr, rows_bound);
         BMS_TRY(prof.end());
-        BMS_TRY(read_scalars(c)); // nnz sizes the column buffer
-        const int64_t nnz = host_slot(c, h, 0);
+        // nnz sizes the column buffer: same rule with the bound min(D, rows * s)
+        int64_t nnz = std::min<int64_t>(D, rows_bound * std::min<int64_t>(s, n1));
+        if (nnz > kNoWaitEntries) {
+            BMS_TRY(read_scalars(c));
+            nnz = host_slot(c, h, 0);
+        }
         BMS_TRY(hb.col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
         w.out_col = hb.col.as<int32_t>();
         BMS_TRY(prof.begin("ldw_extract_copy", h));
         launch_ldw_extract_copy(c.launch, w);
         BMS_TRY(prof.end());
 
-        hb.view = bms_hop_view{};
-        hb.view.nnz = nnz;
-        hb.view.pnnz = pnnz;
-        hb.view.ncols = host_slot(c, h, 1);
+        hb.view = bms_hop_view{}; // the sizes follow after the last read-back
         hb.view.mb_rowoff = mb_rowoff;
         hb.view.row_vertex = row_vertex;
         hb.view.rowptr = hb.rowptr.as<int64_t>();
@@ -755,13 +762,19 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         hb.view.p_off = hb.p_off.as<int64_t>();
         hb.view.p_col = hb.p_col.as<int32_t>();
         hb.view.p_cnt = hb.p_cnt.as<uint32_t>();
-        hb.view.rows = h == 0 ? (int64_t)c.k * c.b : c.res->hops[h - 1].view.ncols;
 
         row_vertex = hb.col_vertex.as<int32_t>();
         mb_rowoff = hb.mb_coloff.as<int64_t>();
         rows_bound = std::max<int64_t>(ncols_bound, 1);
     }
-    HIP_TRY(hipStreamSynchronize(c.stream));
+    BMS_TRY(read_scalars(c));
+    for (int32_t h = 0; h < c.L; ++h) {
+        bms_hop_view &v = c.res->hops[h].view;
+        v.nnz = host_slot(c, h, 0);
+        v.ncols = host_slot(c, h, 1);
+        v.pnnz = host_slot(c, h, 2);
+        v.rows = h == 0 ? (int64_t)c.k * c.b : c.res->hops[h - 1].view.ncols;
+    }
     BMS_TRY(prof.finish());
     return BMS_OK;
 }
