@@ -194,12 +194,14 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
     uint64_t *starts = reinterpret_cast<uint64_t *>(origin_of + kWave);
     const uint64_t below = (1ull << lane) - 1ull, below_incl = below | (1ull << lane);
     const int64_t nblk = (int64_t)a.k * a.nwin;
+    // the counters start at zero and every (minibatch, window) leaves them at zero: the pass that emits the
+    // nonzero ones clears them
+    for (int x = tid; x < kWinWords; x += kAccThreads)
+        cnt[x] = 0;
+    __syncthreads();
     for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
         const int i = (int)(blk / a.nwin), w = (int)(blk % a.nwin);
         const int64_t r0 = a.mb_rowoff[i], r1 = a.mb_rowoff[i + 1];
-        for (int x = tid; x < kWinWords; x += kAccThreads)
-            cnt[x] = 0;
-        __syncthreads();
         const uint32_t *__restrict__ lo_b = a.bounds_t + (int64_t)w * a.rows_bound; // boundary w of every row
         const uint32_t *__restrict__ hi_b = lo_b + a.rows_bound;
         const int32_t id0 = w << kWinShift;
@@ -268,11 +270,23 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         const uint32_t *__restrict__ mine = cnt + wave * kWaveWords;
         uint32_t nz = 0;
         uint64_t wt = 0;
-        for (int it = 0; it < kWaveWords / kWave; ++it) {
-            const uint32_t x = mine[it * kWave + lane];
-            const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
-            nz += (lo != 0) + (hi != 0);
-            wt += ldw_weight(lo, a.squared) + ldw_weight(hi, a.squared);
+        if (a.squared) {
+            for (int it = 0; it < kWaveWords / kWave; ++it) {
+                const uint32_t x = mine[it * kWave + lane];
+                const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
+                nz += (lo != 0) + (hi != 0);
+                wt += (uint64_t)lo * lo + (uint64_t)hi * hi;
+            }
+        } else {
+            uint32_t wt32 = 0; // at most 64 values below 2^16 per lane
+#pragma unroll 8
+            for (int it = 0; it < kWaveWords / kWave; ++it) {
+                const uint32_t x = mine[it * kWave + lane];
+                const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
+                nz += (lo != 0) + (hi != 0);
+                wt32 += lo + hi;
+            }
+            wt = wt32;
         }
         nz = wave_sum(nz);
         wt = wave_sum(wt);
@@ -299,24 +313,33 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         __syncthreads();
         if (nz) { // uniform per wave
             int64_t run = (int64_t)*base_s + wave_nz[wave];
-            for (int it = 0; it < kWaveWords / kWave; ++it) {
-                const int word = wave * kWaveWords + it * kWave + lane;
-                const uint32_t x = cnt[word];
-                const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
-                const uint64_t mlo = __ballot(lo != 0), mhi = __ballot(hi != 0);
-                if ((mlo | mhi) == 0)
-                    continue;
-                int64_t pos = run + __popcll(mlo & below) + __popcll(mhi & below);
-                if (lo) {
-                    a.tmp_col[pos] = id0 + 2 * word;
-                    a.tmp_cnt[pos] = lo;
-                    ++pos;
+            for (int it0 = 0; it0 < kWaveWords / kWave; it0 += 4) {
+                uint32_t x[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    x[q] = cnt[wave * kWaveWords + (it0 + q) * kWave + lane];
+                    if (x[q])
+                        cnt[wave * kWaveWords + (it0 + q) * kWave + lane] = 0;
                 }
-                if (hi) {
-                    a.tmp_col[pos] = id0 + 2 * word + 1;
-                    a.tmp_cnt[pos] = hi;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int word = wave * kWaveWords + (it0 + q) * kWave + lane;
+                    const uint32_t lo = x[q] & 0xFFFFu, hi = x[q] >> 16;
+                    const uint64_t mlo = __ballot(lo != 0), mhi = __ballot(hi != 0);
+                    if ((mlo | mhi) == 0)
+                        continue;
+                    int64_t pos = run + __popcll(mlo & below) + __popcll(mhi & below);
+                    if (lo) {
+                        a.tmp_col[pos] = id0 + 2 * word;
+                        a.tmp_cnt[pos] = lo;
+                        ++pos;
+                    }
+                    if (hi) {
+                        a.tmp_col[pos] = id0 + 2 * word + 1;
+                        a.tmp_cnt[pos] = hi;
+                    }
+                    run += __popcll(mlo) + __popcll(mhi);
                 }
-                run += __popcll(mlo) + __popcll(mhi);
             }
         }
         __syncthreads();
