@@ -21,7 +21,7 @@ def _skewed_csr(n, m, rng):
     return np.cumsum(rowptr), (key % n).astype(np.int32)
 
 
-@pytest.mark.parametrize("case", range(12))
+@pytest.mark.parametrize("case", range(40))
 def test_random_case(case):
     from oracle import bms_oracle as O
     from paper_2311_02909_amd import bms
