@@ -495,6 +495,10 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
                 C = (int32_t)std::max<int64_t>((csr->n + (1LL << cshift) - 1) >> cshift, 1);
                 if (cshift > 20)
                     C = 0; // vertex range too wide for the segment sort: per-minibatch kernel only
+                // few sampled edges per minibatch: the single per-minibatch kernel beats the chain of
+                // chip-wide kernels, whose launches would dominate (unless that path was asked for)
+                if (per_mb <= 4096.0 && !(c.flags & BMS_EXTRACT_SORT))
+                    C = 0;
             }
             const size_t stride = (size_t)std::max<int64_t>(nbuckets, C);
             BMS_TRY(csr->dd_uniq.ensure((size_t)c.k * stride * sizeof(uint32_t)));

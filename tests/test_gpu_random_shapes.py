@@ -40,7 +40,7 @@ def test_random_case(case):
     fanouts = tuple(int(x) for x in rng.choice([1, 2, 3, 5, 8, 15, 20, 40], size=L))
     ref = O.sample_nodewise(rowptr, col, batches, fanouts, seed, mb_base)
     res = None
-    for extract in (None, "buckets", None):   # the last call recycles: no size read-backs
+    for extract in (None, "buckets", "sort", None):   # recycled calls of the same shape skip the size read-backs
         res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fanouts, seed, mb_base=mb_base,
                                   extract=extract, recycle=res)
         assert_hops_equal(res.hops(), ref, what="case %d nodewise fanouts=%s extract=%s" % (case, fanouts, extract))
