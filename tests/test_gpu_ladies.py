@@ -120,3 +120,17 @@ def test_paper_worked_example_on_the_gpu(mods):
         e[hop.p_col] = hop.p_cnt
         assert e.tolist() == [1, 0, 1, 1, 2, 0]
         assert_hops_equal([hop], O.sample_ladies(rowptr, col, batch, (2,), seed, squared=True), with_p=True)
+
+
+@pytest.mark.parametrize("b", [8192, 9000])
+def test_largest_batches_of_each_kernel_path(mods, b):
+    # b = 8192 is the most the LDS-window path takes (seed check by an LDS sort, 16-bit counters); larger batches
+    # run on the dense-counter path by themselves
+    O, bms, synth = mods
+    g = synth.rmat_graph(120_000, 700_000, 0.5, 0.2, 0.2, seed=11, device="cuda")
+    rowptr, col = g.rowptr.cpu().numpy(), g.col.cpu().numpy()
+    rng = np.random.default_rng(b)
+    batches = random_batches(g.n, 2, b, rng)
+    ref = O.sample_ladies(rowptr, col, batches, (300, 100), 4)
+    res = bms.sample_ladies(bms.Csr(g.rowptr, g.col), torch.from_numpy(batches).cuda(), (300, 100), 4)
+    assert_hops_equal(res.hops(), ref, with_p=True, what="b=%d" % b)
