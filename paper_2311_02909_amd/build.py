@@ -32,5 +32,23 @@ def build_lib(verbose: bool = False) -> str:
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "bms_c_client.c")
+C_CLIENT = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "bms_c_client")
+
+
+def build_c_client(verbose: bool = False) -> str:
+    """The plain-C client of the library used by tests/test_gpu_c_abi.py (gcc, C99; links libbms.so and the HIP runtime)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(os.path.dirname(HERE), "include"), "-o", C_CLIENT, C_CLIENT_SRC,
+           "-L", HERE, "-lbms", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2311_02909_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build_lib(verbose=True))
+    print(build_c_client(verbose=True))
