@@ -7,8 +7,11 @@
 //   (scan)     exclusive scan of the tile sums -> where each tile's output starts
 //   nw_sample  SAMPLE: per row, min(degree, s) distinct positions (ITS without replacement,
 //              Sec. 4.1.2), the chosen neighbours gathered, staged through LDS and written
-//              coalesced; their bits set in the minibatch's vertex set
-//   (rank)     vertex set ranked -> kept columns in ascending order (EXTRACT, Sec. 4.1.3)
+//              coalesced as global ids
+// EXTRACT (Sec. 4.1.3: distinct sampled ids ascending = next frontier, global id -> local column) is
+// done by the kernels of kernels_dedup_sort.hip / kernels_dedup.hip.  The first design of it lives
+// here and serves vertex ranges too wide for those: nw_sample also sets the ids' bits in a
+// per-minibatch vertex set in HBM, the set is ranked (kernels_common.hip), and
 //   nw_relabel global id -> local column index = rank in the minibatch's vertex set
 #include "bms_device.h"
 #include "bms_internal.h"
