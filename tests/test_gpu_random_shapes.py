@@ -1,5 +1,7 @@
 """Randomised shapes: both samplers against the oracle on graphs, batch shapes and sampling parameters drawn
 from a seeded stream (skewed and uniform graphs, directed and symmetric, tiny to mid-size frontiers)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -21,7 +23,7 @@ def _skewed_csr(n, m, rng):
     return np.cumsum(rowptr), (key % n).astype(np.int32)
 
 
-@pytest.mark.parametrize("case", range(40))
+@pytest.mark.parametrize("case", range(int(os.environ.get("BMS_RANDOM_CASES", "40"))))
 def test_random_case(case):
     from oracle import bms_oracle as O
     from paper_2311_02909_amd import bms
