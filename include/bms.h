@@ -110,6 +110,7 @@ int bms_csr_info(const bms_csr *csr, int64_t *n, int64_t *nnz, int64_t *max_degr
 
 /*
  * Bulk node-wise (GraphSAGE) sampling, Sec. 4.1 with the stacking of Eq. 1.
+ *   k, L    : 1 <= k <= 65535 minibatches per call, 1 <= L <= 15 hops (else BMS_EINVAL)
  *   batches : k*b seed vertices, row-major (minibatch i = batches[i*b .. (i+1)*b)), host or device;
  *             distinct inside a minibatch, each in [0,n), else BMS_ERANGE.
  *   fanouts : L host integers >= 1; fanouts[h] = s at hop h.  A row of degree <= s keeps every

@@ -18,6 +18,7 @@ namespace {
 constexpr uint32_t kTagCsr = 0x31525343u;    // "CSR1"
 constexpr uint32_t kTagResult = 0x31534552u; // "RES1"
 constexpr int64_t kDefaultScratchLimit = 32LL << 30;
+constexpr int32_t kMaxMinibatches = 65535; // some kernels take the minibatch from the second grid dimension
 constexpr int64_t kNoWaitEntries = 32LL << 20; // result buffers up to this many entries may be sized by a bound
 constexpr int64_t kScanTmpLen = 1 << 17; // partial sums of multi-workgroup scans: arrays up to 2^29 values
 
@@ -231,6 +232,9 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         return fail(BMS_EINVAL, "null argument");
     if (k < 1 || b < 1 || L < 1)
         return fail(BMS_EINVAL, "k, b and L must be >= 1 (k=%d b=%d L=%d)", k, b, L);
+    if (k > kMaxMinibatches)
+        return fail(BMS_EINVAL, "k=%d minibatches per call, at most %d are supported: split the call (mb_base keeps "
+                                "the random streams in step)", k, kMaxMinibatches);
     for (int32_t h = 0; h < L; ++h)
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);

@@ -290,3 +290,16 @@ def test_minibatch_with_more_sampled_edges_than_the_slot_lists_cover(mods):
     for extract in ("sort", "buckets", "sort"):
         res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (15, 10, 5), 3, extract=extract, recycle=res)
         assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
+
+
+def test_thousands_of_small_minibatches_and_the_limit_on_k(mods):
+    O, bms, _ = mods
+    rng = np.random.default_rng(49)
+    rowptr, col = random_csr(60000, 9.0, rng)
+    batches = random_batches(60000, 3000, 4, rng)
+    csr, res, ref = _run_both(mods, rowptr, col, batches, (4, 3), 8)
+    lad = bms.sample_ladies(csr, torch.from_numpy(batches).cuda(), (6, 6), 8)
+    assert_hops_equal(lad.hops(), O.sample_ladies(rowptr, col, batches, (6, 6), 8), with_p=True)
+    with pytest.raises(bms.BmsError) as e:
+        bms.sample_nodewise(csr, torch.zeros((65536, 1), dtype=torch.int32).cuda(), (2,), 1)
+    assert e.value.code == bms.EINVAL
