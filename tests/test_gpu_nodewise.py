@@ -303,3 +303,32 @@ def test_thousands_of_small_minibatches_and_the_limit_on_k(mods):
     with pytest.raises(bms.BmsError) as e:
         bms.sample_nodewise(csr, torch.zeros((65536, 1), dtype=torch.int32).cuda(), (2,), 1)
     assert e.value.code == bms.EINVAL
+
+
+def test_side_stream_and_graph_without_vertices(mods):
+    O, bms, _ = mods
+    rng = np.random.default_rng(50)
+    rowptr, col = random_csr(20000, 10.0, rng)
+    batches = random_batches(20000, 6, 100, rng)
+    ref = O.sample_nodewise(rowptr, col, batches, (6, 4), 2)
+    lref = O.sample_ladies(rowptr, col, batches, (50, 50), 2)
+    side = torch.cuda.Stream()  # default priority
+    with torch.cuda.stream(side):
+        csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+        dev = torch.from_numpy(batches).cuda()
+        res = None
+        for _ in range(3):
+            res = bms.sample_nodewise(csr, dev, (6, 4), 2, recycle=res)
+        lad = bms.sample_ladies(csr, dev, (50, 50), 2)
+        X = bms.fetch_features(torch.ones((20000, 8), device="cuda"), res.hop(1).col_vertex)
+        Y = bms.aggregate_hop(res, 1, X)
+    side.synchronize()
+    assert_hops_equal(res.hops(), ref, what="side stream")
+    assert_hops_equal(lad.hops(), lref, with_p=True, what="side stream")
+    assert torch.equal(Y.cpu(), (torch.from_numpy(np.diff(ref[1].rowptr)) > 0).float()[:, None].repeat(1, 8))
+    # a matrix with no vertices loads; every seed is then out of range
+    empty = bms.Csr(torch.zeros(1, dtype=torch.int64).cuda(), torch.zeros(0, dtype=torch.int32).cuda())
+    for fn in (bms.sample_nodewise, bms.sample_ladies):
+        with pytest.raises(bms.BmsError) as e:
+            fn(empty, np.zeros((1, 1), dtype=np.int32), (2,), 1)
+        assert e.value.code == bms.ERANGE
