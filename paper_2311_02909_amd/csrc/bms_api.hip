@@ -486,13 +486,14 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         if (buckets) {
             BMS_TRY(csr->dd_pairs.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
             BMS_TRY(csr->dd_utmp.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
-            // segments = id ranges of 2^cshift ids: about 500 sampled ids each on average (uniform ids),
+            // segments = id ranges of 2^cshift ids: 240..480 sampled ids each on average (most then fit the
+            // 512-pair sorting network of one wave with little padding),
             // at most kMaxSegments of them, at most 2^20 ids wide (the sort key has 32 bits)
             int32_t C = 0, cshift = 0;
             if (seg_sort) {
                 const double per_mb = (double)nnz_tune / c.k + 1.0;
                 cshift = 0;
-                while (cshift < 20 && (double)(2LL << cshift) * per_mb <= 700.0 * (double)csr->n)
+                while (cshift < 20 && (double)(2LL << cshift) * per_mb <= 480.0 * (double)csr->n)
                     ++cshift;
                 while (((csr->n + (1LL << cshift) - 1) >> cshift) > kMaxSegments)
                     ++cshift;
@@ -507,7 +508,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             const size_t stride = (size_t)std::max<int64_t>(nbuckets, C);
             BMS_TRY(csr->dd_uniq.ensure((size_t)c.k * stride * sizeof(uint32_t)));
             BMS_TRY(csr->dd_seg.ensure(((size_t)c.k * (5 * (size_t)kMaxSegments + 1) + 16) * sizeof(uint32_t)));
-            BMS_TRY(csr->dd_tileoff.ensure(3 * ((size_t)c.k + 1) * sizeof(int64_t)));
+            BMS_TRY(csr->dd_tileoff.ensure(4 * ((size_t)c.k + 1) * sizeof(int64_t)));
             DedupArgs d{};
             d.k = c.k;
             d.nbuckets = (int32_t)nbuckets;
@@ -527,6 +528,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.cshift = cshift;
             d.fuse_back = C ? 1 : 0;
             d.fwd_tileoff = csr->dd_tileoff.as<int64_t>() + 2 * (c.k + 1);
+            d.big_tileoff = csr->dd_tileoff.as<int64_t>() + 3 * (c.k + 1);
             d.fallback = C ? reinterpret_cast<int32_t *>(csr->dd_seg.as<uint32_t>()) : nullptr;
             d.seg_cnt = csr->dd_seg.as<uint32_t>() + 16;
             d.seg_off = d.seg_cnt + (size_t)c.k * kMaxSegments;

@@ -97,6 +97,7 @@ struct DedupArgs {
     uint32_t *seg_off;   // k * (C+1): exclusive scan of the pair counts
     uint32_t *seg_cursor; // k * C
     int64_t *fwd_tileoff; // k+1
+    int64_t *big_tileoff; // k+1: tiles of kSplitTile16 entries
     uint32_t *big_list;  // k * C: segments of 1025..kSegCap pairs
     uint32_t *big_count; // device counter of big_list (the word after `fallback`)
     uint32_t *wide_list; // k * C: segments of 513..1024 pairs (one wave each, in a kernel of their own)
@@ -104,9 +105,10 @@ struct DedupArgs {
     int32_t fuse_back;   // 1: the sorting waves append their entries to the slot lists themselves (no split pass)
     int32_t *fallback;   // device flag: a segment does not fit in LDS, the per-minibatch kernel takes the hop
 };
-constexpr int kFwdTile = 4096;      // sampled ids per tile of the count / split kernels
+constexpr int kFwdTile = 4096;      // sampled ids per tile of the count kernel
+constexpr int kSplitTile16 = 16384; // ... of the split kernel (128 KB of LDS staging: long runs per segment)
 constexpr int kSegCap = 4096;       // pairs of one segment that are sorted in LDS (32 KB)
-constexpr int kMaxSegments = 2048;
+constexpr int kMaxSegments = 2560;  // 3 words each beside the split kernel's staging must fit in 160 KB of LDS
 void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz, const StageMark &mark);
 // returns 0, or -1 when the launch was refused (then nothing ran)
 int launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,

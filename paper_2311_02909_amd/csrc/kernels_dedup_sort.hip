@@ -111,46 +111,49 @@ __global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
         atomicOr(a.fallback, 1);
 }
 
-__global__ __launch_bounds__(256) void dd_split_kernel(DedupArgs a)
+// TILE sampled ids per workgroup step, NT threads.  The larger the tile, the longer the run every segment gets
+// in one step (a step's entries spread over all C segments), i.e. the wider the stores.
+template <int TILE, int NT>
+__global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t *__restrict__ tileoff)
 {
-    __shared__ uint64_t stage[kFwdTile];
-    extern __shared__ uint32_t seg_lds[]; // 3 C words: per-segment count, start in the tile, start in global
-    __shared__ uint32_t smem[4];
+    extern __shared__ uint64_t split_lds[]; // stage[TILE]; then 3 C words: per-segment count, start in the tile, start in global
+    __shared__ uint32_t smem[NT / kWave];
     __shared__ uint32_t carry_s;
     if (*a.fallback)
         return;
-    uint32_t *cnt = seg_lds, *off = seg_lds + a.C, *gpos = seg_lds + 2 * a.C;
+    uint64_t *stage = split_lds;
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(split_lds + TILE), *off = cnt + a.C, *gpos = cnt + 2 * a.C;
     const int tid = threadIdx.x;
-    const int64_t ntiles = a.fwd_tileoff[a.k];
+    const int64_t ntiles = tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int i = locate_segment(a.fwd_tileoff, a.k, t);
+        const int i = locate_segment(tileoff, a.k, t);
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
-        const uint32_t j0 = (uint32_t)(t - a.fwd_tileoff[i]) * kFwdTile;
-        const uint32_t jend = (j0 + kFwdTile < N) ? j0 + kFwdTile : N;
+        const uint32_t j0 = (uint32_t)(t - tileoff[i]) * TILE;
+        const uint32_t jend = (j0 + TILE < N) ? j0 + TILE : N;
         const int32_t *__restrict__ col = a.col + e0;
-        for (int c = tid; c < a.C; c += 256)
+        for (int c = tid; c < a.C; c += NT)
             cnt[c] = 0;
         if (tid == 0)
             carry_s = 0;
         __syncthreads();
-        uint64_t ent[kFwdTile / 256];
-        uint32_t lpos[kFwdTile / 256];
+        uint64_t ent[TILE / NT];
+        uint32_t lpos[TILE / NT];
 #pragma unroll
-        for (int q = 0; q < kFwdTile / 256; ++q) {
-            const uint32_t j = j0 + q * 256 + tid;
+        for (int q = 0; q < TILE / NT; ++q) {
+            const uint32_t j = j0 + q * NT + tid;
             ent[q] = j < jend ? (((uint64_t)(uint32_t)col[j] << 32) | (uint64_t)j) : kNoEntry;
         }
 #pragma unroll
-        for (int q = 0; q < kFwdTile / 256; ++q)
+        for (int q = 0; q < TILE / NT; ++q)
             if (ent[q] != kNoEntry)
                 lpos[q] = atomicAdd(&cnt[(uint32_t)(ent[q] >> 32) >> a.cshift], 1u);
         __syncthreads();
-        for (int base = 0; base < a.C; base += 256) {
+        for (int base = 0; base < a.C; base += NT) {
             const int c = base + tid;
             const uint32_t v = c < a.C ? cnt[c] : 0u;
             uint32_t total;
-            const uint32_t ex = block_exclusive_scan<uint32_t, 256>(v, smem, total);
+            const uint32_t ex = block_exclusive_scan<uint32_t, NT>(v, smem, total);
             const uint32_t carry = carry_s;
             if (c < a.C) {
                 off[c] = carry + ex;
@@ -163,12 +166,12 @@ __global__ __launch_bounds__(256) void dd_split_kernel(DedupArgs a)
             __syncthreads();
         }
 #pragma unroll
-        for (int q = 0; q < kFwdTile / 256; ++q)
+        for (int q = 0; q < TILE / NT; ++q)
             if (ent[q] != kNoEntry)
                 stage[off[(uint32_t)(ent[q] >> 32) >> a.cshift] + lpos[q]] = ent[q];
         __syncthreads();
         uint64_t *__restrict__ pairs = a.pairs + e0;
-        for (uint32_t sidx = tid; sidx < jend - j0; sidx += 256) {
+        for (uint32_t sidx = tid; sidx < jend - j0; sidx += NT) {
             const uint64_t e = stage[sidx];
             const uint32_t c = (uint32_t)(e >> 32) >> a.cshift;
             pairs[gpos[c] + (sidx - off[c])] = e;
@@ -509,7 +512,20 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
     hipLaunchKernelGGL(dd_count_kernel, dim3(grid_for(L, tiles, 8)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
     mark("dd_split");
-    hipLaunchKernelGGL(dd_split_kernel, dim3(grid_for(L, tiles, 4)), dim3(256), 3 * (size_t)a.C * sizeof(uint32_t), L.stream, a);
+    { // 16384 ids per step, one workgroup of 16 waves per compute unit
+        static bool attr_set = false;
+        const size_t lds = (size_t)kSplitTile16 * sizeof(uint64_t) + 3 * (size_t)a.C * sizeof(uint32_t);
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_split_kernel<kSplitTile16, 1024>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(kSplitTile16 * sizeof(uint64_t) + 3 * kMaxSegments * sizeof(uint32_t))) != hipSuccess)
+                (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
+            attr_set = true;
+        }
+        launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile16, a.big_tileoff);
+        hipLaunchKernelGGL((dd_split_kernel<kSplitTile16, 1024>), dim3(grid_for(L, nnz / kSplitTile16 + a.k, 1)), dim3(1024), lds,
+                           L.stream, a, a.big_tileoff);
+    }
     mark("dd_sort");
     launch_plan_tiles(L, a.mb_edgeoff, a.k, kDedupPlaceTile, a.place_tileoff);
     (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kDedupPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
