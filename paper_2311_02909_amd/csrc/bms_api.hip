@@ -508,7 +508,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             const size_t stride = (size_t)std::max<int64_t>(nbuckets, C);
             BMS_TRY(csr->dd_uniq.ensure((size_t)c.k * stride * sizeof(uint32_t)));
             BMS_TRY(csr->dd_seg.ensure(((size_t)c.k * (5 * (size_t)kMaxSegments + 1) + 16) * sizeof(uint32_t)));
-            BMS_TRY(csr->dd_tileoff.ensure(4 * ((size_t)c.k + 1) * sizeof(int64_t)));
+            BMS_TRY(csr->dd_tileoff.ensure(3 * ((size_t)c.k + 1) * sizeof(int64_t)));
             DedupArgs d{};
             d.k = c.k;
             d.nbuckets = (int32_t)nbuckets;
@@ -527,8 +527,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.C = C;
             d.cshift = cshift;
             d.fuse_back = C ? 1 : 0;
-            d.fwd_tileoff = csr->dd_tileoff.as<int64_t>() + 2 * (c.k + 1);
-            d.big_tileoff = csr->dd_tileoff.as<int64_t>() + 3 * (c.k + 1);
+            d.big_tileoff = csr->dd_tileoff.as<int64_t>() + 2 * (c.k + 1);
             d.fallback = C ? reinterpret_cast<int32_t *>(csr->dd_seg.as<uint32_t>()) : nullptr;
             d.seg_cnt = csr->dd_seg.as<uint32_t>() + 16;
             d.seg_off = d.seg_cnt + (size_t)c.k * kMaxSegments;

@@ -96,7 +96,6 @@ struct DedupArgs {
     uint32_t *seg_cnt;   // k * C: pairs per segment, later distinct ids per segment
     uint32_t *seg_off;   // k * (C+1): exclusive scan of the pair counts
     uint32_t *seg_cursor; // k * C
-    int64_t *fwd_tileoff; // k+1
     int64_t *big_tileoff; // k+1: tiles of kSplitTile16 entries
     uint32_t *big_list;  // k * C: segments of 1025..kSegCap pairs
     uint32_t *big_count; // device counter of big_list (the word after `fallback`)
@@ -105,8 +104,8 @@ struct DedupArgs {
     int32_t fuse_back;   // 1: the sorting waves append their entries to the slot lists themselves (no split pass)
     int32_t *fallback;   // device flag: a segment does not fit in LDS, the per-minibatch kernel takes the hop
 };
-constexpr int kFwdTile = 4096;      // sampled ids per tile of the count kernel
-constexpr int kSplitTile16 = 16384; // ... of the split kernel (128 KB of LDS staging: long runs per segment)
+constexpr int kSplitTile16 = 16384; // sampled ids per tile of the count and split kernels (128 KB of LDS staging:
+                                    // long runs per segment)
 constexpr int kSegCap = 4096;       // pairs of one segment that are sorted in LDS (32 KB)
 constexpr int kMaxSegments = 2560;  // 3 words each beside the split kernel's staging must fit in 160 KB of LDS
 void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz, const StageMark &mark);

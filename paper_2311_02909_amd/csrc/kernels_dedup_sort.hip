@@ -3,7 +3,7 @@
 // LDS, so that all random accesses of the dedup happen in LDS and global memory only sees
 // coalesced traffic.  All kernels run on every compute unit, whatever the number of minibatches.
 //
-//   count  per tile of 4096 sampled ids: LDS histogram over the C segments -> global counts
+//   count  per tile of 16384 sampled ids: LDS histogram over the C segments -> global counts
 //   scan   per minibatch: segment offsets; raises the fallback flag when a segment would not
 //          fit in LDS (ids crowded into a narrow range) -- then these kernels do nothing and the
 //          per-minibatch kernel of kernels_dedup.hip does the hop instead
@@ -26,32 +26,33 @@ __device__ inline uint64_t pack_entry(uint32_t payload, uint32_t rank, uint32_t 
     return (uint64_t)payload | ((uint64_t)rank << 32) | ((uint64_t)seg << 48);
 }
 
-__global__ __launch_bounds__(256) void dd_count_kernel(DedupArgs a)
+template <int TILE, int NT>
+__global__ __launch_bounds__(NT) void dd_count_kernel(DedupArgs a, const int64_t *__restrict__ tileoff)
 {
     __shared__ uint32_t hist[kMaxSegments];
     const int tid = threadIdx.x;
-    const int64_t ntiles = a.fwd_tileoff[a.k];
+    const int64_t ntiles = tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int i = locate_segment(a.fwd_tileoff, a.k, t);
+        const int i = locate_segment(tileoff, a.k, t);
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
-        const uint32_t j0 = (uint32_t)(t - a.fwd_tileoff[i]) * kFwdTile;
+        const uint32_t j0 = (uint32_t)(t - tileoff[i]) * TILE;
         const int32_t *__restrict__ col = a.col + e0;
-        for (int c = tid; c < a.C; c += 256)
+        for (int c = tid; c < a.C; c += NT)
             hist[c] = 0;
         __syncthreads();
-        uint32_t g[kFwdTile / 256];
+        uint32_t g[TILE / NT];
 #pragma unroll
-        for (int q = 0; q < kFwdTile / 256; ++q) {
-            const uint32_t j = j0 + q * 256 + tid;
-            g[q] = (j < N && j < j0 + kFwdTile) ? (uint32_t)col[j] : 0xFFFFFFFFu;
+        for (int q = 0; q < TILE / NT; ++q) {
+            const uint32_t j = j0 + q * NT + tid;
+            g[q] = (j < N && j < j0 + TILE) ? (uint32_t)col[j] : 0xFFFFFFFFu;
         }
 #pragma unroll
-        for (int q = 0; q < kFwdTile / 256; ++q)
+        for (int q = 0; q < TILE / NT; ++q)
             if (g[q] != 0xFFFFFFFFu)
                 atomicAdd(&hist[g[q] >> a.cshift], 1u);
         __syncthreads();
-        for (int c = tid; c < a.C; c += 256)
+        for (int c = tid; c < a.C; c += NT)
             if (hist[c])
                 atomicAdd(&a.seg_cnt[(int64_t)i * a.C + c], hist[c]);
         __syncthreads();
@@ -507,9 +508,10 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
     mark("dd_count");
     (void)hipMemsetAsync(a.seg_cnt, 0, (size_t)a.k * a.C * sizeof(uint32_t), L.stream);
     (void)hipMemsetAsync(a.fallback, 0, 3 * sizeof(int32_t), L.stream); // flag, big_count, wide_count
-    launch_plan_tiles(L, a.mb_edgeoff, a.k, kFwdTile, a.fwd_tileoff);
-    const int64_t tiles = nnz / kFwdTile + a.k;
-    hipLaunchKernelGGL(dd_count_kernel, dim3(grid_for(L, tiles, 8)), dim3(256), 0, L.stream, a);
+    launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile16, a.big_tileoff);
+    const int64_t tiles = nnz / kSplitTile16 + a.k;
+    hipLaunchKernelGGL((dd_count_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 2)), dim3(1024), 0, L.stream, a,
+                       a.big_tileoff);
     hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
     mark("dd_split");
     { // 16384 ids per step, one workgroup of 16 waves per compute unit
@@ -522,8 +524,7 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
                 (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
             attr_set = true;
         }
-        launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile16, a.big_tileoff);
-        hipLaunchKernelGGL((dd_split_kernel<kSplitTile16, 1024>), dim3(grid_for(L, nnz / kSplitTile16 + a.k, 1)), dim3(1024), lds,
+        hipLaunchKernelGGL((dd_split_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 1)), dim3(1024), lds,
                            L.stream, a, a.big_tileoff);
     }
     mark("dd_sort");
