@@ -38,6 +38,8 @@ void launch_validate_seeds(const Launch &, const int32_t *seeds, int32_t k, int3
 void launch_clear_seed_bits(const Launch &, const int32_t *seeds, int32_t k, int32_t b, int64_t n, const VSet &);
 void launch_iota_offsets(const Launch &, int64_t *off, int32_t k, int64_t step); // off[i] = i*step, i<=k
 void launch_plan_tiles(const Launch &, const int64_t *seg_off, int32_t k, int32_t tile, int64_t *seg_tileoff);
+void launch_plan_tiles3(const Launch &, const int64_t *seg_off, int32_t k, int32_t tile0, int64_t *off0, int32_t tile1,
+                        int64_t *off1, int32_t tile2, int64_t *off2);
 // exclusive scan of vals[0..*count) in place, vals[*count] = total; total also stored to *total_out and,
 // when tail_ptr != nullptr, to tail_ptr[*tail_idx].  count_bound = host-side upper bound of *count (0: unknown);
 // long arrays are scanned by many workgroups when the launch context carries scratch for it
@@ -115,6 +117,7 @@ int launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out
 void launch_nw_dedup_fixup(const Launch &, const DedupArgs &, const int64_t *mb_coloff, int32_t *col_vertex,
                            int64_t nnz, const StageMark &mark);
 constexpr int kDedupPlaceTile = 8192; // must equal kPlaceTile in kernels_dedup.hip (sizes the cursor array)
+constexpr int kDedupSplitTile = 2048; // must equal kSplitTile in kernels_dedup.hip
 void launch_offsets_from_counts(const Launch &, const int64_t *mb_count, int32_t k, int64_t *mb_off,
                                 int64_t *total_out);
 // seed check without a vertex set: range test + per-minibatch sort in LDS (b <= kMaxSortedSeeds)

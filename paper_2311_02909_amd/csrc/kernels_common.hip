@@ -186,6 +186,44 @@ void launch_plan_tiles(const Launch &L, const int64_t *seg_off, int32_t k, int32
     hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(1024), 0, L.stream, seg_off, k, tile, seg_tileoff);
 }
 
+// three tilings of the same segments in one launch (one workgroup each)
+__global__ __launch_bounds__(1024) void plan_tiles3_kernel(const int64_t *__restrict__ seg_off, int32_t k, int32_t tile0,
+                                                           int64_t *off0, int32_t tile1, int64_t *off1, int32_t tile2,
+                                                           int64_t *off2)
+{
+    __shared__ int64_t smem[16];
+    __shared__ int64_t carry_s;
+    const int32_t tile = blockIdx.x == 0 ? tile0 : blockIdx.x == 1 ? tile1 : tile2;
+    int64_t *seg_tileoff = blockIdx.x == 0 ? off0 : blockIdx.x == 1 ? off1 : off2;
+    if (threadIdx.x == 0)
+        carry_s = 0;
+    __syncthreads();
+    for (int32_t base = 0; base < k; base += 1024) {
+        const int32_t i = base + threadIdx.x;
+        int64_t cnt = 0;
+        if (i < k)
+            cnt = (seg_off[i + 1] - seg_off[i] + tile - 1) / tile;
+        int64_t total;
+        const int64_t ex = block_exclusive_scan<int64_t, 1024>(cnt, smem, total);
+        const int64_t carry = carry_s;
+        if (i < k)
+            seg_tileoff[i] = carry + ex;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            carry_s = carry + total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        seg_tileoff[k] = carry_s;
+}
+
+void launch_plan_tiles3(const Launch &L, const int64_t *seg_off, int32_t k, int32_t tile0, int64_t *off0, int32_t tile1,
+                        int64_t *off1, int32_t tile2, int64_t *off2)
+{
+    hipLaunchKernelGGL(plan_tiles3_kernel, dim3(3), dim3(1024), 0, L.stream, seg_off, k, tile0, off0, tile1, off1, tile2,
+                       off2);
+}
+
 // ---------------------------------------------------------------------------------------------
 // In-place exclusive scan of an int64 array whose length lives on the device.  One workgroup,
 // The arrays scanned here are per-tile sums and per-row counts (up to a few hundred thousand).

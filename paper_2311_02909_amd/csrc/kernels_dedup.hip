@@ -324,17 +324,16 @@ constexpr int kPlaceTile = 8192;
 constexpr int kPlaceShift = 13;
 constexpr int kSplitTile = 2048;
 constexpr int kMaxPlaceTiles = 256;
-static_assert(kPlaceTile == kDedupPlaceTile && (1 << kPlaceShift) == kPlaceTile, "tile constants out of step");
+static_assert(kPlaceTile == kDedupPlaceTile && (1 << kPlaceShift) == kPlaceTile && kSplitTile == kDedupSplitTile,
+              "tile constants out of step");
 
 // big_segments == 0: walks all tiles of `pairs`.  After the per-minibatch kernel (fallback) that is
 // every entry; after the segment sorts only minibatches of more than 256 ranges still have their
 // entries in `pairs` (they are stored directly), the others were split by the sorting waves.
 // big_segments == 1 (segment sorts only): walks the segments sorted by whole workgroups.
-__global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a, int big_segments)
+__device__ inline void dedup_split_pass(const DedupArgs &a, int big_segments, uint64_t *stage, uint32_t *cnt, uint32_t *off,
+                                        uint32_t *gpos, uint32_t *smem)
 {
-    __shared__ uint64_t stage[kSplitTile];
-    __shared__ uint32_t cnt[kMaxPlaceTiles], off[kMaxPlaceTiles], gpos[kMaxPlaceTiles];
-    __shared__ uint32_t smem[4];
     const int tid = threadIdx.x;
     const bool sorted = a.fuse_back && a.fallback && !*a.fallback; // the waves have split their segments
     if (big_segments && !sorted)
@@ -415,6 +414,18 @@ __global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a, int bi
             const uint32_t r = (uint32_t)e >> kPlaceShift;
             back[r * kPlaceTile + gpos[r] + (sidx - off[r])] = e;
         }
+        __syncthreads();
+    }
+}
+
+// passes = 1: big_segments == 0 only; passes = 2: both, one after the other
+__global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a, int passes)
+{
+    __shared__ uint64_t stage[kSplitTile];
+    __shared__ uint32_t cnt[kMaxPlaceTiles], off[kMaxPlaceTiles], gpos[kMaxPlaceTiles];
+    __shared__ uint32_t smem[4];
+    for (int big_segments = 0; big_segments < passes; ++big_segments) {
+        dedup_split_pass(a, big_segments, stage, cnt, off, gpos, smem);
         __syncthreads();
     }
 }
@@ -537,15 +548,13 @@ void launch_nw_dedup_fixup(const Launch &L, const DedupArgs &a, const int64_t *m
         gx = 64;
     hipLaunchKernelGGL(nw_dedup_front_kernel, dim3(gx, a.k), dim3(256), 0, L.stream, a, mb_coloff, col_vertex);
     mark("dd_back_split");
-    launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile, a.split_tileoff);
     if (a.C == 0) { // the segment-sort launcher has done this already (its waves append to the slot lists)
+        launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile, a.split_tileoff);
         launch_plan_tiles(L, a.mb_edgeoff, a.k, kPlaceTile, a.place_tileoff);
         (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
     }
-    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a, 0);
-    if (a.C > 0 && a.fuse_back)
-        hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a,
-                           1);
+    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a,
+                       (a.C > 0 && a.fuse_back) ? 2 : 1);
     mark("dd_place");
     hipLaunchKernelGGL(nw_dedup_place_kernel, dim3(grid_for(L, nnz / kPlaceTile + a.k, 4)), dim3(256), 0, L.stream, a);
 }

@@ -506,9 +506,13 @@ __global__ __launch_bounds__(256) void dd_base_scan_kernel(DedupArgs a)
 void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, const StageMark &mark)
 {
     mark("dd_count");
-    (void)hipMemsetAsync(a.seg_cnt, 0, (size_t)a.k * a.C * sizeof(uint32_t), L.stream);
-    (void)hipMemsetAsync(a.fallback, 0, 3 * sizeof(int32_t), L.stream); // flag, big_count, wide_count
-    launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile16, a.big_tileoff);
+    // the flag, the two list counters and the segment counters lie next to each other: one clear
+    (void)hipMemsetAsync(a.fallback, 0, (size_t)(a.seg_cnt - reinterpret_cast<uint32_t *>(a.fallback)) * sizeof(uint32_t) +
+                                            (size_t)a.k * a.C * sizeof(uint32_t), L.stream);
+    (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kDedupPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
+    // tiles of the count / split kernels, of the placing kernel and of the stand-alone back-split
+    launch_plan_tiles3(L, a.mb_edgeoff, a.k, kSplitTile16, a.big_tileoff, kDedupPlaceTile, a.place_tileoff, kDedupSplitTile,
+                       a.split_tileoff);
     const int64_t tiles = nnz / kSplitTile16 + a.k;
     hipLaunchKernelGGL((dd_count_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 2)), dim3(1024), 0, L.stream, a,
                        a.big_tileoff);
@@ -528,8 +532,6 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
                            L.stream, a, a.big_tileoff);
     }
     mark("dd_sort");
-    launch_plan_tiles(L, a.mb_edgeoff, a.k, kDedupPlaceTile, a.place_tileoff);
-    (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kDedupPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
     hipLaunchKernelGGL(dd_sort_wave_kernel<false>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 4)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_sort_wave_kernel<true>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 2)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 4)), dim3(256), 0, L.stream, a);
