@@ -195,6 +195,28 @@ static_assert(kRangeSize == kDedupPlaceTile && 3 * kRanges <= kWaveSeg, "range c
 // LDS staging index: lanes that hold neighbouring runs of slots would all hit the same banks
 __device__ inline uint32_t swz(uint32_t x) { return x ^ ((x >> 5) & 31u); }
 
+// Value of lane (l ^ MASK) for a power-of-two MASK.  Partners up to 8 lanes away come through the vector
+// unit's lane-permute paths (quad permutes, row shifts and rotates: no LDS traffic); 16 and 32 lanes away through
+// the LDS crossbar.
+template <int MASK>
+__device__ inline uint32_t lane_xor(uint32_t x)
+{
+    if constexpr (MASK == 1) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+    } else if constexpr (MASK == 2) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, true);
+    } else if constexpr (MASK == 4) {
+        // lanes 0-3 and 8-11 of every row of 16 take the lane 4 above, the others the lane 4 below
+        int o = __builtin_amdgcn_update_dpp((int)x, (int)x, 0x104 /* row_shl:4 */, 0xF, 0x5, false);
+        o = __builtin_amdgcn_update_dpp(o, (int)x, 0x114 /* row_shr:4 */, 0xF, 0xA, false);
+        return (uint32_t)o;
+    } else if constexpr (MASK == 8) {
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128 /* row_ror:8 */, 0xF, 0xF, true);
+    } else {
+        return (uint32_t)__shfl_xor((int)x, MASK, kWave);
+    }
+}
+
 // Bitonic network over 64*R values, R per lane; lane l ends up with sorted positions [R l, R l + R).
 template <int R>
 __device__ inline void wave_sort(uint32_t (&c)[R], int lane)
@@ -208,7 +230,9 @@ __device__ inline void wave_sort(uint32_t (&c)[R], int lane)
                 const bool lower = (lane & lmask) == 0;
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    const uint32_t o = __shfl_xor(c[r], lmask, kWave);
+                    const uint32_t o = lmask == 1 ? lane_xor<1>(c[r]) : lmask == 2 ? lane_xor<2>(c[r])
+                                     : lmask == 4 ? lane_xor<4>(c[r]) : lmask == 8 ? lane_xor<8>(c[r])
+                                     : lmask == 16 ? lane_xor<16>(c[r]) : lane_xor<32>(c[r]);
                     const bool asc = ((lane * R + r) & size) == 0; // always true in the last merge
                     c[r] = (lower == asc) ? min(c[r], o) : max(c[r], o);
                 }
