@@ -407,7 +407,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     int64_t rows_bound = (int64_t)c.k * c.b;
     const int32_t *row_vertex = c.res->hops[0].row_vertex.as<int32_t>();
     const int64_t *mb_rowoff = c.res->hops[0].mb_rowoff.as<int64_t>();
-    BMS_TRY(csr->mb_tileoff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+    BMS_TRY(csr->mb_tileoff.ensure(((size_t)c.k + 2) * sizeof(int64_t)));
 
     // Steady state: a recycled result that remembers the sizes of the same call shape lets every hop
     // be enqueued without a host round trip.  Buffers are then sized by the upper bound
@@ -454,7 +454,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         a.rows_bound = rows_bound;
 
         BMS_TRY(prof.begin("nw_rows", h));
-        launch_plan_tiles(c.launch, mb_rowoff, c.k, kRowTile, a.mb_tileoff);
+        launch_plan_tiles(c.launch, mb_rowoff, c.k, kRowTile, a.mb_tileoff, a.mb_tileoff + c.k + 1);
         launch_nw_rows(c.launch, a);
         BMS_TRY(prof.end());
         BMS_TRY(prof.begin("scan_tiles", h));

@@ -37,7 +37,9 @@ void launch_validate_seeds(const Launch &, const int32_t *seeds, int32_t k, int3
                            int32_t *flag);
 void launch_clear_seed_bits(const Launch &, const int32_t *seeds, int32_t k, int32_t b, int64_t n, const VSet &);
 void launch_iota_offsets(const Launch &, int64_t *off, int32_t k, int64_t step); // off[i] = i*step, i<=k
-void launch_plan_tiles(const Launch &, const int64_t *seg_off, int32_t k, int32_t tile, int64_t *seg_tileoff);
+// max_out (optional): receives the largest number of tiles any segment has
+void launch_plan_tiles(const Launch &, const int64_t *seg_off, int32_t k, int32_t tile, int64_t *seg_tileoff,
+                       int64_t *max_out = nullptr);
 void launch_plan_tiles3(const Launch &, const int64_t *seg_off, int32_t k, int32_t tile0, int64_t *off0, int32_t tile1,
                         int64_t *off1, int32_t tile2, int64_t *off2);
 // exclusive scan of vals[0..*count) in place, vals[*count] = total; total also stored to *total_out and,

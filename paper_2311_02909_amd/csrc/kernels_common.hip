@@ -155,7 +155,7 @@ void launch_iota_offsets(const Launch &L, int64_t *off, int32_t k, int64_t step)
 // Single workgroup: k is small (the number of minibatches).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int64_t *__restrict__ seg_off, int32_t k, int32_t tile,
-                                                          int64_t *seg_tileoff)
+                                                          int64_t *seg_tileoff, unsigned long long *max_out)
 {
     __shared__ int64_t smem[16];
     __shared__ int64_t carry_s;
@@ -167,6 +167,8 @@ __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int64_t *__restr
         int64_t cnt = 0;
         if (i < k)
             cnt = (seg_off[i + 1] - seg_off[i] + tile - 1) / tile;
+        if (max_out && cnt > 0)
+            atomicMax(max_out, (unsigned long long)cnt); // *max_out zeroed by the caller
         int64_t total;
         const int64_t ex = block_exclusive_scan<int64_t, 1024>(cnt, smem, total);
         const int64_t carry = carry_s;
@@ -181,9 +183,13 @@ __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int64_t *__restr
         seg_tileoff[k] = carry_s;
 }
 
-void launch_plan_tiles(const Launch &L, const int64_t *seg_off, int32_t k, int32_t tile, int64_t *seg_tileoff)
+void launch_plan_tiles(const Launch &L, const int64_t *seg_off, int32_t k, int32_t tile, int64_t *seg_tileoff,
+                       int64_t *max_out)
 {
-    hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(1024), 0, L.stream, seg_off, k, tile, seg_tileoff);
+    if (max_out)
+        (void)hipMemsetAsync(max_out, 0, sizeof(int64_t), L.stream);
+    hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(1024), 0, L.stream, seg_off, k, tile, seg_tileoff,
+                       reinterpret_cast<unsigned long long *>(max_out));
 }
 
 // three tilings of the same segments in one launch (one workgroup each)

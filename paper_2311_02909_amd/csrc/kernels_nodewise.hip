@@ -22,10 +22,17 @@ __global__ __launch_bounds__(kRowTile) void nw_rows_kernel(NwHop a)
 {
     __shared__ int64_t wsum[kRowTile / kWave];
     const int tid = threadIdx.x;
-    const int64_t ntiles = a.mb_tileoff[a.k];
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int i = locate_segment(a.mb_tileoff, a.k, t);
-        const int64_t r = a.mb_rowoff[i] + (t - a.mb_tileoff[i]) * kRowTile + tid;
+    // Tile j of every minibatch before tile j + 1 of any: the rows of a minibatch ascend by vertex id, so the
+    // workgroups that run at the same time touch the same part of the id range in all minibatches, and lines of
+    // rowptr / col that several minibatches need are still in the last-level cache when the next one asks.
+    const int64_t most = a.mb_tileoff[a.k + 1]; // tiles of the minibatch that has most
+    for (int64_t v = blockIdx.x; v < most * a.k; v += gridDim.x) {
+        const int i = (int)(v % a.k);
+        const int64_t j = v / a.k;
+        if (j >= a.mb_tileoff[i + 1] - a.mb_tileoff[i])
+            continue;
+        const int64_t t = a.mb_tileoff[i] + j;
+        const int64_t r = a.mb_rowoff[i] + j * kRowTile + tid;
         int64_t cnt = 0;
         if (r < a.mb_rowoff[i + 1]) {
             const int32_t v = a.row_vertex[r];
@@ -74,11 +81,15 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
     __shared__ int32_t stage[kRowTile * S];
     __shared__ int32_t wsum[kRowTile / kWave];
     const int tid = threadIdx.x;
-    const int64_t ntiles = a.mb_tileoff[a.k];
+    const int64_t most = a.mb_tileoff[a.k + 1];
     const int32_t s = a.s;
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int i = locate_segment(a.mb_tileoff, a.k, t);
-        const int64_t r = a.mb_rowoff[i] + (t - a.mb_tileoff[i]) * kRowTile + tid;
+    for (int64_t v = blockIdx.x; v < most * a.k; v += gridDim.x) { // same order as nw_rows_kernel
+        const int i = (int)(v % a.k);
+        const int64_t j = v / a.k;
+        if (j >= a.mb_tileoff[i + 1] - a.mb_tileoff[i])
+            continue;
+        const int64_t t = a.mb_tileoff[i] + j;
+        const int64_t r = a.mb_rowoff[i] + j * kRowTile + tid;
         const bool valid = r < a.mb_rowoff[i + 1];
         int64_t beg = 0;
         int32_t deg = 0, cnt = 0;
