@@ -55,6 +55,7 @@ extern "C" {
 #define BMS_EXTRACT_BUCKETS 4u /* node-wise EXTRACT by one workgroup per minibatch over id-range bins      */
 #define BMS_EXTRACT_BITMAP 8u  /* node-wise EXTRACT by per-minibatch bitmaps in HBM (default above 2.6e8 vertices) */
 #define BMS_EXTRACT_SORT 16u   /* node-wise EXTRACT by LDS sorts of id-range segments (default)              */
+#define BMS_PROFILE_MAIN 64u   /* as BMS_PROFILE, but only the sampler's main kernel stage (nw_sample, ldw_accumulate)   */
 #define BMS_LADIES_DENSE 32u   /* LADIES with dense per-minibatch counters in HBM instead of LDS windows     */
                                /* all give identical results; the flags only pick the kernel path          */
 

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libbms.so")
 
 OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
-LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT, LADIES_DENSE = 1, 2, 4, 8, 16, 32
+LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT, LADIES_DENSE, PROFILE_MAIN = 1, 2, 4, 8, 16, 32, 64
 
 
 class BmsError(RuntimeError):
@@ -240,6 +240,13 @@ class Result:
             pass
 
 
+def _profile_flag(profile) -> int:
+    """profile=True: every stage timed; profile="main": only the sampler's main kernel stage (cheaper)."""
+    if profile == "main":
+        return PROFILE_MAIN
+    return PROFILE if profile else 0
+
+
 def _sample(fn, csr: Csr, batches, params: Sequence[int], seed: int, mb_base, stream, recycle, flags, scratch_limit):
     if isinstance(batches, np.ndarray):
         batches = torch.from_numpy(np.ascontiguousarray(batches, dtype=np.int32))
@@ -266,7 +273,7 @@ def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_
                     extract: Optional[str] = None) -> Result:
     """bms_sample_nodewise: bulk GraphSAGE sampling of the k x b seed batches.
     extract: None (library's choice), "sort", "buckets" or "bitmap" -- which EXTRACT kernels run; same result."""
-    flags = (PROFILE if profile else 0) | {None: 0, "buckets": EXTRACT_BUCKETS, "bitmap": EXTRACT_BITMAP,
+    flags = _profile_flag(profile) | {None: 0, "buckets": EXTRACT_BUCKETS, "bitmap": EXTRACT_BITMAP,
                                            "sort": EXTRACT_SORT}[extract]
     return _sample(lib().bms_sample_nodewise, csr, batches, fanouts, seed, mb_base, stream, recycle, flags,
                    scratch_limit)
@@ -278,7 +285,7 @@ def sample_ladies(csr: Csr, batches, s_per_layer: Sequence[int], seed: int, *, m
     """bms_sample_ladies: bulk LADIES sampling of the k x b seed batches.
 
     dense=True picks the kernel path with per-minibatch counters in HBM (same results)."""
-    flags = (PROFILE if profile else 0) | (LADIES_SQUARED if squared else 0) | (LADIES_DENSE if dense else 0)
+    flags = _profile_flag(profile) | (LADIES_SQUARED if squared else 0) | (LADIES_DENSE if dense else 0)
     return _sample(lib().bms_sample_ladies, csr, batches, s_per_layer, seed, mb_base, stream, recycle, flags,
                    scratch_limit)
 

@@ -157,19 +157,35 @@ struct Profiler {
     bms_result *res;
     hipStream_t stream;
     bool on;
+    bool main_only = false; // record only the sampler's main kernel stage (BMS_PROFILE_MAIN)
     bool open = false;
+    bool skipped = false;   // the running stage is not recorded
+    static bool is_main(const char *name)
+    {
+        return !strcmp(name, "nw_sample") || !strcmp(name, "ldw_accumulate") || !strcmp(name, "ld_accumulate");
+    }
+    int next_event(hipEvent_t *e)
+    {
+        while (res->event_pool.size() < res->events_used + 1) {
+            hipEvent_t ev;
+            HIP_TRY(hipEventCreate(&ev));
+            res->event_pool.push_back(ev);
+        }
+        *e = res->event_pool[res->events_used++];
+        return BMS_OK;
+    }
     int begin(const char *name, int32_t hop)
     {
         if (!on)
             return BMS_OK;
-        open = true;
-        while (res->event_pool.size() < res->events_used + 2) {
-            hipEvent_t e;
-            HIP_TRY(hipEventCreate(&e));
-            res->event_pool.push_back(e);
+        if (main_only && !is_main(name)) {
+            skipped = true;
+            return BMS_OK;
         }
-        StageTime st{name, hop, res->event_pool[res->events_used], res->event_pool[res->events_used + 1], 0.f};
-        res->events_used += 2;
+        skipped = false;
+        open = true;
+        StageTime st{name, hop, nullptr, nullptr, 0.f};
+        BMS_TRY(next_event(&st.t0));
         HIP_TRY(hipEventRecord(st.t0, stream));
         res->stages.push_back(st);
         return BMS_OK;
@@ -179,14 +195,27 @@ struct Profiler {
         if (!on || !open)
             return BMS_OK;
         open = false;
-        HIP_TRY(hipEventRecord(res->stages.back().t1, stream));
+        StageTime &st = res->stages.back();
+        BMS_TRY(next_event(&st.t1));
+        HIP_TRY(hipEventRecord(st.t1, stream));
         return BMS_OK;
     }
-    // closes the running stage, if any, and opens the next one
+    // closes the running stage, if any, and opens the next one; one event serves as the end of the first and
+    // the start of the second
     int mark(const char *name, int32_t hop)
     {
-        BMS_TRY(end());
-        return begin(name, hop);
+        if (!on)
+            return BMS_OK;
+        if (!open || (main_only && !is_main(name))) {
+            BMS_TRY(end());
+            return begin(name, hop);
+        }
+        StageTime &prev = res->stages.back();
+        BMS_TRY(next_event(&prev.t1));
+        HIP_TRY(hipEventRecord(prev.t1, stream));
+        StageTime st{name, hop, prev.t1, nullptr, 0.f};
+        res->stages.push_back(st);
+        return BMS_OK;
     }
     int finish()
     {
@@ -239,7 +268,7 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
     if (opts) {
-        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE))
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN))
             return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
         if (opts->recycle && opts->recycle->tag != kTagResult)
             return fail(BMS_EINVAL, "opts->recycle is not a result handle");
@@ -378,7 +407,7 @@ constexpr int32_t kMaxHops = 15; // 4 scalar slots per hop in a 64-entry block
 int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fanouts)
 {
     bms_csr *csr = c.csr;
-    Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
+    Profiler prof{c.res, c.stream, (c.flags & (BMS_PROFILE | BMS_PROFILE_MAIN)) != 0, (c.flags & BMS_PROFILE) == 0};
     // EXTRACT strategy: LDS sorts of id-range segments (with the per-minibatch bin kernel as the
     // fallback for crowded id ranges) whenever the bin table of that fallback fits in LDS; the
     // per-minibatch bitmaps over [0,n) in HBM otherwise.
@@ -605,7 +634,7 @@ bool ladies_windows_apply(const CallCtx &c, const int32_t *s_per_layer)
 int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t *s_per_layer)
 {
     bms_csr *csr = c.csr;
-    Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
+    Profiler prof{c.res, c.stream, (c.flags & (BMS_PROFILE | BMS_PROFILE_MAIN)) != 0, (c.flags & BMS_PROFILE) == 0};
     const int64_t n1 = std::max<int64_t>(csr->n, 1);
     const int32_t nwin = (int32_t)((n1 + (1LL << kWinShift) - 1) >> kWinShift);
     const size_t nw = (size_t)c.k * nwin;
@@ -793,7 +822,7 @@ int sample_ladies_impl(CallCtx &c, const int32_t *batches, const int32_t *s_per_
     if (ladies_windows_apply(c, s_per_layer))
         return sample_ladies_windows_impl(c, batches, s_per_layer);
     bms_csr *csr = c.csr;
-    Profiler prof{c.res, c.stream, (c.flags & BMS_PROFILE) != 0};
+    Profiler prof{c.res, c.stream, (c.flags & (BMS_PROFILE | BMS_PROFILE_MAIN)) != 0, (c.flags & BMS_PROFILE) == 0};
     BMS_TRY(setup_vset(c));
 
     // dense per-minibatch counters e_v, all zero between hops and between calls

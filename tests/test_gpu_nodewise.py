@@ -157,6 +157,15 @@ def test_profile_stages_are_reported(mods):
     res = bms.sample_nodewise(csr, random_batches(4000, 4, 64, rng), (5, 5), 3, profile=True)
     names = [s[0] for s in res.stages()]
     assert names.count("nw_sample") == 2 and all(s[2] >= 0 for s in res.stages())
+    assert len(set(names)) > 3
+    # the cheap mode times the sampling kernel only; without a profile flag nothing is recorded
+    res = bms.sample_nodewise(csr, random_batches(4000, 4, 64, rng), (5, 5), 3, profile="main", recycle=res)
+    assert [(s[0], s[1]) for s in res.stages()] == [("nw_sample", 0), ("nw_sample", 1)]
+    assert all(s[2] > 0 for s in res.stages())
+    lad = bms.sample_ladies(csr, random_batches(4000, 4, 64, rng), (20,), 3, profile="main")
+    assert [s[0] for s in lad.stages()] == ["ldw_accumulate"]
+    res = bms.sample_nodewise(csr, random_batches(4000, 4, 64, rng), (5, 5), 3, recycle=res)
+    assert res.stages() == []
 
 
 def test_bucket_extract_many_buckets_and_large_batches(mods):
