@@ -93,6 +93,9 @@ def main() -> int:
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB mebibytes 5 times "
                          "(calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters against a known size)")
+    ap.add_argument("--gather-probe", type=int, default=0, metavar="LOG2",
+                    help="instead of the benchmark, time 2^28 random 4-byte reads (torch.index_select) over an int32 "
+                         "array of 2^LOG2 elements, 5 launches: the chip's rate for reads that share no memory line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -113,6 +116,23 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read_per_launch": src.numel() * 4,
                           "copy_probe_bytes_written_per_launch": src.numel() * 4, "launches": 5}))
+        return 0
+    if args.gather_probe:
+        span, reads = 1 << args.gather_probe, 1 << 28
+        src = torch.zeros(span, dtype=torch.int32, device="cuda")
+        idx = torch.randint(0, span, (reads,), dtype=torch.int64, device="cuda",
+                            generator=torch.Generator(device="cuda").manual_seed(1))
+        out = torch.index_select(src, 0, idx)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            torch.index_select(src, 0, idx, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        print(json.dumps({"gather_probe_span_bytes": span * 4, "random_reads_per_launch": reads, "launches": 6,
+                          "index_bytes_per_launch": reads * 8, "ms_per_launch": round(ms, 4),
+                          "reads_per_sec": reads / ms * 1e3, "tb_per_sec_at_128B_per_read": reads * 128 / ms / 1e9}))
         return 0
     t0 = time.time()
     g, batches, w = synth.make_workload(args.workload, device="cuda")
