@@ -34,6 +34,12 @@
  *   - LADIES: s draws with replacement from the one row, then duplicates removed.
  *   - EXTRACT orders the surviving columns by ascending vertex id; that list is
  *     the next layer's frontier (no union with the current frontier).
+ *   - Two GraphSAGE variants, off by default: ORC_UNION_DST keeps the current
+ *     frontier's vertices as columns too (next frontier = frontier + sampled
+ *     vertices, the convention of samplers whose layers also use a vertex's own
+ *     features) and reports each row's own column; ORC_REPLACE makes the s draws
+ *     of a row independent (ITS with replacement: the repeat-until-distinct step
+ *     of Sec. 4.1.2 left out) and keeps the distinct picks.
  *   - Random stream: stateless counter hash of (seed, hop, minibatch, vertex,
  *     draw index), defined by orc_rowkey / orc_draw32 / orc_draw64 below.
  *
@@ -140,6 +146,34 @@ void orc_its_distinct(uint64_t key, uint32_t deg, int32_t s, uint32_t *chosen)
     }
 }
 
+/*
+ * Variant ORC_REPLACE of Sec. 4.1.2: the s draws are independent, each one an
+ * integer in [0, deg) (ITS on the unit weights, nothing zeroed, no repetition
+ * when two draws coincide).  The nonzeros of the sampled row are the distinct
+ * picks: `chosen` receives them sorted ascending, the count is returned
+ * (1 <= count <= min(s, deg) for deg >= 1).
+ */
+int32_t orc_its_replace(uint64_t key, uint32_t deg, int32_t s, uint32_t *chosen)
+{
+    int32_t c = 0;
+    for (int32_t j = 0; j < s; ++j) {
+        const uint32_t r = orc_bounded32(orc_draw32(key, (uint32_t)j), deg);
+        int32_t t = 0;
+        while (t < c && chosen[t] < r)
+            ++t;
+        if (t < c && chosen[t] == r)
+            continue; /* this position already is a nonzero of the row */
+        for (int32_t q = c; q > t; --q)
+            chosen[q] = chosen[q - 1];
+        chosen[t] = r;
+        ++c;
+    }
+    return c;
+}
+
+#define ORC_UNION_DST 1 /* columns = sampled vertices and the frontier itself */
+#define ORC_REPLACE 2   /* independent draws, distinct picks kept              */
+
 /* ------------------------------------------------------------------ */
 /* Result containers                                                   */
 /* ------------------------------------------------------------------ */
@@ -155,6 +189,7 @@ typedef struct {
     int64_t *p_off;      /* k+1 : LADIES only, the row of P of each minibatch            */
     int32_t *p_col;      /* pnnz: columns of P ascending                                 */
     uint32_t *p_cnt;     /* pnnz: e_v                                                    */
+    int32_t *row_self;   /* rows: ORC_UNION_DST only, local column of the row's own vertex */
 } orc_hop;
 
 typedef struct {
@@ -171,6 +206,7 @@ typedef struct {
     int32_t *col_vertex;
     int32_t *p_col;
     uint32_t *p_cnt;
+    int32_t *row_self;
 } mb_hop;
 
 static void mb_hop_free(mb_hop *m)
@@ -181,6 +217,7 @@ static void mb_hop_free(mb_hop *m)
     free(m->col_vertex);
     free(m->p_col);
     free(m->p_cnt);
+    free(m->row_self);
     memset(m, 0, sizeof(*m));
 }
 
@@ -243,7 +280,7 @@ static int batch_is_valid(const int32_t *batch, int32_t b, int64_t n)
 /* ------------------------------------------------------------------ */
 
 static void nodewise_one(const int64_t *A_rowptr, const int32_t *A_col, const int32_t *batch, int32_t b,
-                         const int32_t *fanouts, int32_t L, uint64_t seed, uint32_t mb, mb_hop *out)
+                         const int32_t *fanouts, int32_t L, uint64_t seed, uint32_t mb, int variant, mb_hop *out)
 {
     int64_t nF = b;
     int32_t *F = (int32_t *)xmalloc((size_t)nF * sizeof(int32_t));
@@ -255,39 +292,59 @@ static void nodewise_one(const int64_t *A_rowptr, const int32_t *A_col, const in
         o->rows = nF;
         o->row_vertex = F;
 
-        /* P = Q A: row r of P is the neighbour list of F[r]; |row of Q'| = min(deg, s) */
+        /* P = Q A: row r of P is the neighbour list of F[r].  SAMPLE: the nonzeros of Q', as global
+         * vertex ids, ascending within a row; at most min(deg, s) of them (exactly that many unless
+         * the draws are independent) */
         o->rowptr = (int64_t *)xmalloc((size_t)(nF + 1) * sizeof(int64_t));
         o->rowptr[0] = 0;
+        int64_t room = nF; /* the frontier itself (ORC_UNION_DST) + at most min(deg, s) per row */
         for (int64_t r = 0; r < nF; ++r) {
-            int64_t deg = A_rowptr[F[r] + 1] - A_rowptr[F[r]];
-            o->rowptr[r + 1] = o->rowptr[r] + (deg < s ? deg : s);
+            const int64_t deg = A_rowptr[F[r] + 1] - A_rowptr[F[r]];
+            room += deg < s ? deg : s;
         }
-        o->nnz = o->rowptr[nF];
-
-        /* SAMPLE: the nonzeros of Q', as global vertex ids, ascending within a row */
-        int32_t *picked = (int32_t *)xmalloc((size_t)o->nnz * sizeof(int32_t));
+        int32_t *picked = (int32_t *)xmalloc((size_t)room * sizeof(int32_t));
         uint32_t *chosen = (uint32_t *)xmalloc((size_t)(s > 0 ? s : 1) * sizeof(uint32_t));
         for (int64_t r = 0; r < nF; ++r) {
             const int32_t v = F[r];
             const int64_t beg = A_rowptr[v];
             const int64_t deg = A_rowptr[v + 1] - beg;
             int32_t *dst = picked + o->rowptr[r];
-            if (deg <= s) {
+            int64_t len;
+            if (variant & ORC_REPLACE) {
+                len = deg > 0 ? orc_its_replace(orc_rowkey(seed, h, mb, (uint32_t)v), (uint32_t)deg, s, chosen) : 0;
+                for (int64_t t = 0; t < len; ++t)
+                    dst[t] = A_col[beg + chosen[t]];
+            } else if (deg <= s) {
+                len = deg;
                 for (int64_t t = 0; t < deg; ++t)
                     dst[t] = A_col[beg + t];
             } else {
+                len = s;
                 orc_its_distinct(orc_rowkey(seed, h, mb, (uint32_t)v), (uint32_t)deg, s, chosen);
                 for (int32_t t = 0; t < s; ++t)
                     dst[t] = A_col[beg + chosen[t]];
             }
+            o->rowptr[r + 1] = o->rowptr[r] + len;
         }
+        o->nnz = o->rowptr[nF];
         free(chosen);
 
-        /* EXTRACT: drop the empty columns of Q' -> local column = rank among distinct ids */
-        o->ncols = sorted_unique(picked, o->nnz, &o->col_vertex);
+        /* EXTRACT: drop the empty columns of Q' -> local column = rank among the distinct ids
+         * (with ORC_UNION_DST the frontier's own vertices count as nonempty columns too) */
+        int64_t ncand = o->nnz;
+        if (variant & ORC_UNION_DST) {
+            memcpy(picked + ncand, F, (size_t)nF * sizeof(int32_t));
+            ncand += nF;
+        }
+        o->ncols = sorted_unique(picked, ncand, &o->col_vertex);
         o->col = (int32_t *)xmalloc((size_t)o->nnz * sizeof(int32_t));
         for (int64_t e = 0; e < o->nnz; ++e)
             o->col[e] = (int32_t)find_sorted(o->col_vertex, o->ncols, picked[e]);
+        if (variant & ORC_UNION_DST) {
+            o->row_self = (int32_t *)xmalloc((size_t)nF * sizeof(int32_t));
+            for (int64_t r = 0; r < nF; ++r)
+                o->row_self[r] = (int32_t)find_sorted(o->col_vertex, o->ncols, F[r]);
+        }
         free(picked);
 
         /* next Q: one row per distinct sampled vertex */
@@ -406,7 +463,7 @@ static void ladies_one(const int64_t *A_rowptr, const int32_t *A_col, const int3
 /* Bulk: stack the k minibatches (Eq. 1)                               */
 /* ------------------------------------------------------------------ */
 
-static orc_result *stack_minibatches(mb_hop *per, int32_t k, int32_t L, int with_p)
+static orc_result *stack_minibatches(mb_hop *per, int32_t k, int32_t L, int with_p, int with_self)
 {
     orc_result *res = (orc_result *)xmalloc(sizeof(orc_result));
     res->k = k;
@@ -439,12 +496,16 @@ static orc_result *stack_minibatches(mb_hop *per, int32_t k, int32_t L, int with
             o->p_col = (int32_t *)xmalloc((size_t)o->pnnz * sizeof(int32_t));
             o->p_cnt = (uint32_t *)xmalloc((size_t)o->pnnz * sizeof(uint32_t));
         }
+        if (with_self)
+            o->row_self = (int32_t *)xmalloc((size_t)o->rows * sizeof(int32_t));
         int64_t e0 = 0;
         o->rowptr[0] = 0;
         for (int32_t i = 0; i < k; ++i) {
             const mb_hop *m = &per[(size_t)i * L + h];
             const int64_t r0 = o->mb_rowoff[i];
             memcpy(o->row_vertex + r0, m->row_vertex, (size_t)m->rows * sizeof(int32_t));
+            if (with_self)
+                memcpy(o->row_self + r0, m->row_self, (size_t)m->rows * sizeof(int32_t));
             for (int64_t r = 0; r < m->rows; ++r)
                 o->rowptr[r0 + r + 1] = e0 + m->rowptr[r + 1];
             memcpy(o->col + e0, m->col, (size_t)m->nnz * sizeof(int32_t));
@@ -479,23 +540,33 @@ static int check_args(const int64_t *rowptr, const int32_t *col, int64_t n, cons
  * i.e. the paper's layer L).  Minibatch i uses random-stream index mb_base + i.
  * Returns 0, -1 (bad argument) or -2 (seed out of range / repeated in a minibatch).
  */
-int orc_sample_nodewise(const int64_t *rowptr, const int32_t *col, int64_t n, const int32_t *batches, int32_t k,
-                        int32_t b, const int32_t *fanouts, int32_t L, uint64_t seed, int32_t mb_base, orc_result **out)
+int orc_sample_nodewise_variant(const int64_t *rowptr, const int32_t *col, int64_t n, const int32_t *batches,
+                                int32_t k, int32_t b, const int32_t *fanouts, int32_t L, uint64_t seed,
+                                int32_t mb_base, int variant, orc_result **out)
 {
     int rc = check_args(rowptr, col, n, batches, k, b, fanouts, L);
     if (rc)
         return rc;
+    if (variant & ~(ORC_UNION_DST | ORC_REPLACE))
+        return -1;
     mb_hop *per = (mb_hop *)xmalloc((size_t)k * L * sizeof(mb_hop));
     memset(per, 0, (size_t)k * L * sizeof(mb_hop));
 #pragma omp parallel for schedule(dynamic, 1)
     for (int32_t i = 0; i < k; ++i)
-        nodewise_one(rowptr, col, batches + (size_t)i * b, b, fanouts, L, seed, (uint32_t)(mb_base + i),
+        nodewise_one(rowptr, col, batches + (size_t)i * b, b, fanouts, L, seed, (uint32_t)(mb_base + i), variant,
                      per + (size_t)i * L);
-    *out = stack_minibatches(per, k, L, 0);
+    *out = stack_minibatches(per, k, L, 0, variant & ORC_UNION_DST);
     for (size_t q = 0; q < (size_t)k * L; ++q)
         mb_hop_free(&per[q]);
     free(per);
     return 0;
+}
+
+/* the method as the paper states it: no variant */
+int orc_sample_nodewise(const int64_t *rowptr, const int32_t *col, int64_t n, const int32_t *batches, int32_t k,
+                        int32_t b, const int32_t *fanouts, int32_t L, uint64_t seed, int32_t mb_base, orc_result **out)
+{
+    return orc_sample_nodewise_variant(rowptr, col, n, batches, k, b, fanouts, L, seed, mb_base, 0, out);
 }
 
 /*
@@ -515,7 +586,7 @@ int orc_sample_ladies(const int64_t *rowptr, const int32_t *col, int64_t n, cons
     for (int32_t i = 0; i < k; ++i)
         ladies_one(rowptr, col, batches + (size_t)i * b, b, s_per_layer, L, seed, (uint32_t)(mb_base + i), squared,
                    per + (size_t)i * L);
-    *out = stack_minibatches(per, k, L, 1);
+    *out = stack_minibatches(per, k, L, 1, 0);
     for (size_t q = 0; q < (size_t)k * L; ++q)
         mb_hop_free(&per[q]);
     free(per);
@@ -544,6 +615,7 @@ void orc_result_free(orc_result *res)
         free(o->p_off);
         free(o->p_col);
         free(o->p_cnt);
+        free(o->row_self);
     }
     free(res->hop);
     free(res);

@@ -48,6 +48,7 @@ class _Hop(C.Structure):
         ("p_off", C.POINTER(C.c_int64)),
         ("p_col", C.POINTER(C.c_int32)),
         ("p_cnt", C.POINTER(C.c_uint32)),
+        ("row_self", C.POINTER(C.c_int32)),
     ]
 
 
@@ -78,6 +79,10 @@ def lib() -> C.CDLL:
                   C.c_uint64, C.c_int32]
         L.orc_sample_nodewise.restype = C.c_int
         L.orc_sample_nodewise.argtypes = common + [C.POINTER(C.c_void_p)]
+        L.orc_sample_nodewise_variant.restype = C.c_int
+        L.orc_sample_nodewise_variant.argtypes = common + [C.c_int, C.POINTER(C.c_void_p)]
+        L.orc_its_replace.restype = C.c_int32
+        L.orc_its_replace.argtypes = [C.c_uint64, C.c_uint32, C.c_int32, C.POINTER(C.c_uint32)]
         L.orc_sample_ladies.restype = C.c_int
         L.orc_sample_ladies.argtypes = common + [C.c_int, C.POINTER(C.c_void_p)]
         L.orc_result_hop.restype = C.POINTER(_Hop)
@@ -128,6 +133,13 @@ def its_distinct(key: int, deg: int, s: int) -> List[int]:
     buf = (C.c_uint32 * max(s, 1))()
     lib().orc_its_distinct(key, deg, s, buf)
     return [int(buf[i]) for i in range(s)]
+
+
+def its_replace(key: int, deg: int, s: int) -> List[int]:
+    """Distinct positions picked by s independent draws in [0, deg), ascending."""
+    buf = (C.c_uint32 * max(s, 1))()
+    c = lib().orc_its_replace(key, deg, s, buf)
+    return [int(buf[i]) for i in range(c)]
 
 
 def set_threads(nthreads: int = 0) -> int:
@@ -182,6 +194,7 @@ class Hop:
     p_off: Optional[np.ndarray] = None
     p_col: Optional[np.ndarray] = None
     p_cnt: Optional[np.ndarray] = None
+    row_self: Optional[np.ndarray] = None   # union_dst only: local column of each row's own vertex
 
 
 def _copy(ptr, count, dtype):
@@ -203,6 +216,8 @@ def _collect(handle, k: int, L: int, with_p: bool) -> List[Hop]:
             mb_coloff=_copy(hp.mb_coloff, k + 1, np.int64),
             col_vertex=_copy(hp.col_vertex, hp.ncols, np.int32),
         )
+        if hp.row_self:
+            hop.row_self = _copy(hp.row_self, hp.rows, np.int32)
         if with_p:
             hop.p_off = _copy(hp.p_off, k + 1, np.int64)
             hop.p_col = _copy(hp.p_col, hp.pnnz, np.int32)
@@ -221,14 +236,22 @@ def _prep(rowptr, col, batches, params):
     return rowptr, col, batches, params
 
 
+UNION_DST, REPLACE = 1, 2
+
+
 def sample_nodewise(rowptr, col, batches, fanouts: Sequence[int], seed: int, mb_base: int = 0,
-                    collect: bool = True) -> Optional[List[Hop]]:
-    """Bulk GraphSAGE sampling (Sec. 4.1, Eq. 1). With collect=False only runs it (for timing)."""
+                    collect: bool = True, union_dst: bool = False, replace: bool = False) -> Optional[List[Hop]]:
+    """Bulk GraphSAGE sampling (Sec. 4.1, Eq. 1). With collect=False only runs it (for timing).
+
+    union_dst: the frontier's own vertices stay columns (next frontier = frontier + sampled), Hop.row_self filled.
+    replace: the s draws of a row are independent; the row keeps the distinct picks."""
     rowptr, col, batches, fan = _prep(rowptr, col, batches, fanouts)
     k, b = batches.shape
     out = C.c_void_p()
-    rc = lib().orc_sample_nodewise(rowptr.ctypes.data, col.ctypes.data, rowptr.size - 1, batches.ctypes.data, k, b,
-                                   fan.ctypes.data, fan.size, seed & 0xFFFFFFFFFFFFFFFF, mb_base, C.byref(out))
+    variant = (UNION_DST if union_dst else 0) | (REPLACE if replace else 0)
+    rc = lib().orc_sample_nodewise_variant(rowptr.ctypes.data, col.ctypes.data, rowptr.size - 1, batches.ctypes.data,
+                                           k, b, fan.ctypes.data, fan.size, seed & 0xFFFFFFFFFFFFFFFF, mb_base,
+                                           variant, C.byref(out))
     if rc:
         raise ValueError("oracle rejected the input (code %d)" % rc)
     try:

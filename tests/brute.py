@@ -43,9 +43,12 @@ def distinct_positions_literal(key, deg, s):
     return sorted(out)
 
 
-def nodewise(A, batches, fanouts, seed, mb_base=0):
+def nodewise(A, batches, fanouts, seed, mb_base=0, union_dst=False, replace=False):
     """Alg. 1 for GraphSAGE with dense matrices. Returns per minibatch, per hop:
-    (frontier ids, dense sampled adjacency A^l (rows x kept columns), kept column ids)."""
+    (frontier ids, dense sampled adjacency A^l (rows x kept columns), kept column ids).
+
+    replace: every draw is ITS on the untouched unit weights of the row (independent draws), the picks are the
+    nonzeros of Q'.  union_dst: the columns of the frontier's own vertices are kept even when empty."""
     n = A.shape[0]
     out = []
     for i, batch in enumerate(batches):
@@ -59,16 +62,24 @@ def nodewise(A, batches, fanouts, seed, mb_base=0):
             Qnext = np.zeros_like(P)
             for r, v in enumerate(F):
                 w = P[r].copy()
+                key = O.rowkey(seed, h, mb_base + i, v)
+                if replace:
+                    if w.sum() > 0:
+                        for j in range(s):
+                            Qnext[r, its_literal(w, O.bounded32(O.draw32(key, j), int(w.sum())))] = 1
+                    continue
                 if w.sum() <= s:
                     Qnext[r] = (w > 0)
                     continue
-                key = O.rowkey(seed, h, mb_base + i, v)
                 for j in range(s):
                     rr = O.bounded32(O.draw32(key, j), int(w.sum()))
                     t = its_literal(w, rr)
                     Qnext[r, t] = 1
                     w[t] = 0
-            kept = np.nonzero(Qnext.sum(axis=0) > 0)[0]   # remove empty columns
+            nonempty = Qnext.sum(axis=0) > 0              # remove empty columns
+            if union_dst:
+                nonempty = nonempty | (Q.sum(axis=0) > 0)
+            kept = np.nonzero(nonempty)[0]
             hops.append((list(F), Qnext[:, kept], kept))
             F = [int(v) for v in kept]
         out.append(hops)
