@@ -55,6 +55,7 @@ def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0
         "nw_rows": 20 * R,
         "nw_sample": 8 * R + 8 * E,
         "nw_relabel": 8 * E,
+        "nw_strip_self": 4 * R,   # BMS_UNION_DST: each row's own column; the rest of that pass is scratch
         "vset_rank": 4 * U,
         # EXTRACT by segment sorts: the staged ids are read once (4 E, charged to dd_split), the local
         # columns written once (4 E, dd_place), the next frontier written once (4 U, dd_front); the
@@ -90,6 +91,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-feature-fetch", action="store_true",
                     help="skip the feature fetch of the last frontier that is timed after the sampling steps")
+    ap.add_argument("--variant", default="none", choices=["none", "union_dst"],
+                    help="node-wise variant: union_dst keeps the frontier's own vertices as columns (BMS_UNION_DST)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB mebibytes 5 times "
                          "(calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters against a known size)")
@@ -142,6 +145,13 @@ def main() -> int:
     csr = bms.Csr(g.rowptr, g.col)
     nodewise = w["sampler"] == "nodewise"
     fn = bms.sample_nodewise if nodewise else bms.sample_ladies
+    if args.variant != "none":
+        if not nodewise:
+            print("bench.py: --variant applies to node-wise workloads", file=sys.stderr)
+            return 2
+        import functools
+        fn = functools.partial(fn, **{args.variant: True})
+    traffic_key = args.workload if args.variant == "none" else args.workload + "+" + args.variant
     seed = synth.SAMPLING_SEED
     stream = torch.cuda.current_stream()
 
@@ -202,9 +212,9 @@ def main() -> int:
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 5),
         # measured HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated), average over the launches
-        "traffic": (MEASURED_TRAFFIC[(args.workload, dominant)]["bytes_per_step"]
-                    // MEASURED_TRAFFIC[(args.workload, dominant)]["launches"])
-        if (args.workload, dominant) in MEASURED_TRAFFIC else None,
+        "traffic": (MEASURED_TRAFFIC[(traffic_key, dominant)]["bytes_per_step"]
+                    // MEASURED_TRAFFIC[(traffic_key, dominant)]["launches"])
+        if (traffic_key, dominant) in MEASURED_TRAFFIC else None,
         "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"]),
         "avg_launch_ms": round(dom["ms"] / dom["launches"], 4), "launches_per_step": dom["launches"],
         "algorithmic_bytes_per_step": int(dom["bytes"]),
@@ -219,10 +229,10 @@ def main() -> int:
         "kernels_ms_per_step": round(kernels_ms, 4),
         "effective_GBps": round(call_alg / (kernels_ms * 1e-3) / 1e9, 1),
         "effective_frac": round(call_alg / (kernels_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-        "achieved_GBps": round(MEASURED_CALL_TRAFFIC[args.workload] / (kernels_ms * 1e-3) / 1e9, 1)
-        if args.workload in MEASURED_CALL_TRAFFIC else None,
-        "achieved_frac": round(MEASURED_CALL_TRAFFIC[args.workload] / (kernels_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-        if args.workload in MEASURED_CALL_TRAFFIC else None,
+        "achieved_GBps": round(MEASURED_CALL_TRAFFIC[traffic_key] / (kernels_ms * 1e-3) / 1e9, 1)
+        if traffic_key in MEASURED_CALL_TRAFFIC else None,
+        "achieved_frac": round(MEASURED_CALL_TRAFFIC[traffic_key] / (kernels_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        if traffic_key in MEASURED_CALL_TRAFFIC else None,
     }
 
     # The step after sampling (not part of `value`): fetch the feature rows of the last frontier of all k
@@ -281,6 +291,8 @@ def main() -> int:
         rp, cl, bt = g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy()
         cores = O.set_threads(0)
         ofn = O.sample_nodewise if nodewise else O.sample_ladies
+        if args.variant != "none":
+            ofn = functools.partial(ofn, **{args.variant: True})
         t1 = time.perf_counter()
         ofn(rp, cl, bt, w["params"], seed, collect=False)
         cpu_s = time.perf_counter() - t1
@@ -294,7 +306,7 @@ def main() -> int:
         "minibatches_per_sec": round(k / (ms_per_step * 1e-3), 1),
         "config": {"workload": args.workload, "sampler": w["sampler"], "params": list(w["params"]),
                    "batch": w["batch"], "k": k, "n": g.n, "nnz": g.nnz, "max_degree": g.max_degree,
-                   "rows_nnz_cols_per_hop": [list(s) for s in sizes]},
+                   "variant": args.variant, "rows_nnz_cols_per_hop": [list(s) for s in sizes]},
         "roofline": roofline, "cpu_baseline": cpu, "feature_fetch": fetch,
     }
     if not nodewise:

@@ -58,6 +58,9 @@ extern "C" {
 #define BMS_PROFILE_MAIN 64u   /* as BMS_PROFILE, but only the sampler's main kernel stage (nw_sample, ldw_accumulate)   */
 #define BMS_LADIES_DENSE 32u   /* LADIES with dense per-minibatch counters in HBM instead of LDS windows     */
                                /* all give identical results; the flags only pick the kernel path          */
+#define BMS_UNION_DST 128u     /* node-wise variant: the frontier's own vertices stay columns of the sampled     */
+                               /* adjacency, so the next frontier = frontier + sampled vertices (what a layer    */
+                               /* that also uses a vertex's own features needs); fills bms_hop_view.row_self     */
 
 typedef struct bms_csr bms_csr;       /* adjacency matrix on the device + reusable scratch            */
 typedef struct bms_result bms_result; /* owns every device buffer its hop views point to              */
@@ -96,6 +99,8 @@ typedef struct bms_hop_view {
     const int64_t *p_off;      /* k+1   */
     const int32_t *p_col;      /* pnnz  */
     const uint32_t *p_cnt;     /* pnnz  */
+    const int32_t *row_self;   /* rows: only with BMS_UNION_DST (else NULL): local column of the row's own vertex,
+                                  col_vertex[mb_coloff[i] + row_self[r]] == row_vertex[r]                         */
 } bms_hop_view;
 
 /*
@@ -118,6 +123,9 @@ int bms_csr_info(const bms_csr *csr, int64_t *n, int64_t *nnz, int64_t *max_degr
  *             neighbour; otherwise exactly s distinct neighbours are chosen uniformly (ITS without
  *             replacement, Sec. 4.1.2).
  * The next hop's rows are the distinct sampled vertices of the minibatch, ascending.
+ * With BMS_UNION_DST the columns of a hop are the distinct vertices among the sampled ones AND the hop's own rows
+ * (ascending), so every frontier contains the one before it; which neighbours a vertex gets does not change (its
+ * random stream depends on seed, hop, minibatch and vertex only).  That flag is node-wise only (BMS_EINVAL for LADIES).
  */
 int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *fanouts,
                         int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out);

@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libbms.so")
 OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
 LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT, LADIES_DENSE, PROFILE_MAIN = 1, 2, 4, 8, 16, 32, 64
+UNION_DST = 128
 
 
 class BmsError(RuntimeError):
@@ -38,7 +39,7 @@ class _HopView(C.Structure):
     _fields_ = [("rows", C.c_int64), ("nnz", C.c_int64), ("ncols", C.c_int64), ("pnnz", C.c_int64),
                 ("mb_rowoff", C.c_void_p), ("row_vertex", C.c_void_p), ("rowptr", C.c_void_p), ("col", C.c_void_p),
                 ("mb_coloff", C.c_void_p), ("col_vertex", C.c_void_p), ("p_off", C.c_void_p), ("p_col", C.c_void_p),
-                ("p_cnt", C.c_void_p)]
+                ("p_cnt", C.c_void_p), ("row_self", C.c_void_p)]
 
 
 _lib = None
@@ -119,6 +120,7 @@ class Hop:
     p_off: Optional[torch.Tensor]
     p_col: Optional[torch.Tensor]
     p_cnt: Optional[torch.Tensor]
+    row_self: Optional[torch.Tensor] = None   # union_dst only: local column of each row's own vertex
 
     def to_host(self) -> "HostHop":
         def cp(t, dt=None):
@@ -128,7 +130,7 @@ class Hop:
             return a.view(dt) if dt is not None else a
         return HostHop(self.rows, self.nnz, self.ncols, cp(self.mb_rowoff), cp(self.row_vertex), cp(self.rowptr),
                        cp(self.col), cp(self.mb_coloff), cp(self.col_vertex), cp(self.p_off), cp(self.p_col),
-                       cp(self.p_cnt, np.uint32))
+                       cp(self.p_cnt, np.uint32), cp(self.row_self))
 
 
 @dataclass
@@ -145,6 +147,7 @@ class HostHop:
     p_off: Optional[np.ndarray] = None
     p_col: Optional[np.ndarray] = None
     p_cnt: Optional[np.ndarray] = None
+    row_self: Optional[np.ndarray] = None
 
 
 class Csr:
@@ -205,6 +208,7 @@ class Result:
             p_off=_view(v.p_off, k + 1, torch.int64, self) if has_p else None,
             p_col=_view(v.p_col, v.pnnz, torch.int32, self) if has_p else None,
             p_cnt=_view(v.p_cnt, v.pnnz, torch.int32, self) if has_p else None,
+            row_self=_view(v.row_self, v.rows, torch.int32, self) if v.row_self else None,
         )
 
     def hops(self) -> List[Hop]:
@@ -270,11 +274,12 @@ def _sample(fn, csr: Csr, batches, params: Sequence[int], seed: int, mb_base, st
 
 def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_base: int = 0, stream=None,
                     recycle: Optional[Result] = None, profile: bool = False, scratch_limit: int = 0,
-                    extract: Optional[str] = None) -> Result:
+                    extract: Optional[str] = None, union_dst: bool = False) -> Result:
     """bms_sample_nodewise: bulk GraphSAGE sampling of the k x b seed batches.
-    extract: None (library's choice), "sort", "buckets" or "bitmap" -- which EXTRACT kernels run; same result."""
+    extract: None (library's choice), "sort", "buckets" or "bitmap" -- which EXTRACT kernels run; same result.
+    union_dst: BMS_UNION_DST, every frontier contains the one before it and Hop.row_self is filled."""
     flags = _profile_flag(profile) | {None: 0, "buckets": EXTRACT_BUCKETS, "bitmap": EXTRACT_BITMAP,
-                                           "sort": EXTRACT_SORT}[extract]
+                                           "sort": EXTRACT_SORT}[extract] | (UNION_DST if union_dst else 0)
     return _sample(lib().bms_sample_nodewise, csr, batches, fanouts, seed, mb_base, stream, recycle, flags,
                    scratch_limit)
 

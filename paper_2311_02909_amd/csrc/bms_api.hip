@@ -107,6 +107,7 @@ struct bms_csr {
     DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars, scan_tmp;
     DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
     DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count, dd_back, dd_tileoff, dd_cursor, dd_seg; // bucket EXTRACT
+    DevBuf un_rowptr, un_col; // BMS_UNION_DST: the hop's CSR while its rows still carry their own vertex
     DevBuf lw_bounds, lw_win, lw_tmpcol, lw_tmpcnt, lw_sel, lw_xtmp, lw_count, lw_tiles, lw_rowcnt; // LADIES by LDS windows
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
@@ -114,7 +115,7 @@ struct bms_csr {
 
 struct HopBufs {
     DevBuf mb_rowoff, row_vertex; // own storage only at hop 0; later hops alias the previous hop's columns
-    DevBuf rowptr, col, mb_coloff, col_vertex, p_off, p_col, p_cnt;
+    DevBuf rowptr, col, mb_coloff, col_vertex, p_off, p_col, p_cnt, row_self;
     bms_hop_view view;
 };
 
@@ -146,6 +147,7 @@ void result_release(bms_result *r)
         h.p_off.release();
         h.p_col.release();
         h.p_cnt.release();
+        h.row_self.release();
     }
     for (auto e : r->event_pool)
         (void)hipEventDestroy(e);
@@ -268,7 +270,7 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
     if (opts) {
-        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN))
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN | BMS_UNION_DST))
             return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
         if (opts->recycle && opts->recycle->tag != kTagResult)
             return fail(BMS_EINVAL, "opts->recycle is not a result handle");
@@ -441,14 +443,15 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     // Steady state: a recycled result that remembers the sizes of the same call shape lets every hop
     // be enqueued without a host round trip.  Buffers are then sized by the upper bound
     // rows * min(s, max degree) (always enough), tuning parameters by the remembered sizes.
-    std::vector<int32_t> shape{c.k, c.b};
+    const bool union_dst = (c.flags & BMS_UNION_DST) != 0;
+    std::vector<int32_t> shape{c.k, c.b, union_dst ? 1 : 0};
     shape.insert(shape.end(), fanouts, fanouts + c.L);
     bool no_wait = buckets && !c.fresh_result && c.res->hint_csr == csr && c.res->hint_shape == shape &&
                    (int32_t)c.res->hint_nnz.size() == c.L;
     if (no_wait) {
         double bound = (double)rows_bound, total = 0.0;
         for (int32_t h = 0; h < c.L; ++h) {
-            bound *= (double)std::min<int64_t>(fanouts[h], std::max<int64_t>(csr->max_degree, 1));
+            bound *= (double)std::min<int64_t>(fanouts[h], std::max<int64_t>(csr->max_degree, 1)) + (union_dst ? 1.0 : 0.0);
             total += bound * 40.0; // bytes of result + scratch per sampled edge, generously
             bound = std::min(bound, (double)c.k * (double)csr->n);
         }
@@ -464,6 +467,10 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         BMS_TRY(csr->tile_off.ensure((size_t)(tiles_bound + 2) * sizeof(int64_t)));
         BMS_TRY(hb.rowptr.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
         BMS_TRY(hb.mb_coloff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
+        if (union_dst) {
+            BMS_TRY(csr->un_rowptr.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
+            BMS_TRY(hb.row_self.ensure((size_t)std::max<int64_t>(rows_bound, 1) * sizeof(int32_t)));
+        }
 
         NwHop a{};
         a.A_rowptr = csr->rowptr;
@@ -479,8 +486,11 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         a.row_beg = csr->row_beg.as<int64_t>();
         a.row_deg = csr->row_deg.as<int32_t>();
         a.tile_off = csr->tile_off.as<int64_t>();
-        a.out_rowptr = hb.rowptr.as<int64_t>();
+        // with BMS_UNION_DST the hop is built with one more entry per row (the row's own vertex) in scratch
+        // and moved to the result's arrays without it at the end of the hop
+        a.out_rowptr = union_dst ? csr->un_rowptr.as<int64_t>() : hb.rowptr.as<int64_t>();
         a.rows_bound = rows_bound;
+        a.self_entry = union_dst ? 1 : 0;
 
         BMS_TRY(prof.begin("nw_rows", h));
         launch_plan_tiles(c.launch, mb_rowoff, c.k, kRowTile, a.mb_tileoff, a.mb_tileoff + c.k + 1);
@@ -494,8 +504,8 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         // nnz sizes the column buffers: read back (the only host round trip of the hop), or in the
         // steady state bounded from above; nnz_tune only picks tuning parameters
         int64_t nnz, nnz_tune;
-        if (no_wait) {
-            nnz = rows_bound * std::min<int64_t>(fanouts[h], std::max<int64_t>(csr->max_degree, 1));
+        if (no_wait) { // with BMS_UNION_DST nnz counts the rows' own entries too, until the hop's last step
+            nnz = rows_bound * (std::min<int64_t>(fanouts[h], std::max<int64_t>(csr->max_degree, 1)) + a.self_entry);
             nnz_tune = std::max<int64_t>(c.res->hint_nnz[h], 1);
         } else {
             BMS_TRY(read_scalars(c));
@@ -507,7 +517,9 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         const int64_t ncols_bound = std::min<int64_t>(nnz, (int64_t)c.k * csr->n);
         BMS_TRY(hb.col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
         BMS_TRY(hb.col_vertex.ensure((size_t)std::max<int64_t>(ncols_bound, 1) * sizeof(int32_t)));
-        a.out_col = hb.col.as<int32_t>();
+        if (union_dst)
+            BMS_TRY(csr->un_col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
+        a.out_col = union_dst ? csr->un_col.as<int32_t>() : hb.col.as<int32_t>();
 
         BMS_TRY(prof.begin("nw_sample", h));
         launch_nw_sample(c.launch, a, c.vs, !buckets);
@@ -586,8 +598,16 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             BMS_TRY(prof.end());
         }
 
+        if (union_dst) {
+            BMS_TRY(prof.begin("nw_strip_self", h));
+            launch_nw_strip_self(c.launch, a.out_rowptr, a.out_col, mb_rowoff + c.k, rows_bound, hb.rowptr.as<int64_t>(),
+                                 hb.col.as<int32_t>(), hb.row_self.as<int32_t>(), slot(c, h, 0));
+            BMS_TRY(prof.end());
+        }
+
         hb.view = bms_hop_view{};
         hb.view.nnz = nnz;
+        hb.view.row_self = union_dst ? hb.row_self.as<int32_t>() : nullptr;
         hb.view.mb_rowoff = mb_rowoff;
         hb.view.row_vertex = row_vertex;
         hb.view.rowptr = hb.rowptr.as<int64_t>();
@@ -607,7 +627,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         v.nnz = host_slot(c, h, 0);
         v.ncols = host_slot(c, h, 1);
         v.rows = h == 0 ? (int64_t)c.k * c.b : host_slot(c, h - 1, 1);
-        seen_nnz[h] = v.nnz;
+        seen_nnz[h] = v.nnz + (union_dst ? v.rows : 0); // the entries EXTRACT worked on
     }
     c.res->hint_csr = csr;
     c.res->hint_shape = shape;
@@ -1080,6 +1100,8 @@ int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b
     BMS_TRY(check_common(csr, batches, k, b, s_per_layer, L, opts, out));
     if (L > kMaxHops)
         return fail(BMS_EINVAL, "at most %d hops are supported", kMaxHops);
+    if (opts && (opts->flags & BMS_UNION_DST))
+        return fail(BMS_EINVAL, "BMS_UNION_DST applies to node-wise sampling only");
     CallCtx c{};
     int rc = begin_call(c, csr, k, b, L, seed, opts);
     if (rc == BMS_OK)

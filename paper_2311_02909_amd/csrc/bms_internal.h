@@ -72,11 +72,17 @@ struct NwHop {
     int64_t *nnz_out;          // device scalar
     int64_t rows_bound;        // host-side upper bound of the row count
     int32_t max_degree;
+    int32_t self_entry;        // 1: every row carries its own vertex as one more entry after the sampled ones
 };
 void launch_nw_rows(const Launch &, const NwHop &);
 // set_bits: also mark every sampled vertex in the minibatch's vertex set (bitmap EXTRACT path)
 void launch_nw_sample(const Launch &, const NwHop &, const VSet &, bool set_bits);
 void launch_nw_relabel(const Launch &, const NwHop &, const VSet &);
+// rows that carry a trailing entry for their own vertex -> the CSR without it + that entry per row;
+// *rows = number of rows (device), *nnz_slot: entries on input, entries - rows on output
+void launch_nw_strip_self(const Launch &, const int64_t *rowptr_in, const int32_t *col_in, const int64_t *rows,
+                          int64_t rows_bound, int64_t *rowptr_out, int32_t *col_out, int32_t *row_self,
+                          int64_t *nnz_slot);
 
 // EXTRACT by id-range buckets, one workgroup per minibatch (large vertex ranges)
 constexpr int kBucketBits = 15;     // ids per bucket = 2^15 (a 4 KB bitmap per wave in LDS)

@@ -13,6 +13,8 @@
 // here and serves vertex ranges too wide for those: nw_sample also sets the ids' bits in a
 // per-minibatch vertex set in HBM, the set is ranked (kernels_common.hip), and
 //   nw_relabel global id -> local column index = rank in the minibatch's vertex set
+// Variant (the frontier's own vertices stay columns): every row carries its own vertex as one more
+// entry through EXTRACT, and nw_strip_self takes it out of the row again afterwards.
 #include "bms_device.h"
 #include "bms_internal.h"
 
@@ -43,7 +45,7 @@ __global__ __launch_bounds__(kRowTile) void nw_rows_kernel(NwHop a)
             }
             a.row_beg[r] = beg;
             a.row_deg[r] = (int32_t)deg;
-            cnt = deg < a.s ? deg : a.s;
+            cnt = (deg < a.s ? deg : a.s) + a.self_entry;
         }
         cnt = wave_sum(cnt);
         __syncthreads();
@@ -78,7 +80,7 @@ void launch_nw_rows(const Launch &L, const NwHop &a)
 template <int S, bool SET>
 __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
 {
-    __shared__ int32_t stage[kRowTile * S];
+    __shared__ int32_t stage[kRowTile * (S + 1)]; // + 1: the row's own vertex when rows carry it
     __shared__ int32_t wsum[kRowTile / kWave];
     const int tid = threadIdx.x;
     const int64_t most = a.mb_tileoff[a.k + 1];
@@ -99,10 +101,12 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
             cnt = deg < s ? deg : s;
         }
         int32_t tot;
-        const int32_t loc = block_exclusive_scan<int32_t, kRowTile>(cnt, wsum, tot);
+        const int32_t loc = block_exclusive_scan<int32_t, kRowTile>(valid ? cnt + a.self_entry : 0, wsum, tot);
         const int64_t base = a.tile_off[t];
         if (valid)
             a.out_rowptr[r] = base + loc;
+        if (valid && a.self_entry)
+            stage[loc + cnt] = a.row_vertex[r];
         if (cnt > 0) {
             uint32_t c[S];
             if (deg <= s) {
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
         int64_t cnt = 0;
         if (r < rend) {
             const int64_t deg = a.row_deg[r];
-            cnt = deg < s ? deg : s;
+            cnt = (deg < s ? deg : s) + a.self_entry;
         }
         int64_t tot;
         const int64_t loc = block_exclusive_scan<int64_t, kRowTile>(cnt, wsum, tot);
@@ -189,6 +193,12 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
             const int32_t deg = a.row_deg[rr];
             int32_t *__restrict__ dst = a.out_col + row_loc[q];
             const int32_t *__restrict__ src = a.A_col + beg;
+            if (a.self_entry && lane == 0) { // the row's own vertex, after its min(deg, s) sampled ones
+                const int32_t g = a.row_vertex[rr];
+                dst[deg < s ? deg : s] = g;
+                if (SET)
+                    atomicOr(&words[g >> 5], 1u << (g & 31));
+            }
             if (deg <= s) {
                 for (int32_t e = lane; e < deg; e += kWave) {
                     const int32_t g = src[e];
@@ -278,6 +288,87 @@ __global__ __launch_bounds__(256) void nw_relabel_kernel(NwHop a, VSet vs)
         for (int64_t e = a.tile_off[t] + threadIdx.x; e < e1; e += 256)
             a.out_col[e] = vset_rank_of(words, prefix, a.out_col[e]);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rows that carried their own vertex through EXTRACT as a trailing entry (so that it became a column
+// and got a local index like any sampled vertex): the entry leaves the row again.  Row r loses one
+// entry and every row before it one each, so its entries move r places down; the trailing entry is
+// the row's own column.  One tile of kRowTile stacked rows per iteration, one entry per lane per
+// step, the entry's row found in the tile's row offsets held in LDS.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kRowTile) void nw_strip_self_kernel(const int64_t *__restrict__ rowptr_in,
+                                                                 const int32_t *__restrict__ col_in,
+                                                                 const int64_t *__restrict__ rows_ptr,
+                                                                 int64_t *__restrict__ rowptr_out,
+                                                                 int32_t *__restrict__ col_out,
+                                                                 int32_t *__restrict__ row_self,
+                                                                 int64_t *__restrict__ nnz_slot)
+{
+    constexpr int kMapCap = kRowTile * 33; // entries of a tile whose rows hold at most 32 sampled vertices
+    __shared__ int64_t off[kRowTile + 1];
+    __shared__ uint8_t row_of[kMapCap];
+    const int tid = threadIdx.x;
+    const int64_t rows = *rows_ptr;
+    const int64_t ntiles = (rows + kRowTile - 1) / kRowTile;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t r0 = t * kRowTile;
+        const int nr = (int)(rows - r0 < kRowTile ? rows - r0 : kRowTile);
+        const int64_t e0 = rowptr_in[r0];
+        if (tid < nr) {
+            const int64_t p = rowptr_in[r0 + tid];
+            off[tid] = p - e0;
+            rowptr_out[r0 + tid] = p - (r0 + tid);
+        }
+        if (tid == 0)
+            off[nr] = rowptr_in[r0 + nr] - e0;
+        __syncthreads();
+        const int64_t span = off[nr];
+        const bool mapped = span <= kMapCap; // the usual case: every row writes its index over its entries
+        if (mapped && tid < nr) {
+            const int32_t b = (int32_t)off[tid], e = (int32_t)off[tid + 1];
+            for (int32_t q = b; q < e; ++q)
+                row_of[q] = (uint8_t)tid;
+        }
+        if (mapped)
+            __syncthreads();
+        for (int64_t e = tid; e < span; e += kRowTile) {
+            int lo;
+            if (mapped) {
+                lo = row_of[e];
+            } else { // last row with off[row] <= e (rows are never empty: each has its own entry)
+                lo = 0;
+                int hi = nr;
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (off[mid] <= e)
+                        lo = mid;
+                    else
+                        hi = mid;
+                }
+            }
+            const int32_t g = col_in[e0 + e];
+            if (e == off[lo + 1] - 1)
+                row_self[r0 + lo] = g;
+            else
+                col_out[e0 + e - (r0 + lo)] = g;
+        }
+        __syncthreads();
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        const int64_t total = rowptr_in[rows];
+        rowptr_out[rows] = total - rows;
+        *nnz_slot = total - rows;
+    }
+}
+
+void launch_nw_strip_self(const Launch &L, const int64_t *rowptr_in, const int32_t *col_in, const int64_t *rows,
+                          int64_t rows_bound, int64_t *rowptr_out, int32_t *col_out, int32_t *row_self,
+                          int64_t *nnz_slot)
+{
+    const int64_t tiles = rows_bound / kRowTile + 1;
+    hipLaunchKernelGGL(nw_strip_self_kernel, dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, rowptr_in,
+                       col_in, rows, rowptr_out, col_out, row_self, nnz_slot);
 }
 
 void launch_nw_relabel(const Launch &L, const NwHop &a, const VSet &vs)

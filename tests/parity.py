@@ -11,7 +11,11 @@ def assert_hops_equal(gpu_hops, ref_hops, with_p=False, what=""):
         g = g.to_host() if hasattr(g, "to_host") else g
         assert (g.rows, g.nnz, g.ncols) == (r.rows, r.nnz, r.ncols), \
             "%s hop %d sizes %s vs oracle %s" % (what, h, (g.rows, g.nnz, g.ncols), (r.rows, r.nnz, r.ncols))
-        for name in FIELDS + (P_FIELDS if with_p else ()):
+        # the own-column array exists exactly when the oracle's variant has it
+        assert (getattr(g, "row_self", None) is None) == (getattr(r, "row_self", None) is None), \
+            "%s hop %d: row_self present on one side only" % (what, h)
+        extra = ("row_self",) if getattr(r, "row_self", None) is not None else ()
+        for name in FIELDS + (P_FIELDS if with_p else ()) + extra:
             a, b = getattr(g, name), getattr(r, name)
             assert a.shape == b.shape, "%s hop %d %s: shape %s vs %s" % (what, h, name, a.shape, b.shape)
             if not np.array_equal(a, b):

@@ -1,0 +1,101 @@
+"""Parity of the node-wise variants with the CPU oracle (bit-exact), through the C ABI.
+
+union_dst: the frontier's own vertices stay columns (next frontier = frontier + sampled vertices) and every row
+reports its own column."""
+import numpy as np
+import pytest
+import torch
+
+from conftest import random_batches, random_csr
+from parity import assert_hops_equal
+
+pytestmark = pytest.mark.gpu
+
+EXTRACTS = (None, "sort", "buckets", "bitmap")
+
+
+def _check(rowptr, col, batches, fanouts, seed, mb_base=0, extracts=EXTRACTS, **variant):
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    ref = O.sample_nodewise(rowptr, col, batches, fanouts, seed, mb_base, **variant)
+    res = None
+    for extract in extracts:
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fanouts, seed, mb_base=mb_base,
+                                  extract=extract, **variant)
+        assert_hops_equal(res.hops(), ref, what="%s extract=%s fanouts=%s" % (variant, extract, fanouts))
+    return csr, res, ref
+
+
+@pytest.mark.parametrize("fanouts", [(3,), (4, 4), (8, 3, 2), (15, 10, 5), (16, 2), (32, 2), (1, 1, 1), (40, 3), (2048, 2)])
+def test_union_dst_all_lane_capacities(fanouts):
+    rng = np.random.default_rng(100 + sum(fanouts))
+    rowptr, col = random_csr(20000, 24.0, rng)
+    batches = random_batches(20000, 5, 300, rng)
+    _, res, ref = _check(rowptr, col, batches, fanouts, 7, mb_base=3, union_dst=True)
+    for h, hop in enumerate(res.hops()):
+        # every frontier contains the one before it, and a row's own column leads back to its vertex
+        own = hop.col_vertex[(hop.mb_coloff[:-1].repeat_interleave(hop.mb_rowoff[1:] - hop.mb_rowoff[:-1])
+                              + hop.row_self).long()]
+        assert torch.equal(own, hop.row_vertex)
+
+
+def test_union_dst_full_fanout_directed_with_loops_and_isolated_rows():
+    rng = np.random.default_rng(31)
+    rowptr, col = random_csr(3000, 3.0, rng, symmetric=False, allow_loops=True)   # many vertices without out-edges
+    assert (np.diff(rowptr) == 0).sum() > 100
+    maxdeg = int(np.diff(rowptr).max())
+    batches = random_batches(3000, 4, 33, rng)
+    _check(rowptr, col, batches, (maxdeg, 2**31 - 1, maxdeg + 1), 1, union_dst=True)
+    _check(rowptr, col, batches, (2, 1), 1, union_dst=True)
+
+
+def test_union_dst_recycled_calls_and_change_of_variant():
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms
+    rng = np.random.default_rng(32)
+    rowptr, col = random_csr(50000, 12.0, rng)
+    batches = random_batches(50000, 8, 500, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    bt = torch.from_numpy(batches).cuda()
+    fan = (6, 5, 4)
+    ref_u = O.sample_nodewise(rowptr, col, batches, fan, 77, union_dst=True)
+    ref_p = O.sample_nodewise(rowptr, col, batches, fan, 77)
+    res = None
+    for union in (True, True, True, False, False, True):   # the same result handle through both variants
+        res = bms.sample_nodewise(csr, bt, fan, 77, recycle=res, union_dst=union)
+        assert_hops_equal(res.hops(), ref_u if union else ref_p, what="recycled, union=%s" % union)
+
+
+def test_union_dst_many_small_minibatches_and_single_vertex_batches():
+    rng = np.random.default_rng(33)
+    rowptr, col = random_csr(4000, 8.0, rng)
+    _check(rowptr, col, random_batches(4000, 700, 1, rng), (3, 3), 5, extracts=(None, "sort"), union_dst=True)
+    _check(rowptr, col, random_batches(4000, 2, 1500, rng), (5, 5), 5, union_dst=True)
+
+
+def test_union_dst_is_rejected_for_layerwise_sampling():
+    from paper_2311_02909_amd import bms
+    rng = np.random.default_rng(34)
+    rowptr, col = random_csr(500, 5.0, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    import ctypes as C
+    out = C.c_void_p()
+    opts = bms._Opts(stream=None, mb_base=0, flags=bms.UNION_DST, recycle=None, scratch_limit=0)
+    bt = torch.from_numpy(random_batches(500, 2, 8, rng)).cuda()
+    s = (C.c_int32 * 1)(16)
+    rc = bms.lib().bms_sample_ladies(csr.handle, bt.data_ptr(), 2, 8, s, 1, 1, C.byref(opts), C.byref(out))
+    assert rc == bms.EINVAL and not out.value
+
+
+def test_union_dst_on_the_mid_size_workload():
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms, synth
+    g, batches, w = synth.make_workload("mid_sage", device="cuda")
+    csr = bms.Csr(g.rowptr, g.col)
+    res = bms.sample_nodewise(csr, batches, w["params"], synth.SAMPLING_SEED, union_dst=True)
+    res = bms.sample_nodewise(csr, batches, w["params"], synth.SAMPLING_SEED, union_dst=True, recycle=res)
+    print("\n  sizes", res.sizes(), flush=True)
+    ref = O.sample_nodewise(g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy(), w["params"],
+                            synth.SAMPLING_SEED, union_dst=True)
+    assert_hops_equal(res.hops(), ref, what="mid_sage union_dst")
