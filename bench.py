@@ -91,8 +91,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-feature-fetch", action="store_true",
                     help="skip the feature fetch of the last frontier that is timed after the sampling steps")
-    ap.add_argument("--variant", default="none", choices=["none", "union_dst"],
-                    help="node-wise variant: union_dst keeps the frontier's own vertices as columns (BMS_UNION_DST)")
+    ap.add_argument("--variant", default="none", choices=["none", "union_dst", "replace"],
+                    help="node-wise variant: union_dst keeps the frontier's own vertices as columns (BMS_UNION_DST), "
+                         "replace makes a row's draws independent (BMS_NODEWISE_REPLACE)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB mebibytes 5 times "
                          "(calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters against a known size)")

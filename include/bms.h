@@ -61,6 +61,9 @@ extern "C" {
 #define BMS_UNION_DST 128u     /* node-wise variant: the frontier's own vertices stay columns of the sampled     */
                                /* adjacency, so the next frontier = frontier + sampled vertices (what a layer    */
                                /* that also uses a vertex's own features needs); fills bms_hop_view.row_self     */
+#define BMS_NODEWISE_REPLACE 256u /* node-wise variant: the s draws of a row are independent (ITS with           */
+                               /* replacement: the repeat-until-distinct step of Sec. 4.1.2 left out); a row      */
+                               /* keeps the distinct picks, between 1 and min(s, degree) of them                  */
 
 typedef struct bms_csr bms_csr;       /* adjacency matrix on the device + reusable scratch            */
 typedef struct bms_result bms_result; /* owns every device buffer its hop views point to              */
@@ -125,7 +128,10 @@ int bms_csr_info(const bms_csr *csr, int64_t *n, int64_t *nnz, int64_t *max_degr
  * The next hop's rows are the distinct sampled vertices of the minibatch, ascending.
  * With BMS_UNION_DST the columns of a hop are the distinct vertices among the sampled ones AND the hop's own rows
  * (ascending), so every frontier contains the one before it; which neighbours a vertex gets does not change (its
- * random stream depends on seed, hop, minibatch and vertex only).  That flag is node-wise only (BMS_EINVAL for LADIES).
+ * random stream depends on seed, hop, minibatch and vertex only).
+ * With BMS_NODEWISE_REPLACE draw j of a row is floor(u_j * degree / 2^32) whatever the other draws gave, for every
+ * row with degree >= 1 (also when degree <= s); the row's entries are the distinct picks.  Every fanout must then be
+ * <= 2048 (BMS_EINVAL).  Both flags are node-wise only (BMS_EINVAL for LADIES) and may be combined.
  */
 int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *fanouts,
                         int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out);

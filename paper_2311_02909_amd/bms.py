@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libbms.so")
 OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
 LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT, LADIES_DENSE, PROFILE_MAIN = 1, 2, 4, 8, 16, 32, 64
-UNION_DST = 128
+UNION_DST, NODEWISE_REPLACE = 128, 256
 
 
 class BmsError(RuntimeError):
@@ -274,12 +274,14 @@ def _sample(fn, csr: Csr, batches, params: Sequence[int], seed: int, mb_base, st
 
 def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_base: int = 0, stream=None,
                     recycle: Optional[Result] = None, profile: bool = False, scratch_limit: int = 0,
-                    extract: Optional[str] = None, union_dst: bool = False) -> Result:
+                    extract: Optional[str] = None, union_dst: bool = False, replace: bool = False) -> Result:
     """bms_sample_nodewise: bulk GraphSAGE sampling of the k x b seed batches.
     extract: None (library's choice), "sort", "buckets" or "bitmap" -- which EXTRACT kernels run; same result.
-    union_dst: BMS_UNION_DST, every frontier contains the one before it and Hop.row_self is filled."""
+    union_dst: BMS_UNION_DST, every frontier contains the one before it and Hop.row_self is filled.
+    replace: BMS_NODEWISE_REPLACE, independent draws per row, the distinct picks kept."""
     flags = _profile_flag(profile) | {None: 0, "buckets": EXTRACT_BUCKETS, "bitmap": EXTRACT_BITMAP,
-                                           "sort": EXTRACT_SORT}[extract] | (UNION_DST if union_dst else 0)
+                                           "sort": EXTRACT_SORT}[extract] | (UNION_DST if union_dst else 0) | (
+        NODEWISE_REPLACE if replace else 0)
     return _sample(lib().bms_sample_nodewise, csr, batches, fanouts, seed, mb_base, stream, recycle, flags,
                    scratch_limit)
 

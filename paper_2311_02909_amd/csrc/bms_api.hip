@@ -108,6 +108,7 @@ struct bms_csr {
     DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
     DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count, dd_back, dd_tileoff, dd_cursor, dd_seg; // bucket EXTRACT
     DevBuf un_rowptr, un_col; // BMS_UNION_DST: the hop's CSR while its rows still carry their own vertex
+    DevBuf row_cnt;           // BMS_NODEWISE_REPLACE with a fanout above 32: distinct picks per row
     DevBuf lw_bounds, lw_win, lw_tmpcol, lw_tmpcnt, lw_sel, lw_xtmp, lw_count, lw_tiles, lw_rowcnt; // LADIES by LDS windows
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
@@ -270,7 +271,7 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
     if (opts) {
-        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN | BMS_UNION_DST))
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN | BMS_UNION_DST | BMS_NODEWISE_REPLACE))
             return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
         if (opts->recycle && opts->recycle->tag != kTagResult)
             return fail(BMS_EINVAL, "opts->recycle is not a result handle");
@@ -444,7 +445,8 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     // be enqueued without a host round trip.  Buffers are then sized by the upper bound
     // rows * min(s, max degree) (always enough), tuning parameters by the remembered sizes.
     const bool union_dst = (c.flags & BMS_UNION_DST) != 0;
-    std::vector<int32_t> shape{c.k, c.b, union_dst ? 1 : 0};
+    const bool replace = (c.flags & BMS_NODEWISE_REPLACE) != 0;
+    std::vector<int32_t> shape{c.k, c.b, (union_dst ? 1 : 0) | (replace ? 2 : 0)};
     shape.insert(shape.end(), fanouts, fanouts + c.L);
     bool no_wait = buckets && !c.fresh_result && c.res->hint_csr == csr && c.res->hint_shape == shape &&
                    (int32_t)c.res->hint_nnz.size() == c.L;
@@ -491,6 +493,11 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         a.out_rowptr = union_dst ? csr->un_rowptr.as<int64_t>() : hb.rowptr.as<int64_t>();
         a.rows_bound = rows_bound;
         a.self_entry = union_dst ? 1 : 0;
+        a.replace = replace ? 1 : 0;
+        if (replace && a.s > 32) {
+            BMS_TRY(csr->row_cnt.ensure((size_t)std::max<int64_t>(rows_bound, 1) * sizeof(int32_t)));
+            a.row_cnt = csr->row_cnt.as<int32_t>();
+        }
 
         BMS_TRY(prof.begin("nw_rows", h));
         launch_plan_tiles(c.launch, mb_rowoff, c.k, kRowTile, a.mb_tileoff, a.mb_tileoff + c.k + 1);
@@ -1084,6 +1091,11 @@ int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t
                         "fanout %d at hop %d: a fanout above %d must be >= the largest degree (%lld) so that no row "
                         "needs sampling",
                         fanouts[h], h, kMaxSampledFanout, (long long)csr->max_degree);
+    if (opts && (opts->flags & BMS_NODEWISE_REPLACE))
+        for (int32_t h = 0; h < L; ++h)
+            if (fanouts[h] > kMaxSampledFanout)
+                return fail(BMS_EINVAL, "fanout %d at hop %d: with BMS_NODEWISE_REPLACE a fanout is at most %d",
+                            fanouts[h], h, kMaxSampledFanout);
     CallCtx c{};
     int rc = begin_call(c, csr, k, b, L, seed, opts);
     if (rc == BMS_OK)
@@ -1100,8 +1112,8 @@ int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b
     BMS_TRY(check_common(csr, batches, k, b, s_per_layer, L, opts, out));
     if (L > kMaxHops)
         return fail(BMS_EINVAL, "at most %d hops are supported", kMaxHops);
-    if (opts && (opts->flags & BMS_UNION_DST))
-        return fail(BMS_EINVAL, "BMS_UNION_DST applies to node-wise sampling only");
+    if (opts && (opts->flags & (BMS_UNION_DST | BMS_NODEWISE_REPLACE)))
+        return fail(BMS_EINVAL, "BMS_UNION_DST and BMS_NODEWISE_REPLACE apply to node-wise sampling only");
     CallCtx c{};
     int rc = begin_call(c, csr, k, b, L, seed, opts);
     if (rc == BMS_OK)

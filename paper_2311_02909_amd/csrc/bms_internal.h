@@ -73,6 +73,8 @@ struct NwHop {
     int64_t rows_bound;        // host-side upper bound of the row count
     int32_t max_degree;
     int32_t self_entry;        // 1: every row carries its own vertex as one more entry after the sampled ones
+    int32_t replace;           // 1: the s draws of a row are independent, the row keeps the distinct picks
+    int32_t *row_cnt;          // scratch, rows: distinct picks per row (only with replace and s > 32)
 };
 void launch_nw_rows(const Launch &, const NwHop &);
 // set_bits: also mark every sampled vertex in the minibatch's vertex set (bitmap EXTRACT path)

@@ -15,11 +15,88 @@
 //   nw_relabel global id -> local column index = rank in the minibatch's vertex set
 // Variant (the frontier's own vertices stay columns): every row carries its own vertex as one more
 // entry through EXTRACT, and nw_strip_self takes it out of the row again afterwards.
+// Variant (independent draws): the s draws of a row are each an integer in [0, degree), the row keeps
+// the distinct picks; its length is only known after the draws, so nw_rows makes them too.
 #include "bms_device.h"
 #include "bms_internal.h"
 
 namespace bms {
 
+// Independent draws (ITS with replacement on the unit weights of a row): s integers in [0, deg), kept sorted
+// in c[0..s) by one bubble pass per draw.  Returns the number of distinct values.
+template <int S>
+__device__ __forceinline__ int32_t replace_draws(uint64_t key, uint32_t deg, int32_t s, uint32_t (&c)[S])
+{
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+        if (j < s) {
+            c[j] = bounded32(draw32(key, (uint32_t)j), deg);
+#pragma unroll
+            for (int q = j; q > 0; --q) {
+                const uint32_t lo = min(c[q - 1], c[q]);
+                const uint32_t hi = max(c[q - 1], c[q]);
+                c[q - 1] = lo;
+                c[q] = hi;
+            }
+        }
+    }
+    int32_t m = 0;
+#pragma unroll
+    for (int j = 0; j < S; ++j)
+        if (j < s)
+            m += (j == 0 || c[j] != c[j - 1]) ? 1 : 0;
+    return m;
+}
+
+// The same for any s <= kMaxSampledFanout by one wave: the draws are written to `buf` (LDS, room for the next
+// power of two >= max(s, 64)), sorted there by a bitonic network, and the distinct values moved down to
+// buf[0..m) in ascending order.  Returns m (the same value in every lane).
+__device__ inline int32_t wave_replace_draws(volatile uint32_t *buf, uint64_t key, uint32_t deg, int32_t s, int lane)
+{
+    int32_t P = kWave;
+    while (P < s)
+        P <<= 1;
+    for (int32_t j = lane; j < P; j += kWave)
+        buf[j] = j < s ? bounded32(draw32(key, (uint32_t)j), deg) : 0xFFFFFFFFu; // padding sorts last (deg < 2^31)
+    __builtin_amdgcn_wave_barrier();
+    for (int32_t size = 2; size <= P; size <<= 1) {
+        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int32_t t = lane; t < P / 2; t += kWave) {
+                const int32_t lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1)); // bit `stride` clear
+                const int32_t hi = lo | stride;
+                const bool up = (lo & size) == 0;
+                const uint32_t x = buf[lo], y = buf[hi];
+                if ((x > y) == up) {
+                    buf[lo] = y;
+                    buf[hi] = x;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    int32_t m = 0;
+    uint32_t last = 0; // value before this chunk's first one
+    for (int32_t base = 0; base < P; base += kWave) {
+        const int32_t j = base + lane;
+        const uint32_t v = buf[j];
+        uint32_t prev = __shfl_up(v, 1);
+        if (lane == 0)
+            prev = last;
+        const bool head = j < s && (j == 0 || v != prev);
+        const uint64_t heads = __ballot(head);
+        __builtin_amdgcn_wave_barrier(); // the chunk is read before any of it is overwritten (targets are <= sources)
+        if (head)
+            buf[m + __popcll(heads & ((1ull << lane) - 1ull))] = v;
+        m += __popcll(heads);
+        last = __shfl(v, kWave - 1);
+        __builtin_amdgcn_wave_barrier();
+    }
+    return m;
+}
+
+// S = 0: rows keep min(degree, s) entries.  S > 0: independent draws, s <= S; the row's length is the number
+// of distinct picks.
+template <int S>
 __global__ __launch_bounds__(kRowTile) void nw_rows_kernel(NwHop a)
 {
     __shared__ int64_t wsum[kRowTile / kWave];
@@ -45,7 +122,13 @@ __global__ __launch_bounds__(kRowTile) void nw_rows_kernel(NwHop a)
             }
             a.row_beg[r] = beg;
             a.row_deg[r] = (int32_t)deg;
-            cnt = (deg < a.s ? deg : a.s) + a.self_entry;
+            if (S == 0) {
+                cnt = deg < a.s ? deg : a.s;
+            } else if (deg > 0) {
+                uint32_t c[S > 0 ? S : 1];
+                cnt = replace_draws(row_key(a.hopkey, a.mb_base + (uint32_t)i, (uint32_t)v), (uint32_t)deg, a.s, c);
+            }
+            cnt += a.self_entry;
         }
         cnt = wave_sum(cnt);
         __syncthreads();
@@ -62,10 +145,85 @@ __global__ __launch_bounds__(kRowTile) void nw_rows_kernel(NwHop a)
     }
 }
 
+// Independent draws with s > 32: extents by one row per lane as above, then one row per wave: draws sorted in
+// LDS, distinct ones counted; the count is kept per row (row_cnt) so that the sampling kernel can place the
+// rows before it repeats the draws.
+__global__ __launch_bounds__(kRowTile) void nw_rows_replace_wide_kernel(NwHop a)
+{
+    __shared__ uint32_t chosen_all[(kRowTile / kWave) * kMaxSampledFanout];
+    __shared__ int64_t wsum[kRowTile / kWave];
+    __shared__ int32_t deg_of[kRowTile], vert_of[kRowTile], cnt_of[kRowTile];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    volatile uint32_t *buf = chosen_all + wave * kMaxSampledFanout;
+    const int64_t most = a.mb_tileoff[a.k + 1];
+    for (int64_t v = blockIdx.x; v < most * a.k; v += gridDim.x) {
+        const int i = (int)(v % a.k);
+        const int64_t j = v / a.k;
+        if (j >= a.mb_tileoff[i + 1] - a.mb_tileoff[i])
+            continue;
+        const int64_t t = a.mb_tileoff[i] + j;
+        const int64_t r0 = a.mb_rowoff[i] + j * kRowTile;
+        const int64_t r = r0 + tid;
+        const int64_t left = a.mb_rowoff[i + 1] - r0;
+        const int nr = (int)(left < kRowTile ? left : kRowTile);
+        if (tid < nr) {
+            const int32_t vtx = a.row_vertex[r];
+            int64_t beg = 0, deg = 0;
+            if (vtx >= 0 && (int64_t)vtx < a.n) {
+                beg = a.A_rowptr[vtx];
+                deg = a.A_rowptr[vtx + 1] - beg;
+            }
+            a.row_beg[r] = beg;
+            a.row_deg[r] = (int32_t)deg;
+            deg_of[tid] = (int32_t)deg;
+            vert_of[tid] = vtx;
+        }
+        __syncthreads();
+        for (int q = wave; q < nr; q += kRowTile / kWave) {
+            int32_t m = 0;
+            if (deg_of[q] > 0)
+                m = wave_replace_draws(buf, row_key(a.hopkey, a.mb_base + (uint32_t)i, (uint32_t)vert_of[q]),
+                                       (uint32_t)deg_of[q], a.s, lane);
+            if (lane == 0)
+                cnt_of[q] = m;
+        }
+        __syncthreads();
+        int64_t cnt = 0;
+        if (tid < nr) {
+            a.row_cnt[r] = cnt_of[tid];
+            cnt = cnt_of[tid] + a.self_entry;
+        }
+        cnt = wave_sum(cnt);
+        if (lane == 0)
+            wsum[wave] = cnt;
+        __syncthreads();
+        if (tid == 0) {
+            int64_t tot = 0;
+#pragma unroll
+            for (int w = 0; w < kRowTile / kWave; ++w)
+                tot += wsum[w];
+            a.tile_off[t] = tot;
+        }
+        __syncthreads();
+    }
+}
+
 void launch_nw_rows(const Launch &L, const NwHop &a)
 {
     const int64_t tiles = a.rows_bound / kRowTile + a.k;
-    hipLaunchKernelGGL(nw_rows_kernel, dim3(grid_for(L, tiles, 16)), dim3(kRowTile), 0, L.stream, a);
+    const dim3 grid(grid_for(L, tiles, 16)), block(kRowTile);
+    if (!a.replace)
+        hipLaunchKernelGGL(nw_rows_kernel<0>, grid, block, 0, L.stream, a);
+    else if (a.s <= 4)
+        hipLaunchKernelGGL(nw_rows_kernel<4>, grid, block, 0, L.stream, a);
+    else if (a.s <= 8)
+        hipLaunchKernelGGL(nw_rows_kernel<8>, grid, block, 0, L.stream, a);
+    else if (a.s <= 16)
+        hipLaunchKernelGGL(nw_rows_kernel<16>, grid, block, 0, L.stream, a);
+    else if (a.s <= 32)
+        hipLaunchKernelGGL(nw_rows_kernel<32>, grid, block, 0, L.stream, a);
+    else
+        hipLaunchKernelGGL(nw_rows_replace_wide_kernel, dim3(grid_for(L, tiles, 2)), block, 0, L.stream, a);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -77,7 +235,7 @@ void launch_nw_rows(const Launch &L, const NwHop &a)
 // ascending order, turns it into the position; the list is kept sorted by one bubble pass,
 // which also leaves the row's output in ascending column order.
 // ---------------------------------------------------------------------------------------------
-template <int S, bool SET>
+template <int S, bool SET, bool REPLACE>
 __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
 {
     __shared__ int32_t stage[kRowTile * (S + 1)]; // + 1: the row's own vertex when rows carry it
@@ -95,10 +253,15 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
         const bool valid = r < a.mb_rowoff[i + 1];
         int64_t beg = 0;
         int32_t deg = 0, cnt = 0;
+        uint32_t c[S];
         if (valid) {
             beg = a.row_beg[r];
             deg = a.row_deg[r];
-            cnt = deg < s ? deg : s;
+            if (!REPLACE)
+                cnt = deg < s ? deg : s;
+            else if (deg > 0) // independent draws: the row's length is the number of distinct picks
+                cnt = replace_draws(row_key(a.hopkey, a.mb_base + (uint32_t)i, (uint32_t)a.row_vertex[r]),
+                                    (uint32_t)deg, s, c);
         }
         int32_t tot;
         const int32_t loc = block_exclusive_scan<int32_t, kRowTile>(valid ? cnt + a.self_entry : 0, wsum, tot);
@@ -107,8 +270,16 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
             a.out_rowptr[r] = base + loc;
         if (valid && a.self_entry)
             stage[loc + cnt] = a.row_vertex[r];
-        if (cnt > 0) {
-            uint32_t c[S];
+        if (REPLACE) {
+            if (cnt > 0) {
+                const int32_t *__restrict__ src = a.A_col + beg;
+                int32_t m = 0;
+#pragma unroll
+                for (int j = 0; j < S; ++j)
+                    if (j < s && (j == 0 || c[j] != c[j - 1]))
+                        stage[loc + m++] = src[c[j]];
+            }
+        } else if (cnt > 0) {
             if (deg <= s) {
 #pragma unroll
                 for (int j = 0; j < S; ++j)
@@ -157,7 +328,7 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
 // positions that the pick steps over is the count of list entries p_t with p_t - t <= x
 // (p_t - t = unchosen positions before p_t, non-decreasing in t), found by binary search.
 // ---------------------------------------------------------------------------------------------
-template <bool SET>
+template <bool SET, bool REPLACE>
 __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet vs)
 {
     __shared__ uint32_t chosen_all[(kRowTile / kWave) * kMaxSampledFanout];
@@ -175,7 +346,7 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
         int64_t cnt = 0;
         if (r < rend) {
             const int64_t deg = a.row_deg[r];
-            cnt = (deg < s ? deg : s) + a.self_entry;
+            cnt = (REPLACE ? (int64_t)a.row_cnt[r] : (deg < s ? deg : s)) + a.self_entry;
         }
         int64_t tot;
         const int64_t loc = block_exclusive_scan<int64_t, kRowTile>(cnt, wsum, tot);
@@ -193,11 +364,26 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
             const int32_t deg = a.row_deg[rr];
             int32_t *__restrict__ dst = a.out_col + row_loc[q];
             const int32_t *__restrict__ src = a.A_col + beg;
-            if (a.self_entry && lane == 0) { // the row's own vertex, after its min(deg, s) sampled ones
+            if (a.self_entry && lane == 0) { // the row's own vertex, after its sampled ones
                 const int32_t g = a.row_vertex[rr];
-                dst[deg < s ? deg : s] = g;
+                dst[REPLACE ? a.row_cnt[rr] : (deg < s ? deg : s)] = g;
                 if (SET)
                     atomicOr(&words[g >> 5], 1u << (g & 31));
+            }
+            if (REPLACE) { // independent draws: the distinct picks, sorted by the wave in LDS
+                if (deg > 0) {
+                    const int32_t m = wave_replace_draws(
+                        chosen, row_key(a.hopkey, a.mb_base + (uint32_t)i, (uint32_t)a.row_vertex[rr]), (uint32_t)deg, s,
+                        lane);
+                    for (int32_t e = lane; e < m; e += kWave) {
+                        const int32_t g = src[chosen[e]];
+                        dst[e] = g;
+                        if (SET)
+                            atomicOr(&words[g >> 5], 1u << (g & 31));
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+                continue;
             }
             if (deg <= s) {
                 for (int32_t e = lane; e < deg; e += kWave) {
@@ -248,28 +434,34 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
     }
 }
 
-template <bool SET>
+template <bool SET, bool REPLACE>
 static void launch_nw_sample_impl(const Launch &L, const NwHop &a, const VSet &vs)
 {
     const int64_t tiles = a.rows_bound / kRowTile + a.k;
     if (a.s <= 4)
-        hipLaunchKernelGGL((nw_sample_kernel<4, SET>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_kernel<4, SET, REPLACE>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
     else if (a.s <= 8)
-        hipLaunchKernelGGL((nw_sample_kernel<8, SET>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_kernel<8, SET, REPLACE>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
     else if (a.s <= 16)
-        hipLaunchKernelGGL((nw_sample_kernel<16, SET>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_kernel<16, SET, REPLACE>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
     else if (a.s <= 32)
-        hipLaunchKernelGGL((nw_sample_kernel<32, SET>), dim3(grid_for(L, tiles, 4)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_kernel<32, SET, REPLACE>), dim3(grid_for(L, tiles, 4)), dim3(kRowTile), 0, L.stream, a, vs);
     else
-        hipLaunchKernelGGL((nw_sample_wide_kernel<SET>), dim3(grid_for(L, tiles, 2)), dim3(kRowTile), 0, L.stream, a, vs);
+        hipLaunchKernelGGL((nw_sample_wide_kernel<SET, REPLACE>), dim3(grid_for(L, tiles, 2)), dim3(kRowTile), 0, L.stream, a, vs);
 }
 
 void launch_nw_sample(const Launch &L, const NwHop &a, const VSet &vs, bool set_bits)
 {
-    if (set_bits)
-        launch_nw_sample_impl<true>(L, a, vs);
-    else
-        launch_nw_sample_impl<false>(L, a, vs);
+    if (a.replace) {
+        if (set_bits)
+            launch_nw_sample_impl<true, true>(L, a, vs);
+        else
+            launch_nw_sample_impl<false, true>(L, a, vs);
+    } else if (set_bits) {
+        launch_nw_sample_impl<true, false>(L, a, vs);
+    } else {
+        launch_nw_sample_impl<false, false>(L, a, vs);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

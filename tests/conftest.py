@@ -33,6 +33,17 @@ def random_csr(n, avg_deg, rng, symmetric=True, allow_loops=False):
     return rowptr, dst.astype(np.int32)
 
 
+def skewed_csr(n, m, rng):
+    """Directed graph whose edge endpoints follow a power law (hubs on both sides), rows sorted and unique."""
+    src = (n * rng.random(m) ** 3).astype(np.int64)
+    dst = (n * rng.random(m) ** 2).astype(np.int64)
+    perm = rng.permutation(n)
+    key = np.unique(perm[src] * n + perm[dst])
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rowptr, key // n + 1, 1)
+    return np.cumsum(rowptr), (key % n).astype(np.int32)
+
+
 def random_batches(n, k, b, rng, candidates=None):
     """k x b int32, distinct inside each minibatch."""
     pool = np.arange(n) if candidates is None else np.asarray(candidates)

@@ -6,21 +6,10 @@ import numpy as np
 import pytest
 import torch
 
-from conftest import random_batches, random_csr
+from conftest import random_batches, random_csr, skewed_csr
 from parity import assert_hops_equal
 
 pytestmark = pytest.mark.gpu
-
-
-def _skewed_csr(n, m, rng):
-    """Directed graph whose edge endpoints follow a power law (hubs on both sides), rows sorted and unique."""
-    src = (n * rng.random(m) ** 3).astype(np.int64)
-    dst = (n * rng.random(m) ** 2).astype(np.int64)
-    perm = rng.permutation(n)
-    key = np.unique(perm[src] * n + perm[dst])
-    rowptr = np.zeros(n + 1, dtype=np.int64)
-    np.add.at(rowptr, key // n + 1, 1)
-    return np.cumsum(rowptr), (key % n).astype(np.int32)
 
 
 @pytest.mark.parametrize("case", range(int(os.environ.get("BMS_RANDOM_CASES", "40"))))
@@ -30,7 +19,7 @@ def test_random_case(case):
     rng = np.random.default_rng(1000 + case)
     n = int(rng.choice([300, 5_000, 70_000, 400_000]))
     if rng.random() < 0.5:
-        rowptr, col = _skewed_csr(n, int(n * rng.uniform(2, 12)), rng)
+        rowptr, col = skewed_csr(n, int(n * rng.uniform(2, 12)), rng)
     else:
         rowptr, col = random_csr(n, float(rng.uniform(1, 20)), rng, symmetric=bool(rng.random() < 0.5))
     k = int(rng.integers(1, 9))

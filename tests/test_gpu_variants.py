@@ -1,12 +1,12 @@
 """Parity of the node-wise variants with the CPU oracle (bit-exact), through the C ABI.
 
 union_dst: the frontier's own vertices stay columns (next frontier = frontier + sampled vertices) and every row
-reports its own column."""
+reports its own column.  replace: the s draws of a row are independent and the row keeps the distinct picks."""
 import numpy as np
 import pytest
 import torch
 
-from conftest import random_batches, random_csr
+from conftest import random_batches, random_csr, skewed_csr
 from parity import assert_hops_equal
 
 pytestmark = pytest.mark.gpu
@@ -99,3 +99,67 @@ def test_union_dst_on_the_mid_size_workload():
     ref = O.sample_nodewise(g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy(), w["params"],
                             synth.SAMPLING_SEED, union_dst=True)
     assert_hops_equal(res.hops(), ref, what="mid_sage union_dst")
+
+
+@pytest.mark.parametrize("variant", [dict(replace=True), dict(replace=True, union_dst=True)], ids=lambda v: "+".join(sorted(v)))
+@pytest.mark.parametrize("fanouts", [(3,), (4, 4), (8, 3, 2), (15, 10, 5), (16, 2), (32, 2), (1, 1, 1), (33, 3), (40, 40),
+                                     (200, 3), (2048, 2)])
+def test_replace_all_lane_capacities_and_wave_sorted_rows(fanouts, variant):
+    rng = np.random.default_rng(200 + sum(fanouts))
+    rowptr, col = skewed_csr(6000, 100000, rng)     # some rows have thousands of entries, some none
+    assert np.diff(rowptr).max() > 2048 and np.diff(rowptr).min() == 0
+    batches = random_batches(6000, 3, 300, rng)
+    _, res, ref = _check(rowptr, col, batches, fanouts, 11, mb_base=5, **variant)
+    deg = np.diff(rowptr)
+    for h, hop in enumerate(ref):   # the oracle's rows really are shorter than the plain method's somewhere
+        lens = np.diff(hop.rowptr)
+        assert (lens <= np.minimum(deg[hop.row_vertex], fanouts[h])).all()
+    assert max(fanouts) == 1 or any((np.diff(hop.rowptr) < np.minimum(deg[hop.row_vertex], fanouts[h])).any()
+                                    for h, hop in enumerate(ref))
+
+
+def test_replace_recycled_calls_and_change_of_variant():
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms
+    rng = np.random.default_rng(42)
+    rowptr, col = random_csr(50000, 12.0, rng)
+    batches = random_batches(50000, 8, 500, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    bt = torch.from_numpy(batches).cuda()
+    fan = (6, 5, 4)
+    refs = {(u, r): O.sample_nodewise(rowptr, col, batches, fan, 77, union_dst=u, replace=r)
+            for u in (False, True) for r in (False, True)}
+    res = None
+    for u, r in ((False, True), (False, True), (True, True), (True, True), (False, False), (True, False), (False, True)):
+        res = bms.sample_nodewise(csr, bt, fan, 77, recycle=res, union_dst=u, replace=r)
+        assert_hops_equal(res.hops(), refs[(u, r)], what="recycled, union=%s replace=%s" % (u, r))
+
+
+def test_replace_limits():
+    from paper_2311_02909_amd import bms
+    rng = np.random.default_rng(43)
+    rowptr, col = random_csr(500, 5.0, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    bt = torch.from_numpy(random_batches(500, 2, 8, rng)).cuda()
+    with pytest.raises(bms.BmsError) as e:
+        bms.sample_nodewise(csr, bt, (3, 2049), 1, replace=True)
+    assert e.value.code == bms.EINVAL
+    # one draw per row: with and without replacement are the same sample
+    a = bms.sample_nodewise(csr, bt, (1, 1, 1), 9, replace=True)
+    b = bms.sample_nodewise(csr, bt, (1, 1, 1), 9)
+    for ha, hb in zip(a.hops(), b.hops()):
+        assert torch.equal(ha.col, hb.col) and torch.equal(ha.col_vertex, hb.col_vertex) and torch.equal(ha.rowptr, hb.rowptr)
+
+
+def test_replace_on_the_mid_size_workload():
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms, synth
+    g, batches, w = synth.make_workload("mid_sage", device="cuda")
+    csr = bms.Csr(g.rowptr, g.col)
+    res = None
+    for _ in range(2):
+        res = bms.sample_nodewise(csr, batches, w["params"], synth.SAMPLING_SEED, replace=True, recycle=res)
+    print("\n  sizes", res.sizes(), flush=True)
+    ref = O.sample_nodewise(g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy(), w["params"],
+                            synth.SAMPLING_SEED, replace=True)
+    assert_hops_equal(res.hops(), ref, what="mid_sage replace")
