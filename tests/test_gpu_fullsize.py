@@ -100,3 +100,43 @@ def test_layerwise_on_the_largest_graph():
     print("\n  sizes", res.sizes(), flush=True)
     ref = O.sample_ladies(g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy(), s, synth.SAMPLING_SEED, 3)
     assert_hops_equal(res.hops(), ref, with_p=True, what="ladies on the largest graph")
+
+
+def test_vertex_ids_up_to_the_int32_limit():
+    """Maximum size of the id space: n = 2^31 - 1 vertices (ids up to 2^31 - 2, rowptr of 17 GB), edges among two
+    million of them spread over the whole range including both ends.  Node-wise sampling (per-minibatch bitmaps in
+    HBM are the only EXTRACT path for an id range this wide) and LADIES by LDS windows (32 768 windows per
+    minibatch), each against the complete oracle result."""
+    import numpy as np
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms
+    n = 2**31 - 1
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    active = torch.randint(0, n, (2_000_000,), device="cuda", generator=gen)
+    active = torch.unique(torch.cat([active, torch.tensor([0, 1, n - 2, n - 1, 2**30 - 1, 2**30], device="cuda")]))
+    m = 6_000_000
+    src = active[torch.randint(0, active.numel(), (m,), device="cuda", generator=gen)]
+    dst = active[(torch.rand(m, device="cuda", generator=gen) ** 2 * active.numel()).long()]   # a few hubs
+    key = torch.unique(torch.cat([src * n + dst, dst * n + src]))
+    src, dst = key // n, key % n
+    del key
+    rowptr = torch.zeros(n + 1, dtype=torch.int64, device="cuda")
+    rowptr[1:] = torch.cumsum(torch.bincount(src, minlength=n), 0)
+    col = dst.to(torch.int32)
+    del src, dst
+    print("\n  n=%d nnz=%d max degree=%d" % (n, col.numel(), int((rowptr[1:] - rowptr[:-1]).max())), flush=True)
+    csr = bms.Csr(rowptr, col)
+    k, b = 2, 64
+    pick = torch.randperm(active.numel(), device="cuda", generator=gen)[:k * b - 2]
+    batches = torch.cat([active[pick], torch.tensor([0, n - 1], device="cuda")]).to(torch.int32).reshape(k, b).contiguous()
+    rp, cl, bt = rowptr.cpu().numpy(), col.cpu().numpy(), batches.cpu().numpy()
+    for variant in (dict(), dict(union_dst=True)):
+        res = bms.sample_nodewise(csr, batches, (4, 3), 17, **variant)
+        print("  node-wise", variant, res.sizes(), flush=True)
+        ref = O.sample_nodewise(rp, cl, bt, (4, 3), 17, **variant)
+        assert_hops_equal(res.hops(), ref, what="n = 2^31 - 1, node-wise %s" % variant)
+        assert int(res.hop(1).col_vertex.max()) > 2**30
+    res = bms.sample_ladies(csr, batches, (64, 32), 17)
+    print("  ladies", res.sizes(), flush=True)
+    ref = O.sample_ladies(rp, cl, bt, (64, 32), 17)
+    assert_hops_equal(res.hops(), ref, with_p=True, what="n = 2^31 - 1, ladies")
