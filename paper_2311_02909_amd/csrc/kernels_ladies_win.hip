@@ -199,7 +199,19 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
     for (int x = tid; x < kWinWords; x += kAccThreads)
         cnt[x] = 0;
     __syncthreads();
-    for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+    // Workgroups are handed to the chip's 8 dies in turn, and each die has its own last-level cache.  Within a
+    // round of gridDim.x (minibatch, window) pairs, die x takes a run of consecutive windows, so the memory
+    // lines that hold the end of one window's piece and the start of the next one's are fetched once.
+    const int64_t G = gridDim.x;
+    const bool by_die = (G % 8) == 0;
+    for (int64_t slot = blockIdx.x; slot < (nblk + G - 1) / G * G; slot += G) {
+        int64_t blk = slot;
+        if (by_die) {
+            const int64_t p = slot % G;
+            blk = slot - p + (p % 8) * (G / 8) + p / 8;
+        }
+        if (blk >= nblk)
+            continue;
         const int i = (int)(blk / a.nwin), w = (int)(blk % a.nwin);
         const int64_t r0 = a.mb_rowoff[i], r1 = a.mb_rowoff[i + 1];
         const uint32_t *__restrict__ lo_b = a.bounds_t + (int64_t)w * a.rows_bound; // boundary w of every row
