@@ -6,7 +6,8 @@
  *
  *   in : int64 n, nnz, k, b, L, seed; int64 rowptr[n+1]; int32 col[nnz]; int32 batches[k*b]; int32 fanouts[L]
  *   out: per hop  int64 rows, nnz, ncols; int64 mb_rowoff[k+1]; int32 row_vertex[rows]; int64 rowptr[rows+1];
- *                 int32 col[nnz]; int64 mb_coloff[k+1]; int32 col_vertex[ncols]
+ *                 int32 col[nnz]; int64 mb_coloff[k+1]; int32 col_vertex[ncols]; with BMS_UNION_DST int32 row_self[rows]
+ * An optional third argument gives bms_opts.flags (decimal), e.g. 128 for BMS_UNION_DST.
  */
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
@@ -38,10 +39,11 @@ static void dump(FILE *f, const void *dev, size_t count, size_t size)
 
 int main(int argc, char **argv)
 {
-    if (argc != 3) {
-        fprintf(stderr, "usage: %s problem.bin result.bin\n", argv[0]);
+    if (argc != 3 && argc != 4) {
+        fprintf(stderr, "usage: %s problem.bin result.bin [flags]\n", argv[0]);
         return 2;
     }
+    const uint32_t flags = argc == 4 ? (uint32_t)strtoul(argv[3], NULL, 10) : 0u;
     FILE *in = fopen(argv[1], "rb");
     if (!in)
         return 2;
@@ -64,6 +66,7 @@ int main(int argc, char **argv)
         return 1;
     }
     bms_opts opts = {0};
+    opts.flags = flags;
     bms_result *res = NULL;
     rc = bms_sample_nodewise(csr, batches, k, b, fanouts, L, seed, &opts, &res);
     if (rc != BMS_OK) {
@@ -92,6 +95,13 @@ int main(int argc, char **argv)
         dump(out, v.col, (size_t)v.nnz, sizeof(int32_t));
         dump(out, v.mb_coloff, (size_t)k + 1, sizeof(int64_t));
         dump(out, v.col_vertex, (size_t)v.ncols, sizeof(int32_t));
+        if ((flags & BMS_UNION_DST) != 0) {
+            if (!v.row_self)
+                return 1;
+            dump(out, v.row_self, (size_t)v.rows, sizeof(int32_t));
+        } else if (v.row_self) {
+            return 1;
+        }
     }
     fclose(out);
     /* an invalid batch must come back as an error code, not as a crash */

@@ -12,7 +12,8 @@ pytestmark = pytest.mark.gpu
 CLIENT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "bms_c_client")
 
 
-def test_c_client_matches_oracle(tmp_path):
+@pytest.mark.parametrize("variant", [dict(), dict(union_dst=True), dict(replace=True)], ids=["plain", "union_dst", "replace"])
+def test_c_client_matches_oracle(tmp_path, variant):
     from oracle import bms_oracle as O
     assert os.path.exists(CLIENT), "build the C client first: python paper_2311_02909_amd/build.py"
     rng = np.random.default_rng(77)
@@ -26,16 +27,18 @@ def test_c_client_matches_oracle(tmp_path):
         col.astype(np.int32).tofile(f)
         batches.astype(np.int32).tofile(f)
         np.array(fanouts, dtype=np.int32).tofile(f)
-    run = subprocess.run([CLIENT, str(problem), str(result)], capture_output=True, text=True, timeout=120)
+    flags = (128 if variant.get("union_dst") else 0) | (256 if variant.get("replace") else 0)   # values of include/bms.h
+    run = subprocess.run([CLIENT, str(problem), str(result), str(flags)], capture_output=True, text=True, timeout=120)
     assert run.returncode == 0 and run.stdout.strip() == "ok", (run.returncode, run.stdout, run.stderr)
-    ref = O.sample_nodewise(rowptr, col, batches, fanouts, seed)
+    ref = O.sample_nodewise(rowptr, col, batches, fanouts, seed, **variant)
     with open(result, "rb") as f:
         for h, hop in enumerate(ref):
             rows, nnz, ncols = np.fromfile(f, dtype=np.int64, count=3)
             assert (rows, nnz, ncols) == (hop.rows, hop.nnz, hop.ncols), h
             for name, dtype, count in (("mb_rowoff", np.int64, k + 1), ("row_vertex", np.int32, rows),
                                        ("rowptr", np.int64, rows + 1), ("col", np.int32, nnz),
-                                       ("mb_coloff", np.int64, k + 1), ("col_vertex", np.int32, ncols)):
+                                       ("mb_coloff", np.int64, k + 1), ("col_vertex", np.int32, ncols)) + (
+                    (("row_self", np.int32, rows),) if variant.get("union_dst") else ()):
                 got = np.fromfile(f, dtype=dtype, count=int(count))
                 assert np.array_equal(got, getattr(hop, name)), (h, name)
         assert f.read() == b""
