@@ -165,14 +165,18 @@ def main() -> int:
     # every stage costs ~0.2 ms per call in event records, so the full breakdown is taken in extra steps below.
     main_ms, main_n = {}, {}
     t_start = time.perf_counter()
+    step_ms = []   # a call returns after its stream has drained, so the host clock around it times the step
     for _ in range(args.steps):
+        t_step = time.perf_counter()
         res = fn(csr, batches, w["params"], seed, recycle=res, profile="main")
+        step_ms.append((time.perf_counter() - t_step) * 1e3)
         for name, hop, ms in res.stages():
             main_ms[(name, hop)] = main_ms.get((name, hop), 0.0) + ms
             main_n[(name, hop)] = main_n.get((name, hop), 0) + 1
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed / args.steps * 1e3
+    step_ms.sort()
     # per-stage breakdown: a few more steps with every stage timed (not part of `value`)
     stage_ms, stage_n = {}, {}
     for _ in range(max(3, min(args.steps, 10))):
@@ -299,10 +303,24 @@ def main() -> int:
         cpu_s = time.perf_counter() - t1
         cpu = {"value": round(edges / cpu_s, 1), "unit": "edges/s", "cores": cores, "kind": "oracle",
                "sample": "the same %d minibatches, one oracle call (%.2f s), OpenMP over minibatches" % (k, cpu_s)}
+        # one thread, on the first minibatches only (their edges counted from the library's result of the same call)
+        k1 = max(1, k // 16)
+        edges1 = 0
+        for hop in range(len(sizes)):
+            hv = res.hop(hop)
+            edges1 += int(hv.rowptr[int(hv.mb_rowoff[k1].item())].item())
+        O.set_threads(1)
+        t1 = time.perf_counter()
+        ofn(rp, cl, bt[:k1], w["params"], seed, collect=False)
+        cpu1_s = time.perf_counter() - t1
+        O.set_threads(cores)
+        cpu["single_thread"] = {"value": round(edges1 / cpu1_s, 1), "unit": "edges/s", "cores": 1,
+                                "sample": "the first %d minibatches, one oracle call (%.2f s)" % (k1, cpu1_s)}
 
     out = {
         "metric": "sampled_edges_per_sec", "value": round(value, 1), "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(step_ms[len(step_ms) // 2], 4), "ms_per_step_min": round(step_ms[0], 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
         "minibatches_per_sec": round(k / (ms_per_step * 1e-3), 1),
         "config": {"workload": args.workload, "sampler": w["sampler"], "params": list(w["params"]),
