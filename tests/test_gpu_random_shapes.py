@@ -35,6 +35,14 @@ def test_random_case(case):
         res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fanouts, seed, mb_base=mb_base,
                                   extract=extract, recycle=res)
         assert_hops_equal(res.hops(), ref, what="case %d nodewise fanouts=%s extract=%s" % (case, fanouts, extract))
+    variant = dict(union_dst=bool(rng.random() < 0.5), replace=bool(rng.random() < 0.5))
+    if any(variant.values()):
+        vref = O.sample_nodewise(rowptr, col, batches, fanouts, seed, mb_base, **variant)
+        for extract in (None, "bitmap", None):   # the last one recycles: no size read-backs
+            res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fanouts, seed, mb_base=mb_base,
+                                      extract=extract, recycle=res, **variant)
+            assert_hops_equal(res.hops(), vref, what="case %d nodewise %s fanouts=%s extract=%s" % (
+                case, variant, fanouts, extract))
     s = tuple(int(x) for x in rng.choice([1, 4, 33, 200, 1000, 4096], size=L))
     squared = bool(rng.random() < 0.3)
     lref = O.sample_ladies(rowptr, col, batches, s, seed, mb_base, squared)
