@@ -396,6 +396,7 @@ __global__ __launch_bounds__(256) void ldw_win_scan_kernel(LwHop a)
 // windows to their place in P, with the inclusive prefix sums of the weights.  Global accesses are
 // coalesced (lane t of a step takes entries t, t + 512, ...); the running sums need consecutive entries per
 // lane, so weights and sums change layout through LDS.
+constexpr int kPrefixBlock = 64; // entries of P per kept prefix sum
 constexpr int kCopyThreads = 512;
 constexpr int kCopyStep = 4 * kCopyThreads;
 __global__ __launch_bounds__(kCopyThreads) void ldw_p_copy_kernel(LwHop a)
@@ -442,11 +443,13 @@ __global__ __launch_bounds__(kCopyThreads) void ldw_p_copy_kernel(LwHop a)
                 sums[tid * 4 + q] = run;
             }
             __syncthreads();
+            // the draws find their block of kPrefixBlock entries of P by these sums and walk the weights
+            // inside it: only the sum at the last entry of every such block (absolute index in P) is kept
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const uint32_t x = x0 + q * kCopyThreads + tid;
-                if (x < cw)
-                    a.prefix[dst + x] = sums[q * kCopyThreads + tid];
+                if (x < cw && ((dst + x) & (kPrefixBlock - 1)) == kPrefixBlock - 1)
+                    a.prefix[(dst + x) / kPrefixBlock] = sums[q * kCopyThreads + tid];
             }
             carry += total;
             __syncthreads();
@@ -466,14 +469,18 @@ __global__ __launch_bounds__(1024) void ldw_draw_kernel(LwHop a)
     uint32_t M = 1024; // sorted size: a power of two >= s, at least one slot per thread
     while (M < (uint32_t)a.s)
         M <<= 1;
-    const uint64_t *__restrict__ pre = a.prefix + p0;
-    const uint64_t W = C > 0 ? pre[C - 1] : 0;
+    // inclusive weight sums are on record at the last entry of every block of kPrefixBlock entries (absolute
+    // index in P): blocks B0 .. B0 + nb - 1 end inside this minibatch's row; W = the row sum
+    const int64_t B0 = p0 / kPrefixBlock, nb = (p0 + C) / kPrefixBlock - B0;
+    const uint64_t *__restrict__ pre = a.prefix + B0;
+    const int64_t last_win = (int64_t)i * a.nwin + a.nwin - 1;
+    const uint64_t W = a.win_woff[last_win] + a.win_wt[last_win];
     const uint64_t rk = row_key(a.hopkey, a.mb_base + (uint32_t)i, kNoVertex);
     for (uint32_t j = tid; j < M; j += 1024) {
         uint32_t v = kEmptySlot;
         if (j < (uint32_t)a.s && C > 0) { // an empty aggregated neighbourhood samples nothing
             const uint64_t r = bounded64(draw64(rk, j), W);
-            int64_t lo = 0, hi = C - 1;
+            int64_t lo = 0, hi = nb; // first block whose recorded sum exceeds r (nb: the unrecorded tail)
             while (lo < hi) {
                 const int64_t mid = lo + ((hi - lo) >> 1);
                 if (pre[mid] > r)
@@ -481,7 +488,17 @@ __global__ __launch_bounds__(1024) void ldw_draw_kernel(LwHop a)
                 else
                     lo = mid + 1;
             }
-            v = (uint32_t)a.p_col[p0 + lo];
+            uint64_t acc = lo > 0 ? pre[lo - 1] : 0ull;
+            int64_t e = (B0 + lo) * kPrefixBlock;
+            if (e < p0)
+                e = p0;
+            const int64_t end = p0 + C - 1; // the smallest t with prefix[t] > r exists below the row's end: W > r
+            for (; e < end; ++e) {
+                acc += ldw_weight(a.p_cnt[e], a.squared);
+                if (acc > r)
+                    break;
+            }
+            v = (uint32_t)a.p_col[e];
         }
         key[j] = v;
     }
