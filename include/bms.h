@@ -152,6 +152,29 @@ int bms_result_info(const bms_result *res, int32_t *k, int32_t *L);
 int bms_result_hop(const bms_result *res, int32_t hop, bms_hop_view *view);
 
 /*
+ * One minibatch of one hop, cut out of the stacked result: the k minibatches sampled in bulk are trained on one
+ * after the other (Sec. 6), each with its own sampled adjacency matrices A_i.  Pointers point into the result's
+ * stacked arrays (same ownership and lifetime as bms_hop_view), already moved to the minibatch's first row /
+ * entry / column, so that A_i is the CSR (rowptr[r] - edge0 .. rowptr[r+1] - edge0 index `col`, r in [0, rows)).
+ */
+typedef struct bms_mb_view {
+    int64_t rows, nnz, ncols;  /* of this minibatch                                                    */
+    int64_t row0, edge0, col0; /* where it starts in the stacked rows / entries / columns of the hop   */
+    const int32_t *row_vertex; /* rows   */
+    const int64_t *rowptr;     /* rows+1, stacked offsets: subtract edge0                              */
+    const int32_t *col;        /* nnz, local column indices (local to the minibatch as in the stack)   */
+    const int32_t *col_vertex; /* ncols  */
+    const int32_t *row_self;   /* rows, or NULL (see bms_hop_view)                                     */
+} bms_mb_view;
+
+/*
+ * Fill *view for minibatch 0 <= i < k of hop 0 <= hop < L.  The first call on a result copies the per-minibatch
+ * offsets of every hop to the host (three arrays of k+1 integers per hop; it waits for that copy); later calls on
+ * the same result only do pointer arithmetic.  BMS_EINVAL for a bad handle, hop or minibatch index.
+ */
+int bms_result_minibatch(bms_result *res, int32_t hop, int32_t i, bms_mb_view *view);
+
+/*
  * Feature fetching, the part one GPU does (Sec. 6.2): H_i = the rows of the feature matrix H that belong to
  * the vertices of the last frontier.  out[j * f + x] = H[ids[j] * f + x] for j in [0, m), x in [0, f).
  *   H    device, n x f fp32, row-major, caller-owned, read only

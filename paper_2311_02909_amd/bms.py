@@ -42,6 +42,12 @@ class _HopView(C.Structure):
                 ("p_cnt", C.c_void_p), ("row_self", C.c_void_p)]
 
 
+class _MbView(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("nnz", C.c_int64), ("ncols", C.c_int64), ("row0", C.c_int64),
+                ("edge0", C.c_int64), ("col0", C.c_int64), ("row_vertex", C.c_void_p), ("rowptr", C.c_void_p),
+                ("col", C.c_void_p), ("col_vertex", C.c_void_p), ("row_self", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -65,6 +71,8 @@ def lib() -> C.CDLL:
         L.bms_result_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.bms_result_hop.restype = C.c_int
         L.bms_result_hop.argtypes = [C.c_void_p, C.c_int32, C.POINTER(_HopView)]
+        L.bms_result_minibatch.restype = C.c_int
+        L.bms_result_minibatch.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_MbView)]
         L.bms_result_stage.restype = C.c_int
         L.bms_result_stage.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int32),
                                        C.POINTER(C.c_float)]
@@ -131,6 +139,23 @@ class Hop:
         return HostHop(self.rows, self.nnz, self.ncols, cp(self.mb_rowoff), cp(self.row_vertex), cp(self.rowptr),
                        cp(self.col), cp(self.mb_coloff), cp(self.col_vertex), cp(self.p_off), cp(self.p_col),
                        cp(self.p_cnt, np.uint32), cp(self.row_self))
+
+
+@dataclass
+class Minibatch:
+    """One minibatch of one hop (bms_mb_view): views into the stacked arrays; A_i is the CSR
+    (rowptr - edge0, col) over `ncols` local columns whose vertices are col_vertex."""
+    rows: int
+    nnz: int
+    ncols: int
+    row0: int
+    edge0: int
+    col0: int
+    row_vertex: torch.Tensor
+    rowptr: torch.Tensor
+    col: torch.Tensor
+    col_vertex: torch.Tensor
+    row_self: Optional[torch.Tensor] = None
 
 
 @dataclass
@@ -208,6 +233,19 @@ class Result:
             p_off=_view(v.p_off, k + 1, torch.int64, self) if has_p else None,
             p_col=_view(v.p_col, v.pnnz, torch.int32, self) if has_p else None,
             p_cnt=_view(v.p_cnt, v.pnnz, torch.int32, self) if has_p else None,
+            row_self=_view(v.row_self, v.rows, torch.int32, self) if v.row_self else None,
+        )
+
+    def minibatch(self, h: int, i: int) -> Minibatch:
+        """bms_result_minibatch: minibatch i of hop h cut out of the stack (no copies of the arrays)."""
+        v = _MbView()
+        _check(lib().bms_result_minibatch(self.handle, h, i, C.byref(v)))
+        return Minibatch(
+            rows=v.rows, nnz=v.nnz, ncols=v.ncols, row0=v.row0, edge0=v.edge0, col0=v.col0,
+            row_vertex=_view(v.row_vertex, v.rows, torch.int32, self),
+            rowptr=_view(v.rowptr, v.rows + 1, torch.int64, self),
+            col=_view(v.col, v.nnz, torch.int32, self),
+            col_vertex=_view(v.col_vertex, v.ncols, torch.int32, self),
             row_self=_view(v.row_self, v.rows, torch.int32, self) if v.row_self else None,
         )
 

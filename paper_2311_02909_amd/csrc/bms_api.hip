@@ -123,6 +123,7 @@ struct HopBufs {
 struct bms_result {
     uint32_t tag = kTagResult;
     int32_t k = 0, L = 0;
+    int device = 0;
     std::vector<HopBufs> hops;
     std::vector<StageTime> stages;
     std::vector<hipEvent_t> event_pool;
@@ -132,6 +133,10 @@ struct bms_result {
     const bms_csr *hint_csr = nullptr;
     std::vector<int32_t> hint_shape; // k, b, fanouts...
     std::vector<int64_t> hint_nnz;   // per hop
+    // host copies of the per-minibatch offsets (rows, entries, columns: L x 3 x (k+1)), made on demand by
+    // bms_result_minibatch and dropped when the result is written again
+    std::vector<int64_t> mb_offsets;
+    DevBuf mb_edge_tmp;
 };
 
 namespace {
@@ -150,6 +155,7 @@ void result_release(bms_result *r)
         h.p_cnt.release();
         h.row_self.release();
     }
+    r->mb_edge_tmp.release();
     for (auto e : r->event_pool)
         (void)hipEventDestroy(e);
     r->event_pool.clear();
@@ -338,10 +344,12 @@ int begin_call(CallCtx &c, bms_csr *csr, int32_t k, int32_t b, int32_t L, uint64
     }
     c.res->k = k;
     c.res->L = L;
+    c.res->device = csr->device;
     if ((int32_t)c.res->hops.size() < L)
         c.res->hops.resize(L);
     c.res->stages.clear();
     c.res->events_used = 0;
+    c.res->mb_offsets.clear();
     if (!csr->host_pinned)
         HIP_TRY(hipHostMalloc((void **)&csr->host_pinned, 64 * sizeof(int64_t), hipHostMallocDefault));
     BMS_TRY(csr->scalars.ensure(64 * sizeof(int64_t)));
@@ -1142,6 +1150,47 @@ int bms_result_hop(const bms_result *res, int32_t hop, bms_hop_view *view)
     if (hop < 0 || hop >= res->L)
         return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
     *view = res->hops[hop].view;
+    return BMS_OK;
+}
+
+int bms_result_minibatch(bms_result *res, int32_t hop, int32_t i, bms_mb_view *view)
+{
+    if (!res || res->tag != kTagResult || !view)
+        return fail(BMS_EINVAL, "not a result handle, or null view");
+    if (hop < 0 || hop >= res->L)
+        return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
+    if (i < 0 || i >= res->k)
+        return fail(BMS_EINVAL, "minibatch %d outside [0, %d)", i, res->k);
+    const size_t stride = (size_t)res->k + 1;
+    if (res->mb_offsets.empty()) {
+        HIP_TRY(hipSetDevice(res->device));
+        std::vector<int64_t> host((size_t)res->L * 3 * stride);
+        BMS_TRY(res->mb_edge_tmp.ensure(stride * sizeof(int64_t)));
+        for (int32_t h = 0; h < res->L; ++h) {
+            const bms_hop_view &v = res->hops[h].view;
+            int64_t *dst = host.data() + (size_t)h * 3 * stride;
+            launch_mb_edge_offsets(nullptr, v.rowptr, v.mb_rowoff, res->k, res->mb_edge_tmp.as<int64_t>());
+            HIP_TRY(hipMemcpy(dst, v.mb_rowoff, stride * sizeof(int64_t), hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(dst + stride, res->mb_edge_tmp.p, stride * sizeof(int64_t), hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(dst + 2 * stride, v.mb_coloff, stride * sizeof(int64_t), hipMemcpyDeviceToHost));
+        }
+        res->mb_offsets.swap(host);
+    }
+    const bms_hop_view &v = res->hops[hop].view;
+    const int64_t *off = res->mb_offsets.data() + (size_t)hop * 3 * stride;
+    bms_mb_view m{};
+    m.row0 = off[i];
+    m.rows = off[i + 1] - off[i];
+    m.edge0 = off[stride + i];
+    m.nnz = off[stride + i + 1] - off[stride + i];
+    m.col0 = off[2 * stride + i];
+    m.ncols = off[2 * stride + i + 1] - off[2 * stride + i];
+    m.row_vertex = v.row_vertex + m.row0;
+    m.rowptr = v.rowptr + m.row0;
+    m.col = v.col + m.edge0;
+    m.col_vertex = v.col_vertex + m.col0;
+    m.row_self = v.row_self ? v.row_self + m.row0 : nullptr;
+    *view = m;
     return BMS_OK;
 }
 

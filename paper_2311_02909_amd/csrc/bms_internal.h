@@ -128,6 +128,9 @@ void launch_nw_dedup_fixup(const Launch &, const DedupArgs &, const int64_t *mb_
                            int64_t nnz, const StageMark &mark);
 constexpr int kDedupPlaceTile = 8192; // must equal kPlaceTile in kernels_dedup.hip (sizes the cursor array)
 constexpr int kDedupSplitTile = 2048; // must equal kSplitTile in kernels_dedup.hip
+// mb_edgeoff[i] = rowptr[mb_rowoff[i]], i <= k: first entry of every minibatch in the stacked column array
+void launch_mb_edge_offsets(hipStream_t stream, const int64_t *rowptr, const int64_t *mb_rowoff, int32_t k,
+                            int64_t *mb_edgeoff);
 void launch_offsets_from_counts(const Launch &, const int64_t *mb_count, int32_t k, int64_t *mb_off,
                                 int64_t *total_out);
 // seed check without a vertex set: range test + per-minibatch sort in LDS (b <= kMaxSortedSeeds)

@@ -43,6 +43,13 @@ __global__ void mb_edge_offsets_kernel(const int64_t *__restrict__ out_rowptr, c
         mb_edgeoff[i] = out_rowptr[mb_rowoff[i]];
 }
 
+void launch_mb_edge_offsets(hipStream_t stream, const int64_t *rowptr, const int64_t *mb_rowoff, int32_t k,
+                            int64_t *mb_edgeoff)
+{
+    hipLaunchKernelGGL(mb_edge_offsets_kernel, dim3((k + 256) / 256), dim3(256), 0, stream, rowptr, mb_rowoff, k,
+                       mb_edgeoff);
+}
+
 // entry written for every pair / every distinct id: low 32 bits payload, then rank in group, then bin
 __device__ inline uint64_t pack_entry(uint32_t payload, uint32_t rank, uint32_t bin)
 {
