@@ -352,16 +352,17 @@ __device__ inline void dedup_split_pass(const DedupArgs &a, int big_segments, ui
         if (!__syncthreads_or(any))
             return;
     }
-    const int64_t ntiles = big_segments ? 2 * (int64_t)*a.big_count : a.split_tileoff[a.k];
+    constexpr int kTilesPerBig = kSegCap / kSplitTile; // a listed segment holds at most this many tiles of entries
+    const int64_t ntiles = big_segments ? kTilesPerBig * (int64_t)*a.big_count : a.split_tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
         int i;
         uint32_t j0, jend;
-        if (big_segments) { // a listed segment holds at most 2 tiles of entries
-            const int64_t sg = a.big_list[t >> 1];
+        if (big_segments) {
+            const int64_t sg = a.big_list[t / kTilesPerBig];
             i = (int)(sg / a.C);
             const uint32_t *__restrict__ soff = a.seg_off + (int64_t)i * (a.C + 1);
             const uint32_t s0 = soff[sg % a.C], s1 = soff[sg % a.C + 1];
-            j0 = s0 + (uint32_t)(t & 1) * kSplitTile;
+            j0 = s0 + (uint32_t)(t % kTilesPerBig) * kSplitTile;
             jend = (j0 + kSplitTile < s1) ? j0 + kSplitTile : s1;
             if (j0 >= s1)
                 continue;

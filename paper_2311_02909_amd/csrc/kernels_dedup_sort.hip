@@ -9,7 +9,7 @@
 //          per-minibatch kernel of kernels_dedup.hip does the hop instead
 //   split  per tile: counting sort by segment in LDS, every segment's run appended with wide stores
 //   sort   per (minibatch, segment): the pairs are sorted by id -- up to 1024 pairs by one wave in
-//          registers, up to 4096 by a workgroup in LDS (bitonic networks); head flags + scan give
+//          registers, up to 16384 by a workgroup in LDS (bitonic networks); head flags + scan give
 //          the rank among the segment's distinct ids; every pair becomes (segment, rank,
 //          position), the distinct ids are written in rank order at the head of the segment's slots
 //   base   per minibatch: scan of the segments' distinct counts
@@ -438,11 +438,13 @@ __global__ __launch_bounds__(256) void dd_sort_wave_kernel(DedupArgs a)
 template __global__ void dd_sort_wave_kernel<false>(DedupArgs);
 template __global__ void dd_sort_wave_kernel<true>(DedupArgs);
 
-// One workgroup per (minibatch, segment) of 1025..4096 pairs: sort in LDS.
-__global__ __launch_bounds__(256) void dd_sort_kernel(DedupArgs a)
+// One workgroup per (minibatch, segment) of 1025..kSegCap pairs: sort in LDS (dynamic: 8 bytes per pair of
+// the padded segment, at most 128 KB).
+constexpr int kBigThreads = 1024;
+__global__ __launch_bounds__(kBigThreads) void dd_sort_kernel(DedupArgs a)
 {
-    __shared__ uint64_t key[kSegCap];
-    __shared__ uint32_t smem[4];
+    extern __shared__ uint64_t key[]; // kSegCap
+    __shared__ uint32_t smem[kBigThreads / kWave];
     if (*a.fallback)
         return;
     const int tid = threadIdx.x;
@@ -456,15 +458,15 @@ __global__ __launch_bounds__(256) void dd_sort_kernel(DedupArgs a)
         const int64_t e0 = a.mb_edgeoff[i];
         uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
         uint32_t *__restrict__ uids = reinterpret_cast<uint32_t *>(a.utmp) + e0 + s0;
-        uint32_t M = 256; // sorted size: power of two >= m, at least one element per lane
+        uint32_t M = kBigThreads; // sorted size: power of two >= m, at least one element per lane
         while (M < m)
             M <<= 1;
-        for (uint32_t j = tid; j < M; j += 256)
+        for (uint32_t j = tid; j < M; j += kBigThreads)
             key[j] = j < m ? pairs[j] : kNoEntry;
         __syncthreads();
         for (uint32_t size = 2; size <= M; size <<= 1) {
             for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-                for (uint32_t t = tid; t < (M >> 1); t += 256) {
+                for (uint32_t t = tid; t < (M >> 1); t += kBigThreads) {
                     const uint32_t lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
                     const uint32_t hi = lo | stride;
                     const uint64_t x = key[lo], y = key[hi];
@@ -477,13 +479,13 @@ __global__ __launch_bounds__(256) void dd_sort_kernel(DedupArgs a)
             }
         }
         // lane t owns sorted slots [t*per, (t+1)*per)
-        const uint32_t per = M >> 8;
+        const uint32_t per = M / kBigThreads;
         const uint32_t j_lo = tid * per;
         uint32_t heads = 0;
         for (uint32_t j = j_lo; j < j_lo + per && j < m; ++j)
             heads += (j == 0 || (uint32_t)(key[j] >> 32) != (uint32_t)(key[j - 1] >> 32)) ? 1u : 0u;
         uint32_t cnt;
-        uint32_t rank = block_exclusive_scan<uint32_t, 256>(heads, smem, cnt); // heads before my slots
+        uint32_t rank = block_exclusive_scan<uint32_t, kBigThreads>(heads, smem, cnt); // heads before my slots
         for (uint32_t j = j_lo; j < j_lo + per && j < m; ++j) {
             const uint64_t e = key[j];
             const uint32_t id = (uint32_t)(e >> 32);
@@ -558,7 +560,17 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
     mark("dd_sort");
     hipLaunchKernelGGL(dd_sort_wave_kernel<false>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 4)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_sort_wave_kernel<true>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 2)), dim3(256), 0, L.stream, a);
-    hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 4)), dim3(256), 0, L.stream, a);
+    { // segments of more than 1024 pairs: rare, one workgroup with 128 KB of LDS each
+        static bool big_attr_set = false;
+        const size_t lds = (size_t)kSegCap * sizeof(uint64_t);
+        if (!big_attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_sort_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
+            big_attr_set = true;
+        }
+        hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 1)), dim3(kBigThreads), lds, L.stream, a);
+    }
     hipLaunchKernelGGL(dd_base_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
 }
 

@@ -209,9 +209,9 @@ def test_sort_extract_falls_back_when_ids_crowd_one_segment(mods):
     # lands in one id-range segment, which cannot be sorted in LDS -> the per-minibatch kernel runs
     O, bms, _ = mods
     rng = np.random.default_rng(45)
-    n, m = 3_000_000, 600_000
+    n, m = 1_000_000, 3_000_000
     src = rng.integers(0, n, size=m)
-    dst = rng.integers(1000, 60_000, size=m)
+    dst = rng.integers(1000, 5_000, size=m)     # narrower than any segment the library would pick
     key = np.unique(src * n + dst)
     rowptr = np.zeros(n + 1, dtype=np.int64)
     np.add.at(rowptr, key // n + 1, 1)
@@ -220,10 +220,11 @@ def test_sort_extract_falls_back_when_ids_crowd_one_segment(mods):
     sources = np.nonzero(np.diff(rowptr))[0]
     csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
     batches = random_batches(n, 3, 8000, rng, candidates=sources)
-    ref = O.sample_nodewise(rowptr, col, batches, (3, 2), 9)
-    assert ref[0].nnz > 3 * 4096      # more pairs per minibatch than one LDS segment holds
+    ref = O.sample_nodewise(rowptr, col, batches, (6, 2), 9)
+    per_mb = np.diff(ref[0].rowptr[ref[0].mb_rowoff])
+    assert per_mb.min() > 16384       # more pairs in the one segment than a workgroup sorts in LDS
     for extract in ("sort", "buckets", "bitmap"):
-        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 2), 9, extract=extract)
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (6, 2), 9, extract=extract)
         assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
 
 
@@ -279,6 +280,32 @@ def test_sort_extract_segments_sorted_by_whole_workgroups(mods):
     assert 1024 < per_segment.max() <= 4096, per_segment.max()
     for extract in ("sort", None):
         res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 2), 11, extract=extract)
+        assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
+
+
+def test_sort_extract_largest_workgroup_sorted_segments(mods):
+    # as above with most edges into ONE id range of 2^16: its segment holds more than 4096 and at most 16384 pairs,
+    # the largest class a workgroup sorts in LDS (several tiles of the back-split per segment)
+    O, bms, _ = mods
+    rng = np.random.default_rng(49)
+    n, m = 3_000_000, 1_200_000
+    src = rng.integers(0, n, size=m)
+    dst = np.where(rng.random(m) < 0.7, rng.integers(1 << 16, 2 << 16, size=m), rng.integers(0, n, size=m))
+    key = np.unique(src * n + dst)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rowptr, key // n + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    col = (key % n).astype(np.int32)
+    sources = np.nonzero(np.diff(rowptr))[0]
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    batches = random_batches(n, 5, 8000, rng, candidates=sources)
+    ref = O.sample_nodewise(rowptr, col, batches, (3, 2), 12)
+    for i in range(5):
+        e0, e1 = ref[0].rowptr[ref[0].mb_rowoff[i]], ref[0].rowptr[ref[0].mb_rowoff[i + 1]]
+        per_segment = np.bincount(ref[0].col_vertex[ref[0].mb_coloff[i] + ref[0].col[e0:e1]] >> 16)
+        assert 4096 < per_segment.max() <= 16384, per_segment.max()
+    for extract in ("sort", None):
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 2), 12, extract=extract)
         assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
 
 
