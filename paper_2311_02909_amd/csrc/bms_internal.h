@@ -118,7 +118,7 @@ struct DedupArgs {
 };
 constexpr int kSplitTile16 = 16384; // sampled ids per tile of the count and split kernels (128 KB of LDS staging:
                                     // long runs per segment)
-constexpr int kSegCap = 16384;      // pairs of one segment that a workgroup sorts in LDS (128 KB)
+constexpr int kSegCap = 65535;      // most pairs a segment may hold: the rank of an id inside its segment has 16 bits
 constexpr int kMaxSegments = 2560;  // 3 words each beside the split kernel's staging must fit in 160 KB of LDS
 void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz, const StageMark &mark);
 // returns 0, or -1 when the launch was refused (then nothing ran)

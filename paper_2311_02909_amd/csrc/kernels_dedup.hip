@@ -352,34 +352,34 @@ __device__ inline void dedup_split_pass(const DedupArgs &a, int big_segments, ui
         if (!__syncthreads_or(any))
             return;
     }
-    constexpr int kTilesPerBig = kSegCap / kSplitTile; // a listed segment holds at most this many tiles of entries
-    const int64_t ntiles = big_segments ? kTilesPerBig * (int64_t)*a.big_count : a.split_tileoff[a.k];
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    // units of work: tiles of kSplitTile entries, or listed segments (walked tile by tile by one workgroup)
+    const int64_t nunits = big_segments ? (int64_t)*a.big_count : a.split_tileoff[a.k];
+    for (int64_t unit = blockIdx.x; unit < nunits; unit += gridDim.x) {
         int i;
-        uint32_t j0, jend;
+        uint32_t jb, je;
         if (big_segments) {
-            const int64_t sg = a.big_list[t / kTilesPerBig];
+            const int64_t sg = a.big_list[unit];
             i = (int)(sg / a.C);
             const uint32_t *__restrict__ soff = a.seg_off + (int64_t)i * (a.C + 1);
-            const uint32_t s0 = soff[sg % a.C], s1 = soff[sg % a.C + 1];
-            j0 = s0 + (uint32_t)(t % kTilesPerBig) * kSplitTile;
-            jend = (j0 + kSplitTile < s1) ? j0 + kSplitTile : s1;
-            if (j0 >= s1)
-                continue;
+            jb = soff[sg % a.C];
+            je = soff[sg % a.C + 1];
         } else {
-            i = locate_segment(a.split_tileoff, a.k, t);
-            j0 = (uint32_t)(t - a.split_tileoff[i]) * kSplitTile;
+            i = locate_segment(a.split_tileoff, a.k, unit);
+            jb = (uint32_t)(unit - a.split_tileoff[i]) * kSplitTile;
+            je = jb + kSplitTile;
         }
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
         const uint32_t Q = (N + kPlaceTile - 1) >> kPlaceShift;
         if (!big_segments) {
-            jend = (j0 + kSplitTile < N) ? j0 + kSplitTile : N;
+            je = je < N ? je : N;
             if (sorted && Q <= kMaxPlaceTiles)
                 continue; // already split by the sorting waves (and by the big_segments pass)
         } else if (Q > kMaxPlaceTiles) {
             continue; // stored directly by the pass over all tiles
         }
+        for (uint32_t j0 = jb; j0 < je; j0 += kSplitTile) {
+        const uint32_t jend = (j0 + kSplitTile < je) ? j0 + kSplitTile : je;
         const uint64_t *__restrict__ pairs = a.pairs + e0;
         uint64_t ent[kSplitTile / 256];
 #pragma unroll
@@ -423,6 +423,7 @@ __device__ inline void dedup_split_pass(const DedupArgs &a, int big_segments, ui
             back[r * kPlaceTile + gpos[r] + (sidx - off[r])] = e;
         }
         __syncthreads();
+        }
     }
 }
 

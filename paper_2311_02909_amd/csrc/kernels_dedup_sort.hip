@@ -9,7 +9,7 @@
 //          per-minibatch kernel of kernels_dedup.hip does the hop instead
 //   split  per tile: counting sort by segment in LDS, every segment's run appended with wide stores
 //   sort   per (minibatch, segment): the pairs are sorted by id -- up to 1024 pairs by one wave in
-//          registers, up to 16384 by a workgroup in LDS (bitonic networks); head flags + scan give
+//          registers (bitonic network; more pairs: ranked by a workgroup through a bitmap in LDS); head flags + scan give
 //          the rank among the segment's distinct ids; every pair becomes (segment, rank,
 //          position), the distinct ids are written in rank order at the head of the segment's slots
 //   base   per minibatch: scan of the segments' distinct counts
@@ -438,16 +438,35 @@ __global__ __launch_bounds__(256) void dd_sort_wave_kernel(DedupArgs a)
 template __global__ void dd_sort_wave_kernel<false>(DedupArgs);
 template __global__ void dd_sort_wave_kernel<true>(DedupArgs);
 
-// One workgroup per (minibatch, segment) of 1025..kSegCap pairs: sort in LDS (dynamic: 8 bytes per pair of
-// the padded segment, at most 128 KB).
+// One workgroup per (minibatch, segment) of more than 1024 pairs (ids crowded into the segment's range, or one id
+// sampled by many rows): no sort.  The segment spans 2^cshift ids, so a bitmap of that many bits in LDS
+// (at most 128 KB) takes every pair's id; the rank of an id among the distinct ones is the number of set bits
+// below it (a running count per group of 8 words + popcounts inside the group), the distinct ids in rank
+// order are the set bits in order.  The pairs are read twice from memory and never held in LDS, so the
+// cost grows with the number of pairs only linearly and a segment may hold up to kSegCap of them
+// (the rank field of an entry has 16 bits).
 constexpr int kBigThreads = 1024;
+constexpr int kRankGroup = 8; // bitmap words per running count
+size_t dd_rank_lds_bytes(int cshift)
+{
+    size_t words = ((size_t)1 << cshift) / 32;
+    if (words < (size_t)kRankGroup)
+        words = kRankGroup;
+    return words * sizeof(uint32_t) + (words / kRankGroup) * sizeof(uint32_t);
+}
+
 __global__ __launch_bounds__(kBigThreads) void dd_sort_kernel(DedupArgs a)
 {
-    extern __shared__ uint64_t key[]; // kSegCap
+    extern __shared__ uint32_t rank_lds[]; // bitmap words, then one running count per kRankGroup words
     __shared__ uint32_t smem[kBigThreads / kWave];
     if (*a.fallback)
         return;
     const int tid = threadIdx.x;
+    uint32_t nw = (1u << a.cshift) / 32u;
+    if (nw < (uint32_t)kRankGroup)
+        nw = kRankGroup;
+    const uint32_t ng = nw / kRankGroup;
+    uint32_t *bm = rank_lds, *before = rank_lds + nw;
     const uint32_t nbig = *a.big_count;
     for (uint32_t x = blockIdx.x; x < nbig; x += gridDim.x) {
         const int64_t sg = a.big_list[x];
@@ -458,42 +477,46 @@ __global__ __launch_bounds__(kBigThreads) void dd_sort_kernel(DedupArgs a)
         const int64_t e0 = a.mb_edgeoff[i];
         uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
         uint32_t *__restrict__ uids = reinterpret_cast<uint32_t *>(a.utmp) + e0 + s0;
-        uint32_t M = kBigThreads; // sorted size: power of two >= m, at least one element per lane
-        while (M < m)
-            M <<= 1;
-        for (uint32_t j = tid; j < M; j += kBigThreads)
-            key[j] = j < m ? pairs[j] : kNoEntry;
+        const uint32_t id0 = c << a.cshift;
+        for (uint32_t q = tid; q < nw; q += kBigThreads)
+            bm[q] = 0;
         __syncthreads();
-        for (uint32_t size = 2; size <= M; size <<= 1) {
-            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-                for (uint32_t t = tid; t < (M >> 1); t += kBigThreads) {
-                    const uint32_t lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
-                    const uint32_t hi = lo | stride;
-                    const uint64_t x = key[lo], y = key[hi];
-                    if ((x > y) == ((lo & size) == 0)) {
-                        key[lo] = y;
-                        key[hi] = x;
-                    }
+        for (uint32_t j = tid; j < m; j += kBigThreads) {
+            const uint32_t b = (uint32_t)(pairs[j] >> 32) - id0;
+            atomicOr(&bm[b >> 5], 1u << (b & 31u));
+        }
+        __syncthreads();
+        // set bits before every group of kRankGroup words: groups dealt to the threads in contiguous runs
+        const uint32_t per = (ng + kBigThreads - 1) / kBigThreads;
+        const uint32_t g_lo = tid * per, g_hi = (g_lo + per < ng) ? g_lo + per : ng;
+        uint32_t mine = 0;
+        for (uint32_t g = g_lo; g < g_hi; ++g)
+#pragma unroll
+            for (int q = 0; q < kRankGroup; ++q)
+                mine += __popc(bm[g * kRankGroup + q]);
+        uint32_t cnt;
+        uint32_t run = block_exclusive_scan<uint32_t, kBigThreads>(mine, smem, cnt);
+        for (uint32_t g = g_lo; g < g_hi; ++g) {
+            before[g] = run;
+            // the distinct ids of this group in rank order
+            for (int q = 0; q < kRankGroup; ++q) {
+                uint32_t wbits = bm[g * kRankGroup + q];
+                while (wbits) {
+                    const uint32_t bit = (uint32_t)__ffs((int)wbits) - 1u;
+                    uids[run++] = id0 + (g * kRankGroup + q) * 32u + bit;
+                    wbits &= wbits - 1u;
                 }
-                __syncthreads();
             }
         }
-        // lane t owns sorted slots [t*per, (t+1)*per)
-        const uint32_t per = M / kBigThreads;
-        const uint32_t j_lo = tid * per;
-        uint32_t heads = 0;
-        for (uint32_t j = j_lo; j < j_lo + per && j < m; ++j)
-            heads += (j == 0 || (uint32_t)(key[j] >> 32) != (uint32_t)(key[j - 1] >> 32)) ? 1u : 0u;
-        uint32_t cnt;
-        uint32_t rank = block_exclusive_scan<uint32_t, kBigThreads>(heads, smem, cnt); // heads before my slots
-        for (uint32_t j = j_lo; j < j_lo + per && j < m; ++j) {
-            const uint64_t e = key[j];
-            const uint32_t id = (uint32_t)(e >> 32);
-            const bool head = j == 0 || id != (uint32_t)(key[j - 1] >> 32);
-            rank += head ? 1u : 0u; // inclusive count of heads
-            pairs[j] = pack_entry((uint32_t)e, rank - 1u, c);
-            if (head)
-                uids[rank - 1u] = id;
+        __syncthreads();
+        for (uint32_t j = tid; j < m; j += kBigThreads) {
+            const uint64_t p = pairs[j];
+            const uint32_t b = (uint32_t)(p >> 32) - id0;
+            const uint32_t w = b >> 5, g = w / kRankGroup;
+            uint32_t rank = before[g] + __popc(bm[w] & ((1u << (b & 31u)) - 1u));
+            for (uint32_t q = g * kRankGroup; q < w; ++q)
+                rank += __popc(bm[q]);
+            pairs[j] = pack_entry((uint32_t)p, rank, c);
         }
         if (tid == 0)
             a.seg_cnt[sg] = cnt;
@@ -560,16 +583,16 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, co
     mark("dd_sort");
     hipLaunchKernelGGL(dd_sort_wave_kernel<false>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 4)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(dd_sort_wave_kernel<true>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 2)), dim3(256), 0, L.stream, a);
-    { // segments of more than 1024 pairs: rare, one workgroup with 128 KB of LDS each
+    { // segments of more than 1024 pairs: ranked through a bitmap of the segment's id range in LDS
         static bool big_attr_set = false;
-        const size_t lds = (size_t)kSegCap * sizeof(uint64_t);
         if (!big_attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_sort_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)dd_rank_lds_bytes(20)) != hipSuccess)
                 (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
             big_attr_set = true;
         }
-        hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 1)), dim3(kBigThreads), lds, L.stream, a);
+        hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 2)), dim3(kBigThreads),
+                           dd_rank_lds_bytes(a.cshift), L.stream, a);
     }
     hipLaunchKernelGGL(dd_base_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
 }

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from conftest import random_batches, random_csr
+from conftest import random_batches, random_csr, skewed_csr
 from parity import assert_hops_equal
 
 pytestmark = pytest.mark.gpu
@@ -205,13 +205,13 @@ def test_bucket_extract_many_buckets_and_large_batches(mods):
 
 
 def test_sort_extract_falls_back_when_ids_crowd_one_segment(mods):
-    # directed graph whose edges all point into a narrow id range: every sampled id of a minibatch
-    # lands in one id-range segment, which cannot be sorted in LDS -> the per-minibatch kernel runs
+    # directed graph whose edges all point into a narrow id range: every sampled id of a minibatch lands in one
+    # id-range segment, more than a segment may hold -> the per-minibatch kernel runs
     O, bms, _ = mods
     rng = np.random.default_rng(45)
-    n, m = 1_000_000, 3_000_000
+    n, m = 1_000_000, 8_000_000
     src = rng.integers(0, n, size=m)
-    dst = rng.integers(1000, 5_000, size=m)     # narrower than any segment the library would pick
+    dst = rng.integers(1030, 2000, size=m)     # narrower than any segment the library would pick
     key = np.unique(src * n + dst)
     rowptr = np.zeros(n + 1, dtype=np.int64)
     np.add.at(rowptr, key // n + 1, 1)
@@ -219,12 +219,12 @@ def test_sort_extract_falls_back_when_ids_crowd_one_segment(mods):
     col = (key % n).astype(np.int32)
     sources = np.nonzero(np.diff(rowptr))[0]
     csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
-    batches = random_batches(n, 3, 8000, rng, candidates=sources)
-    ref = O.sample_nodewise(rowptr, col, batches, (6, 2), 9)
+    batches = random_batches(n, 3, 12000, rng, candidates=sources)
+    ref = O.sample_nodewise(rowptr, col, batches, (8, 2), 9)
     per_mb = np.diff(ref[0].rowptr[ref[0].mb_rowoff])
-    assert per_mb.min() > 16384       # more pairs in the one segment than a workgroup sorts in LDS
+    assert per_mb.min() > 65535       # more pairs in the one segment than a segment may hold
     for extract in ("sort", "buckets", "bitmap"):
-        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (6, 2), 9, extract=extract)
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (8, 2), 9, extract=extract)
         assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
 
 
@@ -284,8 +284,8 @@ def test_sort_extract_segments_sorted_by_whole_workgroups(mods):
 
 
 def test_sort_extract_largest_workgroup_sorted_segments(mods):
-    # as above with most edges into ONE id range of 2^16: its segment holds more than 4096 and at most 16384 pairs,
-    # the largest class a workgroup sorts in LDS (several tiles of the back-split per segment)
+    # as above with most edges into ONE id range of 2^16: its segment holds several thousand pairs (several tiles
+    # of the back-split per segment), ranked by a workgroup through a bitmap in LDS
     O, bms, _ = mods
     rng = np.random.default_rng(49)
     n, m = 3_000_000, 1_200_000
@@ -307,6 +307,36 @@ def test_sort_extract_largest_workgroup_sorted_segments(mods):
     for extract in ("sort", None):
         res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (3, 2), 12, extract=extract)
         assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
+
+
+def test_vertex_ids_sorted_by_degree(mods):
+    # hubs first: the sampled ids of every minibatch crowd the low end of the id range, so many id-range
+    # segments hold far more pairs than a wave sorts and are ranked through LDS bitmaps, others stay small
+    O, bms, _ = mods
+    rng = np.random.default_rng(50)
+    n = 400_000
+    rowptr, col = skewed_csr(n, 6_000_000, rng)
+    deg = np.diff(rowptr)
+    order = np.argsort(-deg, kind="stable")
+    newid = np.empty(n, dtype=np.int64)
+    newid[order] = np.arange(n)
+    src = np.repeat(np.arange(n), deg)
+    key = np.sort(newid[src] * n + newid[col])
+    rowptr2 = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rowptr2, key // n + 1, 1)
+    rowptr2 = np.cumsum(rowptr2)
+    col2 = (key % n).astype(np.int32)
+    batches = random_batches(n, 6, 2000, rng, candidates=np.nonzero(np.diff(rowptr2) > 0)[0])
+    ref = O.sample_nodewise(rowptr2, col2, batches, (10, 5, 3), 13)
+    e1 = ref[2].rowptr[ref[2].mb_rowoff[1]]
+    first = ref[2].col_vertex[ref[2].col[:e1]]                  # global ids sampled by minibatch 0 at the last hop
+    assert (first < n // 100).mean() > 0.08                      # ten times denser among the top 1 % of the ids
+    assert np.bincount(first >> 9).max() > 2048                  # far more than a wave sorts, in ranges of 512 ids
+    csr = bms.Csr(torch.from_numpy(rowptr2).cuda(), torch.from_numpy(col2).cuda())
+    res = None
+    for extract in ("sort", None, "buckets"):
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (10, 5, 3), 13, extract=extract, recycle=res)
+        assert_hops_equal(res.hops(), ref, what="degree-sorted ids, extract=%s" % extract)
 
 
 def test_minibatch_with_more_sampled_edges_than_the_slot_lists_cover(mods):
