@@ -553,7 +553,9 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
     __shared__ uint32_t hkey[kHashSlots];
     __shared__ uint16_t hval[kHashSlots];
     __shared__ uint32_t maybe[kFilterWords]; // bit h set: some sampled column hashes to h
+    __shared__ uint32_t queue_all[kExtWaves * 2 * kWave]; // per wave: neighbours that passed the filter, in row order
     const int i = blockIdx.y, tid = threadIdx.x, lane = tid & (kWave - 1);
+    uint32_t *queue = queue_all + (tid / kWave) * 2 * kWave;
     const int64_t c0 = a.mb_coloff[i];
     const int32_t ns = (int32_t)(a.mb_coloff[i + 1] - c0);
     const int64_t x0 = a.mb_gtileoff[i], ntiles = a.mb_gtileoff[i + 1] - x0;
@@ -592,6 +594,36 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
             (void)re;
             int32_t *__restrict__ out = a.xtmp + g; // the kept neighbours of a piece start where the piece starts
             uint32_t kept = 0;
+            uint32_t qn = 0; // neighbours waiting in the wave's queue (the same in every lane)
+            // looks the first n <= 64 queued neighbours up in the table, appends the local columns of those found
+            // to the piece's output in queue order, and moves the rest of the queue down
+            auto drain = [&](uint32_t n) {
+                __builtin_amdgcn_wave_barrier();
+                const uint32_t val = (uint32_t)lane < n ? queue[lane] : kEmptySlot;
+                int32_t local = -1;
+                if (val != kEmptySlot) {
+                    uint32_t slot = ldw_hash(val) & (kHashSlots - 1);
+                    uint32_t kx;
+                    while ((kx = hkey[slot]) != kEmptySlot) {
+                        if (kx == val) {
+                            local = hval[slot];
+                            break;
+                        }
+                        slot = (slot + 1) & (kHashSlots - 1);
+                    }
+                }
+                const uint64_t found = __ballot(local >= 0);
+                if (local >= 0)
+                    out[kept + __popcll(found & below)] = local;
+                kept += __popcll(found);
+                const uint32_t rest = qn - n;
+                const uint32_t moved = (uint32_t)lane < rest ? queue[kWave + lane] : 0u;
+                __builtin_amdgcn_wave_barrier();
+                if ((uint32_t)lane < rest)
+                    queue[lane] = moved;
+                qn = rest;
+                __builtin_amdgcn_wave_barrier();
+            };
             for (int64_t p0 = g; p0 < pe; p0 += kStreamUnroll * kWave) {
                 const int32_t *__restrict__ from = a.A_col + (shift + p0); // slot x of the step is position p0 + x
                 const int32_t nslots = (int32_t)min<int64_t>(pe - p0, kStreamUnroll * kWave);
@@ -602,8 +634,9 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
                     v[u] = x < nslots ? (uint32_t)from[x] : kEmptySlot;
                 }
                 // almost no neighbour is a sampled column: one bit per hash value answers "certainly not" for
-                // nearly all of them with a single LDS read each (all of a step's reads in flight together);
-                // the table is searched only for the few that pass
+                // nearly all of them with a single LDS read each (all of a step's reads in flight together).
+                // The few that pass are queued in row order; the table is searched a full wave of them at a
+                // time (and at the end of the piece), not step by step
                 uint32_t word[kStreamUnroll];
 #pragma unroll
                 for (int u = 0; u < kStreamUnroll; ++u)
@@ -611,26 +644,18 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
 #pragma unroll
                 for (int u = 0; u < kStreamUnroll; ++u) {
                     const bool pass = v[u] != kEmptySlot && ((word[u] >> (ldw_hash(v[u]) & 31u)) & 1u);
-                    if (__ballot(pass) == 0)
+                    const uint64_t pm = __ballot(pass);
+                    if (pm == 0)
                         continue;
-                    int32_t local = -1;
-                    if (pass) {
-                        uint32_t slot = ldw_hash(v[u]) & (kHashSlots - 1);
-                        uint32_t kx;
-                        while ((kx = hkey[slot]) != kEmptySlot) {
-                            if (kx == v[u]) {
-                                local = hval[slot];
-                                break;
-                            }
-                            slot = (slot + 1) & (kHashSlots - 1);
-                        }
-                    }
-                    const uint64_t m = __ballot(local >= 0);
-                    if (local >= 0)
-                        out[kept + __popcll(m & below)] = local;
-                    kept += __popcll(m);
+                    if (pass)
+                        queue[qn + __popcll(pm & below)] = v[u];
+                    qn += __popcll(pm);
+                    if (qn >= (uint32_t)kWave)
+                        drain(kWave);
                 }
             }
+            while (qn)
+                drain(qn < (uint32_t)kWave ? qn : (uint32_t)kWave);
             if (lane == 0) {
                 if (g == rs)
                     a.first_cnt[r] = kept; // the piece a row starts with
