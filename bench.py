@@ -232,6 +232,16 @@ def main() -> int:
         "timed_in": "the timed steps" if any(name == dominant for name, _ in main_ms) else "extra steps after the timed ones",
         "all_kernels_ms_per_step": {s: round(v["ms"], 4) for s, v in sorted(per_stage.items())},
     }
+    if dominant == "nw_sample":
+        # what bounds this kernel is memory lines per second, not bytes asked for: every sampled neighbour of a long
+        # row is a 4-byte read that costs one 128-byte line.  Reads that share no line run at 3.87e10 /s on this chip
+        # (bench.py --gather-probe 31, profiles/random_gather_probe.txt); short rows and minibatches that work on
+        # the same id range at the same time share lines, which is how the kernel gets past that rate
+        roofline["random_access"] = {
+            "sampled_reads_per_sec": round(edges / (dom["ms"] * 1e-3), 1),
+            "unshared_line_ceiling_reads_per_sec": 3.87e10,
+            "frac": round(edges / (dom["ms"] * 1e-3) / 3.87e10, 4),
+        }
     # whole call: algorithmic bytes of all stages ("effective") and the profiled HBM bytes ("achieved"),
     # both over the sum of the kernel times measured in this run
     kernels_ms = sum(v["ms"] for v in per_stage.values())
