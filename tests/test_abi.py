@@ -42,3 +42,38 @@ def test_error_strings_and_argument_checks_need_no_gpu():
     rc = lib.bms_sample_nodewise(ctypes.addressof(junk), seeds, 1, 2, fan, 1, 0, None, ctypes.byref(out))
     assert rc == bms.EINVAL and not out.value
     lib.bms_free(None)
+
+
+def test_header_compiles_as_c_and_cpp_and_structs_match_the_binding(tmp_path):
+    # the binding mirrors three structs of the header with ctypes: sizes and field offsets must agree
+    import subprocess
+    src = tmp_path / "layout.c"
+    fields = {
+        "bms_opts": [f[0] for f in bms._Opts._fields_],
+        "bms_hop_view": [f[0] for f in bms._HopView._fields_],
+        "bms_mb_view": [f[0] for f in bms._MbView._fields_],
+    }
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "bms.h"', "int main(void) {"]
+    for struct, names in fields.items():
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (struct, struct))
+        for n in names:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (struct, n, struct, n))
+    lines += ["return 0; }"]
+    src.write_text("\n".join(lines))
+    inc = os.path.join(ROOT, "include")
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, "-o", str(exe), str(src)])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc,
+                           os.path.join(inc, "bms.h")])
+    got = dict(line.split() for line in subprocess.check_output([str(exe)], text=True).splitlines())
+    mirrors = {"bms_opts": bms._Opts, "bms_hop_view": bms._HopView, "bms_mb_view": bms._MbView}
+    for struct, cls in mirrors.items():
+        assert int(got[struct]) == ctypes.sizeof(cls), struct
+        for n in fields[struct]:
+            assert int(got["%s.%s" % (struct, n)]) == getattr(cls, n).offset, (struct, n)
+    # and the flag values the binding hard-codes are the header's
+    text = open(os.path.join(inc, "bms.h")).read()
+    for name in ("LADIES_SQUARED", "PROFILE", "EXTRACT_BUCKETS", "EXTRACT_BITMAP", "EXTRACT_SORT", "LADIES_DENSE",
+                 "PROFILE_MAIN", "UNION_DST", "NODEWISE_REPLACE"):
+        m = re.search(r"#define\s+BMS_%s\s+(\d+)u" % name, text)
+        assert m and int(m.group(1)) == getattr(bms, name), name
