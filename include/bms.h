@@ -13,6 +13,8 @@
  * Conventions
  *   - Every function returns BMS_OK (0) or a negative BMS_E* code, never throws and
  *     never aborts.  On error *out is left untouched; bms_last_error() gives detail.
+ *     A result passed in opts->recycle is empty after a failed call (k = L = 0, every
+ *     accessor returns BMS_EINVAL); it stays valid for bms_free and for recycling again.
  *   - Hop h = 0..L-1 counts outward from the seed vertices: hop 0 is the paper's layer
  *     L (the batch vertices), params[0] applies there.
  *   - Pointers marked "device" are HIP device pointers on the current device; "host"
@@ -184,6 +186,8 @@ int bms_result_minibatch(bms_result *res, int32_t hop, int32_t i, bms_mb_view *v
  * The copy is enqueued on `stream` (hipStream_t, NULL = the null stream); the call returns after it has
  * completed.  Rows are copied bit for bit.  An id outside [0, n) gives BMS_ERANGE (its row is written as
  * zeros, the other rows are valid); n < 0, f < 1, m < 0, or a null pointer while m > 0, give BMS_EINVAL.
+ * May be called from several threads at once (each call has its own error flag; up to 64 calls may be in
+ * flight per device).
  */
 int bms_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids, int64_t m, float *out,
                        void *stream);

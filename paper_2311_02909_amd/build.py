@@ -4,13 +4,16 @@ from __future__ import annotations
 import glob
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbms.so")
 
+OBJ_DIR = os.path.join(HERE, "_build")
+
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
@@ -20,11 +23,30 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_lib(verbose: bool = False) -> str:
-    """Compile every HIP source into paper_2311_02909_amd/libbms.so (always recompiles)."""
+def build_lib(verbose: bool = False, incremental: bool = False) -> str:
+    """Compile every HIP source into paper_2311_02909_amd/libbms.so: one object per source (compiled side by
+    side), then one link.  Always recompiles everything unless `incremental` (then only sources newer than their
+    object, or everything when a header changed)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    include = os.path.join(os.path.dirname(HERE), "include")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(include, "*.h"))
+    newest_header = max(os.path.getmtime(h) for h in headers)
+
+    def compile_one(src):
+        obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+            return obj
+        cmd = [hipcc] + HIPCC_FLAGS + ["-I", include, "-c", "-o", obj, src]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+        objs = list(pool.map(compile_one, sources()))
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(os.path.dirname(HERE), "include"), "-o", tmp] + sources()
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", tmp] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
@@ -50,5 +72,6 @@ def build_c_client(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build_lib(verbose=True))
+    import sys
+    print(build_lib(verbose=True, incremental="--incremental" in sys.argv))
     print(build_c_client(verbose=True))

@@ -53,6 +53,12 @@ struct DevBuf {
     void *p = nullptr;
     size_t cap = 0;
     bool grew = false; // set when the last ensure() reallocated
+    DevBuf() = default;
+    // a buffer that belongs to a handle enters the handle's list, which is what bms_free walks
+    explicit DevBuf(std::vector<DevBuf *> *owner_list) { owner_list->push_back(this); }
+    DevBuf(const DevBuf &) = delete;
+    DevBuf &operator=(const DevBuf &) = delete;
+    DevBuf(DevBuf &&o) noexcept : p(o.p), cap(o.cap), grew(o.grew) { o.p = nullptr; o.cap = 0; } // hop buffers in a vector
     int ensure(size_t bytes)
     {
         grew = false;
@@ -100,16 +106,22 @@ struct bms_csr {
     int64_t n = 0, nnz = 0, max_degree = 0;
     const int64_t *rowptr = nullptr;
     const int32_t *col = nullptr;
-    DevBuf own_rowptr, own_col;
+    std::vector<DevBuf *> bufs; // every device buffer below registers here (declared first: built first)
+#define BMS_BUF(name) DevBuf name{&bufs}
+    BMS_BUF(own_rowptr); BMS_BUF(own_col);
     // scratch reused across calls
-    DevBuf vs_words, vs_prefix, vs_chunks;
+    BMS_BUF(vs_words); BMS_BUF(vs_prefix); BMS_BUF(vs_chunks);
     bool vs_clean = false; // all words zero
-    DevBuf row_beg, row_deg, tile_off, mb_tileoff, scalars, scan_tmp;
-    DevBuf ld_counters, ld_gather_off, ld_row_mb, ld_chunks, ld_prefix, ld_ptileoff, ld_tilesum;
-    DevBuf dd_pairs, dd_utmp, dd_uniq, dd_edgeoff, dd_count, dd_back, dd_tileoff, dd_cursor, dd_seg; // bucket EXTRACT
-    DevBuf un_rowptr, un_col; // BMS_UNION_DST: the hop's CSR while its rows still carry their own vertex
-    DevBuf row_cnt;           // BMS_NODEWISE_REPLACE with a fanout above 32: distinct picks per row
-    DevBuf lw_bounds, lw_win, lw_tmpcol, lw_tmpcnt, lw_sel, lw_xtmp, lw_count, lw_tiles, lw_rowcnt; // LADIES by LDS windows
+    BMS_BUF(row_beg); BMS_BUF(row_deg); BMS_BUF(tile_off); BMS_BUF(mb_tileoff); BMS_BUF(scalars); BMS_BUF(scan_tmp);
+    BMS_BUF(ld_counters); BMS_BUF(ld_gather_off); BMS_BUF(ld_row_mb); BMS_BUF(ld_chunks); BMS_BUF(ld_prefix);
+    BMS_BUF(ld_ptileoff); BMS_BUF(ld_tilesum);
+    BMS_BUF(dd_pairs); BMS_BUF(dd_utmp); BMS_BUF(dd_uniq); BMS_BUF(dd_edgeoff); BMS_BUF(dd_count); BMS_BUF(dd_back);
+    BMS_BUF(dd_tileoff); BMS_BUF(dd_cursor); BMS_BUF(dd_seg); // EXTRACT
+    BMS_BUF(un_rowptr); BMS_BUF(un_col); // BMS_UNION_DST: the hop's CSR while its rows still carry their own vertex
+    BMS_BUF(row_cnt);                    // BMS_NODEWISE_REPLACE with a fanout above 32: distinct picks per row
+    BMS_BUF(lw_bounds); BMS_BUF(lw_win); BMS_BUF(lw_tmpcol); BMS_BUF(lw_tmpcnt); BMS_BUF(lw_sel); BMS_BUF(lw_xtmp);
+    BMS_BUF(lw_count); BMS_BUF(lw_tiles); BMS_BUF(lw_rowcnt); // LADIES by LDS windows
+#undef BMS_BUF
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
 };
@@ -362,6 +374,15 @@ int abort_call(CallCtx &c, int rc)
     if (c.fresh_result && c.res) {
         result_release(c.res);
         delete c.res;
+    } else if (c.res) {
+        // a recycled result is left empty: its buffers may have been reallocated while the views still held the old
+        // pointers and sizes, so no accessor may hand them out (the handle stays valid for bms_free and for recycling)
+        for (auto &h : c.res->hops)
+            h.view = bms_hop_view{};
+        c.res->L = 0;
+        c.res->k = 0;
+        c.res->hint_csr = nullptr;
+        c.res->mb_offsets.clear();
     }
     c.res = nullptr;
     return rc;
@@ -422,7 +443,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     // EXTRACT strategy: LDS sorts of id-range segments (with the per-minibatch bin kernel as the
     // fallback for crowded id ranges) whenever the bin table of that fallback fits in LDS; the
     // per-minibatch bitmaps over [0,n) in HBM otherwise.
-    const int64_t nbuckets = (csr->n + (1LL << kBucketBits) - 1) >> kBucketBits;
+    const int64_t nbuckets = std::max<int64_t>((csr->n + (1LL << kBucketBits) - 1) >> kBucketBits, 1);
     bool buckets = true;
     bool seg_sort = true; // with buckets: sort id-range segments in LDS, per-minibatch kernel as fallback
     if (c.flags & BMS_EXTRACT_SORT)
@@ -1218,12 +1239,7 @@ void bms_free(void *handle)
     if (tag == kTagCsr) {
         bms_csr *c = static_cast<bms_csr *>(handle);
         (void)hipSetDevice(c->device);
-        DevBuf *bufs[] = {&c->own_rowptr, &c->own_col,    &c->vs_words,   &c->vs_prefix,     &c->vs_chunks,
-                          &c->row_beg,    &c->row_deg,    &c->tile_off,   &c->mb_tileoff,    &c->scalars, &c->scan_tmp,
-                          &c->ld_counters, &c->ld_gather_off, &c->ld_row_mb, &c->ld_chunks, &c->ld_prefix,
-                          &c->ld_ptileoff, &c->ld_tilesum, &c->dd_pairs, &c->dd_utmp, &c->dd_uniq, &c->dd_edgeoff, &c->dd_count, &c->dd_back, &c->dd_tileoff, &c->dd_cursor, &c->dd_seg,
-                          &c->lw_bounds, &c->lw_win, &c->lw_tmpcol, &c->lw_tmpcnt, &c->lw_sel, &c->lw_xtmp, &c->lw_count, &c->lw_tiles, &c->lw_rowcnt};
-        for (DevBuf *b : bufs)
+        for (DevBuf *b : c->bufs)
             b->release();
         if (c->host_pinned)
             (void)hipHostFree(c->host_pinned);
@@ -1247,8 +1263,12 @@ int bms_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids,
         return fail(BMS_EINVAL, "null argument");
     int device = 0;
     HIP_TRY(hipGetDevice(&device));
-    // one error flag per device in host memory that the kernel can write: nothing to allocate per call
+    // error flags in host memory that the kernel can write (nothing to allocate per call): a ring of kFlagSlots
+    // words per device, one slot per call, so that fetches running at the same time on different streams do not
+    // share a flag (a slot is reused after kFlagSlots further calls on the device)
+    constexpr int kFlagSlots = 64;
     static int32_t *flags[64] = {nullptr};
+    static uint32_t next_slot[64] = {0};
     static std::mutex flags_lock;
     int32_t *flag = nullptr;
     {
@@ -1256,8 +1276,8 @@ int bms_fetch_features(const float *H, int64_t n, int32_t f, const int32_t *ids,
         if (device < 0 || device >= 64)
             return fail(BMS_EINVAL, "device ordinal %d not supported", device);
         if (!flags[device])
-            HIP_TRY(hipHostMalloc((void **)&flags[device], 64, hipHostMallocMapped));
-        flag = flags[device];
+            HIP_TRY(hipHostMalloc((void **)&flags[device], kFlagSlots * sizeof(int32_t), hipHostMallocMapped));
+        flag = flags[device] + (next_slot[device]++ % kFlagSlots);
     }
     int32_t *flag_dev = nullptr;
     HIP_TRY(hipHostGetDevicePointer((void **)&flag_dev, flag, 0));

@@ -268,8 +268,10 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
         const int64_t base = a.tile_off[t];
         if (valid)
             a.out_rowptr[r] = base + loc;
-        if (valid && a.self_entry)
-            stage[loc + cnt] = a.row_vertex[r];
+        if (valid && a.self_entry) { // a seed outside [0, n) is reported by the seed check; EXTRACT still gets a valid id
+            const int32_t self = a.row_vertex[r];
+            stage[loc + cnt] = (self >= 0 && (int64_t)self < a.n) ? self : 0;
+        }
         if (REPLACE) {
             if (cnt > 0) {
                 const int32_t *__restrict__ src = a.A_col + beg;
@@ -364,8 +366,11 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
             const int32_t deg = a.row_deg[rr];
             int32_t *__restrict__ dst = a.out_col + row_loc[q];
             const int32_t *__restrict__ src = a.A_col + beg;
-            if (a.self_entry && lane == 0) { // the row's own vertex, after its sampled ones
-                const int32_t g = a.row_vertex[rr];
+            if (a.self_entry && lane == 0) { // the row's own vertex, after its sampled ones (kept inside [0, n):
+                                             // a bad seed is reported by the seed check, EXTRACT still gets a valid id)
+                int32_t g = a.row_vertex[rr];
+                if (g < 0 || (int64_t)g >= a.n)
+                    g = 0;
                 dst[REPLACE ? a.row_cnt[rr] : (deg < s ? deg : s)] = g;
                 if (SET)
                     atomicOr(&words[g >> 5], 1u << (g & 31));
