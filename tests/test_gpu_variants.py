@@ -67,6 +67,40 @@ def test_union_dst_recycled_calls_and_change_of_variant():
         assert_hops_equal(res.hops(), ref_u if union else ref_p, what="recycled, union=%s" % union)
 
 
+@pytest.mark.parametrize("extract", [None, "buckets"])
+def test_union_dst_seed_out_of_range_on_the_no_round_trip_path(extract):
+    # a recycled result of a remembered shape enqueues every hop before it reads the seed check back; with union_dst
+    # the seed itself travels through EXTRACT as an entry, so a seed outside [0, n) must be made harmless on the
+    # device: the call reports BMS_ERANGE, the recycled result is left empty, and the handles keep working
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms
+    rng = np.random.default_rng(33)
+    n = 50000
+    rowptr, col = random_csr(n, 12.0, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    fan = (6, 5, 4)
+    res = None
+    for seed in (1, 2):   # the second call runs without host round trips
+        batches = random_batches(n, 8, 500, rng)
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), fan, seed, recycle=res, union_dst=True,
+                                  extract=extract)
+        assert_hops_equal(res.hops(), O.sample_nodewise(rowptr, col, batches, fan, seed, union_dst=True))
+    for bad_id in (n, 2**31 - 1, -1):
+        bad = random_batches(n, 8, 500, rng)
+        bad[3, 17] = bad_id
+        with pytest.raises(bms.BmsError) as e:
+            bms.sample_nodewise(csr, torch.from_numpy(bad).cuda(), fan, 3, recycle=res, union_dst=True, extract=extract)
+        assert e.value.code == bms.ERANGE
+        with pytest.raises(bms.BmsError) as e:   # the recycled result is empty after the failed call
+            res.hop(0)
+        assert e.value.code == bms.EINVAL
+        good = random_batches(n, 8, 500, rng)
+        for seed in (4, 5):   # recovers, and gets back onto the no-round-trip path
+            res = bms.sample_nodewise(csr, torch.from_numpy(good).cuda(), fan, seed, recycle=res, union_dst=True,
+                                      extract=extract)
+            assert_hops_equal(res.hops(), O.sample_nodewise(rowptr, col, good, fan, seed, union_dst=True))
+
+
 def test_union_dst_many_small_minibatches_and_single_vertex_batches():
     rng = np.random.default_rng(33)
     rowptr, col = random_csr(4000, 8.0, rng)
