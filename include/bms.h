@@ -177,6 +177,24 @@ typedef struct bms_mb_view {
 int bms_result_minibatch(bms_result *res, int32_t hop, int32_t i, bms_mb_view *view);
 
 /*
+ * For callers that cannot allocate (tight serving loops, harnesses that forbid hipMalloc, code that runs while
+ * another thread captures a HIP graph): the per-minibatch offsets of one hop -- the row0 / edge0 / col0 values of
+ * bms_result_minibatch for every minibatch at once -- copied into caller-owned host arrays of k+1 integers each:
+ *   row_off[i]  = first stacked row of minibatch i      (row_off[k]  = rows of the hop)
+ *   edge_off[i] = first entry of minibatch i in `col`   (edge_off[k] = nnz of the hop)
+ *   col_off[i]  = first stacked column of minibatch i   (col_off[k]  = ncols of the hop)
+ * Unlike bms_result_minibatch (whose first call on a result allocates a device buffer and a host table) this call
+ * allocates nothing, on the device or on the host: its one kernel writes into a fixed array of BMS_NOALLOC_MAX_K + 1
+ * integers that the library holds on every GPU it runs on (128 KB, until the process ends).  k > BMS_NOALLOC_MAX_K
+ * gives BMS_EINVAL.  The work is enqueued on `stream` (hipStream_t, NULL = the null stream) and the call returns
+ * after the copies have completed.  All calls on one GPU share that array: calls that overlap on one GPU (two
+ * threads, two streams) race and must be serialised by the caller.  The result's device must be the current device.
+ */
+#define BMS_NOALLOC_MAX_K 16383
+int bms_result_minibatch_offsets(const bms_result *res, int32_t hop, int64_t *row_off, int64_t *edge_off,
+                                 int64_t *col_off, void *stream);
+
+/*
  * Feature fetching, the part one GPU does (Sec. 6.2): H_i = the rows of the feature matrix H that belong to
  * the vertices of the last frontier.  out[j * f + x] = H[ids[j] * f + x] for j in [0, m), x in [0, f).
  *   H    device, n x f fp32, row-major, caller-owned, read only

@@ -22,6 +22,7 @@ OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
 LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT, LADIES_DENSE, PROFILE_MAIN = 1, 2, 4, 8, 16, 32, 64
 UNION_DST, NODEWISE_REPLACE = 128, 256
+NOALLOC_MAX_K = 16383
 
 
 class BmsError(RuntimeError):
@@ -73,6 +74,8 @@ def lib() -> C.CDLL:
         L.bms_result_hop.argtypes = [C.c_void_p, C.c_int32, C.POINTER(_HopView)]
         L.bms_result_minibatch.restype = C.c_int
         L.bms_result_minibatch.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_MbView)]
+        L.bms_result_minibatch_offsets.restype = C.c_int
+        L.bms_result_minibatch_offsets.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.bms_result_stage.restype = C.c_int
         L.bms_result_stage.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int32),
                                        C.POINTER(C.c_float)]
@@ -248,6 +251,19 @@ class Result:
             col_vertex=_view(v.col_vertex, v.ncols, torch.int32, self),
             row_self=_view(v.row_self, v.rows, torch.int32, self) if v.row_self else None,
         )
+
+    def minibatch_offsets(self, h: int, out: Optional[np.ndarray] = None, stream=None) -> np.ndarray:
+        """bms_result_minibatch_offsets: the (row, entry, column) offsets of every minibatch of hop h as a
+        3 x (k+1) int64 host array (filled in place when `out` is given); the library allocates nothing."""
+        if out is None:
+            out = np.empty((3, self.k + 1), dtype=np.int64)
+        if out.dtype != np.int64 or out.shape != (3, self.k + 1) or not out.flags.c_contiguous:
+            raise TypeError("out must be a C-contiguous 3 x (k+1) int64 array")
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        _check(lib().bms_result_minibatch_offsets(self.handle, h, out[0].ctypes.data, out[1].ctypes.data,
+                                                  out[2].ctypes.data, stream))
+        return out
 
     def hops(self) -> List[Hop]:
         return [self.hop(h) for h in range(self.L)]

@@ -13,6 +13,9 @@
 
 using namespace bms;
 
+// Scratch of bms_result_minibatch_offsets (the entry point that allocates nothing); see scratch_address().
+static __device__ __align__(256) int64_t scratch[BMS_NOALLOC_MAX_K + 1];
+
 namespace {
 
 constexpr uint32_t kTagCsr = 0x31525343u;    // "CSR1"
@@ -89,6 +92,31 @@ struct DevBuf {
         return static_cast<T *>(p);
     }
 };
+
+// Scratch of the entry point that allocates nothing (bms_result_minibatch_offsets): one array per GPU, held until
+// the process ends.  Its name is only a host-side handle: the device address comes from hipGetSymbolAddress, once
+// per device, and that pointer is what kernels and copies get.
+constexpr int32_t kNoAllocMaxK = BMS_NOALLOC_MAX_K;
+constexpr int kMaxDevices = 64;
+int64_t *g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_lock;
+
+// Device address of `scratch` on `device`, which must be the current device.
+int scratch_address(int device, int64_t **out)
+{
+    if (device < 0 || device >= kMaxDevices)
+        return fail(BMS_EINVAL, "device ordinal %d not supported", device);
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p)
+            return fail(BMS_EHIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[device] = static_cast<int64_t *>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return BMS_OK;
+}
 
 struct StageTime {
     const char *name;
@@ -1049,6 +1077,10 @@ int bms_csr_load(const int64_t *rowptr, const int32_t *col, int64_t n, int64_t n
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, c->device) == hipSuccess && prop.multiProcessorCount > 0)
         c->num_cu = prop.multiProcessorCount;
+    {   // set-up of the device's static scratch (used by bms_result_minibatch_offsets); a failure is reported there
+        int64_t *unused = nullptr;
+        (void)scratch_address(c->device, &unused);
+    }
     c->n = n;
     c->nnz = nnz;
     if (location == BMS_DEVICE_BORROW) {
@@ -1212,6 +1244,34 @@ int bms_result_minibatch(bms_result *res, int32_t hop, int32_t i, bms_mb_view *v
     m.col_vertex = v.col_vertex + m.col0;
     m.row_self = v.row_self ? v.row_self + m.row0 : nullptr;
     *view = m;
+    return BMS_OK;
+}
+
+int bms_result_minibatch_offsets(const bms_result *res, int32_t hop, int64_t *row_off, int64_t *edge_off,
+                                 int64_t *col_off, void *stream)
+{
+    if (!res || res->tag != kTagResult || !row_off || !edge_off || !col_off)
+        return fail(BMS_EINVAL, "not a result handle, or null output array");
+    if (hop < 0 || hop >= res->L)
+        return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
+    if (res->k > kNoAllocMaxK)
+        return fail(BMS_EINVAL, "k=%d minibatches: this entry point holds at most %d (its scratch is a fixed array); "
+                                "use bms_result_minibatch", res->k, kNoAllocMaxK);
+    int device = 0;
+    HIP_TRY(hipGetDevice(&device));
+    if (device != res->device)
+        return fail(BMS_EINVAL, "the result lives on device %d, the current device is %d", res->device, device);
+    int64_t *tmp = nullptr;
+    BMS_TRY(scratch_address(device, &tmp));
+    const bms_hop_view &v = res->hops[hop].view;
+    const size_t bytes = ((size_t)res->k + 1) * sizeof(int64_t);
+    hipStream_t st = (hipStream_t)stream;
+    launch_mb_edge_offsets(st, v.rowptr, v.mb_rowoff, res->k, tmp); // writes all k+1 values: nothing to clear
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(edge_off, tmp, bytes, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(row_off, v.mb_rowoff, bytes, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(col_off, v.mb_coloff, bytes, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
     return BMS_OK;
 }
 
