@@ -23,6 +23,8 @@ constexpr uint32_t kTagResult = 0x31534552u; // "RES1"
 constexpr int64_t kDefaultScratchLimit = 32LL << 30;
 constexpr int32_t kMaxMinibatches = 65535; // some kernels take the minibatch from the second grid dimension
 constexpr int64_t kNoWaitEntries = 32LL << 20; // result buffers up to this many entries may be sized by a bound
+constexpr double kBitmapIdsPerEntry = 128.0; // EXTRACT ranks by bitmap when a minibatch samples at least n / this many ids
+                                            // (measured: by bitmap wins at 4..15 ids of [0, n) per sampled id, by counting at 580)
 constexpr int64_t kScanTmpLen = 1 << 17; // partial sums of multi-workgroup scans: arrays up to 2^29 values
 
 thread_local char g_err[512] = "";
@@ -144,7 +146,7 @@ struct bms_csr {
     BMS_BUF(ld_counters); BMS_BUF(ld_gather_off); BMS_BUF(ld_row_mb); BMS_BUF(ld_chunks); BMS_BUF(ld_prefix);
     BMS_BUF(ld_ptileoff); BMS_BUF(ld_tilesum);
     BMS_BUF(dd_pairs); BMS_BUF(dd_utmp); BMS_BUF(dd_uniq); BMS_BUF(dd_edgeoff); BMS_BUF(dd_count); BMS_BUF(dd_back);
-    BMS_BUF(dd_tileoff); BMS_BUF(dd_cursor); BMS_BUF(dd_seg); // EXTRACT
+    BMS_BUF(dd_tileoff); BMS_BUF(dd_cursor); BMS_BUF(dd_seg); BMS_BUF(dd_runs); // EXTRACT
     BMS_BUF(un_rowptr); BMS_BUF(un_col); // BMS_UNION_DST: the hop's CSR while its rows still carry their own vertex
     BMS_BUF(row_cnt);                    // BMS_NODEWISE_REPLACE with a fanout above 32: distinct picks per row
     BMS_BUF(lw_bounds); BMS_BUF(lw_win); BMS_BUF(lw_tmpcol); BMS_BUF(lw_tmpcnt); BMS_BUF(lw_sel); BMS_BUF(lw_xtmp);
@@ -585,36 +587,42 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             BMS_TRY(csr->un_col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
         a.out_col = union_dst ? csr->un_col.as<int32_t>() : hb.col.as<int32_t>();
 
-        BMS_TRY(prof.begin("nw_sample", h));
-        launch_nw_sample(c.launch, a, c.vs, !buckets);
-        BMS_TRY(prof.end());
+        DedupArgs d{};
+        bool counted = false;
         if (buckets) {
             BMS_TRY(csr->dd_pairs.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
             BMS_TRY(csr->dd_utmp.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(uint64_t)));
-            // segments = id ranges of 2^cshift ids: 240..480 sampled ids each on average (most then fit the
-            // 512-pair sorting network of one wave with little padding),
-            // at most kMaxSegments of them, at most 2^20 ids wide (the sort key has 32 bits)
-            int32_t C = 0, cshift = 0;
+            // segments = id ranges of 2^cshift ids holding 1500..3000 sampled ids each on average (one workgroup ranks
+            // up to 4096 in LDS; the longer a segment, the longer the runs the cut appends to it per tile),
+            // at most kMaxSegments of them
+            int32_t C = 0, cshift = 0, by_bitmap = 0;
             if (seg_sort) {
                 const double per_mb = (double)nnz_tune / c.k + 1.0;
+                // ids dense enough in [0, n) that a pass over a bitmap of a segment's id range costs less than sorting
+                // its ids: segments as wide as the bitmap kernel takes, as long as they hold well under 2^16 ids
+                by_bitmap = (double)csr->n <= kBitmapIdsPerEntry * per_mb ? 1 : 0;
+                const double target = by_bitmap ? 16384.0 : 3000.0;
+                const int32_t most = by_bitmap ? kMaxBitmapShift : 31;
                 cshift = 0;
-                while (cshift < 20 && (double)(2LL << cshift) * per_mb <= 480.0 * (double)csr->n)
+                while (cshift < most && (double)(2LL << cshift) * per_mb <= target * (double)csr->n)
                     ++cshift;
                 while (((csr->n + (1LL << cshift) - 1) >> cshift) > kMaxSegments)
                     ++cshift;
+                if (cshift > kMaxBitmapShift)
+                    by_bitmap = 0;
                 C = (int32_t)std::max<int64_t>((csr->n + (1LL << cshift) - 1) >> cshift, 1);
-                if (cshift > 20)
-                    C = 0; // vertex range too wide for the segment sort: per-minibatch kernel only
                 // few sampled edges per minibatch: the single per-minibatch kernel beats the chain of
                 // chip-wide kernels, whose launches would dominate (unless that path was asked for)
                 if (per_mb <= 4096.0 && !(c.flags & BMS_EXTRACT_SORT))
                     C = 0;
             }
             const size_t stride = (size_t)std::max<int64_t>(nbuckets, C);
+            const size_t kC = (size_t)c.k * (size_t)C;
+            const int64_t xtiles = nnz / kSplitTile16 + c.k; // tiles of the cut
             BMS_TRY(csr->dd_uniq.ensure((size_t)c.k * stride * sizeof(uint32_t)));
-            BMS_TRY(csr->dd_seg.ensure(((size_t)c.k * (5 * (size_t)kMaxSegments + 1) + 16) * sizeof(uint32_t)));
+            BMS_TRY(csr->dd_seg.ensure((4 * kC + (size_t)c.k + 16) * sizeof(uint32_t)));
+            BMS_TRY(csr->dd_runs.ensure(2 * (size_t)xtiles * (size_t)std::max(C, 1) * sizeof(uint32_t)));
             BMS_TRY(csr->dd_tileoff.ensure(3 * ((size_t)c.k + 1) * sizeof(int64_t)));
-            DedupArgs d{};
             d.k = c.k;
             d.nbuckets = (int32_t)nbuckets;
             d.mb_edgeoff = csr->dd_edgeoff.as<int64_t>();
@@ -631,20 +639,37 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.stride = (int32_t)stride;
             d.C = C;
             d.cshift = cshift;
-            d.fuse_back = C ? 1 : 0;
+            d.by_bitmap = by_bitmap;
             d.big_tileoff = csr->dd_tileoff.as<int64_t>() + 2 * (c.k + 1);
             d.fallback = C ? reinterpret_cast<int32_t *>(csr->dd_seg.as<uint32_t>()) : nullptr;
-            d.seg_cnt = csr->dd_seg.as<uint32_t>() + 16;
-            d.seg_off = d.seg_cnt + (size_t)c.k * kMaxSegments;
-            d.seg_cursor = d.seg_off + (size_t)c.k * (kMaxSegments + 1);
-            d.big_list = d.seg_cursor + (size_t)c.k * kMaxSegments;
             d.big_count = csr->dd_seg.as<uint32_t>() + 1;
-            d.wide_list = d.big_list + (size_t)c.k * kMaxSegments;
-            d.wide_count = csr->dd_seg.as<uint32_t>() + 2;
+            d.seg_cnt = csr->dd_seg.as<uint32_t>() + 16;
+            d.seg_off = d.seg_cnt + kC;
+            d.seg_cursor = d.seg_off + kC + c.k;
+            d.big_list = d.seg_cursor + kC;
+            // the segment path keeps the ids grouped by segment and the per-position words in the first buffer,
+            // the distinct ids and the 16-bit ranks in the second (the per-minibatch path uses both as 8-byte entries)
+            d.ids_seg = csr->dd_pairs.as<uint32_t>();
+            d.loc = d.ids_seg + std::max<int64_t>(nnz, 1);
+            d.uids = csr->dd_utmp.as<uint32_t>();
+            d.ranks = reinterpret_cast<uint16_t *>(d.uids + std::max<int64_t>(nnz, 1));
+            d.run_gpos = csr->dd_runs.as<uint32_t>();
+            d.run_cnt = d.run_gpos + (size_t)xtiles * (size_t)std::max(C, 1);
             d.mb_count = csr->dd_count.as<int64_t>();
+            launch_nw_dedup_prepare(c.launch, d, nnz);
+            if (C > 0) { // the sampling kernel counts the ids per segment while it has them in LDS, when it can
+                a.seg_cnt = d.seg_cnt;
+                a.seg_C = C;
+                a.seg_shift = cshift;
+            }
+        }
+        BMS_TRY(prof.begin("nw_sample", h));
+        counted = launch_nw_sample(c.launch, a, c.vs, !buckets);
+        BMS_TRY(prof.end());
+        if (buckets) {
             const StageMark mark = [&](const char *name) { (void)prof.mark(name, h); };
             if (launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
-                                       slot(c, h, 1), nnz, mark) != 0)
+                                       slot(c, h, 1), nnz, counted, mark) != 0)
                 return fail(BMS_EHIP, "launch of the bucket EXTRACT kernel was refused");
             launch_nw_dedup_fixup(c.launch, d, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), nnz, mark);
             BMS_TRY(prof.end());

@@ -77,6 +77,19 @@ __device__ inline T wave_inclusive_scan(T v)
     return v;
 }
 
+// The same for 32-bit counts through the vector unit's lane-permute paths only (no LDS crossbar): shifts inside
+// each row of 16 lanes, then the last lane of rows 0 and 2 broadcast into rows 1 and 3, then lane 31 into rows 2, 3.
+__device__ inline uint32_t wave_inclusive_scan_dpp(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111 /* row_shr:1 */, 0xF, 0xF, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112 /* row_shr:2 */, 0xF, 0xF, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114 /* row_shr:4 */, 0xF, 0xF, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118 /* row_shr:8 */, 0xF, 0xF, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142 /* row_bcast:15 */, 0xA, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143 /* row_bcast:31 */, 0xC, 0xF, false);
+    return v;
+}
+
 template <class T>
 __device__ inline T wave_sum(T v)
 {

@@ -75,10 +75,17 @@ struct NwHop {
     int32_t self_entry;        // 1: every row carries its own vertex as one more entry after the sampled ones
     int32_t replace;           // 1: the s draws of a row are independent, the row keeps the distinct picks
     int32_t *row_cnt;          // scratch, rows: distinct picks per row (only with replace and s > 32)
+    // EXTRACT's count of sampled ids per (minibatch, id-range segment), taken while the ids are staged in LDS
+    // (nullptr: not wanted); the caller has zeroed the counters
+    uint32_t *seg_cnt;         // k * seg_C
+    int32_t seg_C, seg_shift;  // segment of an id = id >> seg_shift, < seg_C <= kMaxFusedSegments
 };
+constexpr int kMaxFusedSegments = 512;
 void launch_nw_rows(const Launch &, const NwHop &);
-// set_bits: also mark every sampled vertex in the minibatch's vertex set (bitmap EXTRACT path)
-void launch_nw_sample(const Launch &, const NwHop &, const VSet &, bool set_bits);
+// set_bits: also mark every sampled vertex in the minibatch's vertex set (bitmap EXTRACT path).
+// Returns true when the kernel also took the per-segment counts asked for in NwHop::seg_cnt (it can when every
+// workgroup stays with one minibatch: one row per lane, no more minibatches than workgroups).
+bool launch_nw_sample(const Launch &, const NwHop &, const VSet &, bool set_bits);
 void launch_nw_relabel(const Launch &, const NwHop &, const VSet &);
 // rows that carry a trailing entry for their own vertex -> the CSR without it + that entry per row;
 // *rows = number of rows (device), *nnz_slot: entries on input, entries - rows on output
@@ -86,7 +93,10 @@ void launch_nw_strip_self(const Launch &, const int64_t *rowptr_in, const int32_
                           int64_t rows_bound, int64_t *rowptr_out, int32_t *col_out, int32_t *row_self,
                           int64_t *nnz_slot);
 
-// EXTRACT by id-range buckets, one workgroup per minibatch (large vertex ranges)
+// EXTRACT ("remove empty columns", Sec. 4.1.3).  Main path: the sampled ids of every minibatch are cut into C
+// id-range segments, the segments are ranked in LDS, and the ranks travel back to the entries' positions through the
+// run structure of the cut (kernels_dedup_sort.hip).  Fallback for crowded id ranges and path of small hops: one
+// workgroup per minibatch over id-range bins (kernels_dedup.hip).
 constexpr int kBucketBits = 15;     // ids per bucket = 2^15 (a 4 KB bitmap per wave in LDS)
 constexpr int kMaxBuckets = 8000;   // two uint32 per bucket must fit beside 16 wave bitmaps in 160 KB of LDS
 struct DedupArgs {
@@ -94,36 +104,45 @@ struct DedupArgs {
     int32_t nbuckets;    // ceil(n / 2^kBucketBits) <= kMaxBuckets
     int64_t *mb_edgeoff; // k+1, scratch
     int32_t *col;        // in: sampled global ids (stacked), out: local column indices
-    uint64_t *pairs;     // nnz, scratch: (id << 32 | position in minibatch) partitioned by bin, then (bin, rank, position)
-    uint64_t *utmp;      // nnz, scratch: (bin, rank, id) of every distinct id, at its group's slots
-    uint32_t *bin_base;  // k * nbuckets, scratch: distinct ids of the minibatch before each bin's group
-    uint64_t *back;      // nnz, scratch: (local column << 32 | position) grouped by destination range
-    int64_t *split_tileoff, *place_tileoff; // k+1 each, scratch
-    uint32_t *place_cursor;                 // one per destination range, scratch
+    uint64_t *pairs;     // nnz, scratch (bin path): (id << 32 | position in minibatch) partitioned by bin, then (bin, rank, position)
+    uint64_t *utmp;      // nnz, scratch (bin path): (bin, rank, id) of every distinct id, at its group's slots
+    uint32_t *bin_base;  // k * stride, scratch: distinct ids of the minibatch before each bin's group / each segment
+    uint64_t *back;      // nnz, scratch (bin path): (local column << 32 | position) grouped by destination range
+    int64_t *split_tileoff, *place_tileoff; // k+1 each, scratch (bin path)
+    uint32_t *place_cursor;                 // one per destination range, scratch (bin path)
     int64_t *mb_count;   // k, scratch: distinct ids per minibatch
     int32_t stride;      // entries of bin_base per minibatch (>= nbuckets and >= C)
-    // segment-sort path (C == 0: not used)
+    // segment path (C == 0: not used)
     int32_t C;           // id-range segments per minibatch = ceil(n / 2^cshift) <= kMaxSegments
     int32_t cshift;      // segment of an id = id >> cshift
-    uint32_t *seg_cnt;   // k * C: pairs per segment, later distinct ids per segment
-    uint32_t *seg_off;   // k * (C+1): exclusive scan of the pair counts
+    int32_t by_bitmap;   // 1: every segment is ranked through a bitmap of its id range (dense hops); 0: by sorting
+    uint32_t *seg_cnt;   // k * C: entries per segment, later distinct ids per segment
+    uint32_t *seg_off;   // k * (C+1): exclusive scan of the entry counts
     uint32_t *seg_cursor; // k * C
-    int64_t *big_tileoff; // k+1: tiles of kSplitTile16 entries
-    uint32_t *big_list;  // k * C: segments of 1025..kSegCap pairs
+    int64_t *big_tileoff; // k+1: tiles of kSplitTile16 positions
+    uint32_t *big_list;  // k * C: segments that one workgroup of the ranking kernel does not take (too many entries, or
+                         // too many of them in one narrow id range): ranked through a bitmap of the id range
     uint32_t *big_count; // device counter of big_list (the word after `fallback`)
-    uint32_t *wide_list; // k * C: segments of 513..1024 pairs (one wave each, in a kernel of their own)
-    uint32_t *wide_count; // device counter of wide_list (the word after big_count)
-    int32_t fuse_back;   // 1: the sorting waves append their entries to the slot lists themselves (no split pass)
-    int32_t *fallback;   // device flag: a segment does not fit in LDS, the per-minibatch kernel takes the hop
+    int32_t *fallback;   // device flag: a segment fits neither ranking kernel, the per-minibatch kernel takes the hop
+    uint32_t *ids_seg;   // nnz: the sampled ids grouped by segment (minibatch i, segment c at mb_edgeoff[i] + seg_off[c])
+    uint32_t *loc;       // nnz, by position: segment << 14 | place inside the run its tile appended to that segment
+    uint32_t *run_gpos;  // tiles * C: where the run of (tile, segment) starts inside the minibatch's part of ids_seg
+    uint32_t *run_cnt;   // tiles * C: its length
+    uint16_t *ranks;     // nnz, parallel to ids_seg: rank of the id among the distinct ids of its segment
+    uint32_t *uids;      // nnz: the distinct ids of a segment in ascending order, at the head of the segment's slots
 };
-constexpr int kSplitTile16 = 16384; // sampled ids per tile of the count and split kernels (128 KB of LDS staging:
-                                    // long runs per segment)
-constexpr int kSegCap = 65535;      // most pairs a segment may hold: the rank of an id inside its segment has 16 bits
-constexpr int kMaxSegments = 2560;  // 3 words each beside the split kernel's staging must fit in 160 KB of LDS
-void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz, const StageMark &mark);
+constexpr int kSplitTile16 = 16384; // positions per tile of the count, split and un-split kernels
+constexpr int kSegCap = 65535;      // most entries a segment may hold: the rank of an id inside its segment has 16 bits
+constexpr int kMaxSegments = 2560;  // 3 words each beside the staging of the split / un-split kernels must fit in 160 KB of LDS
+constexpr int kMaxBitmapShift = 20; // the bitmap ranking kernel holds 2^cshift bits in LDS (128 KB)
+// clears the counters of the segment path (before the sampling kernel, which may count into them)
+void launch_nw_dedup_prepare(const Launch &, const DedupArgs &, int64_t nnz);
+// counted: the per-segment counts are there already
+void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz, bool counted, const StageMark &mark);
+void launch_nw_dedup_unsplit(const Launch &, const DedupArgs &, int64_t nnz);
 // returns 0, or -1 when the launch was refused (then nothing ran)
 int launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz, const StageMark &mark);
+                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz, bool counted, const StageMark &mark);
 void launch_nw_dedup_fixup(const Launch &, const DedupArgs &, const int64_t *mb_coloff, int32_t *col_vertex,
                            int64_t nnz, const StageMark &mark);
 constexpr int kDedupPlaceTile = 8192; // must equal kPlaceTile in kernels_dedup.hip (sizes the cursor array)

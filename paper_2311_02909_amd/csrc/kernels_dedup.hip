@@ -334,58 +334,29 @@ constexpr int kMaxPlaceTiles = 256;
 static_assert(kPlaceTile == kDedupPlaceTile && (1 << kPlaceShift) == kPlaceTile && kSplitTile == kDedupSplitTile,
               "tile constants out of step");
 
-// big_segments == 0: walks all tiles of `pairs`.  After the per-minibatch kernel (fallback) that is
-// every entry; after the segment sorts only minibatches of more than 256 ranges still have their
-// entries in `pairs` (they are stored directly), the others were split by the sorting waves.
-// big_segments == 1 (segment sorts only): walks the segments sorted by whole workgroups.
-__device__ inline void dedup_split_pass(const DedupArgs &a, int big_segments, uint64_t *stage, uint32_t *cnt, uint32_t *off,
-                                        uint32_t *gpos, uint32_t *smem)
+// Runs after the per-minibatch kernel only (a hop that the segment kernels handled has nothing here).
+__global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a)
 {
-    const int tid = threadIdx.x;
-    const bool sorted = a.fuse_back && a.fallback && !*a.fallback; // the waves have split their segments
-    if (big_segments && !sorted)
+    __shared__ uint64_t stage[kSplitTile];
+    __shared__ uint32_t cnt[kMaxPlaceTiles], off[kMaxPlaceTiles], gpos[kMaxPlaceTiles];
+    __shared__ uint32_t smem[4];
+    if (a.fallback && !*a.fallback)
         return;
-    if (sorted && !big_segments) { // nothing to do unless some minibatch is stored directly
-        bool any = false;
-        for (int i = tid; i < a.k; i += 256)
-            any |= a.mb_edgeoff[i + 1] - a.mb_edgeoff[i] > (int64_t)kMaxPlaceTiles * kPlaceTile;
-        if (!__syncthreads_or(any))
-            return;
-    }
-    // units of work: tiles of kSplitTile entries, or listed segments (walked tile by tile by one workgroup)
-    const int64_t nunits = big_segments ? (int64_t)*a.big_count : a.split_tileoff[a.k];
+    const int tid = threadIdx.x;
+    const int64_t nunits = a.split_tileoff[a.k];
     for (int64_t unit = blockIdx.x; unit < nunits; unit += gridDim.x) {
-        int i;
-        uint32_t jb, je;
-        if (big_segments) {
-            const int64_t sg = a.big_list[unit];
-            i = (int)(sg / a.C);
-            const uint32_t *__restrict__ soff = a.seg_off + (int64_t)i * (a.C + 1);
-            jb = soff[sg % a.C];
-            je = soff[sg % a.C + 1];
-        } else {
-            i = locate_segment(a.split_tileoff, a.k, unit);
-            jb = (uint32_t)(unit - a.split_tileoff[i]) * kSplitTile;
-            je = jb + kSplitTile;
-        }
+        const int i = locate_segment(a.split_tileoff, a.k, unit);
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
         const uint32_t Q = (N + kPlaceTile - 1) >> kPlaceShift;
-        if (!big_segments) {
-            je = je < N ? je : N;
-            if (sorted && Q <= kMaxPlaceTiles)
-                continue; // already split by the sorting waves (and by the big_segments pass)
-        } else if (Q > kMaxPlaceTiles) {
-            continue; // stored directly by the pass over all tiles
-        }
-        for (uint32_t j0 = jb; j0 < je; j0 += kSplitTile) {
-        const uint32_t jend = (j0 + kSplitTile < je) ? j0 + kSplitTile : je;
+        const uint32_t j0 = (uint32_t)(unit - a.split_tileoff[i]) * kSplitTile;
+        const uint32_t jend = (j0 + kSplitTile < N) ? j0 + kSplitTile : N;
         const uint64_t *__restrict__ pairs = a.pairs + e0;
         uint64_t ent[kSplitTile / 256];
 #pragma unroll
         for (int q = 0; q < kSplitTile / 256; ++q) {
             const uint32_t j = j0 + q * 256 + tid;
-            ent[q] = j < jend ? pairs[j] : kNoEntry; // (bin or segment, rank, position)
+            ent[q] = j < jend ? pairs[j] : kNoEntry; // (bin, rank, position)
         }
         if (Q > kMaxPlaceTiles) { // uniform for the workgroup
             int32_t *__restrict__ col = a.col + e0;
@@ -423,25 +394,14 @@ __device__ inline void dedup_split_pass(const DedupArgs &a, int big_segments, ui
             back[r * kPlaceTile + gpos[r] + (sidx - off[r])] = e;
         }
         __syncthreads();
-        }
-    }
-}
-
-// passes = 1: big_segments == 0 only; passes = 2: both, one after the other
-__global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a, int passes)
-{
-    __shared__ uint64_t stage[kSplitTile];
-    __shared__ uint32_t cnt[kMaxPlaceTiles], off[kMaxPlaceTiles], gpos[kMaxPlaceTiles];
-    __shared__ uint32_t smem[4];
-    for (int big_segments = 0; big_segments < passes; ++big_segments) {
-        dedup_split_pass(a, big_segments, stage, cnt, off, gpos, smem);
-        __syncthreads();
     }
 }
 
 __global__ __launch_bounds__(256) void nw_dedup_place_kernel(DedupArgs a)
 {
     __shared__ int32_t tile[kPlaceTile];
+    if (a.fallback && !*a.fallback)
+        return; // the segment kernels handled this hop
     const int tid = threadIdx.x;
     const int64_t ntiles = a.place_tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
@@ -484,26 +444,53 @@ __global__ __launch_bounds__(256) void nw_dedup_front_kernel(DedupArgs a, const 
     const uint32_t *__restrict__ base = a.bin_base + (int64_t)i * a.stride;
     int32_t *__restrict__ front = col_vertex + mb_coloff[i];
     if (a.fallback && !*a.fallback) {
-        // segment sorts: segment c left its distinct ids, in rank order, at the head of its slots
-        const uint32_t *__restrict__ uids = reinterpret_cast<const uint32_t *>(a.utmp) + e0;
+        // segment path: segment c left its distinct ids, in rank order, at the head of its slots; the minibatch's
+        // columns are those lists one after the other.  Walked by destination, 512 columns per wave and step, so the
+        // work is even whatever the segments' lengths: the segment of a column is found in the segments' bases (LDS)
+        extern __shared__ uint32_t front_lds[]; // base[C + 1], then the segments' first slots
+        uint32_t *base_l = front_lds, *soff_l = front_lds + a.C + 1;
+        const uint32_t *__restrict__ uids = a.uids + e0;
         const uint32_t *__restrict__ soff = a.seg_off + (int64_t)i * (a.C + 1);
-        const uint32_t *__restrict__ scnt = a.seg_cnt + (int64_t)i * a.C;
+        const uint32_t U = (uint32_t)a.mb_count[i];
+        for (int32_t c = threadIdx.x; c < a.C; c += 256) {
+            base_l[c] = base[c];
+            soff_l[c] = soff[c];
+        }
+        if (threadIdx.x == 0)
+            base_l[a.C] = U;
+        __syncthreads();
         const int lane = threadIdx.x & (kWave - 1);
-        for (int32_t c = blockIdx.x * 4 + threadIdx.x / kWave; c < a.C; c += gridDim.x * 4) {
-            const uint32_t cnt = scnt[c], s0 = soff[c], b0 = base[c];
-            for (uint32_t r0 = 0; r0 < cnt; r0 += 8 * kWave) { // 8 independent loads in flight per lane
-                uint32_t v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const uint32_t r = r0 + u * kWave + lane;
-                    v[u] = r < cnt ? uids[s0 + r] : 0u;
+        const uint32_t wv = blockIdx.x * 4 + threadIdx.x / kWave, nwv = gridDim.x * 4;
+        for (uint32_t d0 = wv * (8 * kWave); d0 < U; d0 += nwv * (8 * kWave)) {
+            // last segment c with base[c] <= d (segments without distinct ids share their base with the next one)
+            uint32_t d = d0 + lane;
+            int32_t c = 0;
+            if (d < U) {
+                int32_t hi = a.C;
+                while (hi - c > 1) {
+                    const int32_t mid = (c + hi) >> 1;
+                    if (base_l[mid] <= d)
+                        c = mid;
+                    else
+                        hi = mid;
                 }
+            }
+            uint32_t v[8]; // 8 independent loads in flight per lane
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const uint32_t r = r0 + u * kWave + lane;
-                    if (r < cnt)
-                        front[b0 + r] = (int32_t)v[u];
+            for (int u = 0; u < 8; ++u) {
+                d = d0 + u * kWave + lane;
+                v[u] = 0;
+                if (d < U) {
+                    while (base_l[c + 1] <= d) // the lane's columns ascend: the segment only moves forward
+                        ++c;
+                    v[u] = uids[soff_l[c] + (d - base_l[c])];
                 }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                d = d0 + u * kWave + lane;
+                if (d < U)
+                    front[d] = (int32_t)v[u];
             }
         }
         return;
@@ -525,7 +512,7 @@ __global__ __launch_bounds__(256) void nw_dedup_front_kernel(DedupArgs a, const 
 }
 
 int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz, const StageMark &mark)
+                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz, bool counted, const StageMark &mark)
 {
     static bool attr_set = false;
     if (!attr_set) {
@@ -537,7 +524,7 @@ int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *o
     hipLaunchKernelGGL(mb_edge_offsets_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, out_rowptr, mb_rowoff,
                        a.k, a.mb_edgeoff);
     if (a.C > 0)
-        launch_nw_dedup_sorted(L, a, nnz, mark);
+        launch_nw_dedup_sorted(L, a, nnz, counted, mark);
     else
         mark("dd_bins");
     hipLaunchKernelGGL(nw_dedup_bucket_kernel, dim3(a.k), dim3(kDedupWaves * kWave), dedup_lds_bytes(a.nbuckets),
@@ -555,15 +542,19 @@ void launch_nw_dedup_fixup(const Launch &L, const DedupArgs &a, const int64_t *m
     int gx = (int)((nnz / a.k + 2047) / 2048) + 1; // about one workgroup per 2048 entries of a minibatch
     if (gx > 64)
         gx = 64;
-    hipLaunchKernelGGL(nw_dedup_front_kernel, dim3(gx, a.k), dim3(256), 0, L.stream, a, mb_coloff, col_vertex);
-    mark("dd_back_split");
-    if (a.C == 0) { // the segment-sort launcher has done this already (its waves append to the slot lists)
+    hipLaunchKernelGGL(nw_dedup_front_kernel, dim3(gx, a.k), dim3(256), (2 * (size_t)a.C + 1) * sizeof(uint32_t), L.stream, a,
+                       mb_coloff, col_vertex);
+    if (a.C > 0) {
+        mark("dd_unsplit");
+        launch_nw_dedup_unsplit(L, a, nnz);
+    }
+    mark("dd_back_split"); // after the per-minibatch kernel only: both kernels return at once otherwise
+    if (a.C == 0) { // the segment launcher has done this already
         launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile, a.split_tileoff);
         launch_plan_tiles(L, a.mb_edgeoff, a.k, kPlaceTile, a.place_tileoff);
         (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
     }
-    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a,
-                       (a.C > 0 && a.fuse_back) ? 2 : 1);
+    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a);
     mark("dd_place");
     hipLaunchKernelGGL(nw_dedup_place_kernel, dim3(grid_for(L, nnz / kPlaceTile + a.k, 4)), dim3(256), 0, L.stream, a);
 }

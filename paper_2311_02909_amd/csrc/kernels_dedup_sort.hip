@@ -1,30 +1,36 @@
-// EXTRACT for the node-wise sampler, fast path (Sec. 4.1.3: "remove empty columns"): every
-// minibatch's sampled ids are cut into C id ranges ("segments") small enough to be sorted inside
+// EXTRACT for the node-wise sampler, main path (Sec. 4.1.3: "remove empty columns"): every
+// minibatch's sampled ids are cut into C id ranges ("segments") small enough to be ranked inside
 // LDS, so that all random accesses of the dedup happen in LDS and global memory only sees
-// coalesced traffic.  All kernels run on every compute unit, whatever the number of minibatches.
+// coalesced traffic.  Positions never travel with the ids: the cut remembers, per position, which
+// segment its id went to and where inside the run that its tile appended to that segment, so the
+// ranks come back along the same runs.  All kernels run on every compute unit, whatever the
+// number of minibatches.
 //
-//   count  per tile of 16384 sampled ids: LDS histogram over the C segments -> global counts
-//   scan   per minibatch: segment offsets; raises the fallback flag when a segment would not
-//          fit in LDS (ids crowded into a narrow range) -- then these kernels do nothing and the
-//          per-minibatch kernel of kernels_dedup.hip does the hop instead
-//   split  per tile: counting sort by segment in LDS, every segment's run appended with wide stores
-//   sort   per (minibatch, segment): the pairs are sorted by id -- up to 1024 pairs by one wave in
-//          registers (bitonic network; more pairs: ranked by a workgroup through a bitmap in LDS); head flags + scan give
-//          the rank among the segment's distinct ids; every pair becomes (segment, rank,
-//          position), the distinct ids are written in rank order at the head of the segment's slots
-//   base   per minibatch: scan of the segments' distinct counts
-// The fix-up kernels of kernels_dedup.hip then add the bases and put everything in place.
+//   count    per tile of 16384 positions: LDS histogram over the C segments -> global counts
+//   scan     per minibatch: segment offsets; segments too long for one workgroup are listed for the
+//            bitmap kernel; raises the fallback flag when a segment fits neither (ids crowded into a
+//            narrow range) -- then these kernels do nothing and the per-minibatch kernel of
+//            kernels_dedup.hip does the hop instead
+//   split    per tile: counting sort by segment in LDS, every segment's run of ids appended to the
+//            segment with wide stores; per position (segment, place in run); per (tile, segment)
+//            where the run went
+//   rank     per (minibatch, segment): a workgroup counts the segment's ids into buckets of about
+//            one id (LDS), every id compares itself with the few ids of its bucket, head bits and a
+//            popcount prefix give every id its rank among the segment's distinct ids; the distinct
+//            ids are written in rank order at the head of the segment's slots
+//   bitmap   the listed segments: rank = set bits below the id in a bitmap of the segment's id range
+//   base     per minibatch: scan of the segments' distinct counts
+//   un-split per tile: the runs' ranks read back with wide loads, base of the segment added, scattered
+//            to their positions inside LDS, written out as the tile's local column indices
 #include "bms_device.h"
 #include "bms_internal.h"
 
+#include <algorithm>
+
 namespace bms {
 
-constexpr uint64_t kNoEntry = ~0ULL;
-
-__device__ inline uint64_t pack_entry(uint32_t payload, uint32_t rank, uint32_t seg)
-{
-    return (uint64_t)payload | ((uint64_t)rank << 32) | ((uint64_t)seg << 48);
-}
+constexpr int kLocShift = 14; // bits of the place inside a run (a tile holds 2^14 positions)
+static_assert(kSplitTile16 == (1 << kLocShift) && kMaxSegments <= (1 << (32 - kLocShift)), "loc word out of step");
 
 template <int TILE, int NT>
 __global__ __launch_bounds__(NT) void dd_count_kernel(DedupArgs a, const int64_t *__restrict__ tileoff)
@@ -75,6 +81,8 @@ __device__ inline void wave_append(uint32_t *__restrict__ list, uint32_t *__rest
         list[base + __popcll(mask & ((1ull << lane) - 1ull))] = value;
 }
 
+constexpr int kRankCapFwd = 4096; // = kRankCap (defined with the ranking kernel below)
+
 // one workgroup per minibatch: seg_off = exclusive scan of the counts (C+1 entries), cursors zeroed
 __global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
 {
@@ -90,10 +98,12 @@ __global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
     for (int base = 0; base < a.C; base += 256) {
         const int c = base + tid;
         const uint32_t v = c < a.C ? cnt[c] : 0u;
-        too_big |= v > (uint32_t)kSegCap;
-        // too many pairs for one wave: listed for the workgroup sort; 513..1024: listed for the wide wave sort
-        wave_append(a.big_list, a.big_count, v > 1024u && v <= (uint32_t)kSegCap, (uint32_t)(i * a.C + c));
-        wave_append(a.wide_list, a.wide_count, v > 512u && v <= 1024u, (uint32_t)(i * a.C + c));
+        // too many entries for one workgroup of the ranking kernel: listed for the bitmap kernel, which holds the
+        // segment's id range as bits in LDS; a segment wider or fuller than that kernel takes sends the hop to the
+        // per-minibatch kernel
+        const bool big = !a.by_bitmap && v > (uint32_t)kRankCapFwd;
+        too_big |= v > (uint32_t)kSegCap || (big && a.cshift > kMaxBitmapShift);
+        wave_append(a.big_list, a.big_count, big && v <= (uint32_t)kSegCap, (uint32_t)(i * a.C + c));
         uint32_t total;
         const uint32_t ex = block_exclusive_scan<uint32_t, 256>(v, smem, total);
         const uint32_t carry = carry_s;
@@ -112,18 +122,18 @@ __global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
         atomicOr(a.fallback, 1);
 }
 
-// TILE sampled ids per workgroup step, NT threads.  The larger the tile, the longer the run every segment gets
-// in one step (a step's entries spread over all C segments), i.e. the wider the stores.
+// TILE positions per workgroup step, NT threads.  The larger the tile, the longer the run every segment gets
+// in one step (a step's ids spread over all C segments), i.e. the wider the stores.
 template <int TILE, int NT>
 __global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t *__restrict__ tileoff)
 {
-    extern __shared__ uint64_t split_lds[]; // stage[TILE]; then 3 C words: per-segment count, start in the tile, start in global
+    extern __shared__ uint32_t split_lds[]; // stage[TILE]; then 3 C words: per-segment count, start in the tile, start in global - start in the tile
     __shared__ uint32_t smem[NT / kWave];
     __shared__ uint32_t carry_s;
     if (*a.fallback)
         return;
-    uint64_t *stage = split_lds;
-    uint32_t *cnt = reinterpret_cast<uint32_t *>(split_lds + TILE), *off = cnt + a.C, *gpos = cnt + 2 * a.C;
+    uint32_t *stage = split_lds;
+    uint32_t *cnt = split_lds + TILE, *off = cnt + a.C, *gpos = cnt + 2 * a.C;
     const int tid = threadIdx.x;
     const int64_t ntiles = tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
@@ -138,18 +148,24 @@ __global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t
         if (tid == 0)
             carry_s = 0;
         __syncthreads();
-        uint64_t ent[TILE / NT];
+        uint32_t id[TILE / NT];
         uint32_t lpos[TILE / NT];
 #pragma unroll
         for (int q = 0; q < TILE / NT; ++q) {
             const uint32_t j = j0 + q * NT + tid;
-            ent[q] = j < jend ? (((uint64_t)(uint32_t)col[j] << 32) | (uint64_t)j) : kNoEntry;
+            id[q] = j < jend ? (uint32_t)col[j] : 0xFFFFFFFFu; // ids are < 2^31
         }
 #pragma unroll
         for (int q = 0; q < TILE / NT; ++q)
-            if (ent[q] != kNoEntry)
-                lpos[q] = atomicAdd(&cnt[(uint32_t)(ent[q] >> 32) >> a.cshift], 1u);
+            if (id[q] != 0xFFFFFFFFu)
+                lpos[q] = atomicAdd(&cnt[id[q] >> a.cshift], 1u);
+        uint32_t *__restrict__ loc = a.loc + e0;
+#pragma unroll
+        for (int q = 0; q < TILE / NT; ++q)
+            if (id[q] != 0xFFFFFFFFu)
+                loc[j0 + q * NT + tid] = ((id[q] >> a.cshift) << kLocShift) | lpos[q];
         __syncthreads();
+        uint32_t *__restrict__ run_gpos = a.run_gpos + t * a.C, *__restrict__ run_cnt = a.run_cnt + t * a.C;
         for (int base = 0; base < a.C; base += NT) {
             const int c = base + tid;
             const uint32_t v = c < a.C ? cnt[c] : 0u;
@@ -158,8 +174,12 @@ __global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t
             const uint32_t carry = carry_s;
             if (c < a.C) {
                 off[c] = carry + ex;
+                uint32_t g = 0;
                 if (v)
-                    gpos[c] = a.seg_off[(int64_t)i * (a.C + 1) + c] + atomicAdd(&a.seg_cursor[(int64_t)i * a.C + c], v);
+                    g = a.seg_off[(int64_t)i * (a.C + 1) + c] + atomicAdd(&a.seg_cursor[(int64_t)i * a.C + c], v);
+                gpos[c] = g - (carry + ex); // start in global - start in the tile
+                run_gpos[c] = g;
+                run_cnt[c] = v;
             }
             __syncthreads();
             if (tid == 0)
@@ -168,358 +188,389 @@ __global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t
         }
 #pragma unroll
         for (int q = 0; q < TILE / NT; ++q)
-            if (ent[q] != kNoEntry)
-                stage[off[(uint32_t)(ent[q] >> 32) >> a.cshift] + lpos[q]] = ent[q];
+            if (id[q] != 0xFFFFFFFFu)
+                stage[off[id[q] >> a.cshift] + lpos[q]] = id[q];
         __syncthreads();
-        uint64_t *__restrict__ pairs = a.pairs + e0;
+        uint32_t *__restrict__ ids_seg = a.ids_seg + e0;
         for (uint32_t sidx = tid; sidx < jend - j0; sidx += NT) {
-            const uint64_t e = stage[sidx];
-            const uint32_t c = (uint32_t)(e >> 32) >> a.cshift;
-            pairs[gpos[c] + (sidx - off[c])] = e;
+            const uint32_t g = stage[sidx];
+            ids_seg[gpos[g >> a.cshift] + sidx] = g;
         }
         __syncthreads();
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// One wave per (minibatch, segment) of at most 1024 pairs: the sort runs in registers.
-// Sort key = (id - first id of the segment) << 12 | slot, 32 bits (segments span <= 2^20 ids).
-// Lane l holds sorted positions [16 l, 16 l + 16): compare-exchanges at distance < 16 stay inside
-// a lane, larger distances pair the same register of two lanes (one cross-lane move each).
-// ---------------------------------------------------------------------------------------------
-constexpr int kWaveSeg = 1024; // pairs per segment handled by one wave
-constexpr int kRanges = 256;    // destination ranges per minibatch the fused back-split handles (kMaxPlaceTiles)
-constexpr int kRangeShift = 13; // 8192 positions per destination range (kDedupPlaceTile)
-constexpr int kRangeSize = 1 << kRangeShift;
-static_assert(kRangeSize == kDedupPlaceTile && 3 * kRanges <= kWaveSeg, "range constants out of step");
-// LDS staging index: lanes that hold neighbouring runs of slots would all hit the same banks
-__device__ inline uint32_t swz(uint32_t x) { return x ^ ((x >> 5) & 31u); }
+// One workgroup per (minibatch, segment) of at most kRankCap ids: ranks by counting, no sorting network.
+// Every thread keeps its ids (slot j = q NT + tid) in registers through all steps.
+//   1  the ids are counted into up to 4096 buckets by their leading bits (about one id per bucket)
+//   2  exclusive scan of the bucket sizes (every wave a contiguous part, 16 bytes per lane and access);
+//      a bucket of more than kRankMaxInBucket ids (one id sampled by many rows, ids crowded into a narrow range)
+//      hands the segment to the bitmap kernel, or the hop to the per-minibatch kernel when the segment is too
+//      wide for that
+//   3  every id goes to its bucket's place in LDS
+//   4  every id looks at the few ids of its bucket: `less` of them are smaller, `eqb` are equal and came before
+//      it; with eqb = 0 it is the head of its run of equal ids and sets bit (bucket start + less) = the run's
+//      place in ascending order
+//   5  popcount prefix over the head bits: the rank of an id among the distinct ones = heads before its run
+//   6  ranks leave in slot order; the heads leave their ids at their rank, copied out as the distinct ids
+constexpr int kRankCap = 4096;    // ids of a segment that one workgroup of the ranking kernel takes
+constexpr int kRankThreads = 512;
+constexpr int kRankBucketBits = 12; // at most 4096 buckets
+constexpr int kRankMaxInBucket = 32;
+static_assert(kRankCap == kRankCapFwd, "segment capacity out of step");
 
-// Value of lane (l ^ MASK) for a power-of-two MASK.  Partners up to 8 lanes away come through the vector
-// unit's lane-permute paths (quad permutes, row shifts and rotates: no LDS traffic); 16 and 32 lanes away through
-// the LDS crossbar.
-template <int MASK>
-__device__ inline uint32_t lane_xor(uint32_t x)
+__global__ __launch_bounds__(kRankThreads) void dd_rank_kernel(DedupArgs a)
 {
-    if constexpr (MASK == 1) {
-        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
-    } else if constexpr (MASK == 2) {
-        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, true);
-    } else if constexpr (MASK == 4) {
-        // lanes 0-3 and 8-11 of every row of 16 take the lane 4 above, the others the lane 4 below
-        int o = __builtin_amdgcn_update_dpp((int)x, (int)x, 0x104 /* row_shl:4 */, 0xF, 0x5, false);
-        o = __builtin_amdgcn_update_dpp(o, (int)x, 0x114 /* row_shr:4 */, 0xF, 0xA, false);
-        return (uint32_t)o;
-    } else if constexpr (MASK == 8) {
-        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128 /* row_ror:8 */, 0xF, 0xF, true);
-    } else {
-        return (uint32_t)__shfl_xor((int)x, MASK, kWave);
+    constexpr int NT = kRankThreads, NW = NT / kWave, PER = kRankCap / NT, NB = 1 << kRankBucketBits;
+    __shared__ uint4 cnt4[NB / 4 + 1];           // bucket sizes, then bucket starts; start[nb] = m
+    __shared__ uint32_t sorted[kRankCap];        // ids by bucket (relative to the segment's first id); then the distinct ones
+    __shared__ uint32_t hbits[kRankCap / 32], hpre[kRankCap / 32];
+    __shared__ uint32_t wtot[NW];
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(cnt4);
+    if (*a.fallback)
+        return;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t nseg = (int64_t)a.k * a.C;
+    for (int64_t w = blockIdx.x; w < nseg; w += gridDim.x) {
+        // workgroups that run at the same time take segments of different minibatches
+        const int64_t i = w % a.k;
+        const uint32_t cseg = (uint32_t)(w / a.k);
+        const int64_t sg = i * a.C + cseg;
+        const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
+        const uint32_t s0 = soff[cseg], m = soff[cseg + 1] - s0;
+        if (m > (uint32_t)kRankCap)
+            continue; // listed for the bitmap kernel by the scan
+        if (m == 0) {
+            if (tid == 0)
+                a.seg_cnt[sg] = 0;
+            continue;
+        }
+        const int64_t e0 = a.mb_edgeoff[i];
+        const uint32_t *__restrict__ ids = a.ids_seg + e0 + s0;
+        const uint32_t id0 = cseg << a.cshift;
+        uint32_t key[PER];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const uint32_t j = q * NT + tid;
+            key[q] = j < m ? ids[j] - id0 : 0xFFFFFFFFu;
+        }
+        // buckets: a power of two >= m, 512..4096, no more than the segment has ids
+        int nbits = 32 - __clz(m - 1u); // ceil(log2 m); m = 1: __clz(0) = 32
+        if (m == 1u || nbits < 9)
+            nbits = 9;
+        if (nbits > kRankBucketBits)
+            nbits = kRankBucketBits;
+        if (nbits > a.cshift)
+            nbits = a.cshift;
+        const int bshift = a.cshift - nbits;
+        const int nb = 1 << nbits;
+        const int nqd = nb >= 4 ? nb / 4 : 1;                  // 16-byte quads of counters
+        const int qw = (nqd + NW - 1) / NW;                    // per wave
+        const int its = (qw + kWave - 1) / kWave;              // per lane: 1 or 2
+        for (int qd = tid; qd < nqd; qd += NT)
+            cnt4[qd] = make_uint4(0, 0, 0, 0);
+        for (uint32_t x = tid; x < (m + 31u) / 32u; x += NT)
+            hbits[x] = 0;
+        __syncthreads();
+        uint32_t slot[PER];
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+            if (key[q] != 0xFFFFFFFFu)
+                slot[q] = atomicAdd(&cnt[key[q] >> bshift], 1u);
+        __syncthreads();
+        // exclusive scan of the bucket sizes, in place
+        uint4 cv[2];
+        uint32_t inc[2], mine[2];
+        uint32_t wave_total = 0;
+        bool crowded = false;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            cv[it] = make_uint4(0, 0, 0, 0);
+            mine[it] = inc[it] = 0;
+            if (it < its) {
+                const int lq = it * kWave + lane; // quad inside this wave's part
+                if (lq < qw && wave * qw + lq < nqd)
+                    cv[it] = cnt4[wave * qw + lq];
+                crowded |= cv[it].x > (uint32_t)kRankMaxInBucket || cv[it].y > (uint32_t)kRankMaxInBucket ||
+                           cv[it].z > (uint32_t)kRankMaxInBucket || cv[it].w > (uint32_t)kRankMaxInBucket;
+                mine[it] = cv[it].x + cv[it].y + cv[it].z + cv[it].w;
+                inc[it] = wave_inclusive_scan_dpp(mine[it]) + wave_total;
+                wave_total = (uint32_t)__builtin_amdgcn_readlane((int)inc[it], kWave - 1);
+            }
+        }
+        if (lane == 0)
+            wtot[wave] = wave_total;
+        if (__syncthreads_or(crowded)) { // uniform for the workgroup
+            if (tid == 0) {
+                if (a.cshift <= kMaxBitmapShift)
+                    a.big_list[atomicAdd(a.big_count, 1u)] = (uint32_t)sg;
+                else
+                    atomicOr(a.fallback, 1);
+            }
+            continue;
+        }
+        uint32_t run = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2)
+            run += w2 < wave ? wtot[w2] : 0u;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            if (it < its) {
+                const int lq = it * kWave + lane;
+                if (lq < qw && wave * qw + lq < nqd) {
+                    const uint32_t s = run + inc[it] - mine[it];
+                    cnt4[wave * qw + lq] = make_uint4(s, s + cv[it].x, s + cv[it].x + cv[it].y, s + cv[it].x + cv[it].y + cv[it].z);
+                }
+            }
+        }
+        if (tid == 0)
+            cnt[nb] = m;
+        __syncthreads();
+        uint32_t bs[PER]; // start of the id's bucket; from step 4 on: place of its run
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+            if (key[q] != 0xFFFFFFFFu) {
+                bs[q] = cnt[key[q] >> bshift];
+                sorted[bs[q] + slot[q]] = key[q];
+            }
+        __syncthreads();
+        // place of every id's run of equal ids in ascending order; heads
+        if (bshift == 0) { // one id per bucket: the run is the bucket
+#pragma unroll
+            for (int q = 0; q < PER; ++q)
+                if (key[q] != 0xFFFFFFFFu && slot[q] == 0)
+                    atomicOr(&hbits[bs[q] >> 5], 1u << (bs[q] & 31u));
+        } else {
+#pragma unroll
+            for (int q = 0; q < PER; ++q)
+                if (key[q] != 0xFFFFFFFFu) {
+                    const uint32_t be = cnt[(key[q] >> bshift) + 1u], me = bs[q] + slot[q];
+                    uint32_t less = 0, eqb = 0;
+                    for (uint32_t t = bs[q]; t < be; ++t) {
+                        const uint32_t o = sorted[t];
+                        less += o < key[q] ? 1u : 0u;
+                        eqb += (o == key[q] && t < me) ? 1u : 0u;
+                    }
+                    bs[q] += less;
+                    slot[q] = eqb; // from here on: 0 marks the head of a run
+                    if (eqb == 0)
+                        atomicOr(&hbits[bs[q] >> 5], 1u << (bs[q] & 31u));
+                }
+        }
+        __syncthreads();
+        const uint32_t nwd = (m + 31u) / 32u; // <= 128 words of head bits
+        if (wave == 0) {
+            uint32_t carry = 0;
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const uint32_t x = it * kWave + lane;
+                const uint32_t pcw = x < nwd ? __popc(hbits[x]) : 0u;
+                const uint32_t in2 = wave_inclusive_scan_dpp(pcw) + carry;
+                if (x < nwd)
+                    hpre[x] = in2 - pcw;
+                carry = (uint32_t)__builtin_amdgcn_readlane((int)in2, kWave - 1);
+            }
+            if (lane == 0) {
+                wtot[0] = carry;
+                a.seg_cnt[sg] = carry;
+            }
+        }
+        __syncthreads();
+        const uint32_t cnt_distinct = wtot[0];
+        uint16_t *__restrict__ ranks = a.ranks + e0 + s0;
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+            if (key[q] != 0xFFFFFFFFu) {
+                const uint32_t p = bs[q];
+                const uint32_t r = hpre[p >> 5] + __popc(hbits[p >> 5] & ((1u << (p & 31u)) - 1u));
+                ranks[q * NT + tid] = (uint16_t)r;
+                if (slot[q] == 0)
+                    sorted[r] = key[q]; // every id has been looked at (step 4): their place now takes the distinct ones
+            }
+        __syncthreads();
+        uint32_t *__restrict__ uids = a.uids + e0 + s0;
+        for (uint32_t r = tid; r < cnt_distinct; r += NT)
+            uids[r] = id0 + sorted[r];
+        __syncthreads();
     }
 }
 
-// Bitonic network over 64*R values, R per lane; lane l ends up with sorted positions [R l, R l + R).
-template <int R>
-__device__ inline void wave_sort(uint32_t (&c)[R], int lane)
+// Ranking through a bitmap of the segment's id range in LDS (2^cshift bits, at most 128 KB): no sort.  The rank
+// of an id among the segment's distinct ids is the number of set bits below it, the distinct ids in rank order are
+// the set bits in order.  Work per segment = one pass over the bitmap (16 bytes per lane and access, no bank
+// conflicts) + a few operations per id, whatever the ids' multiplicities; a segment may hold up to kSegCap ids (a
+// rank has 16 bits).  LISTED = false: every segment of the hop (hops whose ids are dense enough that the pass over
+// the bitmap costs less than sorting); LISTED = true: the segments that the sorting kernel handed over.
+//   1  the ids' bits are set (LDS atomics); the first kBmKeep ids of every thread stay in registers
+//   2  every wave owns a contiguous part of the bitmap, in "quads" of 128 bits, quad it*64 + lane of the part in
+//      iteration it: popcounts, wave totals -> set bits before the wave's part; running count before every quad
+//      (16 bits, kept in LDS); the set bits of the quads leave as the distinct ids
+//   3  rank of an id = count before its quad + set bits below it inside the quad
+//   4  the bitmap is cleared again: word by word through the ids when they are few, else as a whole
+constexpr int kBmThreads = 1024;
+constexpr int kBmWaves = kBmThreads / kWave;
+constexpr int kBmKeep = 4;  // ids per thread kept in registers between the passes (segments up to 4096 ids)
+constexpr int kBmIts = 8;   // quads per lane: 16 waves x 64 lanes x 8 quads x 128 bits = 2^20 bits
+static_assert(kBmWaves * kWave * kBmIts * 128 == (1 << kMaxBitmapShift), "bitmap geometry out of step");
+size_t dd_bitmap_lds_bytes(int cshift)
 {
+    size_t quads = ((size_t)1 << cshift) / 128;
+    if (quads < (size_t)kBmWaves * kWave)
+        quads = (size_t)kBmWaves * kWave; // every lane owns at least one quad
+    return quads * 16 + quads * sizeof(uint16_t);
+}
+
+template <bool LISTED>
+__global__ __launch_bounds__(kBmThreads) void dd_bitmap_kernel(DedupArgs a)
+{
+    extern __shared__ uint4 bm_lds[]; // quads, then one 16-bit running count per quad
+    __shared__ uint32_t wtot[kBmWaves];
+    if (*a.fallback || a.cshift > kMaxBitmapShift)
+        return;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    uint32_t nq = (1u << a.cshift) / 128u;
+    if (nq < (uint32_t)(kBmWaves * kWave))
+        nq = kBmWaves * kWave;
+    const int its = (int)(nq / (kBmWaves * kWave)); // quads per lane: 1, 2, 4 or 8
+    uint4 *quads = bm_lds;
+    uint32_t *words = reinterpret_cast<uint32_t *>(bm_lds);
+    uint16_t *qpre = reinterpret_cast<uint16_t *>(bm_lds + nq);
+    const uint32_t q_wave = (uint32_t)wave * (uint32_t)(its * kWave); // first quad of this wave's part
+    for (int it = 0; it < its; ++it)
+        quads[q_wave + it * kWave + lane] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+    const int64_t nwork = LISTED ? (int64_t)*a.big_count : (int64_t)a.k * a.C;
+    // a segment's first ids are fetched while the segment before it is worked on
+    struct Seg {
+        int64_t sg, e0;
+        uint32_t s0, m, c;
+        uint32_t keep[kBmKeep]; // the first kBmKeep ids of this thread, relative to the segment's first id
+    };
+    auto fetch = [&](int64_t x, Seg &g) {
+        g.m = 0;
+        g.sg = -1;
+        if (x >= nwork)
+            return;
+        if (LISTED)
+            g.sg = a.big_list[x];
+        else // workgroups that run at the same time take segments of different minibatches
+            g.sg = (x % a.k) * a.C + x / a.k;
+        const int64_t i = g.sg / a.C;
+        g.c = (uint32_t)(g.sg % a.C);
+        const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
+        g.s0 = soff[g.c];
+        g.m = soff[g.c + 1] - g.s0;
+        g.e0 = a.mb_edgeoff[i];
+        const uint32_t *__restrict__ ids = a.ids_seg + g.e0 + g.s0;
+        const uint32_t id0 = g.c << a.cshift;
 #pragma unroll
-    for (int size = 2; size <= kWave * R; size <<= 1) {
+        for (int q = 0; q < kBmKeep; ++q) {
+            const uint32_t j = q * kBmThreads + tid;
+            g.keep[q] = j < g.m ? ids[j] - id0 : 0xFFFFFFFFu;
+        }
+    };
+    Seg nxt;
+    fetch(blockIdx.x, nxt);
+    for (int64_t x = blockIdx.x; x < nwork; x += gridDim.x) {
+        const Seg cur = nxt;
+        fetch(x + gridDim.x, nxt);
+        const uint32_t m = cur.m;
+        if (m == 0) {
+            if (tid == 0)
+                a.seg_cnt[cur.sg] = 0;
+            continue;
+        }
+        const uint32_t *__restrict__ ids = a.ids_seg + cur.e0 + cur.s0;
+        uint16_t *__restrict__ ranks = a.ranks + cur.e0 + cur.s0;
+        uint32_t *__restrict__ uids = a.uids + cur.e0 + cur.s0;
+        const uint32_t id0 = cur.c << a.cshift;
+        const int64_t sg = cur.sg;
+        const uint32_t(&keep)[kBmKeep] = cur.keep;
+        // 1: set bits
 #pragma unroll
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            if (stride >= R) {
-                const int lmask = stride / R;
-                const bool lower = (lane & lmask) == 0;
+        for (int q = 0; q < kBmKeep; ++q)
+            if (keep[q] != 0xFFFFFFFFu)
+                atomicOr(&words[keep[q] >> 5], 1u << (keep[q] & 31u));
+        for (uint32_t j = kBmKeep * kBmThreads + tid; j < m; j += kBmThreads) {
+            const uint32_t b = ids[j] - id0;
+            atomicOr(&words[b >> 5], 1u << (b & 31u));
+        }
+        __syncthreads();
+        // 2: counts before every quad, distinct ids
+        uint32_t pc[kBmIts], inc[kBmIts];
+        uint32_t wave_total = 0;
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const uint32_t o = lmask == 1 ? lane_xor<1>(c[r]) : lmask == 2 ? lane_xor<2>(c[r])
-                                     : lmask == 4 ? lane_xor<4>(c[r]) : lmask == 8 ? lane_xor<8>(c[r])
-                                     : lmask == 16 ? lane_xor<16>(c[r]) : lane_xor<32>(c[r]);
-                    const bool asc = ((lane * R + r) & size) == 0; // always true in the last merge
-                    c[r] = (lower == asc) ? min(c[r], o) : max(c[r], o);
-                }
-            } else {
+        for (int it = 0; it < kBmIts; ++it) {
+            pc[it] = 0;
+            inc[it] = 0;
+            if (it < its) {
+                const uint4 qv = quads[q_wave + it * kWave + lane];
+                pc[it] = __popc(qv.x) + __popc(qv.y) + __popc(qv.z) + __popc(qv.w);
+                inc[it] = wave_inclusive_scan_dpp(pc[it]) + wave_total; // set bits of this wave's part up to this quad
+                wave_total = (uint32_t)__builtin_amdgcn_readlane((int)inc[it], kWave - 1);
+            }
+        }
+        if (lane == 0)
+            wtot[wave] = wave_total;
+        __syncthreads();
+        uint32_t run = 0, cnt = 0; // set bits before this wave's part; in the whole bitmap
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    if ((r & stride) == 0) {
-                        const uint32_t x = c[r], y = c[r | stride];
-                        const uint32_t lo = min(x, y), hi = max(x, y);
-                        const bool asc = ((lane * R + r) & size) == 0;
-                        c[r] = asc ? lo : hi;
-                        c[r | stride] = asc ? hi : lo;
+        for (int w = 0; w < kBmWaves; ++w) {
+            const uint32_t t = wtot[w];
+            run += w < wave ? t : 0u;
+            cnt += t;
+        }
+#pragma unroll
+        for (int it = 0; it < kBmIts; ++it) {
+            if (it < its) {
+                uint32_t before = run + inc[it] - pc[it];
+                qpre[q_wave + it * kWave + lane] = (uint16_t)before;
+                if (pc[it]) { // the quad is read again: holding all of them in registers since the first pass costs more
+                    const uint32_t first = id0 + (q_wave + it * kWave + lane) * 128u;
+                    const uint4 qv = quads[q_wave + it * kWave + lane];
+                    const uint32_t xs[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        uint32_t wbits = xs[u];
+                        while (wbits) {
+                            const uint32_t bit = (uint32_t)__ffs((int)wbits) - 1u;
+                            uids[before++] = first + u * 32u + bit;
+                            wbits &= wbits - 1u;
+                        }
                     }
                 }
             }
         }
-    }
-}
-
-// Sorts one segment of m <= 64 R pairs and writes its entries; returns the number of distinct ids.
-// When `back` is not null the entries go straight to the slot lists of their destination ranges
-// (the wave counting-sorts them by range in LDS and appends every run with wide stores, see the
-// fix-up kernels); otherwise they return to `pairs` for the stand-alone split kernel.
-template <int R>
-__device__ inline uint32_t rank_segment_wave(uint64_t *__restrict__ pairs, uint32_t *__restrict__ uids, uint32_t m,
-                                             uint32_t id0, uint32_t cseg, uint32_t *idx_l, uint64_t *out_l, int lane,
-                                             uint64_t *__restrict__ back, uint32_t *__restrict__ range_cursor, int nq)
-{
-    uint32_t c[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint32_t j = r * kWave + lane;
-        c[r] = 0xFFFFFFFFu;
-        if (j < m) {
-            const uint64_t p = pairs[j];
-            idx_l[j] = (uint32_t)p;
-            c[r] = (((uint32_t)(p >> 32) - id0) << 12) | j;
-        }
-    }
-    wave_sort<R>(c, lane);
-    __builtin_amdgcn_wave_barrier();
-    // sorted position e = R lane + r; heads = first occurrence of an id
-    const uint32_t last_below = __shfl_up(c[R - 1], 1, kWave);
-    uint32_t heads = 0;
-    bool head[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint32_t prev = r ? c[r - 1] : last_below;
-        const bool first = (r == 0 && lane == 0);
-        head[r] = c[r] != 0xFFFFFFFFu && (first || (c[r] >> 12) != (prev >> 12));
-        heads += head[r] ? 1u : 0u;
-    }
-    const uint32_t inc = wave_inclusive_scan(heads);
-    const uint32_t cnt = __shfl(inc, kWave - 1, kWave);
-    uint32_t rank = inc - heads; // heads before this lane
-    if (back == nullptr) {
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            rank += head[r] ? 1u : 0u;
-            if (c[r] != 0xFFFFFFFFu) // back to the slot the pair came from: the order of the pairs is free
-                out_l[swz(c[r] & 0xFFFu)] = pack_entry(idx_l[c[r] & 0xFFFu], rank - 1u, cseg);
-        }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const uint32_t j = r * kWave + lane;
-            if (j < m)
-                pairs[j] = out_l[swz(j)];
-        }
-    } else {
-        uint32_t pidx[R]; // position of the pair in its minibatch; its destination range is pidx >> 13
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            pidx[r] = c[r] != 0xFFFFFFFFu ? idx_l[c[r] & 0xFFFu] : 0xFFFFFFFFu;
-        __builtin_amdgcn_wave_barrier();
-        // the position table is no longer needed: its LDS now holds, per destination range, the entry
-        // count, the start inside this wave's staging and (start in the slot list - start in the staging)
-        uint32_t *cntq = idx_l, *offq = idx_l + kRanges, *gdelta = idx_l + 2 * kRanges;
-        for (int u = 0; u < nq; ++u)
-            cntq[u * kWave + lane] = 0;
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int r = 0; r < R; ++r) // the slot number in the key's low bits gives way to the place within the range
-            if (pidx[r] != 0xFFFFFFFFu)
-                c[r] = (c[r] & ~0xFFFu) | atomicAdd(&cntq[pidx[r] >> kRangeShift], 1u);
-        __builtin_amdgcn_wave_barrier();
-        uint32_t carry = 0;
-        for (int u = 0; u < nq; ++u) { // lane owns range 64 u + lane
-            const uint32_t q = u * kWave + lane;
-            const uint32_t mine = cntq[q];
-            const uint32_t inc_q = wave_inclusive_scan(mine);
-            const uint32_t start = carry + inc_q - mine;
-            offq[q] = start;
-            if (mine)
-                gdelta[q] = q * kRangeSize + atomicAdd(&range_cursor[q], mine) - start;
-            carry += __shfl(inc_q, kWave - 1, kWave);
-        }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            rank += head[r] ? 1u : 0u;
-            if (pidx[r] != 0xFFFFFFFFu)
-                out_l[swz(offq[pidx[r] >> kRangeShift] + (c[r] & 0xFFFu))] = pack_entry(pidx[r], rank - 1u, cseg);
-        }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const uint32_t t = r * kWave + lane;
-            if (t < m) {
-                const uint64_t e = out_l[swz(t)];
-                back[gdelta[(uint32_t)e >> kRangeShift] + t] = e;
-            }
-        }
-    }
-    __builtin_amdgcn_wave_barrier();
-    rank = inc - heads;
-    uint32_t *ids_l = reinterpret_cast<uint32_t *>(out_l); // the distinct ids in rank order, staged for wide stores
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        rank += head[r] ? 1u : 0u;
-        if (head[r])
-            ids_l[swz(rank - 1u)] = id0 + (c[r] >> 12);
-    }
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint32_t j = r * kWave + lane;
-        if (j < cnt)
-            uids[j] = ids_l[swz(j)];
-    }
-    __builtin_amdgcn_wave_barrier();
-    return cnt;
-}
-
-// WIDE = false: segments of at most 512 pairs; WIDE = true: those of 513..1024 pairs, whose sorting
-// network needs twice the registers (two kernels, so that the common small segments run at the
-// higher occupancy)
-template <bool WIDE>
-__global__ __launch_bounds__(256) void dd_sort_wave_kernel(DedupArgs a)
-{
-    constexpr int kIdxWords = WIDE ? kWaveSeg : 3 * kRanges; // per wave; also holds the three range tables
-    constexpr int kOutSlots = WIDE ? kWaveSeg : kWaveSeg / 2;
-    __shared__ uint32_t idx_all[4 * kIdxWords];  // position of every pair of the segment
-    __shared__ uint64_t out_all[4 * kOutSlots];  // staging for coalesced stores
-    if (*a.fallback)
-        return;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    uint32_t *idx_l = idx_all + wave * kIdxWords;
-    uint64_t *out_l = out_all + wave * kOutSlots;
-    const int64_t nseg = WIDE ? (int64_t)*a.wide_count : (int64_t)a.k * ((a.C + 3) & ~3);
-    for (int64_t w = (int64_t)blockIdx.x * 4 + wave; w < nseg; w += (int64_t)gridDim.x * 4) {
-        int64_t i, sg;
-        uint32_t cseg;
-        if (WIDE) {
-            sg = a.wide_list[w];
-            i = sg / a.C;
-            cseg = (uint32_t)(sg % a.C);
-        } else {
-            // workgroups that run at the same time take segments of different minibatches, so that their
-            // appends to the slot lists do not queue up on the cursors of one minibatch; the 4 waves of a
-            // workgroup take neighbouring segments of one minibatch
-            const int64_t grp = w >> 2;
-            i = grp % a.k;
-            cseg = (uint32_t)((grp / a.k) * 4 + (w & 3));
-            if (cseg >= (uint32_t)a.C)
-                continue;
-            sg = i * a.C + cseg;
-        }
-        const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
-        const uint32_t s0 = soff[cseg], m = soff[cseg + 1] - s0;
-        if (m > (uint32_t)kWaveSeg)
-            continue; // sorted by a whole workgroup in dd_sort_kernel
-        if ((m > 512u) != WIDE)
-            continue;
-        uint32_t cnt = 0;
-        if (m > 0) {
-            const int64_t e0 = a.mb_edgeoff[i];
-            uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
-            uint32_t *__restrict__ uids = reinterpret_cast<uint32_t *>(a.utmp) + e0 + s0;
-            const uint32_t id0 = cseg << a.cshift;
-            // minibatches of at most 256 destination ranges take the fused back-split
-            const uint32_t Ni = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
-            const uint32_t Q = (Ni + kRangeSize - 1) >> kRangeShift;
-            const bool fused = a.fuse_back && Q <= (uint32_t)kRanges;
-            const int nq = (int)((Q + kWave - 1) / kWave); // groups of 64 ranges in use
-            uint64_t *back = fused ? a.back + e0 : nullptr;
-            uint32_t *cursor = a.place_cursor + a.place_tileoff[i];
-            if (WIDE)
-                cnt = rank_segment_wave<16>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
-            else if (m <= 64)
-                cnt = rank_segment_wave<1>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
-            else if (m <= 128)
-                cnt = rank_segment_wave<2>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
-            else if (m <= 256)
-                cnt = rank_segment_wave<4>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
-            else
-                cnt = rank_segment_wave<8>(pairs, uids, m, id0, cseg, idx_l, out_l, lane, back, cursor, nq);
-        }
-        if (lane == 0)
-            a.seg_cnt[sg] = cnt;
-    }
-}
-template __global__ void dd_sort_wave_kernel<false>(DedupArgs);
-template __global__ void dd_sort_wave_kernel<true>(DedupArgs);
-
-// One workgroup per (minibatch, segment) of more than 1024 pairs (ids crowded into the segment's range, or one id
-// sampled by many rows): no sort.  The segment spans 2^cshift ids, so a bitmap of that many bits in LDS
-// (at most 128 KB) takes every pair's id; the rank of an id among the distinct ones is the number of set bits
-// below it (a running count per group of 8 words + popcounts inside the group), the distinct ids in rank
-// order are the set bits in order.  The pairs are read twice from memory and never held in LDS, so the
-// cost grows with the number of pairs only linearly and a segment may hold up to kSegCap of them
-// (the rank field of an entry has 16 bits).
-constexpr int kBigThreads = 1024;
-constexpr int kRankGroup = 8; // bitmap words per running count
-size_t dd_rank_lds_bytes(int cshift)
-{
-    size_t words = ((size_t)1 << cshift) / 32;
-    if (words < (size_t)kRankGroup)
-        words = kRankGroup;
-    return words * sizeof(uint32_t) + (words / kRankGroup) * sizeof(uint32_t);
-}
-
-__global__ __launch_bounds__(kBigThreads) void dd_sort_kernel(DedupArgs a)
-{
-    extern __shared__ uint32_t rank_lds[]; // bitmap words, then one running count per kRankGroup words
-    __shared__ uint32_t smem[kBigThreads / kWave];
-    if (*a.fallback)
-        return;
-    const int tid = threadIdx.x;
-    uint32_t nw = (1u << a.cshift) / 32u;
-    if (nw < (uint32_t)kRankGroup)
-        nw = kRankGroup;
-    const uint32_t ng = nw / kRankGroup;
-    uint32_t *bm = rank_lds, *before = rank_lds + nw;
-    const uint32_t nbig = *a.big_count;
-    for (uint32_t x = blockIdx.x; x < nbig; x += gridDim.x) {
-        const int64_t sg = a.big_list[x];
-        const int64_t i = sg / a.C;
-        const uint32_t c = (uint32_t)(sg % a.C);
-        const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
-        const uint32_t s0 = soff[c], m = soff[c + 1] - s0;
-        const int64_t e0 = a.mb_edgeoff[i];
-        uint64_t *__restrict__ pairs = a.pairs + e0 + s0;
-        uint32_t *__restrict__ uids = reinterpret_cast<uint32_t *>(a.utmp) + e0 + s0;
-        const uint32_t id0 = c << a.cshift;
-        for (uint32_t q = tid; q < nw; q += kBigThreads)
-            bm[q] = 0;
-        __syncthreads();
-        for (uint32_t j = tid; j < m; j += kBigThreads) {
-            const uint32_t b = (uint32_t)(pairs[j] >> 32) - id0;
-            atomicOr(&bm[b >> 5], 1u << (b & 31u));
-        }
-        __syncthreads();
-        // set bits before every group of kRankGroup words: groups dealt to the threads in contiguous runs
-        const uint32_t per = (ng + kBigThreads - 1) / kBigThreads;
-        const uint32_t g_lo = tid * per, g_hi = (g_lo + per < ng) ? g_lo + per : ng;
-        uint32_t mine = 0;
-        for (uint32_t g = g_lo; g < g_hi; ++g)
-#pragma unroll
-            for (int q = 0; q < kRankGroup; ++q)
-                mine += __popc(bm[g * kRankGroup + q]);
-        uint32_t cnt;
-        uint32_t run = block_exclusive_scan<uint32_t, kBigThreads>(mine, smem, cnt);
-        for (uint32_t g = g_lo; g < g_hi; ++g) {
-            before[g] = run;
-            // the distinct ids of this group in rank order
-            for (int q = 0; q < kRankGroup; ++q) {
-                uint32_t wbits = bm[g * kRankGroup + q];
-                while (wbits) {
-                    const uint32_t bit = (uint32_t)__ffs((int)wbits) - 1u;
-                    uids[run++] = id0 + (g * kRankGroup + q) * 32u + bit;
-                    wbits &= wbits - 1u;
-                }
-            }
-        }
-        __syncthreads();
-        for (uint32_t j = tid; j < m; j += kBigThreads) {
-            const uint64_t p = pairs[j];
-            const uint32_t b = (uint32_t)(p >> 32) - id0;
-            const uint32_t w = b >> 5, g = w / kRankGroup;
-            uint32_t rank = before[g] + __popc(bm[w] & ((1u << (b & 31u)) - 1u));
-            for (uint32_t q = g * kRankGroup; q < w; ++q)
-                rank += __popc(bm[q]);
-            pairs[j] = pack_entry((uint32_t)p, rank, c);
-        }
         if (tid == 0)
             a.seg_cnt[sg] = cnt;
+        __syncthreads();
+        // 3: ranks
+        auto rank_of = [&](uint32_t b) -> uint32_t {
+            const uint4 v = quads[b >> 7];
+            const uint32_t w = (b >> 5) & 3u, below = (1u << (b & 31u)) - 1u;
+            const uint32_t word = w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
+            return qpre[b >> 7] + (w > 0 ? __popc(v.x) : 0) + (w > 1 ? __popc(v.y) : 0) + (w > 2 ? __popc(v.z) : 0) +
+                   __popc(word & below);
+        };
+#pragma unroll
+        for (int q = 0; q < kBmKeep; ++q)
+            if (keep[q] != 0xFFFFFFFFu)
+                ranks[q * kBmThreads + tid] = (uint16_t)rank_of(keep[q]);
+        for (uint32_t j = kBmKeep * kBmThreads + tid; j < m; j += kBmThreads)
+            ranks[j] = (uint16_t)rank_of(ids[j] - id0);
+        __syncthreads();
+        // 4: clear
+        if (m * 4u < nq) {
+#pragma unroll
+            for (int q = 0; q < kBmKeep; ++q)
+                if (keep[q] != 0xFFFFFFFFu)
+                    words[keep[q] >> 5] = 0u;
+            for (uint32_t j = kBmKeep * kBmThreads + tid; j < m; j += kBmThreads)
+                words[(ids[j] - id0) >> 5] = 0u;
+        } else {
+            for (int it = 0; it < its; ++it)
+                quads[q_wave + it * kWave + lane] = make_uint4(0, 0, 0, 0);
+        }
         __syncthreads();
     }
 }
@@ -552,49 +603,161 @@ __global__ __launch_bounds__(256) void dd_base_scan_kernel(DedupArgs a)
         a.mb_count[i] = carry_s;
 }
 
-void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, const StageMark &mark)
+// The cut in reverse: tile t appended, for every segment c, one run of ids to the segment; the ranks of those
+// ids lie at the same places.  Per tile: the runs' ranks are read back run by run (wide loads), the distinct
+// ids before the segment are added, the value goes to the position that put the id there (scatter inside
+// LDS), and the tile's local column indices leave in position order.
+template <int TILE, int NT>
+__global__ __launch_bounds__(NT) void dd_unsplit_kernel(DedupArgs a, const int64_t *__restrict__ tileoff)
 {
-    mark("dd_count");
-    // the flag, the two list counters and the segment counters lie next to each other: one clear
+    extern __shared__ uint32_t unsplit_lds[]; // stage[TILE], out[TILE]; then 3 C words: start in the tile, start in global - start in the tile, base
+    __shared__ uint32_t smem[NT / kWave];
+    __shared__ uint32_t carry_s;
+    if (*a.fallback)
+        return;
+    uint32_t *stage = unsplit_lds, *out = unsplit_lds + TILE;
+    uint32_t *off = unsplit_lds + 2 * TILE, *delta = off + a.C, *base_l = off + 2 * a.C;
+    const int tid = threadIdx.x;
+    const int64_t ntiles = tileoff[a.k];
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int i = locate_segment(tileoff, a.k, t);
+        const int64_t e0 = a.mb_edgeoff[i];
+        const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
+        const uint32_t j0 = (uint32_t)(t - tileoff[i]) * TILE;
+        const uint32_t jend = (j0 + TILE < N) ? j0 + TILE : N;
+        const uint32_t *__restrict__ loc = a.loc + e0;
+        uint32_t lc[TILE / NT];
+#pragma unroll
+        for (int q = 0; q < TILE / NT; ++q) {
+            const uint32_t j = j0 + q * NT + tid;
+            lc[q] = j < jend ? loc[j] : 0xFFFFFFFFu;
+        }
+        if (tid == 0)
+            carry_s = 0;
+        __syncthreads();
+        const uint32_t *__restrict__ run_gpos = a.run_gpos + t * a.C, *__restrict__ run_cnt = a.run_cnt + t * a.C;
+        for (int base = 0; base < a.C; base += NT) {
+            const int c = base + tid;
+            const uint32_t v = c < a.C ? run_cnt[c] : 0u;
+            uint32_t total;
+            const uint32_t ex = block_exclusive_scan<uint32_t, NT>(v, smem, total);
+            const uint32_t carry = carry_s;
+            if (c < a.C) {
+                off[c] = carry + ex;
+                delta[c] = run_gpos[c] - (carry + ex);
+                base_l[c] = a.bin_base[(int64_t)i * a.stride + c];
+            }
+            __syncthreads();
+            if (tid == 0)
+                carry_s = carry + total;
+            __syncthreads();
+        }
+#pragma unroll
+        for (int q = 0; q < TILE / NT; ++q)
+            if (lc[q] != 0xFFFFFFFFu) {
+                const uint32_t c = lc[q] >> kLocShift;
+                stage[off[c] + (lc[q] & (TILE - 1))] = (c << kLocShift) | (uint32_t)(q * NT + tid);
+            }
+        __syncthreads();
+        const uint16_t *__restrict__ ranks = a.ranks + e0;
+        for (uint32_t s0 = 0; s0 < jend - j0; s0 += 4 * NT) { // four independent loads in flight per lane
+            uint32_t x[4], r[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t sidx = s0 + u * NT + tid;
+                x[u] = sidx < jend - j0 ? stage[sidx] : 0xFFFFFFFFu;
+                if (x[u] != 0xFFFFFFFFu) {
+                    const uint32_t c = x[u] >> kLocShift;
+                    r[u] = base_l[c] + ranks[delta[c] + sidx];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (x[u] != 0xFFFFFFFFu)
+                    out[x[u] & (TILE - 1)] = r[u];
+        }
+        __syncthreads();
+        int32_t *__restrict__ col = a.col + e0 + j0;
+        for (uint32_t idx = tid; idx < jend - j0; idx += NT)
+            col[idx] = (int32_t)out[idx];
+        __syncthreads();
+    }
+}
+
+void launch_nw_dedup_prepare(const Launch &L, const DedupArgs &a, int64_t nnz)
+{
+    if (a.C == 0)
+        return;
+    // the flag, the list counter and the segment counters lie next to each other: one clear
     (void)hipMemsetAsync(a.fallback, 0, (size_t)(a.seg_cnt - reinterpret_cast<uint32_t *>(a.fallback)) * sizeof(uint32_t) +
                                             (size_t)a.k * a.C * sizeof(uint32_t), L.stream);
     (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kDedupPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
-    // tiles of the count / split kernels, of the placing kernel and of the stand-alone back-split
+}
+
+void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, bool counted, const StageMark &mark)
+{
+    mark("dd_count");
+    // tiles of the count / split / un-split kernels; of the placing kernel and the split of the per-minibatch path
     launch_plan_tiles3(L, a.mb_edgeoff, a.k, kSplitTile16, a.big_tileoff, kDedupPlaceTile, a.place_tileoff, kDedupSplitTile,
                        a.split_tileoff);
     const int64_t tiles = nnz / kSplitTile16 + a.k;
-    hipLaunchKernelGGL((dd_count_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 2)), dim3(1024), 0, L.stream, a,
-                       a.big_tileoff);
+    if (!counted)
+        hipLaunchKernelGGL((dd_count_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 2)), dim3(1024), 0, L.stream, a,
+                           a.big_tileoff);
     hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
     mark("dd_split");
-    { // 16384 ids per step, one workgroup of 16 waves per compute unit
+    { // 16384 ids per step, two workgroups of 16 waves per compute unit
         static bool attr_set = false;
-        const size_t lds = (size_t)kSplitTile16 * sizeof(uint64_t) + 3 * (size_t)a.C * sizeof(uint32_t);
+        const size_t lds = (size_t)kSplitTile16 * sizeof(uint32_t) + 3 * (size_t)a.C * sizeof(uint32_t);
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_split_kernel<kSplitTile16, 1024>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)(kSplitTile16 * sizeof(uint64_t) + 3 * kMaxSegments * sizeof(uint32_t))) != hipSuccess)
+                                    (int)(kSplitTile16 * sizeof(uint32_t) + 3 * kMaxSegments * sizeof(uint32_t))) != hipSuccess)
                 (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
             attr_set = true;
         }
-        hipLaunchKernelGGL((dd_split_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 1)), dim3(1024), lds,
+        hipLaunchKernelGGL((dd_split_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 2)), dim3(1024), lds,
                            L.stream, a, a.big_tileoff);
     }
-    mark("dd_sort");
-    hipLaunchKernelGGL(dd_sort_wave_kernel<false>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 4)), dim3(256), 0, L.stream, a);
-    hipLaunchKernelGGL(dd_sort_wave_kernel<true>, dim3(grid_for(L, ((int64_t)a.k * a.C + 3) / 4, 2)), dim3(256), 0, L.stream, a);
-    { // segments of more than 1024 pairs: ranked through a bitmap of the segment's id range in LDS
-        static bool big_attr_set = false;
-        if (!big_attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_sort_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)dd_rank_lds_bytes(20)) != hipSuccess)
-                (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
-            big_attr_set = true;
-        }
-        hipLaunchKernelGGL(dd_sort_kernel, dim3(grid_for(L, nnz / 1024 + 1, 2)), dim3(kBigThreads),
-                           dd_rank_lds_bytes(a.cshift), L.stream, a);
+    mark("dd_rank");
+    static bool big_attr_set = false;
+    if (!big_attr_set) {
+        const int most = (int)dd_bitmap_lds_bytes(kMaxBitmapShift);
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_bitmap_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, most) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(dd_bitmap_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, most) != hipSuccess)
+            (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
+        big_attr_set = true;
+    }
+    const size_t bm_lds = dd_bitmap_lds_bytes(a.cshift);
+    const int bm_per_cu = (int)std::max<size_t>(1, std::min<size_t>(2, (size_t)(156 * 1024) / bm_lds));
+    if (a.by_bitmap) {
+        hipLaunchKernelGGL(dd_bitmap_kernel<false>, dim3(grid_for(L, (int64_t)a.k * a.C, bm_per_cu)), dim3(kBmThreads),
+                           bm_lds, L.stream, a);
+    } else {
+        hipLaunchKernelGGL(dd_rank_kernel, dim3(grid_for(L, (int64_t)a.k * a.C, 4)), dim3(kRankThreads), 0, L.stream, a);
+        if (a.cshift <= kMaxBitmapShift) // segments the sorting kernel did not take
+            hipLaunchKernelGGL(dd_bitmap_kernel<true>, dim3(grid_for(L, nnz / 1024 + 1, bm_per_cu)), dim3(kBmThreads),
+                               bm_lds, L.stream, a);
     }
     hipLaunchKernelGGL(dd_base_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
+}
+
+void launch_nw_dedup_unsplit(const Launch &L, const DedupArgs &a, int64_t nnz)
+{
+    static bool attr_set = false;
+    const size_t lds = 2 * (size_t)kSplitTile16 * sizeof(uint32_t) + (3 * (size_t)a.C + 1) * sizeof(uint32_t);
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_unsplit_kernel<kSplitTile16, 1024>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)(2 * kSplitTile16 * sizeof(uint32_t) + (3 * kMaxSegments + 1) * sizeof(uint32_t))) != hipSuccess)
+            (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
+        attr_set = true;
+    }
+    const int64_t tiles = nnz / kSplitTile16 + a.k;
+    hipLaunchKernelGGL((dd_unsplit_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 1)), dim3(1024), lds, L.stream, a,
+                       a.big_tileoff);
 }
 
 } // namespace bms

@@ -20,6 +20,8 @@
 #include "bms_device.h"
 #include "bms_internal.h"
 
+#include <algorithm>
+
 namespace bms {
 
 // Independent draws (ITS with replacement on the unit weights of a row): s integers in [0, deg), kept sorted
@@ -240,9 +242,17 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
 {
     __shared__ int32_t stage[kRowTile * (S + 1)]; // + 1: the row's own vertex when rows carry it
     __shared__ int32_t wsum[kRowTile / kWave];
+    __shared__ uint32_t seg_hist[kMaxFusedSegments]; // sampled ids per id-range segment, of this workgroup's minibatch
     const int tid = threadIdx.x;
     const int64_t most = a.mb_tileoff[a.k + 1];
     const int32_t s = a.s;
+    const bool count = a.seg_cnt != nullptr; // then gridDim.x is a multiple of k: every tile of this workgroup belongs
+                                             // to minibatch blockIdx.x % k
+    if (count) {
+        for (int c = tid; c < a.seg_C; c += kRowTile)
+            seg_hist[c] = 0;
+        __syncthreads();
+    }
     for (int64_t v = blockIdx.x; v < most * a.k; v += gridDim.x) { // same order as nw_rows_kernel
         const int i = (int)(v % a.k);
         const int64_t j = v / a.k;
@@ -319,8 +329,16 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
             a.out_col[base + e] = g;
             if (SET)
                 atomicOr(&words[g >> 5], 1u << (g & 31));
+            if (count)
+                atomicAdd(&seg_hist[(uint32_t)g >> a.seg_shift], 1u);
         }
         __syncthreads();
+    }
+    if (count) {
+        uint32_t *__restrict__ out = a.seg_cnt + (int64_t)(blockIdx.x % a.k) * a.seg_C;
+        for (int c = tid; c < a.seg_C; c += kRowTile)
+            if (seg_hist[c])
+                atomicAdd(&out[c], seg_hist[c]);
     }
 }
 
@@ -440,33 +458,43 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_wide_kernel(NwHop a, VSet 
 }
 
 template <bool SET, bool REPLACE>
-static void launch_nw_sample_impl(const Launch &L, const NwHop &a, const VSet &vs)
+static bool launch_nw_sample_impl(const Launch &L, const NwHop &a_in, const VSet &vs)
 {
+    NwHop a = a_in;
     const int64_t tiles = a.rows_bound / kRowTile + a.k;
-    if (a.s <= 4)
-        hipLaunchKernelGGL((nw_sample_kernel<4, SET, REPLACE>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
-    else if (a.s <= 8)
-        hipLaunchKernelGGL((nw_sample_kernel<8, SET, REPLACE>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
-    else if (a.s <= 16)
-        hipLaunchKernelGGL((nw_sample_kernel<16, SET, REPLACE>), dim3(grid_for(L, tiles, 8)), dim3(kRowTile), 0, L.stream, a, vs);
-    else if (a.s <= 32)
-        hipLaunchKernelGGL((nw_sample_kernel<32, SET, REPLACE>), dim3(grid_for(L, tiles, 4)), dim3(kRowTile), 0, L.stream, a, vs);
-    else
+    if (a.s > 32) {
+        a.seg_cnt = nullptr; // one row per wave: its workgroups walk the tiles in stacked order, across minibatches
         hipLaunchKernelGGL((nw_sample_wide_kernel<SET, REPLACE>), dim3(grid_for(L, tiles, 2)), dim3(kRowTile), 0, L.stream, a, vs);
+        return false;
+    }
+    int grid = grid_for(L, tiles, a.s <= 16 ? 8 : 4);
+    // counting per segment needs every workgroup to stay with one minibatch: tile v belongs to minibatch v % k,
+    // so a grid that is a multiple of k does it
+    if (a.seg_cnt && a.seg_C <= kMaxFusedSegments && a.k <= L.num_cu * (a.s <= 16 ? 8 : 4))
+        grid = std::max(grid / a.k, 1) * a.k;
+    else
+        a.seg_cnt = nullptr;
+    if (a.s <= 4)
+        hipLaunchKernelGGL((nw_sample_kernel<4, SET, REPLACE>), dim3(grid), dim3(kRowTile), 0, L.stream, a, vs);
+    else if (a.s <= 8)
+        hipLaunchKernelGGL((nw_sample_kernel<8, SET, REPLACE>), dim3(grid), dim3(kRowTile), 0, L.stream, a, vs);
+    else if (a.s <= 16)
+        hipLaunchKernelGGL((nw_sample_kernel<16, SET, REPLACE>), dim3(grid), dim3(kRowTile), 0, L.stream, a, vs);
+    else
+        hipLaunchKernelGGL((nw_sample_kernel<32, SET, REPLACE>), dim3(grid), dim3(kRowTile), 0, L.stream, a, vs);
+    return a.seg_cnt != nullptr;
 }
 
-void launch_nw_sample(const Launch &L, const NwHop &a, const VSet &vs, bool set_bits)
+bool launch_nw_sample(const Launch &L, const NwHop &a, const VSet &vs, bool set_bits)
 {
     if (a.replace) {
         if (set_bits)
-            launch_nw_sample_impl<true, true>(L, a, vs);
-        else
-            launch_nw_sample_impl<false, true>(L, a, vs);
-    } else if (set_bits) {
-        launch_nw_sample_impl<true, false>(L, a, vs);
-    } else {
-        launch_nw_sample_impl<false, false>(L, a, vs);
+            return launch_nw_sample_impl<true, true>(L, a, vs);
+        return launch_nw_sample_impl<false, true>(L, a, vs);
     }
+    if (set_bits)
+        return launch_nw_sample_impl<true, false>(L, a, vs);
+    return launch_nw_sample_impl<false, false>(L, a, vs);
 }
 
 // ---------------------------------------------------------------------------------------------
