@@ -398,3 +398,61 @@ def test_side_stream_and_graph_without_vertices(mods):
         with pytest.raises(bms.BmsError) as e:
             fn(empty, np.zeros((1, 1), dtype=np.int32), (2,), 1)
         assert e.value.code == bms.ERANGE
+
+
+def _hub_graph(n, hub_share, rng):
+    """Directed graph: every vertex points at one random vertex, and a share of them also at one hub."""
+    hub = 12345
+    dst = rng.integers(0, n, size=n)
+    dst[dst == np.arange(n)] = (dst[dst == np.arange(n)] + 1) % n
+    has_hub = rng.random(n) < hub_share
+    has_hub[hub] = False
+    has_hub &= dst != hub
+    deg = 1 + has_hub.astype(np.int64)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(deg)
+    col = np.empty(rowptr[-1], dtype=np.int32)
+    first = np.where(has_hub, np.minimum(dst, hub), dst)
+    col[rowptr[:-1]] = first
+    col[rowptr[:-1][has_hub] + 1] = np.maximum(dst, hub)[has_hub]
+    return rowptr, col, hub
+
+
+@pytest.mark.parametrize("b,hub_share,what", [
+    (16000, 0.02, "one id in more than 32 rows of a segment that one workgroup ranks: handed to the bitmap kernel"),
+    (16000, 0.6, "the hub's segment holds more ids than one workgroup ranks: listed for the bitmap kernel"),
+    (900, 0.2, "segments wider than the bitmap kernel takes: the per-minibatch kernel redoes the hop"),
+])
+def test_sort_extract_one_vertex_sampled_by_many_rows(mods, b, hub_share, what):
+    # sparse hop (far fewer sampled ids than vertices): the ids of a segment are ranked by counting them into buckets
+    # of about one id; a hub that many rows of a minibatch sample crowds one bucket
+    O, bms, _ = mods
+    rng = np.random.default_rng(51)
+    n = 1 << 22
+    rowptr, col, hub = _hub_graph(n, hub_share, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    batches = random_batches(n, 3, b, rng)
+    ref = O.sample_nodewise(rowptr, col, batches, (2, 1), 21)
+    picked = ref[0].col_vertex[ref[0].col[:ref[0].rowptr[ref[0].mb_rowoff[1]]]]
+    assert (picked == hub).sum() > 32, what
+    for extract in ("sort", None, "buckets"):
+        res = None
+        for _ in range(2):   # the second call runs without host round trips
+            res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (2, 1), 21, extract=extract, recycle=res)
+            assert_hops_equal(res.hops(), ref, what="%s, extract=%s" % (what, extract))
+
+
+def test_sort_extract_dense_hops_ranked_by_bitmap_with_many_duplicates(mods):
+    # dense hop (a minibatch samples a large share of the vertices): every segment is ranked through a bitmap of
+    # its id range; most ids are sampled several times, segments hold tens of thousands of ids
+    O, bms, _ = mods
+    rng = np.random.default_rng(52)
+    n = 60000
+    rowptr, col = random_csr(n, 30.0, rng)
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    batches = random_batches(n, 4, 6000, rng)
+    ref = O.sample_nodewise(rowptr, col, batches, (8, 4), 22)
+    assert ref[1].nnz / 4 > 50000 and ref[1].nnz > 2 * ref[1].ncols
+    for extract in ("sort", None):
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (8, 4), 22, extract=extract)
+        assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
