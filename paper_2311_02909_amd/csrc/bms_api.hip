@@ -146,7 +146,8 @@ struct bms_csr {
     BMS_BUF(ld_counters); BMS_BUF(ld_gather_off); BMS_BUF(ld_row_mb); BMS_BUF(ld_chunks); BMS_BUF(ld_prefix);
     BMS_BUF(ld_ptileoff); BMS_BUF(ld_tilesum);
     BMS_BUF(dd_pairs); BMS_BUF(dd_utmp); BMS_BUF(dd_uniq); BMS_BUF(dd_edgeoff); BMS_BUF(dd_count); BMS_BUF(dd_back);
-    BMS_BUF(dd_tileoff); BMS_BUF(dd_cursor); BMS_BUF(dd_seg); BMS_BUF(dd_runs); // EXTRACT
+    BMS_BUF(dd_tileoff); BMS_BUF(dd_cursor); BMS_BUF(dd_seg); BMS_BUF(dd_runs); BMS_BUF(dd_segcnt); BMS_BUF(dd_done); // EXTRACT
+    bool segcnt_clean = false; // every segment counter zero (kept so by the kernels; lost when a call is interrupted)
     BMS_BUF(un_rowptr); BMS_BUF(un_col); // BMS_UNION_DST: the hop's CSR while its rows still carry their own vertex
     BMS_BUF(row_cnt);                    // BMS_NODEWISE_REPLACE with a fanout above 32: distinct picks per row
     BMS_BUF(lw_bounds); BMS_BUF(lw_win); BMS_BUF(lw_tmpcol); BMS_BUF(lw_tmpcnt); BMS_BUF(lw_sel); BMS_BUF(lw_xtmp);
@@ -175,6 +176,8 @@ struct bms_result {
     const bms_csr *hint_csr = nullptr;
     std::vector<int32_t> hint_shape; // k, b, fanouts...
     std::vector<int64_t> hint_nnz;   // per hop
+    uint32_t hint_bins = 0;          // hops (bits) whose EXTRACT goes to the per-minibatch kernel: their sampled ids crowd
+                                     // id ranges so much that the segment kernels gave up on them before
     // host copies of the per-minibatch offsets (rows, entries, columns: L x 3 x (k+1)), made on demand by
     // bms_result_minibatch and dropped when the result is written again
     std::vector<int64_t> mb_offsets;
@@ -466,7 +469,17 @@ inline int64_t host_slot(CallCtx &c, int32_t hop, int which) { return c.csr->hos
 
 constexpr int32_t kMaxHops = 15; // 4 scalar slots per hop in a 64-entry block
 
-int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fanouts)
+// what a recycled result remembers a call by
+std::vector<int32_t> nodewise_shape(const CallCtx &c, const int32_t *fanouts)
+{
+    std::vector<int32_t> shape{c.k, c.b, ((c.flags & BMS_UNION_DST) ? 1 : 0) | ((c.flags & BMS_NODEWISE_REPLACE) ? 2 : 0)};
+    shape.insert(shape.end(), fanouts, fanouts + c.L);
+    return shape;
+}
+
+// One attempt.  *redo receives the hops (bits) whose EXTRACT by id-range segments gave up (ids crowded into a narrow
+// range): the result is then incomplete and the caller repeats the call with those hops added to `bins`.
+int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fanouts, uint32_t bins, uint32_t *redo)
 {
     bms_csr *csr = c.csr;
     Profiler prof{c.res, c.stream, (c.flags & (BMS_PROFILE | BMS_PROFILE_MAIN)) != 0, (c.flags & BMS_PROFILE) == 0};
@@ -493,7 +506,12 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     if (buckets) {
         BMS_TRY(csr->dd_edgeoff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
         BMS_TRY(csr->dd_count.ensure((size_t)c.k * sizeof(int64_t)));
+        BMS_TRY(csr->dd_done.ensure(256));
+        HIP_TRY(hipMemsetAsync(csr->dd_done.p, 0, 256, c.stream));
     }
+    bool tiles_planned = false;        // the hop's row tiles were written by the hop before it
+    bool counters_zero = csr->segcnt_clean; // the segment counters are all zero between hops: the kernels clear what they
+    csr->segcnt_clean = false;              // read; a fresh buffer, or one an interrupted call left behind, is cleared here
 
     int64_t rows_bound = (int64_t)c.k * c.b;
     const int32_t *row_vertex = c.res->hops[0].row_vertex.as<int32_t>();
@@ -505,8 +523,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     // rows * min(s, max degree) (always enough), tuning parameters by the remembered sizes.
     const bool union_dst = (c.flags & BMS_UNION_DST) != 0;
     const bool replace = (c.flags & BMS_NODEWISE_REPLACE) != 0;
-    std::vector<int32_t> shape{c.k, c.b, (union_dst ? 1 : 0) | (replace ? 2 : 0)};
-    shape.insert(shape.end(), fanouts, fanouts + c.L);
+    const std::vector<int32_t> shape = nodewise_shape(c, fanouts);
     bool no_wait = buckets && !c.fresh_result && c.res->hint_csr == csr && c.res->hint_shape == shape &&
                    (int32_t)c.res->hint_nnz.size() == c.L;
     if (no_wait) {
@@ -559,7 +576,9 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         }
 
         BMS_TRY(prof.begin("nw_rows", h));
-        launch_plan_tiles(c.launch, mb_rowoff, c.k, kRowTile, a.mb_tileoff, a.mb_tileoff + c.k + 1);
+        if (!tiles_planned)
+            launch_plan_tiles(c.launch, mb_rowoff, c.k, kRowTile, a.mb_tileoff, a.mb_tileoff + c.k + 1);
+        tiles_planned = false;
         launch_nw_rows(c.launch, a);
         BMS_TRY(prof.end());
         BMS_TRY(prof.begin("scan_tiles", h));
@@ -596,7 +615,7 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             // up to 4096 in LDS; the longer a segment, the longer the runs the cut appends to it per tile),
             // at most kMaxSegments of them
             int32_t C = 0, cshift = 0, by_bitmap = 0;
-            if (seg_sort) {
+            if (seg_sort && !((bins >> h) & 1u)) {
                 const double per_mb = (double)nnz_tune / c.k + 1.0;
                 // ids dense enough in [0, n) that a pass over a bitmap of a segment's id range costs less than sorting
                 // its ids: segments as wide as the bitmap kernel takes, as long as they hold well under 2^16 ids
@@ -620,7 +639,12 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             const size_t kC = (size_t)c.k * (size_t)C;
             const int64_t xtiles = nnz / kSplitTile16 + c.k; // tiles of the cut
             BMS_TRY(csr->dd_uniq.ensure((size_t)c.k * stride * sizeof(uint32_t)));
-            BMS_TRY(csr->dd_seg.ensure((4 * kC + (size_t)c.k + 16) * sizeof(uint32_t)));
+            BMS_TRY(csr->dd_seg.ensure((3 * kC + (size_t)c.k + 16) * sizeof(uint32_t)));
+            BMS_TRY(csr->dd_segcnt.ensure(std::max<size_t>(kC, 1) * sizeof(uint32_t)));
+            if (csr->dd_segcnt.grew || !counters_zero) {
+                HIP_TRY(hipMemsetAsync(csr->dd_segcnt.p, 0, csr->dd_segcnt.cap, c.stream));
+                counters_zero = true;
+            }
             BMS_TRY(csr->dd_runs.ensure(2 * (size_t)xtiles * (size_t)std::max(C, 1) * sizeof(uint32_t)));
             BMS_TRY(csr->dd_tileoff.ensure(3 * ((size_t)c.k + 1) * sizeof(int64_t)));
             d.k = c.k;
@@ -641,10 +665,12 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.cshift = cshift;
             d.by_bitmap = by_bitmap;
             d.big_tileoff = csr->dd_tileoff.as<int64_t>() + 2 * (c.k + 1);
-            d.fallback = C ? reinterpret_cast<int32_t *>(csr->dd_seg.as<uint32_t>()) : nullptr;
-            d.big_count = csr->dd_seg.as<uint32_t>() + 1;
-            d.seg_cnt = csr->dd_seg.as<uint32_t>() + 16;
-            d.seg_off = d.seg_cnt + kC;
+            // flag and list counter of the hop: two 32-bit words of a scalar slot, zeroed with the slots at the start of
+            // the call and read back with the sizes at its end
+            d.fallback = C ? reinterpret_cast<int32_t *>(slot(c, h, 2)) : nullptr;
+            d.big_count = reinterpret_cast<uint32_t *>(slot(c, h, 2)) + 1;
+            d.seg_cnt = csr->dd_segcnt.as<uint32_t>();
+            d.seg_off = csr->dd_seg.as<uint32_t>();
             d.seg_cursor = d.seg_off + kC + c.k;
             d.big_list = d.seg_cursor + kC;
             // the segment path keeps the ids grouped by segment and the per-position words in the first buffer,
@@ -656,7 +682,6 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.run_gpos = csr->dd_runs.as<uint32_t>();
             d.run_cnt = d.run_gpos + (size_t)xtiles * (size_t)std::max(C, 1);
             d.mb_count = csr->dd_count.as<int64_t>();
-            launch_nw_dedup_prepare(c.launch, d, nnz);
             if (C > 0) { // the sampling kernel counts the ids per segment while it has them in LDS, when it can
                 a.seg_cnt = d.seg_cnt;
                 a.seg_C = C;
@@ -668,10 +693,15 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
         BMS_TRY(prof.end());
         if (buckets) {
             const StageMark mark = [&](const char *name) { (void)prof.mark(name, h); };
-            if (launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
-                                       slot(c, h, 1), nnz, counted, mark) != 0)
+            if (d.C > 0) {
+                launch_nw_extract_segments(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
+                                           hb.col_vertex.as<int32_t>(), slot(c, h, 1), csr->mb_tileoff.as<int64_t>(),
+                                           csr->dd_done.as<uint32_t>(), nnz, counted, mark);
+                tiles_planned = true;
+            } else if (launch_nw_dedup_bucket(c.launch, d, a.out_rowptr, mb_rowoff, hb.mb_coloff.as<int64_t>(),
+                                              hb.col_vertex.as<int32_t>(), slot(c, h, 1), nnz, mark) != 0) {
                 return fail(BMS_EHIP, "launch of the bucket EXTRACT kernel was refused");
-            launch_nw_dedup_fixup(c.launch, d, hb.mb_coloff.as<int64_t>(), hb.col_vertex.as<int32_t>(), nnz, mark);
+            }
             BMS_TRY(prof.end());
         } else {
             BMS_TRY(prof.begin("vset_rank", h));
@@ -711,6 +741,12 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     BMS_TRY(read_scalars(c));
     if (no_wait)
         BMS_TRY(seed_flag_error(c));
+    csr->segcnt_clean = true; // every hop's kernels have run: the counters are back to zero
+    for (int32_t h = 0; h < c.L; ++h)
+        if (buckets && (host_slot(c, h, 2) & 0xFFFFFFFFLL))
+            *redo |= 1u << h;
+    if (*redo)
+        return BMS_OK; // the caller repeats the call
     for (int32_t h = 0; h < c.L; ++h) {
         bms_hop_view &v = c.res->hops[h].view;
         v.nnz = host_slot(c, h, 0);
@@ -721,10 +757,29 @@ int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fano
     c.res->hint_csr = csr;
     c.res->hint_shape = shape;
     c.res->hint_nnz = seen_nnz;
+    c.res->hint_bins = bins;
     BMS_TRY(prof.finish());
     if (!buckets || !seeds_by_sort)
         csr->vs_clean = true;
     return BMS_OK;
+}
+
+int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fanouts)
+{
+    // hops that gave up on the segment kernels in an earlier call of this shape go to the per-minibatch kernel at once
+    uint32_t bins = 0;
+    if (!c.fresh_result && c.res->hint_csr == c.csr && c.res->hint_shape == nodewise_shape(c, fanouts))
+        bins = c.res->hint_bins;
+    for (int32_t attempt = 0; attempt <= c.L; ++attempt) {
+        uint32_t redo = 0;
+        BMS_TRY(sample_nodewise_once(c, batches, fanouts, bins, &redo));
+        if (!redo)
+            return BMS_OK;
+        bins |= redo;
+        c.res->stages.clear();
+        c.res->events_used = 0;
+    }
+    return fail(BMS_EHIP, "EXTRACT did not settle on a kernel path");
 }
 
 // LADIES with the column counts of P accumulated in LDS, one window of 2^16 vertex ids at a time.

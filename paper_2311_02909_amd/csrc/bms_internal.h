@@ -135,16 +135,17 @@ constexpr int kSplitTile16 = 16384; // positions per tile of the count, split an
 constexpr int kSegCap = 65535;      // most entries a segment may hold: the rank of an id inside its segment has 16 bits
 constexpr int kMaxSegments = 2560;  // 3 words each beside the staging of the split / un-split kernels must fit in 160 KB of LDS
 constexpr int kMaxBitmapShift = 20; // the bitmap ranking kernel holds 2^cshift bits in LDS (128 KB)
-// clears the counters of the segment path (before the sampling kernel, which may count into them)
-void launch_nw_dedup_prepare(const Launch &, const DedupArgs &, int64_t nnz);
-// counted: the per-segment counts are there already
-void launch_nw_dedup_sorted(const Launch &, const DedupArgs &, int64_t nnz, bool counted, const StageMark &mark);
+// EXTRACT of a hop by id-range segments (C > 0).  counted: the per-segment counts are there already.  Also writes
+// the next hop's row tiles (next_tileoff, k + 2 entries as launch_plan_tiles with max_out gives them).  `done` is a
+// device word that is zero between launches.
+void launch_nw_extract_segments(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,
+                                int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t *next_tileoff,
+                                uint32_t *done, int64_t nnz, bool counted, const StageMark &mark);
 void launch_nw_dedup_unsplit(const Launch &, const DedupArgs &, int64_t nnz);
-// returns 0, or -1 when the launch was refused (then nothing ran)
+void launch_nw_dedup_front(const Launch &, const DedupArgs &, const int64_t *mb_coloff, int32_t *col_vertex, int64_t nnz);
+// EXTRACT of a hop by the per-minibatch kernel (C == 0); returns 0, or -1 when the launch was refused
 int launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz, bool counted, const StageMark &mark);
-void launch_nw_dedup_fixup(const Launch &, const DedupArgs &, const int64_t *mb_coloff, int32_t *col_vertex,
-                           int64_t nnz, const StageMark &mark);
+                           int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t nnz, const StageMark &mark);
 constexpr int kDedupPlaceTile = 8192; // must equal kPlaceTile in kernels_dedup.hip (sizes the cursor array)
 constexpr int kDedupSplitTile = 2048; // must equal kSplitTile in kernels_dedup.hip
 // mb_edgeoff[i] = rowptr[mb_rowoff[i]], i <= k: first entry of every minibatch in the stacked column array

@@ -344,7 +344,7 @@ void launch_scan_i64(const Launch &L, int64_t *vals, const int64_t *count, int64
                      const int64_t *tail_idx, int64_t count_bound)
 {
     const int64_t chunks_bound = (count_bound + 4095) / 4096;
-    if (count_bound > 32768 && L.scan_tmp && chunks_bound + 3 <= L.scan_tmp_len) {
+    if (count_bound > 524288 && L.scan_tmp && chunks_bound + 3 <= L.scan_tmp_len) { // one workgroup below that: fewer launches
         int64_t *sums = L.scan_tmp;                 // chunks_bound + 1 values
         int64_t *nsums = L.scan_tmp + chunks_bound + 2; // device-side length of `sums` for the middle scan
         const int grid = grid_for(L, chunks_bound, 2);

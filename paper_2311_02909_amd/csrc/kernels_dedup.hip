@@ -146,8 +146,6 @@ __global__ __launch_bounds__(kDedupWaves *kWave) void nw_dedup_bucket_kernel(Ded
     uint16_t *wpre = reinterpret_cast<uint16_t *>(wbm + kBinWords);
     uint64_t *win = reinterpret_cast<uint64_t *>(wbm); // pair window, aliases the bitmap
 
-    if (a.fallback && !*a.fallback)
-        return; // the segment-sort kernels handled this hop
     for (int32_t i = blockIdx.x; i < a.k; i += gridDim.x) {
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t N = (uint32_t)(a.mb_edgeoff[i + 1] - e0);
@@ -334,14 +332,11 @@ constexpr int kMaxPlaceTiles = 256;
 static_assert(kPlaceTile == kDedupPlaceTile && (1 << kPlaceShift) == kPlaceTile && kSplitTile == kDedupSplitTile,
               "tile constants out of step");
 
-// Runs after the per-minibatch kernel only (a hop that the segment kernels handled has nothing here).
 __global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a)
 {
     __shared__ uint64_t stage[kSplitTile];
     __shared__ uint32_t cnt[kMaxPlaceTiles], off[kMaxPlaceTiles], gpos[kMaxPlaceTiles];
     __shared__ uint32_t smem[4];
-    if (a.fallback && !*a.fallback)
-        return;
     const int tid = threadIdx.x;
     const int64_t nunits = a.split_tileoff[a.k];
     for (int64_t unit = blockIdx.x; unit < nunits; unit += gridDim.x) {
@@ -400,8 +395,6 @@ __global__ __launch_bounds__(256) void nw_dedup_split_kernel(DedupArgs a)
 __global__ __launch_bounds__(256) void nw_dedup_place_kernel(DedupArgs a)
 {
     __shared__ int32_t tile[kPlaceTile];
-    if (a.fallback && !*a.fallback)
-        return; // the segment kernels handled this hop
     const int tid = threadIdx.x;
     const int64_t ntiles = a.place_tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
@@ -443,7 +436,9 @@ __global__ __launch_bounds__(256) void nw_dedup_front_kernel(DedupArgs a, const 
     const int64_t e0 = a.mb_edgeoff[i];
     const uint32_t *__restrict__ base = a.bin_base + (int64_t)i * a.stride;
     int32_t *__restrict__ front = col_vertex + mb_coloff[i];
-    if (a.fallback && !*a.fallback) {
+    if (a.C > 0) {
+        if (*a.fallback)
+            return; // the hop is repeated with the per-minibatch kernel
         // segment path: segment c left its distinct ids, in rank order, at the head of its slots; the minibatch's
         // columns are those lists one after the other.  Walked by destination, 512 columns per wave and step, so the
         // work is even whatever the segments' lengths: the segment of a column is found in the segments' bases (LDS)
@@ -511,8 +506,9 @@ __global__ __launch_bounds__(256) void nw_dedup_front_kernel(DedupArgs a, const 
     }
 }
 
+// EXTRACT of a hop by the per-minibatch kernel (C == 0)
 int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *out_rowptr, const int64_t *mb_rowoff,
-                           int64_t *mb_coloff, int64_t *ncols_out, int64_t nnz, bool counted, const StageMark &mark)
+                           int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t nnz, const StageMark &mark)
 {
     static bool attr_set = false;
     if (!attr_set) {
@@ -521,42 +517,33 @@ int launch_nw_dedup_bucket(const Launch &L, const DedupArgs &a, const int64_t *o
             (void)hipGetLastError(); // not required on every runtime; the launch below reports real failures
         attr_set = true;
     }
+    mark("dd_bins");
     hipLaunchKernelGGL(mb_edge_offsets_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, out_rowptr, mb_rowoff,
                        a.k, a.mb_edgeoff);
-    if (a.C > 0)
-        launch_nw_dedup_sorted(L, a, nnz, counted, mark);
-    else
-        mark("dd_bins");
     hipLaunchKernelGGL(nw_dedup_bucket_kernel, dim3(a.k), dim3(kDedupWaves * kWave), dedup_lds_bytes(a.nbuckets),
                        L.stream, a);
     if (hipGetLastError() != hipSuccess)
         return -1;
     launch_offsets_from_counts(L, a.mb_count, a.k, mb_coloff, ncols_out);
+    mark("dd_front");
+    launch_nw_dedup_front(L, a, mb_coloff, col_vertex, nnz);
+    mark("dd_back_split");
+    launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile, a.split_tileoff);
+    launch_plan_tiles(L, a.mb_edgeoff, a.k, kPlaceTile, a.place_tileoff);
+    (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
+    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a);
+    mark("dd_place");
+    hipLaunchKernelGGL(nw_dedup_place_kernel, dim3(grid_for(L, nnz / kPlaceTile + a.k, 4)), dim3(256), 0, L.stream, a);
     return 0;
 }
 
-void launch_nw_dedup_fixup(const Launch &L, const DedupArgs &a, const int64_t *mb_coloff, int32_t *col_vertex,
-                           int64_t nnz, const StageMark &mark)
+void launch_nw_dedup_front(const Launch &L, const DedupArgs &a, const int64_t *mb_coloff, int32_t *col_vertex, int64_t nnz)
 {
-    mark("dd_front");
     int gx = (int)((nnz / a.k + 2047) / 2048) + 1; // about one workgroup per 2048 entries of a minibatch
     if (gx > 64)
         gx = 64;
     hipLaunchKernelGGL(nw_dedup_front_kernel, dim3(gx, a.k), dim3(256), (2 * (size_t)a.C + 1) * sizeof(uint32_t), L.stream, a,
                        mb_coloff, col_vertex);
-    if (a.C > 0) {
-        mark("dd_unsplit");
-        launch_nw_dedup_unsplit(L, a, nnz);
-    }
-    mark("dd_back_split"); // after the per-minibatch kernel only: both kernels return at once otherwise
-    if (a.C == 0) { // the segment launcher has done this already
-        launch_plan_tiles(L, a.mb_edgeoff, a.k, kSplitTile, a.split_tileoff);
-        launch_plan_tiles(L, a.mb_edgeoff, a.k, kPlaceTile, a.place_tileoff);
-        (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
-    }
-    hipLaunchKernelGGL(nw_dedup_split_kernel, dim3(grid_for(L, nnz / kSplitTile + a.k, 8)), dim3(256), 0, L.stream, a);
-    mark("dd_place");
-    hipLaunchKernelGGL(nw_dedup_place_kernel, dim3(grid_for(L, nnz / kPlaceTile + a.k, 4)), dim3(256), 0, L.stream, a);
 }
 
 } // namespace bms

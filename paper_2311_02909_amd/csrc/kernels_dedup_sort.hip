@@ -84,11 +84,9 @@ __device__ inline void wave_append(uint32_t *__restrict__ list, uint32_t *__rest
 constexpr int kRankCapFwd = 4096; // = kRankCap (defined with the ranking kernel below)
 
 // one workgroup per minibatch: seg_off = exclusive scan of the counts (C+1 entries), cursors zeroed
-__global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
+__device__ inline void seg_scan_block(const DedupArgs &a, int i, uint32_t *smem, uint32_t &carry_s)
 {
-    __shared__ uint32_t smem[4];
-    __shared__ uint32_t carry_s;
-    const int i = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const uint32_t *__restrict__ cnt = a.seg_cnt + (int64_t)i * a.C;
     uint32_t *__restrict__ off = a.seg_off + (int64_t)i * (a.C + 1);
     if (tid == 0)
@@ -120,6 +118,57 @@ __global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
         off[a.C] = carry_s;
     if (too_big)
         atomicOr(a.fallback, 1);
+}
+
+// Planning of a hop's EXTRACT in one launch.  Workgroup k: first entry of every minibatch in the stacked column
+// array (mb_edgeoff[i] = rowptr[mb_rowoff[i]]) and the tiles of the cut (tiles never straddle minibatches).
+// Workgroups 0..k-1 (only with `scan`, i.e. when the counts per segment are there already): the segment offsets
+// of minibatch i.
+__global__ __launch_bounds__(256) void dd_plan_kernel(DedupArgs a, const int64_t *__restrict__ out_rowptr,
+                                                      const int64_t *__restrict__ mb_rowoff, int scan)
+{
+    __shared__ uint32_t smem[4];
+    __shared__ uint32_t carry_s;
+    __shared__ int64_t smem64[4];
+    __shared__ int64_t carry64_s;
+    if ((int)blockIdx.x < a.k) {
+        if (scan)
+            seg_scan_block(a, blockIdx.x, smem, carry_s);
+        return;
+    }
+    const int tid = threadIdx.x;
+    if (tid == 0)
+        carry64_s = 0;
+    __syncthreads();
+    for (int32_t base = 0; base < a.k; base += 256) {
+        const int32_t i = base + tid;
+        int64_t cnt = 0;
+        if (i < a.k) {
+            const int64_t e0 = out_rowptr[mb_rowoff[i]], e1 = out_rowptr[mb_rowoff[i + 1]];
+            a.mb_edgeoff[i] = e0;
+            if (i == a.k - 1)
+                a.mb_edgeoff[a.k] = e1;
+            cnt = (e1 - e0 + kSplitTile16 - 1) / kSplitTile16;
+        }
+        int64_t total;
+        const int64_t ex = block_exclusive_scan<int64_t, 256>(cnt, smem64, total);
+        const int64_t carry = carry64_s;
+        if (i < a.k)
+            a.big_tileoff[i] = carry + ex;
+        __syncthreads();
+        if (tid == 0)
+            carry64_s = carry + total;
+        __syncthreads();
+    }
+    if (tid == 0)
+        a.big_tileoff[a.k] = carry64_s;
+}
+
+__global__ __launch_bounds__(256) void dd_seg_scan_kernel(DedupArgs a)
+{
+    __shared__ uint32_t smem[4];
+    __shared__ uint32_t carry_s;
+    seg_scan_block(a, blockIdx.x, smem, carry_s);
 }
 
 // TILE positions per workgroup step, NT threads.  The larger the tile, the longer the run every segment gets
@@ -436,10 +485,12 @@ __global__ __launch_bounds__(kBmThreads) void dd_bitmap_kernel(DedupArgs a)
     uint32_t *words = reinterpret_cast<uint32_t *>(bm_lds);
     uint16_t *qpre = reinterpret_cast<uint16_t *>(bm_lds + nq);
     const uint32_t q_wave = (uint32_t)wave * (uint32_t)(its * kWave); // first quad of this wave's part
+    const int64_t nwork = LISTED ? (int64_t)*a.big_count : (int64_t)a.k * a.C;
+    if ((int64_t)blockIdx.x >= nwork)
+        return; // usually nothing is listed
     for (int it = 0; it < its; ++it)
         quads[q_wave + it * kWave + lane] = make_uint4(0, 0, 0, 0);
     __syncthreads();
-    const int64_t nwork = LISTED ? (int64_t)*a.big_count : (int64_t)a.k * a.C;
     // a segment's first ids are fetched while the segment before it is worked on
     struct Seg {
         int64_t sg, e0;
@@ -575,20 +626,31 @@ __global__ __launch_bounds__(kBmThreads) void dd_bitmap_kernel(DedupArgs a)
     }
 }
 
-// one workgroup per minibatch: distinct ids before each segment; distinct ids of the minibatch
-__global__ __launch_bounds__(256) void dd_base_scan_kernel(DedupArgs a)
+// One workgroup per minibatch: distinct ids before each segment; distinct ids of the minibatch.  The segment
+// counters are left all zero for the next hop.  The workgroup that finishes last then turns the minibatches' counts
+// into the stacked column offsets (= the next hop's row offsets), the hop's column count, and the next hop's row
+// tiles.  When a segment fitted no ranking kernel (flag), the hop's outputs are written as empty: the caller sees the
+// flag with the sizes and repeats the call with the per-minibatch kernel on this hop.
+__global__ __launch_bounds__(256) void dd_base_scan_kernel(DedupArgs a, int64_t *mb_coloff, int64_t *ncols_out,
+                                                           int64_t *next_tileoff /* k + 2 */, uint32_t *done)
 {
     __shared__ uint32_t smem[4];
     __shared__ uint32_t carry_s;
-    if (*a.fallback)
-        return;
+    __shared__ int64_t smem64[4];
+    __shared__ int64_t carry64_s, carry64b_s;
+    __shared__ uint32_t last_s;
+    const bool failed = *a.fallback != 0;
     const int i = blockIdx.x, tid = threadIdx.x;
     if (tid == 0)
         carry_s = 0;
     __syncthreads();
     for (int base = 0; base < a.C; base += 256) {
         const int c = base + tid;
-        const uint32_t v = c < a.C ? a.seg_cnt[(int64_t)i * a.C + c] : 0u;
+        uint32_t v = 0;
+        if (c < a.C) {
+            v = a.seg_cnt[(int64_t)i * a.C + c];
+            a.seg_cnt[(int64_t)i * a.C + c] = 0;
+        }
         uint32_t total;
         const uint32_t ex = block_exclusive_scan<uint32_t, 256>(v, smem, total);
         const uint32_t carry = carry_s;
@@ -599,8 +661,58 @@ __global__ __launch_bounds__(256) void dd_base_scan_kernel(DedupArgs a)
             carry_s = carry + total;
         __syncthreads();
     }
-    if (tid == 0)
-        a.mb_count[i] = carry_s;
+    if (tid == 0) {
+        __hip_atomic_store(&a.mb_count[i], failed ? (int64_t)0 : (int64_t)carry_s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        last_s = atomicAdd(done, 1u) == (uint32_t)a.k - 1u ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!last_s)
+        return;
+    __threadfence();
+    if (tid == 0) {
+        carry64_s = 0;
+        carry64b_s = 0;
+        *done = 0; // for the next hop
+    }
+    __syncthreads();
+    int64_t most = 0;
+    for (int32_t base = 0; base < a.k; base += 256) {
+        const int32_t j = base + tid;
+        const int64_t v = j < a.k ? __hip_atomic_load(&a.mb_count[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+        const int64_t tiles = (v + kRowTile - 1) / kRowTile;
+        most = tiles > most ? tiles : most;
+        int64_t total, total_t;
+        const int64_t ex = block_exclusive_scan<int64_t, 256>(v, smem64, total);
+        const int64_t ex_t = block_exclusive_scan<int64_t, 256>(tiles, smem64, total_t);
+        const int64_t carry = carry64_s, carry_t = carry64b_s;
+        if (j < a.k) {
+            mb_coloff[j] = carry + ex;
+            next_tileoff[j] = carry_t + ex_t;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            carry64_s = carry + total;
+            carry64b_s = carry_t + total_t;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+        const int64_t o = __shfl_xor(most, d, kWave);
+        most = o > most ? o : most;
+    }
+    if ((tid & (kWave - 1)) == 0)
+        smem64[tid / kWave] = most;
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w)
+            most = smem64[w] > most ? smem64[w] : most;
+        mb_coloff[a.k] = carry64_s;
+        *ncols_out = carry64_s;
+        next_tileoff[a.k] = carry64b_s;
+        next_tileoff[a.k + 1] = most;
+    }
 }
 
 // The cut in reverse: tile t appended, for every segment c, one run of ids to the segment; the ranks of those
@@ -684,27 +796,18 @@ __global__ __launch_bounds__(NT) void dd_unsplit_kernel(DedupArgs a, const int64
     }
 }
 
-void launch_nw_dedup_prepare(const Launch &L, const DedupArgs &a, int64_t nnz)
+void launch_nw_extract_segments(const Launch &L, const DedupArgs &a, const int64_t *out_rowptr, const int64_t *mb_rowoff,
+                                int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t *next_tileoff,
+                                uint32_t *done, int64_t nnz, bool counted, const StageMark &mark)
 {
-    if (a.C == 0)
-        return;
-    // the flag, the list counter and the segment counters lie next to each other: one clear
-    (void)hipMemsetAsync(a.fallback, 0, (size_t)(a.seg_cnt - reinterpret_cast<uint32_t *>(a.fallback)) * sizeof(uint32_t) +
-                                            (size_t)a.k * a.C * sizeof(uint32_t), L.stream);
-    (void)hipMemsetAsync(a.place_cursor, 0, (size_t)(nnz / kDedupPlaceTile + a.k + 1) * sizeof(uint32_t), L.stream);
-}
-
-void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, bool counted, const StageMark &mark)
-{
-    mark("dd_count");
-    // tiles of the count / split / un-split kernels; of the placing kernel and the split of the per-minibatch path
-    launch_plan_tiles3(L, a.mb_edgeoff, a.k, kSplitTile16, a.big_tileoff, kDedupPlaceTile, a.place_tileoff, kDedupSplitTile,
-                       a.split_tileoff);
+    mark("dd_plan");
     const int64_t tiles = nnz / kSplitTile16 + a.k;
-    if (!counted)
+    hipLaunchKernelGGL(dd_plan_kernel, dim3(a.k + 1), dim3(256), 0, L.stream, a, out_rowptr, mb_rowoff, counted ? 1 : 0);
+    if (!counted) {
         hipLaunchKernelGGL((dd_count_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 2)), dim3(1024), 0, L.stream, a,
                            a.big_tileoff);
-    hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
+        hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
+    }
     mark("dd_split");
     { // 16384 ids per step, two workgroups of 16 waves per compute unit
         static bool attr_set = false;
@@ -737,11 +840,15 @@ void launch_nw_dedup_sorted(const Launch &L, const DedupArgs &a, int64_t nnz, bo
                            bm_lds, L.stream, a);
     } else {
         hipLaunchKernelGGL(dd_rank_kernel, dim3(grid_for(L, (int64_t)a.k * a.C, 4)), dim3(kRankThreads), 0, L.stream, a);
-        if (a.cshift <= kMaxBitmapShift) // segments the sorting kernel did not take
+        if (a.cshift <= kMaxBitmapShift) // segments the counting kernel did not take
             hipLaunchKernelGGL(dd_bitmap_kernel<true>, dim3(grid_for(L, nnz / 1024 + 1, bm_per_cu)), dim3(kBmThreads),
                                bm_lds, L.stream, a);
     }
-    hipLaunchKernelGGL(dd_base_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
+    hipLaunchKernelGGL(dd_base_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a, mb_coloff, ncols_out, next_tileoff, done);
+    mark("dd_front");
+    launch_nw_dedup_front(L, a, mb_coloff, col_vertex, nnz);
+    mark("dd_unsplit");
+    launch_nw_dedup_unsplit(L, a, nnz);
 }
 
 void launch_nw_dedup_unsplit(const Launch &L, const DedupArgs &a, int64_t nnz)
