@@ -278,29 +278,35 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
             addr = next_addr;
         }
         __syncthreads();
-        // each wave compacts kWaveWords consecutive words: first how many, then where, then the entries
-        const uint32_t *__restrict__ mine = cnt + wave * kWaveWords;
+        // Each wave compacts kWaveWords consecutive words, 16 bytes (8 counters) per lane and access, quad
+        // it * 64 + lane of its part in iteration it: nonzero counters and weight per quad; their running count over
+        // the wave's part in ascending column order (lane scans, no LDS); then, where the whole window starts in the
+        // staging arrays (one cursor claim per workgroup), the nonzero counters are written out and cleared.
+        constexpr int kQuadIts = kWaveWords / 4 / kWave; // quads per lane
+        const uint4 *mine4 = reinterpret_cast<const uint4 *>(cnt + wave * kWaveWords);
+        uint32_t nzq[kQuadIts], incq[kQuadIts];
         uint32_t nz = 0;
         uint64_t wt = 0;
-        if (a.squared) {
-            for (int it = 0; it < kWaveWords / kWave; ++it) {
-                const uint32_t x = mine[it * kWave + lane];
-                const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
-                nz += (lo != 0) + (hi != 0);
-                wt += (uint64_t)lo * lo + (uint64_t)hi * hi;
+#pragma unroll
+        for (int it = 0; it < kQuadIts; ++it) {
+            const uint4 q = mine4[it * kWave + lane];
+            const uint32_t xs[4] = {q.x, q.y, q.z, q.w};
+            uint32_t c = 0, w32 = 0;
+            uint64_t w64 = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t lo = xs[u] & 0xFFFFu, hi = xs[u] >> 16;
+                c += (lo != 0) + (hi != 0);
+                if (a.squared)
+                    w64 += (uint64_t)lo * lo + (uint64_t)hi * hi;
+                else
+                    w32 += lo + hi; // at most 64 values below 2^16 per lane
             }
-        } else {
-            uint32_t wt32 = 0; // at most 64 values below 2^16 per lane
-#pragma unroll 8
-            for (int it = 0; it < kWaveWords / kWave; ++it) {
-                const uint32_t x = mine[it * kWave + lane];
-                const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
-                nz += (lo != 0) + (hi != 0);
-                wt32 += lo + hi;
-            }
-            wt = wt32;
+            wt += a.squared ? w64 : (uint64_t)w32;
+            nzq[it] = c;
+            incq[it] = wave_inclusive_scan_dpp(c) + nz; // nonzero counters of the wave's part up to this quad
+            nz = (uint32_t)__builtin_amdgcn_readlane((int)incq[it], kWave - 1);
         }
-        nz = wave_sum(nz);
         wt = wave_sum(wt);
         if (lane == 0) {
             wave_nz[wave] = nz;
@@ -323,7 +329,9 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
             a.win_base[blk] = (int64_t)base;
         }
         __syncthreads();
-        if (nz) { // uniform per wave
+        if (nz * 4u > (uint32_t)kWaveWords) {
+            // most counters are nonzero: word by word, the nonzero ones of 64 consecutive words packed by a ballot,
+            // so that every store instruction writes a run of consecutive entries
             int64_t run = (int64_t)*base_s + wave_nz[wave];
             for (int it0 = 0; it0 < kWaveWords / kWave; it0 += 4) {
                 uint32_t x[4];
@@ -351,6 +359,33 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
                         a.tmp_cnt[pos] = hi;
                     }
                     run += __popcll(mlo) + __popcll(mhi);
+                }
+            }
+        } else if (nz) { // few: only the quads that hold any are read again (uniform per wave)
+            const int64_t run = (int64_t)*base_s + wave_nz[wave];
+            uint4 *mine4w = reinterpret_cast<uint4 *>(cnt + wave * kWaveWords);
+#pragma unroll
+            for (int it = 0; it < kQuadIts; ++it) {
+                if (nzq[it] == 0)
+                    continue;
+                const uint4 q = mine4w[it * kWave + lane];
+                mine4w[it * kWave + lane] = make_uint4(0, 0, 0, 0);
+                const uint32_t xs[4] = {q.x, q.y, q.z, q.w};
+                int64_t pos = run + (incq[it] - nzq[it]);
+                const int32_t col0 = id0 + 2 * (wave * kWaveWords + 4 * (it * kWave + lane));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t lo = xs[u] & 0xFFFFu, hi = xs[u] >> 16;
+                    if (lo) {
+                        a.tmp_col[pos] = col0 + 2 * u;
+                        a.tmp_cnt[pos] = lo;
+                        ++pos;
+                    }
+                    if (hi) {
+                        a.tmp_col[pos] = col0 + 2 * u + 1;
+                        a.tmp_cnt[pos] = hi;
+                        ++pos;
+                    }
                 }
             }
         }
