@@ -25,23 +25,19 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch of the dominant kernel, in bytes, scaled by the
-# factor a plain copy kernel of known size reads on the same counters (see profiles/); keyed by
-# (workload, kernel stage).  None = not measured for this build of the kernel.
+# Bytes that crossed from the L2 caches to the memory fabric (reads + writes), from rocprofv3 request counters:
+# read requests by size (TCC_EA0_RDREQ_32B / _64B / _128B x 32 / 64 / 128 bytes) and write requests
+# (TCC_EA0_WRREQ_64B x 64, the others x 32).  The counters sit between L2 and the fabric: a request that the
+# 256 MB memory-side cache answers is counted like one that reaches HBM ("fabric traffic", an upper bound of the
+# HBM traffic).  Keyed by (workload, kernel stage): bytes per step summed over the stage's launches.  Each value is
+# the line "bench constant ..." of profiles/<workload>_hbm_traffic.txt (tests/test_bench_constants.py compares
+# them); a kernel that has changed since its profile was taken has no entry (None in the output).
 MEASURED_TRAFFIC = {
-    # profiles/large_sage_hbm_traffic.txt: nw_sample_kernel<8> + <16>, read + write, bytes per step (3 launches)
-    ("large_sage", "nw_sample"): {"bytes_per_step": 6_014_789_272, "launches": 3},
-    # profiles/dense_ladies_hbm_traffic.txt: ldw_accumulate_kernel, read + write, bytes per step (3 launches)
-    ("dense_ladies", "ldw_accumulate"): {"bytes_per_step": 4_266_784_848, "launches": 3},
-    # the same from profiles/mid_sage_*, dense_sage_*, mid_ladies_* (working sets of the mid-size graph partly fit
-    # the 256 MB last-level cache, so its counters under-read what the kernels ask for)
-    ("mid_sage", "nw_sample"): {"bytes_per_step": 3_195_063_744, "launches": 3},
-    ("dense_sage", "nw_sample"): {"bytes_per_step": 10_804_163_934, "launches": 3},
-    ("mid_ladies", "ldw_accumulate"): {"bytes_per_step": 196_948_363, "launches": 3},
 }
-# the same counters summed over every kernel of one bulk call (bytes per step)
-MEASURED_CALL_TRAFFIC = {"large_sage": 11_142_667_881, "dense_ladies": 13_140_816_911, "mid_sage": 5_521_056_036,
-                         "dense_sage": 17_732_272_358, "mid_ladies": 630_883_846}
+# the same summed over every kernel of one bulk call (bytes per step)
+MEASURED_CALL_TRAFFIC = {
+}
+OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
 
 
 def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0, gathered: int = 0) -> float:
@@ -63,13 +59,14 @@ def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0
         "nw_relabel": 8 * E,
         "nw_strip_self": 4 * R,   # BMS_UNION_DST: each row's own column; the rest of that pass is scratch
         "vset_rank": 4 * U,
-        # EXTRACT by segment sorts: the staged ids are read once (4 E, charged to dd_split), the local
-        # columns written once (4 E, dd_place), the next frontier written once (4 U, dd_front); the
-        # other kernels of the path (dd_count, dd_sort, dd_back_split) move scratch only
+        # EXTRACT by id-range segments: the staged ids are read once (4 E, charged to dd_split), the local
+        # columns written once (4 E, dd_unsplit), the next frontier written once (4 U, dd_front); everything else
+        # these kernels and dd_plan / dd_rank move is scratch.  dd_bins..dd_place: the per-minibatch kernel path
         "dd_split": 4 * E,
-        "dd_place": 4 * E,
+        "dd_unsplit": 4 * E,
         "dd_front": 4 * U,
-        "dd_bins": 8 * E + 4 * U,
+        "dd_bins": 4 * E,
+        "dd_place": 4 * E,
         "ld_rows": 20 * R,
         # LADIES by LDS windows (default): the neighbours are read once to build P (ldw_accumulate) and once
         # to extract (ldw_extract); ldw_bounds is a third pass that moves scratch only
@@ -100,6 +97,9 @@ def main() -> int:
     ap.add_argument("--variant", default="none", choices=["none", "union_dst", "replace"],
                     help="node-wise variant: union_dst keeps the frontier's own vertices as columns (BMS_UNION_DST), "
                          "replace makes a row's draws independent (BMS_NODEWISE_REPLACE)")
+    ap.add_argument("--others", default="auto", choices=["auto", "yes", "no"],
+                    help="also run the other workloads of the build's configs (fewer steps) and report them under "
+                         "other_workloads; auto = only with the default workload")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB mebibytes 5 times "
                          "(calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters against a known size)")
@@ -144,6 +144,39 @@ def main() -> int:
                           "index_bytes_per_launch": reads * 8, "ms_per_launch": round(ms, 4),
                           "reads_per_sec": reads / ms * 1e3, "tb_per_sec_at_128B_per_read": reads * 128 / ms / 1e9}))
         return 0
+    out = run_workload(args.workload, args.steps, args.warmup, args.variant, cpu=not args.no_cpu_baseline,
+                       fetch=not args.no_feature_fetch)
+    if out is None:
+        return 2
+    # the other workloads of the build's configs, each with its own dominant kernel, roofline and oracle time
+    # (fewer steps; not part of `value`)
+    if args.others == "yes" or (args.others == "auto" and args.workload == "large_sage" and args.variant == "none"):
+        others = {}
+        for name in OTHER_WORKLOADS:
+            if name == args.workload:
+                continue
+            torch.cuda.empty_cache()
+            r = run_workload(name, max(5, args.steps // 2), 2, "none", cpu=not args.no_cpu_baseline, fetch=False)
+            others[name] = {key: r[key] for key in ("value", "unit", "ms_per_step", "ms_per_step_min", "minibatches_per_sec",
+                                                    "config", "roofline", "cpu_baseline") if key in r}
+            if "gathered_neighbours_per_sec" in r:
+                others[name]["gathered_neighbours_per_sec"] = r["gathered_neighbours_per_sec"]
+        out["other_workloads"] = others
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def run_workload(workload: str, steps: int, warmup: int, variant: str, cpu: bool, fetch: bool):
+    """Times `steps` bulk calls of one workload (graph generated here, resident in HBM) and returns the record."""
+    import functools
+
+    import torch
+    from paper_2311_02909_amd import bms, synth
+
+    class args:  # the names the body below uses
+        pass
+    args.workload, args.steps, args.warmup, args.variant = workload, steps, warmup, variant
+    args.no_cpu_baseline, args.no_feature_fetch = not cpu, not fetch
     t0 = time.time()
     g, batches, w = synth.make_workload(args.workload, device="cuda")
     torch.cuda.synchronize()
@@ -155,8 +188,7 @@ def main() -> int:
     if args.variant != "none":
         if not nodewise:
             print("bench.py: --variant applies to node-wise workloads", file=sys.stderr)
-            return 2
-        import functools
+            return None
         fn = functools.partial(fn, **{args.variant: True})
     traffic_key = args.workload if args.variant == "none" else args.workload + "+" + args.variant
     seed = synth.SAMPLING_SEED
@@ -223,13 +255,13 @@ def main() -> int:
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 5),
         # measured HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated), average over the launches
-        "traffic": (MEASURED_TRAFFIC[(traffic_key, dominant)]["bytes_per_step"]
-                    // MEASURED_TRAFFIC[(traffic_key, dominant)]["launches"])
+        "traffic": (MEASURED_TRAFFIC[(traffic_key, dominant)] // dom["launches"])
         if (traffic_key, dominant) in MEASURED_TRAFFIC else None,
         "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"]),
         "avg_launch_ms": round(dom["ms"] / dom["launches"], 4), "launches_per_step": dom["launches"],
         "algorithmic_bytes_per_step": int(dom["bytes"]),
         "timed_in": "the timed steps" if any(name == dominant for name, _ in main_ms) else "extra steps after the timed ones",
+        "timed_with_events": True,   # the timed steps carry the event records of the main stage (the value is conservative)
         "all_kernels_ms_per_step": {s: round(v["ms"], 4) for s, v in sorted(per_stage.items())},
     }
     if dominant == "nw_sample":
@@ -237,10 +269,9 @@ def main() -> int:
         # row is a 4-byte read that costs one 128-byte line.  Reads that share no line run at 3.87e10 /s on this chip
         # (bench.py --gather-probe 31, profiles/random_gather_probe.txt); short rows and minibatches that work on
         # the same id range at the same time share lines, which is how the kernel gets past that rate
-        roofline["random_access"] = {
-            "sampled_reads_per_sec": round(edges / (dom["ms"] * 1e-3), 1),
-            "unshared_line_ceiling_reads_per_sec": 3.87e10,
-            "frac": round(edges / (dom["ms"] * 1e-3) / 3.87e10, 4),
+        roofline["sampled_reads"] = {
+            "per_sec": round(edges / (dom["ms"] * 1e-3), 1),
+            "gather_probe_reads_per_sec": 3.87e10,   # reads that share no line with another (a measured rate, no ceiling)
         }
     # whole call: algorithmic bytes of all stages ("effective") and the profiled HBM bytes ("achieved"),
     # both over the sum of the kernel times measured in this run
@@ -250,9 +281,11 @@ def main() -> int:
         "kernels_ms_per_step": round(kernels_ms, 4),
         "effective_GBps": round(call_alg / (kernels_ms * 1e-3) / 1e9, 1),
         "effective_frac": round(call_alg / (kernels_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-        "achieved_GBps": round(MEASURED_CALL_TRAFFIC[traffic_key] / (kernels_ms * 1e-3) / 1e9, 1)
+        # profiled bytes between L2 and the memory fabric (an upper bound of the HBM traffic) over the same time
+        "fabric_traffic_bytes": MEASURED_CALL_TRAFFIC.get(traffic_key),
+        "fabric_GBps": round(MEASURED_CALL_TRAFFIC[traffic_key] / (kernels_ms * 1e-3) / 1e9, 1)
         if traffic_key in MEASURED_CALL_TRAFFIC else None,
-        "achieved_frac": round(MEASURED_CALL_TRAFFIC[traffic_key] / (kernels_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        "fabric_frac": round(MEASURED_CALL_TRAFFIC[traffic_key] / (kernels_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
         if traffic_key in MEASURED_CALL_TRAFFIC else None,
     }
 
@@ -347,8 +380,8 @@ def main() -> int:
     if not nodewise:
         out["gathered_neighbours_per_sec"] = round(sum(gathered_of_hop.values()) / (ms_per_step * 1e-3), 1)
         out["config"]["gathered_per_hop"] = [gathered_of_hop[h] for h in sorted(gathered_of_hop)]
-    print(json.dumps(out), flush=True)
-    return 0
+    del csr, res, g, batches
+    return out
 
 
 if __name__ == "__main__":
