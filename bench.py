@@ -33,9 +33,36 @@ HBM_PEAK_GBS = 8000.0
 # the line "bench constant ..." of profiles/<workload>_hbm_traffic.txt (tests/test_bench_constants.py compares
 # them); a kernel that has changed since its profile was taken has no entry (None in the output).
 MEASURED_TRAFFIC = {
+    ("dense_ladies", "ldw_accumulate"): 4_266_667_492,
+    ("dense_ladies", "ldw_extract"): 2_046_597_627,
+    ("dense_sage", "nw_sample"): 10_771_843_227,
+    ("dense_sage", "nw_rows"): 1_379_481_513,
+    ("dense_sage", "dd_split"): 1_126_571_515,
+    ("dense_sage", "dd_unsplit"): 963_112_969,
+    ("dense_sage", "dd_rank"): 875_177_261,
+    ("dense_sage", "dd_front"): 616_755_712,
+    ("large_sage", "nw_sample"): 5_987_876_772,
+    ("large_sage", "nw_rows"): 1_648_071_323,
+    ("large_sage", "dd_split"): 740_678_125,
+    ("large_sage", "dd_unsplit"): 649_420_918,
+    ("large_sage", "dd_rank"): 598_387_163,
+    ("large_sage", "dd_front"): 473_538_464,
+    ("mid_ladies", "ldw_accumulate"): 196_442_491,
+    ("mid_ladies", "ldw_extract"): 89_716_772,
+    ("mid_sage", "nw_sample"): 3_183_651_204,
+    ("mid_sage", "dd_split"): 423_725_540,
+    ("mid_sage", "dd_unsplit"): 358_696_429,
+    ("mid_sage", "nw_rows"): 352_067_442,
+    ("mid_sage", "dd_rank"): 313_301_188,
+    ("mid_sage", "dd_front"): 204_167_876,
 }
 # the same summed over every kernel of one bulk call (bytes per step)
 MEASURED_CALL_TRAFFIC = {
+    "dense_ladies": 13_130_045_915,
+    "dense_sage": 15_735_199_405,
+    "large_sage": 10_101_181_440,
+    "mid_ladies": 629_599_807,
+    "mid_sage": 4_836_655_373,
 }
 OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
 
