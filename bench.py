@@ -124,6 +124,8 @@ def main() -> int:
     ap.add_argument("--variant", default="none", choices=["none", "union_dst", "replace"],
                     help="node-wise variant: union_dst keeps the frontier's own vertices as columns (BMS_UNION_DST), "
                          "replace makes a row's draws independent (BMS_NODEWISE_REPLACE)")
+    ap.add_argument("--relabel", default=None, choices=["degree"],
+                    help="renumber the graph's vertices by descending degree (hubs first) instead of the recipe's random ids")
     ap.add_argument("--others", default="auto", choices=["auto", "yes", "no"],
                     help="also run the other workloads of the build's configs (fewer steps) and report them under "
                          "other_workloads; auto = only with the default workload")
@@ -172,12 +174,12 @@ def main() -> int:
                           "reads_per_sec": reads / ms * 1e3, "tb_per_sec_at_128B_per_read": reads * 128 / ms / 1e9}))
         return 0
     out = run_workload(args.workload, args.steps, args.warmup, args.variant, cpu=not args.no_cpu_baseline,
-                       fetch=not args.no_feature_fetch)
+                       fetch=not args.no_feature_fetch, relabel=args.relabel)
     if out is None:
         return 2
     # the other workloads of the build's configs, each with its own dominant kernel, roofline and oracle time
     # (fewer steps; not part of `value`)
-    if args.others == "yes" or (args.others == "auto" and args.workload == "large_sage" and args.variant == "none"):
+    if args.others == "yes" or (args.others == "auto" and args.workload == "large_sage" and args.variant == "none" and not args.relabel):
         others = {}
         for name in OTHER_WORKLOADS:
             if name == args.workload:
@@ -193,7 +195,7 @@ def main() -> int:
     return 0
 
 
-def run_workload(workload: str, steps: int, warmup: int, variant: str, cpu: bool, fetch: bool):
+def run_workload(workload: str, steps: int, warmup: int, variant: str, cpu: bool, fetch: bool, relabel=None):
     """Times `steps` bulk calls of one workload (graph generated here, resident in HBM) and returns the record."""
     import functools
 
@@ -205,7 +207,7 @@ def run_workload(workload: str, steps: int, warmup: int, variant: str, cpu: bool
     args.workload, args.steps, args.warmup, args.variant = workload, steps, warmup, variant
     args.no_cpu_baseline, args.no_feature_fetch = not cpu, not fetch
     t0 = time.time()
-    g, batches, w = synth.make_workload(args.workload, device="cuda")
+    g, batches, w = synth.make_workload(args.workload, device="cuda", relabel=relabel)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     print("[bench] %s: %s (generated in %.1f s)" % (args.workload, g.describe(), gen_s), file=sys.stderr, flush=True)
@@ -218,6 +220,8 @@ def run_workload(workload: str, steps: int, warmup: int, variant: str, cpu: bool
             return None
         fn = functools.partial(fn, **{args.variant: True})
     traffic_key = args.workload if args.variant == "none" else args.workload + "+" + args.variant
+    if relabel:
+        traffic_key += "+" + relabel
     seed = synth.SAMPLING_SEED
     stream = torch.cuda.current_stream()
 
@@ -401,7 +405,7 @@ def run_workload(workload: str, steps: int, warmup: int, variant: str, cpu: bool
         "minibatches_per_sec": round(k / (ms_per_step * 1e-3), 1),
         "config": {"workload": args.workload, "sampler": w["sampler"], "params": list(w["params"]),
                    "batch": w["batch"], "k": k, "n": g.n, "nnz": g.nnz, "max_degree": g.max_degree,
-                   "variant": args.variant, "rows_nnz_cols_per_hop": [list(s) for s in sizes]},
+                   "variant": args.variant, "relabel": relabel or "random", "rows_nnz_cols_per_hop": [list(s) for s in sizes]},
         "roofline": roofline, "cpu_baseline": cpu, "feature_fetch": fetch,
     }
     if not nodewise:

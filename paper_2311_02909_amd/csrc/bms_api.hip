@@ -146,7 +146,7 @@ struct bms_csr {
     BMS_BUF(ld_counters); BMS_BUF(ld_gather_off); BMS_BUF(ld_row_mb); BMS_BUF(ld_chunks); BMS_BUF(ld_prefix);
     BMS_BUF(ld_ptileoff); BMS_BUF(ld_tilesum);
     BMS_BUF(dd_pairs); BMS_BUF(dd_utmp); BMS_BUF(dd_uniq); BMS_BUF(dd_edgeoff); BMS_BUF(dd_count); BMS_BUF(dd_back);
-    BMS_BUF(dd_tileoff); BMS_BUF(dd_cursor); BMS_BUF(dd_seg); BMS_BUF(dd_runs); BMS_BUF(dd_segcnt); BMS_BUF(dd_done); // EXTRACT
+    BMS_BUF(dd_tileoff); BMS_BUF(dd_cursor); BMS_BUF(dd_seg); BMS_BUF(dd_runs); BMS_BUF(dd_segcnt); BMS_BUF(dd_done); BMS_BUF(dd_hist); // EXTRACT
     bool segcnt_clean = false; // every segment counter zero (kept so by the kernels; lost when a call is interrupted)
     BMS_BUF(un_rowptr); BMS_BUF(un_col); // BMS_UNION_DST: the hop's CSR while its rows still carry their own vertex
     BMS_BUF(row_cnt);                    // BMS_NODEWISE_REPLACE with a fanout above 32: distinct picks per row
@@ -160,6 +160,7 @@ struct bms_csr {
 struct HopBufs {
     DevBuf mb_rowoff, row_vertex; // own storage only at hop 0; later hops alias the previous hop's columns
     DevBuf rowptr, col, mb_coloff, col_vertex, p_off, p_col, p_cnt, row_self;
+    DevBuf seg_tab; // node-wise EXTRACT with segments of unequal width: cell -> segment table, then the segments' first cells
     bms_hop_view view;
 };
 
@@ -176,8 +177,11 @@ struct bms_result {
     const bms_csr *hint_csr = nullptr;
     std::vector<int32_t> hint_shape; // k, b, fanouts...
     std::vector<int64_t> hint_nnz;   // per hop
-    uint32_t hint_bins = 0;          // hops (bits) whose EXTRACT goes to the per-minibatch kernel: their sampled ids crowd
-                                     // id ranges so much that the segment kernels gave up on them before
+    // how each hop's EXTRACT went before: 0 = segments of equal width did, 1 = ids crowd parts of [0, n): segments of
+    // unequal width from a table (kept in the hop's seg_tab once built), 2 = the per-minibatch kernel
+    std::vector<uint8_t> hint_mode;
+    std::vector<uint8_t> hint_table_ready; // per hop: seg_tab holds the table for hint_table_C segments
+    std::vector<int32_t> hint_table_C;
     // host copies of the per-minibatch offsets (rows, entries, columns: L x 3 x (k+1)), made on demand by
     // bms_result_minibatch and dropped when the result is written again
     std::vector<int64_t> mb_offsets;
@@ -199,6 +203,7 @@ void result_release(bms_result *r)
         h.p_col.release();
         h.p_cnt.release();
         h.row_self.release();
+        h.seg_tab.release();
     }
     r->mb_edge_tmp.release();
     for (auto e : r->event_pool)
@@ -478,8 +483,9 @@ std::vector<int32_t> nodewise_shape(const CallCtx &c, const int32_t *fanouts)
 }
 
 // One attempt.  *redo receives the hops (bits) whose EXTRACT by id-range segments gave up (ids crowded into a narrow
-// range): the result is then incomplete and the caller repeats the call with those hops added to `bins`.
-int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fanouts, uint32_t bins, uint32_t *redo)
+// range): the result is then incomplete and the caller repeats the call with those hops moved to the next mode.
+int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fanouts, const std::vector<uint8_t> &mode,
+                         uint32_t *redo)
 {
     bms_csr *csr = c.csr;
     Profiler prof{c.res, c.stream, (c.flags & (BMS_PROFILE | BMS_PROFILE_MAIN)) != 0, (c.flags & BMS_PROFILE) == 0};
@@ -509,6 +515,8 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
         BMS_TRY(csr->dd_done.ensure(256));
         HIP_TRY(hipMemsetAsync(csr->dd_done.p, 0, 256, c.stream));
     }
+    std::vector<int32_t> table_built((size_t)c.L, 0); // per hop: segments of the table in use (0: none)
+    int32_t table_pending = -1;
     bool tiles_planned = false;        // the hop's row tiles were written by the hop before it
     bool counters_zero = csr->segcnt_clean; // the segment counters are all zero between hops: the kernels clear what they
     csr->segcnt_clean = false;              // read; a fresh buffer, or one an interrupted call left behind, is cleared here
@@ -614,8 +622,9 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
             // segments = id ranges of 2^cshift ids holding 1500..3000 sampled ids each on average (one workgroup ranks
             // up to 4096 in LDS; the longer a segment, the longer the runs the cut appends to it per tile),
             // at most kMaxSegments of them
-            int32_t C = 0, cshift = 0, by_bitmap = 0;
-            if (seg_sort && !((bins >> h) & 1u)) {
+            int32_t C = 0, cshift = 0, by_bitmap = 0, fshift = 0, wbits_max = 0, target_per_mb = 0;
+            const bool by_table = mode[h] == 1;
+            if (seg_sort && mode[h] < 2) {
                 const double per_mb = (double)nnz_tune / c.k + 1.0;
                 // ids dense enough in [0, n) that a pass over a bitmap of a segment's id range costs less than sorting
                 // its ids: segments as wide as the bitmap kernel takes, as long as they hold well under 2^16 ids
@@ -630,6 +639,21 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
                 if (cshift > kMaxBitmapShift)
                     by_bitmap = 0;
                 C = (int32_t)std::max<int64_t>((csr->n + (1LL << cshift) - 1) >> cshift, 1);
+                wbits_max = std::min(cshift, kMaxBitmapShift);
+                if (by_table) {
+                    // segments of unequal width: cells of 2^fshift ids (at most kMaxCells of them) dealt to segments of
+                    // about 2/3 of what the ranking kernels take; room for twice the expected number of segments
+                    while (((csr->n + (1LL << fshift) - 1) >> fshift) > kMaxCells)
+                        ++fshift;
+                    target_per_mb = by_bitmap ? 16384 : 2500;
+                    wbits_max = by_bitmap ? std::max(cshift, fshift) : kMaxBitmapShift;
+                    const int64_t cells = std::max<int64_t>((csr->n + (1LL << fshift) - 1) >> fshift, 1);
+                    const int64_t forced = by_bitmap ? (cells >> std::max(wbits_max - fshift, 0)) + 2 : 3;
+                    C = (int32_t)std::min<int64_t>(kMaxSegments, (int64_t)(2.0 * per_mb / target_per_mb) + forced + 8);
+                    if (!c.fresh_result && h < (int32_t)c.res->hint_table_ready.size() && c.res->hint_table_ready[h] &&
+                        no_wait)
+                        C = c.res->hint_table_C[h]; // the table at hand was built for this many
+                }
                 // few sampled edges per minibatch: the single per-minibatch kernel beats the chain of
                 // chip-wide kernels, whose launches would dominate (unless that path was asked for)
                 if (per_mb <= 4096.0 && !(c.flags & BMS_EXTRACT_SORT))
@@ -664,6 +688,18 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.C = C;
             d.cshift = cshift;
             d.by_bitmap = by_bitmap;
+            d.wbits_max = wbits_max;
+            bool build_table = false;
+            if (C > 0 && by_table) {
+                BMS_TRY(hb.seg_tab.ensure((size_t)(kMaxCells + 2) * sizeof(uint16_t) + ((size_t)kMaxSegments + 2) * sizeof(uint32_t)));
+                BMS_TRY(csr->dd_hist.ensure(((size_t)kMaxCells + 2) * sizeof(uint32_t)));
+                d.tab = hb.seg_tab.as<uint16_t>();
+                d.seg_first = reinterpret_cast<const uint32_t *>(hb.seg_tab.as<uint16_t>() + kMaxCells + 2);
+                d.fshift = fshift;
+                const bool ready = no_wait && h < (int32_t)c.res->hint_table_ready.size() && c.res->hint_table_ready[h] &&
+                                   c.res->hint_table_C[h] == C && !hb.seg_tab.grew;
+                build_table = !ready;
+            }
             d.big_tileoff = csr->dd_tileoff.as<int64_t>() + 2 * (c.k + 1);
             // flag and list counter of the hop: two 32-bit words of a scalar slot, zeroed with the slots at the start of
             // the call and read back with the sizes at its end
@@ -682,15 +718,26 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
             d.run_gpos = csr->dd_runs.as<uint32_t>();
             d.run_cnt = d.run_gpos + (size_t)xtiles * (size_t)std::max(C, 1);
             d.mb_count = csr->dd_count.as<int64_t>();
-            if (C > 0) { // the sampling kernel counts the ids per segment while it has them in LDS, when it can
+            if (C > 0 && !build_table) { // the sampling kernel counts the ids per segment while it has them in LDS, when it can
                 a.seg_cnt = d.seg_cnt;
                 a.seg_C = C;
-                a.seg_shift = cshift;
+                a.seg_shift = by_table ? fshift : cshift;
+                a.seg_tab = d.tab;
             }
+            table_built[h] = (C > 0 && by_table) ? C : 0;
+            if (build_table)
+                table_pending = h;
         }
         BMS_TRY(prof.begin("nw_sample", h));
         counted = launch_nw_sample(c.launch, a, c.vs, !buckets);
         BMS_TRY(prof.end());
+        if (table_pending == h) { // the table of this hop's segments, from a sample of the ids just staged
+            BMS_TRY(prof.begin("dd_table", h));
+            launch_nw_dedup_table(c.launch, a.out_col, slot(c, h, 0), nnz, csr->n, c.k, d.fshift, d.C,
+                                  d.by_bitmap ? 16384 : 2500, d.by_bitmap ? d.wbits_max : 31, csr->dd_hist.as<uint32_t>(),
+                                  const_cast<uint16_t *>(d.tab), const_cast<uint32_t *>(d.seg_first));
+            BMS_TRY(prof.end());
+        }
         if (buckets) {
             const StageMark mark = [&](const char *name) { (void)prof.mark(name, h); };
             if (d.C > 0) {
@@ -757,7 +804,11 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
     c.res->hint_csr = csr;
     c.res->hint_shape = shape;
     c.res->hint_nnz = seen_nnz;
-    c.res->hint_bins = bins;
+    c.res->hint_mode = mode;
+    c.res->hint_table_C = table_built;
+    c.res->hint_table_ready.assign((size_t)c.L, 0);
+    for (int32_t h = 0; h < c.L; ++h)
+        c.res->hint_table_ready[h] = table_built[h] > 0 ? 1 : 0;
     BMS_TRY(prof.finish());
     if (!buckets || !seeds_by_sort)
         csr->vs_clean = true;
@@ -766,16 +817,19 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
 
 int sample_nodewise_impl(CallCtx &c, const int32_t *batches, const int32_t *fanouts)
 {
-    // hops that gave up on the segment kernels in an earlier call of this shape go to the per-minibatch kernel at once
-    uint32_t bins = 0;
-    if (!c.fresh_result && c.res->hint_csr == c.csr && c.res->hint_shape == nodewise_shape(c, fanouts))
-        bins = c.res->hint_bins;
-    for (int32_t attempt = 0; attempt <= c.L; ++attempt) {
+    // hops that gave up on a kernel path in an earlier call of this shape start with the path that worked then
+    std::vector<uint8_t> mode((size_t)c.L, 0);
+    if (!c.fresh_result && c.res->hint_csr == c.csr && c.res->hint_shape == nodewise_shape(c, fanouts) &&
+        (int32_t)c.res->hint_mode.size() == c.L)
+        mode = c.res->hint_mode;
+    for (int32_t attempt = 0; attempt <= 2 * c.L; ++attempt) {
         uint32_t redo = 0;
-        BMS_TRY(sample_nodewise_once(c, batches, fanouts, bins, &redo));
+        BMS_TRY(sample_nodewise_once(c, batches, fanouts, mode, &redo));
         if (!redo)
             return BMS_OK;
-        bins |= redo;
+        for (int32_t h = 0; h < c.L; ++h)
+            if ((redo >> h) & 1u)
+                mode[h] = (uint8_t)std::min<int>(mode[h] + 1, 2);
         c.res->stages.clear();
         c.res->events_used = 0;
     }

@@ -79,6 +79,7 @@ struct NwHop {
     // (nullptr: not wanted); the caller has zeroed the counters
     uint32_t *seg_cnt;         // k * seg_C
     int32_t seg_C, seg_shift;  // segment of an id = id >> seg_shift, < seg_C <= kMaxFusedSegments
+    const uint16_t *seg_tab;   // not nullptr: segment of an id = seg_tab[id >> seg_shift] (kMaxCells + 1 entries at most)
 };
 constexpr int kMaxFusedSegments = 512;
 void launch_nw_rows(const Launch &, const NwHop &);
@@ -115,7 +116,14 @@ struct DedupArgs {
     // segment path (C == 0: not used)
     int32_t C;           // id-range segments per minibatch = ceil(n / 2^cshift) <= kMaxSegments
     int32_t cshift;      // segment of an id = id >> cshift
-    int32_t by_bitmap;   // 1: every segment is ranked through a bitmap of its id range (dense hops); 0: by sorting
+    int32_t by_bitmap;   // 1: every segment is ranked through a bitmap of its id range (dense hops); 0: by counting
+    // Segments of unequal width (ids that crowd parts of [0, n), e.g. ids sorted by degree): cells of 2^fshift ids,
+    // tab[id >> fshift] = segment of the cell, seg_first[c] = first cell of segment c (C + 1 entries; segments
+    // past the last one in use are empty).  tab == nullptr: every segment is 2^cshift ids wide.
+    const uint16_t *tab;
+    const uint32_t *seg_first;
+    int32_t fshift;
+    int32_t wbits_max;   // log2 of the ids the bitmap kernel's LDS holds: no segment it is given is wider
     uint32_t *seg_cnt;   // k * C: entries per segment, later distinct ids per segment
     uint32_t *seg_off;   // k * (C+1): exclusive scan of the entry counts
     uint32_t *seg_cursor; // k * C
@@ -134,6 +142,7 @@ struct DedupArgs {
 constexpr int kSplitTile16 = 16384; // positions per tile of the count, split and un-split kernels
 constexpr int kSegCap = 65535;      // most entries a segment may hold: the rank of an id inside its segment has 16 bits
 constexpr int kMaxSegments = 2560;  // 3 words each beside the staging of the split / un-split kernels must fit in 160 KB of LDS
+constexpr int kMaxCells = 4096;      // cells of the table that maps ids to segments of unequal width
 constexpr int kMaxBitmapShift = 20; // the bitmap ranking kernel holds 2^cshift bits in LDS (128 KB)
 // EXTRACT of a hop by id-range segments (C > 0).  counted: the per-segment counts are there already.  Also writes
 // the next hop's row tiles (next_tileoff, k + 2 entries as launch_plan_tiles with max_out gives them).  `done` is a
@@ -142,6 +151,12 @@ void launch_nw_extract_segments(const Launch &, const DedupArgs &, const int64_t
                                 int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t *next_tileoff,
                                 uint32_t *done, int64_t nnz, bool counted, const StageMark &mark);
 void launch_nw_dedup_unsplit(const Launch &, const DedupArgs &, int64_t nnz);
+// Builds the table of segments of unequal width for a hop from a sample of its staged ids: tab (cells + 1 entries),
+// seg_first (C + 1), at most C segments, each holding about target_per_mb ids of a minibatch and at most
+// 2^max_wbits ids wide (max_wbits >= 32: any width).  hist: scratch of kMaxCells + 1 words.
+void launch_nw_dedup_table(const Launch &, const int32_t *col, const int64_t *nnz, int64_t nnz_bound, int64_t n, int32_t k,
+                           int32_t fshift, int32_t C, int32_t target_per_mb, int32_t max_wbits, uint32_t *hist,
+                           uint16_t *tab, uint32_t *seg_first);
 void launch_nw_dedup_front(const Launch &, const DedupArgs &, const int64_t *mb_coloff, int32_t *col_vertex, int64_t nnz);
 // EXTRACT of a hop by the per-minibatch kernel (C == 0); returns 0, or -1 when the launch was refused
 int launch_nw_dedup_bucket(const Launch &, const DedupArgs &, const int64_t *out_rowptr, const int64_t *mb_rowoff,

@@ -32,11 +32,39 @@ namespace bms {
 constexpr int kLocShift = 14; // bits of the place inside a run (a tile holds 2^14 positions)
 static_assert(kSplitTile16 == (1 << kLocShift) && kMaxSegments <= (1 << (32 - kLocShift)), "loc word out of step");
 
+// The table of segments of unequal width, copied to LDS by the kernels that look ids up (tab_l: kMaxCells + 1 entries).
+__device__ inline void load_seg_table(const DedupArgs &a, uint16_t *tab_l, int nthreads)
+{
+    if (a.tab == nullptr)
+        return;
+    for (int x = threadIdx.x; x <= kMaxCells; x += nthreads)
+        tab_l[x] = a.tab[x];
+    __syncthreads();
+}
+__device__ inline uint32_t seg_of(const DedupArgs &a, const uint16_t *tab_l, uint32_t id)
+{
+    return a.tab ? (uint32_t)tab_l[id >> a.fshift] : id >> a.cshift;
+}
+// first id of segment c and log2 (rounded up) of the number of ids it spans
+__device__ inline void seg_range(const DedupArgs &a, uint32_t c, uint32_t &id0, int &wbits)
+{
+    if (a.tab) {
+        const uint32_t f0 = a.seg_first[c], width = (a.seg_first[c + 1] - f0) << a.fshift;
+        id0 = f0 << a.fshift;
+        wbits = width <= 1u ? 0 : 32 - __clz(width - 1u);
+    } else {
+        id0 = c << a.cshift;
+        wbits = a.cshift;
+    }
+}
+
 template <int TILE, int NT>
 __global__ __launch_bounds__(NT) void dd_count_kernel(DedupArgs a, const int64_t *__restrict__ tileoff)
 {
     __shared__ uint32_t hist[kMaxSegments];
+    __shared__ uint16_t tab_l[kMaxCells + 1];
     const int tid = threadIdx.x;
+    load_seg_table(a, tab_l, NT);
     const int64_t ntiles = tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
         const int i = locate_segment(tileoff, a.k, t);
@@ -56,7 +84,7 @@ __global__ __launch_bounds__(NT) void dd_count_kernel(DedupArgs a, const int64_t
 #pragma unroll
         for (int q = 0; q < TILE / NT; ++q)
             if (g[q] != 0xFFFFFFFFu)
-                atomicAdd(&hist[g[q] >> a.cshift], 1u);
+                atomicAdd(&hist[seg_of(a, tab_l, g[q])], 1u);
         __syncthreads();
         for (int c = tid; c < a.C; c += NT)
             if (hist[c])
@@ -100,7 +128,12 @@ __device__ inline void seg_scan_block(const DedupArgs &a, int i, uint32_t *smem,
         // segment's id range as bits in LDS; a segment wider or fuller than that kernel takes sends the hop to the
         // per-minibatch kernel
         const bool big = !a.by_bitmap && v > (uint32_t)kRankCapFwd;
-        too_big |= v > (uint32_t)kSegCap || (big && a.cshift > kMaxBitmapShift);
+        if (big || v > (uint32_t)kSegCap) {
+            uint32_t id0;
+            int wbits;
+            seg_range(a, (uint32_t)c, id0, wbits);
+            too_big |= v > (uint32_t)kSegCap || wbits > a.wbits_max;
+        }
         wave_append(a.big_list, a.big_count, big && v <= (uint32_t)kSegCap, (uint32_t)(i * a.C + c));
         uint32_t total;
         const uint32_t ex = block_exclusive_scan<uint32_t, 256>(v, smem, total);
@@ -179,11 +212,13 @@ __global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t
     extern __shared__ uint32_t split_lds[]; // stage[TILE]; then 3 C words: per-segment count, start in the tile, start in global - start in the tile
     __shared__ uint32_t smem[NT / kWave];
     __shared__ uint32_t carry_s;
+    __shared__ uint16_t tab_l[kMaxCells + 1];
     if (*a.fallback)
         return;
     uint32_t *stage = split_lds;
     uint32_t *cnt = split_lds + TILE, *off = cnt + a.C, *gpos = cnt + 2 * a.C;
     const int tid = threadIdx.x;
+    load_seg_table(a, tab_l, NT);
     const int64_t ntiles = tileoff[a.k];
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
         const int i = locate_segment(tileoff, a.k, t);
@@ -198,7 +233,7 @@ __global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t
             carry_s = 0;
         __syncthreads();
         uint32_t id[TILE / NT];
-        uint32_t lpos[TILE / NT];
+        uint32_t lpos[TILE / NT]; // segment << kLocShift | place in the tile's run for that segment
 #pragma unroll
         for (int q = 0; q < TILE / NT; ++q) {
             const uint32_t j = j0 + q * NT + tid;
@@ -206,13 +241,15 @@ __global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t
         }
 #pragma unroll
         for (int q = 0; q < TILE / NT; ++q)
-            if (id[q] != 0xFFFFFFFFu)
-                lpos[q] = atomicAdd(&cnt[id[q] >> a.cshift], 1u);
+            if (id[q] != 0xFFFFFFFFu) {
+                const uint32_t c = seg_of(a, tab_l, id[q]);
+                lpos[q] = (c << kLocShift) | atomicAdd(&cnt[c], 1u);
+            }
         uint32_t *__restrict__ loc = a.loc + e0;
 #pragma unroll
         for (int q = 0; q < TILE / NT; ++q)
             if (id[q] != 0xFFFFFFFFu)
-                loc[j0 + q * NT + tid] = ((id[q] >> a.cshift) << kLocShift) | lpos[q];
+                loc[j0 + q * NT + tid] = lpos[q];
         __syncthreads();
         uint32_t *__restrict__ run_gpos = a.run_gpos + t * a.C, *__restrict__ run_cnt = a.run_cnt + t * a.C;
         for (int base = 0; base < a.C; base += NT) {
@@ -238,12 +275,12 @@ __global__ __launch_bounds__(NT) void dd_split_kernel(DedupArgs a, const int64_t
 #pragma unroll
         for (int q = 0; q < TILE / NT; ++q)
             if (id[q] != 0xFFFFFFFFu)
-                stage[off[id[q] >> a.cshift] + lpos[q]] = id[q];
+                stage[off[lpos[q] >> kLocShift] + (lpos[q] & (TILE - 1))] = id[q];
         __syncthreads();
         uint32_t *__restrict__ ids_seg = a.ids_seg + e0;
         for (uint32_t sidx = tid; sidx < jend - j0; sidx += NT) {
             const uint32_t g = stage[sidx];
-            ids_seg[gpos[g >> a.cshift] + sidx] = g;
+            ids_seg[gpos[seg_of(a, tab_l, g)] + sidx] = g;
         }
         __syncthreads();
     }
@@ -296,7 +333,9 @@ __global__ __launch_bounds__(kRankThreads) void dd_rank_kernel(DedupArgs a)
         }
         const int64_t e0 = a.mb_edgeoff[i];
         const uint32_t *__restrict__ ids = a.ids_seg + e0 + s0;
-        const uint32_t id0 = cseg << a.cshift;
+        uint32_t id0;
+        int wbits;
+        seg_range(a, cseg, id0, wbits);
         uint32_t key[PER];
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
@@ -309,9 +348,9 @@ __global__ __launch_bounds__(kRankThreads) void dd_rank_kernel(DedupArgs a)
             nbits = 9;
         if (nbits > kRankBucketBits)
             nbits = kRankBucketBits;
-        if (nbits > a.cshift)
-            nbits = a.cshift;
-        const int bshift = a.cshift - nbits;
+        if (nbits > wbits)
+            nbits = wbits;
+        const int bshift = wbits - nbits;
         const int nb = 1 << nbits;
         const int nqd = nb >= 4 ? nb / 4 : 1;                  // 16-byte quads of counters
         const int qw = (nqd + NW - 1) / NW;                    // per wave
@@ -351,7 +390,7 @@ __global__ __launch_bounds__(kRankThreads) void dd_rank_kernel(DedupArgs a)
             wtot[wave] = wave_total;
         if (__syncthreads_or(crowded)) { // uniform for the workgroup
             if (tid == 0) {
-                if (a.cshift <= kMaxBitmapShift)
+                if (wbits <= a.wbits_max)
                     a.big_list[atomicAdd(a.big_count, 1u)] = (uint32_t)sg;
                 else
                     atomicOr(a.fallback, 1);
@@ -474,10 +513,10 @@ __global__ __launch_bounds__(kBmThreads) void dd_bitmap_kernel(DedupArgs a)
 {
     extern __shared__ uint4 bm_lds[]; // quads, then one 16-bit running count per quad
     __shared__ uint32_t wtot[kBmWaves];
-    if (*a.fallback || a.cshift > kMaxBitmapShift)
+    if (*a.fallback || a.wbits_max > kMaxBitmapShift)
         return;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    uint32_t nq = (1u << a.cshift) / 128u;
+    uint32_t nq = (1u << a.wbits_max) / 128u;
     if (nq < (uint32_t)(kBmWaves * kWave))
         nq = kBmWaves * kWave;
     const int its = (int)(nq / (kBmWaves * kWave)); // quads per lane: 1, 2, 4 or 8
@@ -494,7 +533,7 @@ __global__ __launch_bounds__(kBmThreads) void dd_bitmap_kernel(DedupArgs a)
     // a segment's first ids are fetched while the segment before it is worked on
     struct Seg {
         int64_t sg, e0;
-        uint32_t s0, m, c;
+        uint32_t s0, m, c, id0;
         uint32_t keep[kBmKeep]; // the first kBmKeep ids of this thread, relative to the segment's first id
     };
     auto fetch = [&](int64_t x, Seg &g) {
@@ -513,7 +552,10 @@ __global__ __launch_bounds__(kBmThreads) void dd_bitmap_kernel(DedupArgs a)
         g.m = soff[g.c + 1] - g.s0;
         g.e0 = a.mb_edgeoff[i];
         const uint32_t *__restrict__ ids = a.ids_seg + g.e0 + g.s0;
-        const uint32_t id0 = g.c << a.cshift;
+        uint32_t id0;
+        int wbits;
+        seg_range(a, g.c, id0, wbits);
+        g.id0 = id0;
 #pragma unroll
         for (int q = 0; q < kBmKeep; ++q) {
             const uint32_t j = q * kBmThreads + tid;
@@ -534,7 +576,7 @@ __global__ __launch_bounds__(kBmThreads) void dd_bitmap_kernel(DedupArgs a)
         const uint32_t *__restrict__ ids = a.ids_seg + cur.e0 + cur.s0;
         uint16_t *__restrict__ ranks = a.ranks + cur.e0 + cur.s0;
         uint32_t *__restrict__ uids = a.uids + cur.e0 + cur.s0;
-        const uint32_t id0 = cur.c << a.cshift;
+        const uint32_t id0 = cur.id0;
         const int64_t sg = cur.sg;
         const uint32_t(&keep)[kBmKeep] = cur.keep;
         // 1: set bits
@@ -796,6 +838,113 @@ __global__ __launch_bounds__(NT) void dd_unsplit_kernel(DedupArgs a, const int64
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Segments of unequal width.  Ids that crowd parts of [0, n) (ids sorted by degree put every hub at one end)
+// overfill segments of equal width.  The hop's staged ids are sampled (every 8th block of 2048) into a histogram
+// over cells of 2^fshift ids; the cells are then dealt to segments in id order so that every segment holds about
+// the same share of the sample -- a cell that alone holds more stays a segment of its own, narrow enough for the
+// bitmap kernel.  The table is the same for all minibatches of the hop (they sample the same graph), and a
+// recycled result keeps it for the next call.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dd_hist_kernel(const int32_t *__restrict__ col, const int64_t *__restrict__ nnz_ptr,
+                                                      int32_t fshift, int32_t cells, uint32_t *__restrict__ hist)
+{
+    __shared__ uint32_t h[kMaxCells + 1];
+    const int tid = threadIdx.x;
+    for (int x = tid; x <= cells; x += 256)
+        h[x] = 0;
+    __syncthreads();
+    const int64_t nnz = *nnz_ptr;
+    for (int64_t b0 = (int64_t)blockIdx.x * 8 * 2048; b0 < nnz; b0 += (int64_t)gridDim.x * 8 * 2048) {
+        uint32_t g[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int64_t j = b0 + q * 256 + tid;
+            g[q] = j < nnz ? (uint32_t)col[j] : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (g[q] != 0xFFFFFFFFu)
+                atomicAdd(&h[g[q] >> fshift], 1u);
+    }
+    __syncthreads();
+    for (int x = tid; x < cells; x += 256)
+        if (h[x])
+            atomicAdd(&hist[x], h[x]);
+}
+
+// one workgroup: thread t owns cells 4 t .. 4 t + 3
+__global__ __launch_bounds__(1024) void dd_table_kernel(const uint32_t *__restrict__ hist, const int64_t *__restrict__ nnz_ptr,
+                                                        int32_t k, int32_t cells, int32_t C, int32_t target_per_mb,
+                                                        int32_t max_cells, uint16_t *__restrict__ tab,
+                                                        uint32_t *__restrict__ seg_first)
+{
+    __shared__ uint64_t smem[16];
+    __shared__ uint32_t smem32[16];
+    const int tid = threadIdx.x;
+    uint64_t h[4], mine = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int cell = 4 * tid + u;
+        h[u] = cell < cells ? hist[cell] : 0u;
+        mine += h[u];
+    }
+    uint64_t S;
+    uint64_t before = block_exclusive_scan<uint64_t, 1024>(mine, smem, S);
+    // ids of the sample per segment: the share target_per_mb has in a minibatch's ids, and never so few that more
+    // than C segments come out (breaks forced by the width limit counted in)
+    const uint64_t per_mb = (uint64_t)(*nnz_ptr / k) + 1u;
+    const int64_t forced = cells / max_cells + 2;
+    const uint64_t room = (uint64_t)(C - forced > 1 ? C - forced : 1);
+    uint64_t target = S * (uint64_t)target_per_mb / per_mb + 1u;
+    if (target < S / room + 1u)
+        target = S / room + 1u;
+    uint32_t flags = 0, nflag = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int cell = 4 * tid + u;
+        if (cell < cells) {
+            const uint64_t prev_before = cell ? before - (u ? h[u - 1] : (uint64_t)hist[cell - 1]) : 0u;
+            const bool brk = cell == 0 || before / target != prev_before / target || cell / max_cells != (cell - 1) / max_cells;
+            flags |= brk ? 1u << u : 0u;
+            nflag += brk ? 1u : 0u;
+        }
+        before += h[u];
+    }
+    uint32_t nseg;
+    uint32_t seg = block_exclusive_scan<uint32_t, 1024>(nflag, smem32, nseg); // segments that start before this thread's cells
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int cell = 4 * tid + u;
+        if (cell < cells) {
+            if (flags & (1u << u)) {
+                seg_first[seg] = (uint32_t)cell;
+                ++seg;
+            }
+            tab[cell] = (uint16_t)(seg - 1u);
+        }
+    }
+    if (tid == 0)
+        tab[cells] = (uint16_t)(nseg - 1u); // ids at the very end of the last cell's range never occur; kept in bounds
+    for (uint32_t c = nseg + tid; c <= (uint32_t)C; c += 1024)
+        seg_first[c] = (uint32_t)cells; // the segments past the last one in use are empty
+}
+
+void launch_nw_dedup_table(const Launch &L, const int32_t *col, const int64_t *nnz, int64_t nnz_bound, int64_t n, int32_t k,
+                           int32_t fshift, int32_t C, int32_t target_per_mb, int32_t max_wbits, uint32_t *hist,
+                           uint16_t *tab, uint32_t *seg_first)
+{
+    const int32_t cells = (int32_t)(((n > 0 ? n : 1) + (1LL << fshift) - 1) >> fshift); // <= kMaxCells
+    int64_t max_cells = max_wbits >= 31 ? (int64_t)cells + 1 : (1LL << (max_wbits > fshift ? max_wbits - fshift : 0));
+    if (max_cells > cells)
+        max_cells = cells + 1;
+    (void)hipMemsetAsync(hist, 0, ((size_t)cells + 1) * sizeof(uint32_t), L.stream);
+    hipLaunchKernelGGL(dd_hist_kernel, dim3(grid_for(L, nnz_bound / (8 * 2048) + 1, 2)), dim3(256), 0, L.stream, col, nnz,
+                       fshift, cells, hist);
+    hipLaunchKernelGGL(dd_table_kernel, dim3(1), dim3(1024), 0, L.stream, hist, nnz, k, cells, C, target_per_mb,
+                       (int32_t)max_cells, tab, seg_first);
+}
+
 void launch_nw_extract_segments(const Launch &L, const DedupArgs &a, const int64_t *out_rowptr, const int64_t *mb_rowoff,
                                 int64_t *mb_coloff, int32_t *col_vertex, int64_t *ncols_out, int64_t *next_tileoff,
                                 uint32_t *done, int64_t nnz, bool counted, const StageMark &mark)
@@ -833,14 +982,14 @@ void launch_nw_extract_segments(const Launch &L, const DedupArgs &a, const int64
             (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
         big_attr_set = true;
     }
-    const size_t bm_lds = dd_bitmap_lds_bytes(a.cshift);
+    const size_t bm_lds = dd_bitmap_lds_bytes(a.wbits_max <= kMaxBitmapShift ? a.wbits_max : kMaxBitmapShift);
     const int bm_per_cu = (int)std::max<size_t>(1, std::min<size_t>(2, (size_t)(156 * 1024) / bm_lds));
     if (a.by_bitmap) {
         hipLaunchKernelGGL(dd_bitmap_kernel<false>, dim3(grid_for(L, (int64_t)a.k * a.C, bm_per_cu)), dim3(kBmThreads),
                            bm_lds, L.stream, a);
     } else {
         hipLaunchKernelGGL(dd_rank_kernel, dim3(grid_for(L, (int64_t)a.k * a.C, 4)), dim3(kRankThreads), 0, L.stream, a);
-        if (a.cshift <= kMaxBitmapShift) // segments the counting kernel did not take
+        if (a.tab || a.cshift <= kMaxBitmapShift) // segments the counting kernel did not take (none can be listed otherwise)
             hipLaunchKernelGGL(dd_bitmap_kernel<true>, dim3(grid_for(L, nnz / 1024 + 1, bm_per_cu)), dim3(kBmThreads),
                                bm_lds, L.stream, a);
     }

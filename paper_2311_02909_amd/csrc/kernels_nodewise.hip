@@ -243,14 +243,19 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
     __shared__ int32_t stage[kRowTile * (S + 1)]; // + 1: the row's own vertex when rows carry it
     __shared__ int32_t wsum[kRowTile / kWave];
     __shared__ uint32_t seg_hist[kMaxFusedSegments]; // sampled ids per id-range segment, of this workgroup's minibatch
+    __shared__ uint16_t seg_tab_l[kMaxCells + 1];    // segment of every cell of ids, when the segments differ in width
     const int tid = threadIdx.x;
     const int64_t most = a.mb_tileoff[a.k + 1];
     const int32_t s = a.s;
     const bool count = a.seg_cnt != nullptr; // then gridDim.x is a multiple of k: every tile of this workgroup belongs
                                              // to minibatch blockIdx.x % k
+    const bool by_table = count && a.seg_tab != nullptr;
     if (count) {
         for (int c = tid; c < a.seg_C; c += kRowTile)
             seg_hist[c] = 0;
+        if (by_table)
+            for (int x = tid; x <= kMaxCells; x += kRowTile)
+                seg_tab_l[x] = a.seg_tab[x];
         __syncthreads();
     }
     for (int64_t v = blockIdx.x; v < most * a.k; v += gridDim.x) { // same order as nw_rows_kernel
@@ -330,7 +335,7 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
             if (SET)
                 atomicOr(&words[g >> 5], 1u << (g & 31));
             if (count)
-                atomicAdd(&seg_hist[(uint32_t)g >> a.seg_shift], 1u);
+                atomicAdd(&seg_hist[by_table ? (uint32_t)seg_tab_l[(uint32_t)g >> a.seg_shift] : (uint32_t)g >> a.seg_shift], 1u);
         }
         __syncthreads();
     }

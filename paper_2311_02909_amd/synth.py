@@ -157,6 +157,35 @@ def rmat_graph(n: int, pairs: int, a: float, b: float, c: float, seed: int, devi
                  isolated=int((counts == 0).sum().item()))
 
 
+def relabel_by_degree(g: Graph, parts: Optional[int] = None) -> Graph:
+    """The same graph with its vertices renumbered by descending degree (hubs first, ties by old id): the id
+    layout of datasets whose ids correlate with degree, the opposite of rmat_graph's random relabelling."""
+    n, device = g.n, g.rowptr.device
+    deg = g.rowptr[1:] - g.rowptr[:-1]
+    order = torch.sort(deg, descending=True, stable=True).indices          # new id -> old id
+    newid = torch.empty(n, dtype=torch.int64, device=device)
+    newid[order] = torch.arange(n, dtype=torch.int64, device=device)
+    keys = torch.repeat_interleave(newid, deg) * n                           # new source of every entry
+    keys += newid[g.col.long()] if g.nnz < (1 << 28) else torch.index_select(newid, 0, g.col)
+    if parts is None:
+        parts = max(1, math.ceil(g.nnz / (1 << 28)))
+    span = (n + parts - 1) // parts
+    cols = []
+    for p in range(parts):
+        lo, hi = p * span, min(n, (p + 1) * span)
+        if lo >= hi:
+            break
+        seg = keys if parts == 1 else keys[(keys >= lo * n) & (keys < hi * n)]
+        seg = torch.sort(seg).values
+        cols.append((seg % n).to(torch.int32))
+        del seg
+    del keys
+    col = torch.cat(cols) if cols else torch.zeros(0, dtype=torch.int32, device=device)
+    rowptr = torch.zeros(n + 1, dtype=torch.int64, device=device)
+    rowptr[1:] = torch.cumsum(deg[order], 0)
+    return Graph(n=n, nnz=g.nnz, rowptr=rowptr, col=col, max_degree=g.max_degree, isolated=g.isolated)
+
+
 def train_batches(n: int, frac: float, k: int, b: int, seed: int, device="cpu", first: int = 0) -> torch.Tensor:
     """k x b int32 seed vertices: minibatches first..first+k-1 of the seeded train split."""
     ntrain = int(math.ceil(frac * n))
@@ -193,9 +222,14 @@ SPLIT_SEED = 2
 SAMPLING_SEED = 42
 
 
-def make_workload(name: str, device="cpu") -> Tuple[Graph, torch.Tensor, dict]:
-    """(graph, batches k x b int32, workload dict) for one named workload."""
+def make_workload(name: str, device="cpu", relabel: Optional[str] = None) -> Tuple[Graph, torch.Tensor, dict]:
+    """(graph, batches k x b int32, workload dict) for one named workload.  relabel="degree": vertex ids sorted by
+    descending degree instead of the recipe's random relabelling."""
     w = WORKLOADS[name]
     g = rmat_graph(device=device, **w["graph"])
+    if relabel == "degree":
+        g = relabel_by_degree(g)
+    elif relabel is not None:
+        raise ValueError("unknown relabel %r" % relabel)
     batches = train_batches(g.n, w["frac"], w["k"], w["batch"], SPLIT_SEED, device)
     return g, batches, w

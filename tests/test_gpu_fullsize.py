@@ -42,6 +42,34 @@ def test_workload_matches_oracle(name):
             assert ((hop.mb_coloff[1:] - hop.mb_coloff[:-1]) <= w["params"][h]).all()
 
 
+@pytest.mark.parametrize("name", ["mid_sage", "large_sage"])
+def test_workload_with_ids_sorted_by_degree_matches_oracle(name):
+    """The same graphs with their vertices renumbered hubs first: the sampled ids of every minibatch crowd the low end
+    of the id range, EXTRACT falls back from segments of equal width to segments dealt by a table (built in the
+    first call, reused by the recycled ones).  Three calls: the one that finds out, the one that builds the table,
+    and steady state."""
+    from oracle import bms_oracle as O
+    from paper_2311_02909_amd import bms, synth
+    g, batches, w = synth.make_workload(name, device="cuda", relabel="degree")
+    deg = g.rowptr[1:] - g.rowptr[:-1]
+    assert bool((deg[:-1] >= deg[1:]).all())
+    csr = bms.Csr(g.rowptr, g.col)
+    rp, cl, bt = g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy()
+    ref = O.sample_nodewise(rp, cl, bt, w["params"], synth.SAMPLING_SEED)
+    res = None
+    for call in range(3):
+        res = bms.sample_nodewise(csr, batches, w["params"], synth.SAMPLING_SEED, recycle=res, profile=True)
+        assert_hops_equal(res.hops(), ref, what="%s by degree, call %d" % (name, call))
+    stages = {s for s, _, _ in res.stages()}
+    assert "dd_unsplit" in stages, "no hop of the steady-state call went through the segment kernels: %s" % sorted(stages)
+    # other batches of the same split keep using the table
+    other = synth.train_batches(g.n, w["frac"], 8, w["batch"], synth.SPLIT_SEED, "cuda", first=w["k"]) \
+        if name == "mid_sage" else None
+    if other is not None:
+        r2 = bms.sample_nodewise(csr, other, w["params"], 7)
+        assert_hops_equal(r2.hops(), O.sample_nodewise(rp, cl, other.cpu().numpy(), w["params"], 7), what="other batches")
+
+
 def test_fetch_and_aggregate_at_full_size_on_sampled_outputs():
     """The two consumer steps on the mid-size node-wise workload at its real shape (f = 100 as in Table 3),
     in the launch configuration bench.py times; checked on outputs the oracle computes one by one:
