@@ -22,6 +22,17 @@
  *   - Work is enqueued on opts->stream; a call returns after the stream has drained
  *     (it reads the output sizes back), so result pointers are immediately readable
  *     by any stream that is ordered after that point.
+ *   - With BMS_ASYNC a node-wise call that recycles a result of the same call shape (same csr, k, b,
+ *     fanouts, variant flags) returns as soon as its kernels are enqueued: the sizes, the seed check and
+ *     the device times are read when the result is first looked at -- every accessor of a result
+ *     (bms_result_info / _hop / _minibatch / _minibatch_offsets / _stage, bms_aggregate_hop) and
+ *     bms_result_wait first wait for the call's completion event and then report what the call would have
+ *     returned: BMS_ERANGE for a bad seed, BMS_EAGAIN when the kernels gave up on the input (ids crowded
+ *     into a narrow range; the result is empty, and the repeated call takes another kernel path).
+ *     Ordering rules: the next sampling call on the same bms_csr must be enqueued on the same stream (it
+ *     reuses the handle's scratch in stream order); other streams that read the result's buffers must be
+ *     ordered after the call (bms_result_wait, or an event recorded on opts->stream after the call).
+ *     Calls that do not qualify (first call of a shape, LADIES) ignore the flag and return synchronously.
  *   - A handle is not thread-safe; different handles may be used from different threads.
  *     One bms_csr must not be used by two sampling calls at the same time (it owns the
  *     scratch memory both would use).
@@ -45,6 +56,8 @@ extern "C" {
 #define BMS_EFORMAT (-3) /* CSR not monotone, row not strictly ascending, column outside [0,n)      */
 #define BMS_ENOMEM (-4)  /* device or host allocation failed, or scratch limit too small            */
 #define BMS_EHIP (-5)    /* a HIP runtime call failed                                               */
+#define BMS_EAGAIN (-6)  /* deferred result of a BMS_ASYNC call: the kernel path it had enqueued gave up on  */
+                         /* this input (see BMS_ASYNC); the result is empty, repeat the call                 */
 
 /* where the arrays handed to bms_csr_load live */
 #define BMS_HOST 0          /* host arrays, copied to the device                                    */
@@ -67,6 +80,8 @@ extern "C" {
                                /* replacement: the repeat-until-distinct step of Sec. 4.1.2 left out); a row      */
                                /* keeps the distinct picks, between 1 and min(s, degree) of them                  */
 
+#define BMS_ASYNC 512u         /* the call may return while its kernels still run on opts->stream (see below)     */
+
 typedef struct bms_csr bms_csr;       /* adjacency matrix on the device + reusable scratch            */
 typedef struct bms_result bms_result; /* owns every device buffer its hop views point to              */
 
@@ -77,6 +92,14 @@ typedef struct bms_opts {   /* zero-initialised = defaults                      
     bms_result *recycle;    /* result of an earlier call whose buffers may be reused; it becomes the  */
                             /* returned handle (its old contents are overwritten); NULL = allocate    */
     int64_t scratch_limit;  /* bytes of scratch the call may hold in the csr handle; 0 = 32 GiB        */
+    /* Device allocator for the buffers a result exposes (e.g. one that hands out a framework's cached memory).
+     * alloc returns device memory of at least `bytes` bytes, 256-byte aligned, on the current device, or NULL;
+     * dealloc takes back exactly what alloc returned.  Both NULL = hipMalloc / hipFree.  A result keeps the
+     * allocator it was created with (ctx must outlive it); a recycled result ignores these fields.  Scratch
+     * memory in the csr handle always comes from hipMalloc. */
+    void *(*alloc)(size_t bytes, void *ctx);
+    void (*dealloc)(void *ptr, void *ctx);
+    void *alloc_ctx;
 } bms_opts;
 
 /*
@@ -146,6 +169,15 @@ int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t
  */
 int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *s_per_layer,
                       int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out);
+
+/*
+ * Completion of a BMS_ASYNC call.  bms_result_wait blocks until the call that last wrote `res` has finished and
+ * returns its deferred status (BMS_OK, BMS_ERANGE, BMS_EAGAIN, BMS_EHIP); on a result that is not pending it
+ * returns BMS_OK at once.  bms_result_ready returns 1 when bms_result_wait would not block, 0 when the call is
+ * still running, BMS_EINVAL for a bad handle; it never blocks.
+ */
+int bms_result_wait(bms_result *res);
+int bms_result_ready(const bms_result *res);
 
 /* k and L of a result (either pointer may be NULL). */
 int bms_result_info(const bms_result *res, int32_t *k, int32_t *L);

@@ -18,10 +18,10 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbms.so")
 
-OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP, EAGAIN = 0, -1, -2, -3, -4, -5, -6
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
 LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT, LADIES_DENSE, PROFILE_MAIN = 1, 2, 4, 8, 16, 32, 64
-UNION_DST, NODEWISE_REPLACE = 128, 256
+UNION_DST, NODEWISE_REPLACE, ASYNC = 128, 256, 512
 NOALLOC_MAX_K = 16383
 
 
@@ -31,9 +31,38 @@ class BmsError(RuntimeError):
         self.code = code
 
 
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+DEALLOC_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+
 class _Opts(C.Structure):
     _fields_ = [("stream", C.c_void_p), ("mb_base", C.c_int32), ("flags", C.c_uint32),
-                ("recycle", C.c_void_p), ("scratch_limit", C.c_int64)]
+                ("recycle", C.c_void_p), ("scratch_limit", C.c_int64),
+                ("alloc", ALLOC_FN), ("dealloc", DEALLOC_FN), ("alloc_ctx", C.c_void_p)]
+
+
+class TorchAllocator:
+    """bms_opts.alloc / dealloc served by torch.empty: the result's buffers then live in PyTorch's caching
+    allocator.  Keep the object alive as long as any result created with it."""
+
+    def __init__(self, device="cuda"):
+        self.device = device
+        self.live = {}
+        self.calls = 0
+
+        def _alloc(nbytes, _ctx):
+            try:
+                t = torch.empty(int(nbytes), dtype=torch.uint8, device=self.device)
+            except RuntimeError:
+                return None
+            self.live[t.data_ptr()] = t
+            self.calls += 1
+            return t.data_ptr()
+
+        def _dealloc(ptr, _ctx):
+            self.live.pop(ptr, None)
+
+        self.alloc, self.dealloc = ALLOC_FN(_alloc), DEALLOC_FN(_dealloc)
 
 
 class _HopView(C.Structure):
@@ -68,6 +97,10 @@ def lib() -> C.CDLL:
             fn.restype = C.c_int
             fn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_uint64,
                            C.POINTER(_Opts), C.POINTER(C.c_void_p)]
+        L.bms_result_wait.restype = C.c_int
+        L.bms_result_wait.argtypes = [C.c_void_p]
+        L.bms_result_ready.restype = C.c_int
+        L.bms_result_ready.argtypes = [C.c_void_p]
         L.bms_result_info.restype = C.c_int
         L.bms_result_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.bms_result_hop.restype = C.c_int
@@ -220,6 +253,14 @@ class Result:
         _check(lib().bms_result_info(handle, C.byref(k), C.byref(L)))
         self.k, self.L = k.value, L.value
 
+    def wait(self):
+        """bms_result_wait: blocks until an asynchronous call has completed; raises its deferred error."""
+        _check(lib().bms_result_wait(self.handle))
+
+    def ready(self) -> bool:
+        """bms_result_ready: False while an asynchronous call still runs."""
+        return lib().bms_result_ready(self.handle) == 1
+
     def hop(self, h: int) -> Hop:
         v = _HopView()
         _check(lib().bms_result_hop(self.handle, h, C.byref(v)))
@@ -305,7 +346,8 @@ def _profile_flag(profile) -> int:
     return PROFILE if profile else 0
 
 
-def _sample(fn, csr: Csr, batches, params: Sequence[int], seed: int, mb_base, stream, recycle, flags, scratch_limit):
+def _sample(fn, csr: Csr, batches, params: Sequence[int], seed: int, mb_base, stream, recycle, flags, scratch_limit,
+            allocator=None):
     if isinstance(batches, np.ndarray):
         batches = torch.from_numpy(np.ascontiguousarray(batches, dtype=np.int32))
     if batches.dtype != torch.int32 or batches.dim() != 2:
@@ -317,38 +359,45 @@ def _sample(fn, csr: Csr, batches, params: Sequence[int], seed: int, mb_base, st
         stream = torch.cuda.current_stream().cuda_stream
     opts = _Opts(stream=stream, mb_base=mb_base, flags=flags,
                  recycle=recycle.handle if recycle is not None else None, scratch_limit=scratch_limit)
+    if allocator is not None:
+        opts.alloc, opts.dealloc = allocator.alloc, allocator.dealloc
     out = C.c_void_p()
     _check(fn(csr.handle, batches.data_ptr(), k, b, par, len(params), seed & 0xFFFFFFFFFFFFFFFF, C.byref(opts),
               C.byref(out)))
     if recycle is not None:
         recycle.k, recycle.L = k, len(params)
         return recycle
-    return Result(out)
+    r = Result(out)
+    r._allocator = allocator   # the callbacks must outlive the result
+    return r
 
 
 def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_base: int = 0, stream=None,
                     recycle: Optional[Result] = None, profile: bool = False, scratch_limit: int = 0,
-                    extract: Optional[str] = None, union_dst: bool = False, replace: bool = False) -> Result:
+                    extract: Optional[str] = None, union_dst: bool = False, replace: bool = False,
+                    allocator=None, async_: bool = False) -> Result:
     """bms_sample_nodewise: bulk GraphSAGE sampling of the k x b seed batches.
     extract: None (library's choice), "sort", "buckets" or "bitmap" -- which EXTRACT kernels run; same result.
     union_dst: BMS_UNION_DST, every frontier contains the one before it and Hop.row_self is filled.
-    replace: BMS_NODEWISE_REPLACE, independent draws per row, the distinct picks kept."""
+    replace: BMS_NODEWISE_REPLACE, independent draws per row, the distinct picks kept.
+    allocator: e.g. TorchAllocator(): where the result's buffers come from (bms_opts.alloc / dealloc).
+    async_: BMS_ASYNC, a recycled call of a remembered shape returns before its kernels have run."""
     flags = _profile_flag(profile) | {None: 0, "buckets": EXTRACT_BUCKETS, "bitmap": EXTRACT_BITMAP,
                                            "sort": EXTRACT_SORT}[extract] | (UNION_DST if union_dst else 0) | (
-        NODEWISE_REPLACE if replace else 0)
+        NODEWISE_REPLACE if replace else 0) | (ASYNC if async_ else 0)
     return _sample(lib().bms_sample_nodewise, csr, batches, fanouts, seed, mb_base, stream, recycle, flags,
-                   scratch_limit)
+                   scratch_limit, allocator)
 
 
 def sample_ladies(csr: Csr, batches, s_per_layer: Sequence[int], seed: int, *, mb_base: int = 0, squared: bool = False,
                   stream=None, recycle: Optional[Result] = None, profile: bool = False,
-                  scratch_limit: int = 0, dense: bool = False) -> Result:
+                  scratch_limit: int = 0, dense: bool = False, allocator=None) -> Result:
     """bms_sample_ladies: bulk LADIES sampling of the k x b seed batches.
 
     dense=True picks the kernel path with per-minibatch counters in HBM (same results)."""
     flags = _profile_flag(profile) | (LADIES_SQUARED if squared else 0) | (LADIES_DENSE if dense else 0)
     return _sample(lib().bms_sample_ladies, csr, batches, s_per_layer, seed, mb_base, stream, recycle, flags,
-                   scratch_limit)
+                   scratch_limit, allocator)
 
 
 def fetch_features(H: torch.Tensor, ids: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

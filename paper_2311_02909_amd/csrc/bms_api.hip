@@ -53,41 +53,56 @@ int fail(int code, const char *fmt, ...)
             return rc_;                                                                                                \
     } while (0)
 
+// Where a result's buffers come from (bms_opts.alloc / dealloc / alloc_ctx); both null = hipMalloc / hipFree
+struct Allocator {
+    void *(*alloc)(size_t, void *) = nullptr;
+    void (*dealloc)(void *, void *) = nullptr;
+    void *ctx = nullptr;
+};
+
 // Growable device buffer; contents are not preserved across growth.
 struct DevBuf {
     void *p = nullptr;
     size_t cap = 0;
     bool grew = false; // set when the last ensure() reallocated
+    const Allocator *al = nullptr; // not null: the caller's allocator (buffers a result exposes)
     DevBuf() = default;
     // a buffer that belongs to a handle enters the handle's list, which is what bms_free walks
     explicit DevBuf(std::vector<DevBuf *> *owner_list) { owner_list->push_back(this); }
     DevBuf(const DevBuf &) = delete;
     DevBuf &operator=(const DevBuf &) = delete;
-    DevBuf(DevBuf &&o) noexcept : p(o.p), cap(o.cap), grew(o.grew) { o.p = nullptr; o.cap = 0; } // hop buffers in a vector
+    DevBuf(DevBuf &&o) noexcept : p(o.p), cap(o.cap), grew(o.grew), al(o.al) { o.p = nullptr; o.cap = 0; } // hop buffers in a vector
+    void drop()
+    {
+        if (!p)
+            return;
+        if (al && al->dealloc)
+            al->dealloc(p, al->ctx);
+        else
+            (void)hipFree(p);
+        p = nullptr;
+        cap = 0;
+    }
     int ensure(size_t bytes)
     {
         grew = false;
         if (bytes <= cap && p)
             return BMS_OK;
-        if (p) {
-            (void)hipFree(p);
-            p = nullptr;
-            cap = 0;
-        }
+        drop();
         if (bytes < 256)
             bytes = 256;
-        HIP_TRY(hipMalloc(&p, bytes));
+        if (al && al->alloc) {
+            p = al->alloc(bytes, al->ctx);
+            if (!p)
+                return fail(BMS_ENOMEM, "the caller's allocator returned no memory for %zu bytes", bytes);
+        } else {
+            HIP_TRY(hipMalloc(&p, bytes));
+        }
         cap = bytes;
         grew = true;
         return BMS_OK;
     }
-    void release()
-    {
-        if (p)
-            (void)hipFree(p);
-        p = nullptr;
-        cap = 0;
-    }
+    void release() { drop(); }
     template <class T>
     T *as() const
     {
@@ -162,6 +177,22 @@ struct HopBufs {
     DevBuf rowptr, col, mb_coloff, col_vertex, p_off, p_col, p_cnt, row_self;
     DevBuf seg_tab; // node-wise EXTRACT with segments of unequal width: cell -> segment table, then the segments' first cells
     bms_hop_view view;
+    void bind(const Allocator *al) // the buffers the hop views point to come from the result's allocator
+    {
+        for (DevBuf *b : {&mb_rowoff, &row_vertex, &rowptr, &col, &mb_coloff, &col_vertex, &p_off, &p_col, &p_cnt, &row_self})
+            if (!b->p)
+                b->al = al;
+    }
+};
+
+// what a BMS_ASYNC node-wise call leaves for the first look at its result
+struct PendingNodewise {
+    bms_csr *csr = nullptr;
+    int32_t k = 0, b = 0, L = 0;
+    bool union_dst = false;
+    std::vector<int32_t> shape;
+    std::vector<uint8_t> mode;
+    std::vector<int32_t> table_built;
 };
 
 struct bms_result {
@@ -186,12 +217,21 @@ struct bms_result {
     // bms_result_minibatch and dropped when the result is written again
     std::vector<int64_t> mb_offsets;
     DevBuf mb_edge_tmp;
+    Allocator al;               // of the buffers the hop views point to
+    // BMS_ASYNC: the call has returned, its kernels may still run
+    bool pending = false;
+    hipEvent_t done_ev = nullptr;
+    int64_t *host_scalars = nullptr; // pinned, 64 values: where the call's sizes and flags arrive
+    PendingNodewise deferred;
 };
 
 namespace {
 
 void result_release(bms_result *r)
 {
+    if (r->pending && r->done_ev)
+        (void)hipEventSynchronize(r->done_ev); // its kernels still use the buffers
+    r->pending = false;
     for (auto &h : r->hops) {
         h.mb_rowoff.release();
         h.row_vertex.release();
@@ -206,6 +246,12 @@ void result_release(bms_result *r)
         h.seg_tab.release();
     }
     r->mb_edge_tmp.release();
+    if (r->done_ev)
+        (void)hipEventDestroy(r->done_ev);
+    r->done_ev = nullptr;
+    if (r->host_scalars)
+        (void)hipHostFree(r->host_scalars);
+    r->host_scalars = nullptr;
     for (auto e : r->event_pool)
         (void)hipEventDestroy(e);
     r->event_pool.clear();
@@ -327,12 +373,14 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
     if (opts) {
-        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN | BMS_UNION_DST | BMS_NODEWISE_REPLACE))
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN | BMS_UNION_DST | BMS_NODEWISE_REPLACE | BMS_ASYNC))
             return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
         if (opts->recycle && opts->recycle->tag != kTagResult)
             return fail(BMS_EINVAL, "opts->recycle is not a result handle");
         if (opts->scratch_limit < 0)
             return fail(BMS_EINVAL, "negative scratch_limit");
+        if ((opts->alloc == nullptr) != (opts->dealloc == nullptr))
+            return fail(BMS_EINVAL, "bms_opts.alloc and bms_opts.dealloc must be given together");
     }
     return BMS_OK;
 }
@@ -370,6 +418,8 @@ int setup_vset(CallCtx &c)
     return BMS_OK;
 }
 
+int settle_result(bms_result *res);
+
 int begin_call(CallCtx &c, bms_csr *csr, int32_t k, int32_t b, int32_t L, uint64_t seed, const bms_opts *opts)
 {
     c.csr = csr;
@@ -389,14 +439,23 @@ int begin_call(CallCtx &c, bms_csr *csr, int32_t k, int32_t b, int32_t L, uint64
         c.res = new (std::nothrow) bms_result();
         if (!c.res)
             return fail(BMS_ENOMEM, "host allocation failed");
+        if (opts) {
+            c.res->al.alloc = opts->alloc;
+            c.res->al.dealloc = opts->dealloc;
+            c.res->al.ctx = opts->alloc_ctx;
+        }
     } else {
         c.res = opts->recycle;
+        if (c.res->pending)
+            (void)settle_result(c.res); // the call before this one: its status belongs to a result nobody looked at
     }
     c.res->k = k;
     c.res->L = L;
     c.res->device = csr->device;
     if ((int32_t)c.res->hops.size() < L)
         c.res->hops.resize(L);
+    for (auto &hb : c.res->hops)
+        hb.bind(&c.res->al);
     c.res->stages.clear();
     c.res->events_used = 0;
     c.res->mb_offsets.clear();
@@ -421,6 +480,7 @@ int abort_call(CallCtx &c, int rc)
         c.res->k = 0;
         c.res->hint_csr = nullptr;
         c.res->mb_offsets.clear();
+        c.res->stages.clear();
     }
     c.res = nullptr;
     return rc;
@@ -473,6 +533,81 @@ inline int64_t *slot(CallCtx &c, int32_t hop, int which) { return c.csr->scalars
 inline int64_t host_slot(CallCtx &c, int32_t hop, int which) { return c.csr->host_pinned[hop * 4 + which]; }
 
 constexpr int32_t kMaxHops = 15; // 4 scalar slots per hop in a 64-entry block
+
+// The end of a node-wise call, once its sizes and flags are on the host: deferred seed errors, hops whose EXTRACT
+// gave up (*redo), the views' sizes, what the result remembers for the next call of this shape, the stage times.
+int finish_nodewise(bms_result *res, const PendingNodewise &pn, const int64_t *host, bool check_seeds, uint32_t *redo)
+{
+    if (check_seeds) {
+        const int32_t flag = (int32_t)(host[63] & 0xFFFFFFFF);
+        if (flag & 1)
+            return fail(BMS_ERANGE, "a seed vertex lies outside [0, %lld)", (long long)pn.csr->n);
+        if (flag & 2)
+            return fail(BMS_ERANGE, "a seed vertex is repeated inside one minibatch");
+    }
+    for (int32_t h = 0; h < pn.L; ++h)
+        if (host[h * 4 + 2] & 0xFFFFFFFFLL)
+            *redo |= 1u << h;
+    if (*redo)
+        return BMS_OK; // the call is repeated
+    std::vector<int64_t> seen_nnz((size_t)pn.L, 0);
+    for (int32_t h = 0; h < pn.L; ++h) {
+        bms_hop_view &v = res->hops[h].view;
+        v.nnz = host[h * 4 + 0];
+        v.ncols = host[h * 4 + 1];
+        v.rows = h == 0 ? (int64_t)pn.k * pn.b : host[(h - 1) * 4 + 1];
+        seen_nnz[h] = v.nnz + (pn.union_dst ? v.rows : 0); // the entries EXTRACT worked on
+    }
+    res->hint_csr = pn.csr;
+    res->hint_shape = pn.shape;
+    res->hint_nnz = seen_nnz;
+    res->hint_mode = pn.mode;
+    res->hint_table_C = pn.table_built;
+    res->hint_table_ready.assign((size_t)pn.L, 0);
+    for (int32_t h = 0; h < pn.L; ++h)
+        res->hint_table_ready[h] = pn.table_built[h] > 0 ? 1 : 0;
+    for (auto &st : res->stages)
+        HIP_TRY(hipEventElapsedTime(&st.ms, st.t0, st.t1));
+    return BMS_OK;
+}
+
+void empty_result(bms_result *r, bool keep_hints)
+{
+    for (auto &h : r->hops)
+        h.view = bms_hop_view{};
+    r->L = 0;
+    r->k = 0;
+    if (!keep_hints)
+        r->hint_csr = nullptr;
+    r->mb_offsets.clear();
+}
+
+// First look at the result of a BMS_ASYNC call: waits for it and returns what the call would have returned.
+int settle_result(bms_result *res)
+{
+    if (!res->pending)
+        return BMS_OK;
+    res->pending = false;
+    HIP_TRY(hipSetDevice(res->device));
+    HIP_TRY(hipEventSynchronize(res->done_ev));
+    uint32_t redo = 0;
+    const int rc = finish_nodewise(res, res->deferred, res->host_scalars, true, &redo);
+    if (rc != BMS_OK) {
+        empty_result(res, false);
+        return rc;
+    }
+    if (redo) {
+        // the next call of this shape starts with the kernel path after the one that gave up
+        if ((int32_t)res->hint_mode.size() == res->deferred.L)
+            for (int32_t h = 0; h < res->deferred.L; ++h)
+                if ((redo >> h) & 1u)
+                    res->hint_mode[h] = (uint8_t)std::min<int>(res->hint_mode[h] + 1, 2);
+        empty_result(res, true);
+        return fail(BMS_EAGAIN, "the asynchronous call's EXTRACT gave up on this input (sampled ids crowd a narrow id range): "
+                                "repeat the call");
+    }
+    return BMS_OK;
+}
 
 // what a recycled result remembers a call by
 std::vector<int32_t> nodewise_shape(const CallCtx &c, const int32_t *fanouts)
@@ -543,7 +678,6 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
         }
         no_wait = total < (double)c.scratch_limit;
     }
-    std::vector<int64_t> seen_nnz((size_t)c.L, 0);
 
     for (int32_t h = 0; h < c.L; ++h) {
         HopBufs &hb = c.res->hops[h];
@@ -605,7 +739,6 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
             if (h == 0)
                 BMS_TRY(seed_flag_error(c));
             nnz = nnz_tune = host_slot(c, h, 0);
-            seen_nnz[h] = nnz;
         }
         const int64_t ncols_bound = std::min<int64_t>(nnz, (int64_t)c.k * csr->n);
         BMS_TRY(hb.col.ensure((size_t)std::max<int64_t>(nnz, 1) * sizeof(int32_t)));
@@ -785,32 +918,32 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
         mb_rowoff = hb.mb_coloff.as<int64_t>();
         rows_bound = ncols_bound;
     }
-    BMS_TRY(read_scalars(c));
-    if (no_wait)
-        BMS_TRY(seed_flag_error(c));
-    csr->segcnt_clean = true; // every hop's kernels have run: the counters are back to zero
-    for (int32_t h = 0; h < c.L; ++h)
-        if (buckets && (host_slot(c, h, 2) & 0xFFFFFFFFLL))
-            *redo |= 1u << h;
-    if (*redo)
-        return BMS_OK; // the caller repeats the call
-    for (int32_t h = 0; h < c.L; ++h) {
-        bms_hop_view &v = c.res->hops[h].view;
-        v.nnz = host_slot(c, h, 0);
-        v.ncols = host_slot(c, h, 1);
-        v.rows = h == 0 ? (int64_t)c.k * c.b : host_slot(c, h - 1, 1);
-        seen_nnz[h] = v.nnz + (union_dst ? v.rows : 0); // the entries EXTRACT worked on
+    csr->segcnt_clean = true; // every hop's kernels are enqueued: they leave the counters at zero again
+    PendingNodewise pn;
+    pn.csr = csr;
+    pn.k = c.k;
+    pn.b = c.b;
+    pn.L = c.L;
+    pn.union_dst = union_dst;
+    pn.shape = shape;
+    pn.mode = mode;
+    pn.table_built = table_built;
+    if ((c.flags & BMS_ASYNC) && no_wait && seeds_by_sort) {
+        // steady state, asynchronous: the sizes and flags travel to pinned memory of the result behind the kernels,
+        // an event marks their arrival, and the first look at the result does what follows below
+        if (!c.res->host_scalars)
+            HIP_TRY(hipHostMalloc((void **)&c.res->host_scalars, 64 * sizeof(int64_t), hipHostMallocDefault));
+        if (!c.res->done_ev)
+            HIP_TRY(hipEventCreateWithFlags(&c.res->done_ev, hipEventDisableTiming));
+        HIP_TRY(hipMemcpyAsync(c.res->host_scalars, csr->scalars.p, 64 * sizeof(int64_t), hipMemcpyDeviceToHost, c.stream));
+        HIP_TRY(hipEventRecord(c.res->done_ev, c.stream));
+        c.res->deferred = std::move(pn);
+        c.res->pending = true;
+        return BMS_OK;
     }
-    c.res->hint_csr = csr;
-    c.res->hint_shape = shape;
-    c.res->hint_nnz = seen_nnz;
-    c.res->hint_mode = mode;
-    c.res->hint_table_C = table_built;
-    c.res->hint_table_ready.assign((size_t)c.L, 0);
-    for (int32_t h = 0; h < c.L; ++h)
-        c.res->hint_table_ready[h] = table_built[h] > 0 ? 1 : 0;
-    BMS_TRY(prof.finish());
-    if (!buckets || !seeds_by_sort)
+    BMS_TRY(read_scalars(c));
+    BMS_TRY(finish_nodewise(c.res, pn, csr->host_pinned, no_wait, redo));
+    if (!*redo && (!buckets || !seeds_by_sort))
         csr->vs_clean = true;
     return BMS_OK;
 }
@@ -1319,10 +1452,32 @@ int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b
     return BMS_OK;
 }
 
+int bms_result_wait(bms_result *res)
+{
+    if (!res || res->tag != kTagResult)
+        return fail(BMS_EINVAL, "not a result handle");
+    return settle_result(res);
+}
+
+int bms_result_ready(const bms_result *res)
+{
+    if (!res || res->tag != kTagResult)
+        return fail(BMS_EINVAL, "not a result handle");
+    if (!res->pending)
+        return 1;
+    const hipError_t e = hipEventQuery(res->done_ev);
+    if (e == hipErrorNotReady) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return 1;
+}
+
 int bms_result_info(const bms_result *res, int32_t *k, int32_t *L)
 {
     if (!res || res->tag != kTagResult)
         return fail(BMS_EINVAL, "not a result handle");
+    BMS_TRY(settle_result(const_cast<bms_result *>(res)));
     if (k)
         *k = res->k;
     if (L)
@@ -1334,6 +1489,7 @@ int bms_result_hop(const bms_result *res, int32_t hop, bms_hop_view *view)
 {
     if (!res || res->tag != kTagResult || !view)
         return fail(BMS_EINVAL, "not a result handle, or null view");
+    BMS_TRY(settle_result(const_cast<bms_result *>(res)));
     if (hop < 0 || hop >= res->L)
         return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
     *view = res->hops[hop].view;
@@ -1344,6 +1500,7 @@ int bms_result_minibatch(bms_result *res, int32_t hop, int32_t i, bms_mb_view *v
 {
     if (!res || res->tag != kTagResult || !view)
         return fail(BMS_EINVAL, "not a result handle, or null view");
+    BMS_TRY(settle_result(res));
     if (hop < 0 || hop >= res->L)
         return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
     if (i < 0 || i >= res->k)
@@ -1386,6 +1543,7 @@ int bms_result_minibatch_offsets(const bms_result *res, int32_t hop, int64_t *ro
 {
     if (!res || res->tag != kTagResult || !row_off || !edge_off || !col_off)
         return fail(BMS_EINVAL, "not a result handle, or null output array");
+    BMS_TRY(settle_result(const_cast<bms_result *>(res)));
     if (hop < 0 || hop >= res->L)
         return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
     if (res->k > kNoAllocMaxK)
@@ -1413,6 +1571,7 @@ int bms_result_stage(const bms_result *res, int32_t idx, const char **name, int3
 {
     if (!res || res->tag != kTagResult)
         return fail(BMS_EINVAL, "not a result handle");
+    BMS_TRY(settle_result(const_cast<bms_result *>(res)));
     if (idx < 0 || idx >= (int32_t)res->stages.size())
         return BMS_EINVAL; // past the end: not an error worth a message
     const StageTime &st = res->stages[idx];
@@ -1495,6 +1654,7 @@ int bms_aggregate_hop(const bms_result *res, int32_t hop, const float *X, int32_
 {
     if (!res || res->tag != kTagResult)
         return fail(BMS_EINVAL, "not a result handle");
+    BMS_TRY(settle_result(const_cast<bms_result *>(res)));
     if (hop < 0 || hop >= res->L)
         return fail(BMS_EINVAL, "hop %d outside [0, %d)", hop, res->L);
     if (f < 1)
@@ -1532,6 +1692,7 @@ const char *bms_strerror(int code)
     case BMS_EFORMAT: return "malformed CSR matrix";
     case BMS_ENOMEM: return "out of memory or scratch limit too small";
     case BMS_EHIP: return "HIP runtime error";
+    case BMS_EAGAIN: return "the asynchronous call gave up on its kernel path: repeat the call";
     default: return "unknown error code";
     }
 }
