@@ -80,6 +80,8 @@ extern "C" {
                                /* replacement: the repeat-until-distinct step of Sec. 4.1.2 left out); a row      */
                                /* keeps the distinct picks, between 1 and min(s, degree) of them                  */
 
+#define BMS_LADIES_NO_INDEX 1024u /* LADIES by LDS windows: do not build or use the per-graph index of where adjacency */
+                               /* lists cross the window boundaries (see bms_sample_ladies); same results           */
 #define BMS_ASYNC 512u         /* the call may return while its kernels still run on opts->stream (see below)     */
 
 typedef struct bms_csr bms_csr;       /* adjacency matrix on the device + reusable scratch            */
@@ -166,6 +168,10 @@ int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t
  * frontier (p_cnt = number of frontier vertices adjacent to the column), s_per_layer[h] draws by ITS
  * with replacement over the integer weights, duplicates removed (so ncols per minibatch <= s), then
  * the frontier's rows restricted to the sampled columns (Q_R A Q_C, Sec. 4.2.3).
+ * The first call on a csr handle may build an index of the graph (for every vertex, where its sorted adjacency list
+ * crosses the multiples of 2^16 in vertex id) and keep it in the handle until bms_free: n * (ceil(n / 2^16) + 1)
+ * 32-bit words, built only when that is at most twice the size of the column array and a quarter of
+ * opts->scratch_limit.  That call also waits for the stream once.  BMS_LADIES_NO_INDEX: neither build nor use it.
  */
 int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *s_per_layer,
                       int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out);

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libbms.so")
 OK, EINVAL, ERANGE, EFORMAT, ENOMEM, EHIP, EAGAIN = 0, -1, -2, -3, -4, -5, -6
 HOST, DEVICE_BORROW, DEVICE_COPY = 0, 1, 2
 LADIES_SQUARED, PROFILE, EXTRACT_BUCKETS, EXTRACT_BITMAP, EXTRACT_SORT, LADIES_DENSE, PROFILE_MAIN = 1, 2, 4, 8, 16, 32, 64
-UNION_DST, NODEWISE_REPLACE, ASYNC = 128, 256, 512
+UNION_DST, NODEWISE_REPLACE, ASYNC, LADIES_NO_INDEX = 128, 256, 512, 1024
 NOALLOC_MAX_K = 16383
 
 
@@ -391,11 +391,11 @@ def sample_nodewise(csr: Csr, batches, fanouts: Sequence[int], seed: int, *, mb_
 
 def sample_ladies(csr: Csr, batches, s_per_layer: Sequence[int], seed: int, *, mb_base: int = 0, squared: bool = False,
                   stream=None, recycle: Optional[Result] = None, profile: bool = False,
-                  scratch_limit: int = 0, dense: bool = False, allocator=None) -> Result:
-    """bms_sample_ladies: bulk LADIES sampling of the k x b seed batches.
+                  scratch_limit: int = 0, dense: bool = False, allocator=None, index: bool = True) -> Result:
+    """bms_sample_ladies: bulk LADIES sampling of the k x b seed batches.  index=False: BMS_LADIES_NO_INDEX.
 
     dense=True picks the kernel path with per-minibatch counters in HBM (same results)."""
-    flags = _profile_flag(profile) | (LADIES_SQUARED if squared else 0) | (LADIES_DENSE if dense else 0)
+    flags = _profile_flag(profile) | (LADIES_SQUARED if squared else 0) | (LADIES_DENSE if dense else 0) | (0 if index else LADIES_NO_INDEX)
     return _sample(lib().bms_sample_ladies, csr, batches, s_per_layer, seed, mb_base, stream, recycle, flags,
                    scratch_limit, allocator)
 

@@ -167,6 +167,9 @@ struct bms_csr {
     BMS_BUF(row_cnt);                    // BMS_NODEWISE_REPLACE with a fanout above 32: distinct picks per row
     BMS_BUF(lw_bounds); BMS_BUF(lw_win); BMS_BUF(lw_tmpcol); BMS_BUF(lw_tmpcnt); BMS_BUF(lw_sel); BMS_BUF(lw_xtmp);
     BMS_BUF(lw_count); BMS_BUF(lw_tiles); BMS_BUF(lw_rowcnt); // LADIES by LDS windows
+    BMS_BUF(lw_index);           // where every vertex's adjacency list crosses the window boundaries: n * (nwin + 1)
+    bool lw_index_ready = false; // built by the first layer-wise call that finds room for it
+    bool lw_index_tried = false;
 #undef BMS_BUF
     bool ld_clean = false; // all dense counters zero
     int64_t *host_pinned = nullptr; // 64 int64
@@ -373,7 +376,7 @@ int check_common(const bms_csr *csr, const int32_t *batches, int32_t k, int32_t 
         if (params[h] < 1)
             return fail(BMS_EINVAL, "sampling parameter of hop %d is %d, must be >= 1", h, params[h]);
     if (opts) {
-        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN | BMS_UNION_DST | BMS_NODEWISE_REPLACE | BMS_ASYNC))
+        if (opts->flags & ~(BMS_LADIES_SQUARED | BMS_PROFILE | BMS_EXTRACT_BUCKETS | BMS_EXTRACT_BITMAP | BMS_EXTRACT_SORT | BMS_LADIES_DENSE | BMS_PROFILE_MAIN | BMS_UNION_DST | BMS_NODEWISE_REPLACE | BMS_ASYNC | BMS_LADIES_NO_INDEX))
             return fail(BMS_EINVAL, "unknown flag bits 0x%x", opts->flags);
         if (opts->recycle && opts->recycle->tag != kTagResult)
             return fail(BMS_EINVAL, "opts->recycle is not a result handle");
@@ -982,6 +985,48 @@ bool ladies_windows_apply(const CallCtx &c, const int32_t *s_per_layer)
     return true;
 }
 
+// The window boundaries of every vertex's adjacency list, once per graph: the boundary pass of a hop whose one
+// minibatch has all n vertices as rows.  Built when the lists take no more room than twice the adjacency's
+// column array and a quarter of the scratch limit; a call that cannot build it computes its rows' lists itself.
+int build_window_index(CallCtx &c, int32_t nwin)
+{
+    bms_csr *csr = c.csr;
+    csr->lw_index_tried = true;
+    const size_t ibytes = (size_t)csr->n * (size_t)(nwin + 1) * sizeof(uint32_t);
+    if (csr->n == 0 || csr->nnz == 0 || ibytes > 2 * (size_t)csr->nnz * sizeof(int32_t) ||
+        (int64_t)ibytes > c.scratch_limit / 4)
+        return BMS_OK;
+    if (csr->lw_index.ensure(ibytes) != BMS_OK) {
+        (void)hipGetLastError(); // no room: the hops go without
+        return BMS_OK;
+    }
+    LwHop g{};
+    g.A_rowptr = csr->rowptr;
+    g.A_col = csr->col;
+    g.n = csr->n;
+    g.k = 1;
+    g.nwin = nwin;
+    g.tile = kLwTileMax;
+    g.tiles_bound = csr->nnz / g.tile + 1;
+    BMS_TRY(csr->lw_tiles.ensure((size_t)g.tiles_bound * (sizeof(int64_t) + sizeof(uint32_t)) + 64));
+    int64_t *small = csr->lw_count.as<int64_t>(); // at least 8 words
+    launch_iota_offsets(c.launch, small, 1, csr->n); // the one minibatch: rows 0 .. n
+    g.mb_rowoff = small;
+    g.mb_goff = small + 2;
+    g.mb_gtileoff = small + 4;
+    g.rows_bound = csr->n;
+    g.gather_off = csr->rowptr; // the gathered order of all rows is the adjacency itself
+    g.row_beg = csr->rowptr;
+    g.tile_row = csr->lw_tiles.as<int64_t>();
+    g.bounds = csr->lw_index.as<uint32_t>();
+    HIP_TRY(hipMemsetAsync(g.bounds, 0, ibytes, c.stream)); // vertices without neighbours get no list
+    launch_ldw_index(c.launch, g);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(c.stream)); // later calls may come on other streams
+    csr->lw_index_ready = true;
+    return BMS_OK;
+}
+
 int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t *s_per_layer)
 {
     bms_csr *csr = c.csr;
@@ -991,6 +1036,10 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
     const size_t nw = (size_t)c.k * nwin;
     BMS_TRY(csr->lw_win.ensure(nw * (sizeof(uint32_t) + 4 * sizeof(int64_t)) + 64));
     BMS_TRY(csr->lw_count.ensure((4 * (size_t)c.k + 4) * sizeof(int64_t)));
+    if (!csr->lw_index_tried && !(c.flags & BMS_LADIES_NO_INDEX))
+        BMS_TRY(build_window_index(c, nwin));
+    const uint32_t *index = csr->lw_index_ready && !(c.flags & BMS_LADIES_NO_INDEX) ? csr->lw_index.as<uint32_t>() : nullptr;
+    const size_t blists = index ? 1 : 2; // boundary lists held per hop: window-major only, or row-major as well
     BMS_TRY(stage_seeds(c, batches, prof, false));
 
     int64_t rows_bound = (int64_t)c.k * c.b;
@@ -1002,14 +1051,14 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         const int32_t s = s_per_layer[h];
         const int64_t ncols_bound = (int64_t)c.k * std::min<int64_t>(s, n1);
         const size_t bbytes = (size_t)(nwin + 1) * (size_t)rows_bound * sizeof(uint32_t);
-        if ((int64_t)(2 * bbytes) > c.scratch_limit)
+        if ((int64_t)(blists * bbytes) > c.scratch_limit)
             return fail(BMS_ENOMEM, "window boundaries of %lld rows need %zu bytes of scratch, limit is %lld: raise "
                                     "bms_opts.scratch_limit or sample fewer minibatches per call",
-                        (long long)rows_bound, 2 * bbytes, (long long)c.scratch_limit);
+                        (long long)rows_bound, blists * bbytes, (long long)c.scratch_limit);
         BMS_TRY(csr->row_beg.ensure((size_t)rows_bound * sizeof(int64_t)));
         BMS_TRY(csr->ld_gather_off.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
         BMS_TRY(csr->ld_row_mb.ensure((size_t)rows_bound * sizeof(int32_t)));
-        BMS_TRY(csr->lw_bounds.ensure(2 * bbytes));
+        BMS_TRY(csr->lw_bounds.ensure(blists * bbytes));
         BMS_TRY(csr->lw_sel.ensure((size_t)c.k * (size_t)s * sizeof(int32_t)));
         BMS_TRY(hb.rowptr.ensure((size_t)(rows_bound + 1) * sizeof(int64_t)));
         BMS_TRY(hb.mb_coloff.ensure(((size_t)c.k + 1) * sizeof(int64_t)));
@@ -1046,8 +1095,9 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         w.row_beg = a.row_beg;
         w.gather_off = a.gather_off;
         w.nwin = nwin;
-        w.bounds = csr->lw_bounds.as<uint32_t>();
-        w.bounds_t = w.bounds + (size_t)(nwin + 1) * (size_t)rows_bound;
+        w.index = index;
+        w.bounds = index ? nullptr : csr->lw_bounds.as<uint32_t>() + (size_t)(nwin + 1) * (size_t)rows_bound;
+        w.bounds_t = csr->lw_bounds.as<uint32_t>();
         w.win_wt = csr->lw_win.as<uint64_t>();
         w.win_woff = w.win_wt + nw;
         w.win_base = reinterpret_cast<int64_t *>(w.win_woff + nw);
@@ -1075,10 +1125,10 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         const int64_t D = host_slot(c, h, 3);
         const int64_t tmp_cap = std::max<int64_t>(std::min<int64_t>(D, (int64_t)c.k * n1), 1);
         const size_t tbytes = (size_t)tmp_cap * 8 + (size_t)std::max<int64_t>(D, 1) * 4;
-        if ((int64_t)(tbytes + 2 * bbytes) > c.scratch_limit)
+        if ((int64_t)(tbytes + blists * bbytes) > c.scratch_limit)
             return fail(BMS_ENOMEM, "%lld gathered neighbours need %zu bytes of scratch, limit is %lld: raise "
                                     "bms_opts.scratch_limit or sample fewer minibatches per call",
-                        (long long)D, tbytes + 2 * bbytes, (long long)c.scratch_limit);
+                        (long long)D, tbytes + blists * bbytes, (long long)c.scratch_limit);
         BMS_TRY(csr->lw_tmpcol.ensure((size_t)tmp_cap * sizeof(int32_t)));
         BMS_TRY(csr->lw_tmpcnt.ensure((size_t)tmp_cap * sizeof(uint32_t)));
         BMS_TRY(csr->lw_xtmp.ensure((size_t)std::max<int64_t>(D, 1) * sizeof(int32_t)));

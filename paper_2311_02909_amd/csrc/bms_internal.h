@@ -253,6 +253,7 @@ struct LwHop {
     unsigned long long *tile_queue; // k+1 counters, zeroed per hop: next tile of each minibatch (extraction), of the hop (boundaries)
     int32_t nwin;              // ceil(n / 2^kWinShift)
     uint32_t *bounds;          // rows_bound * (nwin+1), one list per row
+    const uint32_t *index;     // n * (nwin+1): the list of every vertex's whole row, built once per graph; or null
     uint32_t *bounds_t;        // (nwin+1) * rows_bound, the same window-major
     uint32_t *win_cnt;         // k * nwin: columns of P inside the window
     uint64_t *win_wt;          // k * nwin: their weight
@@ -274,7 +275,8 @@ struct LwHop {
     int64_t *out_rowptr;       // rows+1
     int32_t *out_col;
 };
-void launch_ldw_bounds(const Launch &, const LwHop &);
+void launch_ldw_bounds(const Launch &, const LwHop &); // with an index: the rows' lists are copied from it
+void launch_ldw_index(const Launch &, const LwHop &);  // boundary lists of the rows of a hop that is the whole graph
 int launch_ldw_accumulate(const Launch &, const LwHop &); // also scans the windows; -1: launch refused
 void launch_ldw_p_copy(const Launch &, const LwHop &);
 void launch_ldw_draw(const Launch &, const LwHop &);

@@ -9,7 +9,9 @@
 //                   row each tile starts in
 //   ldw_bounds      one wave per tile streams its pieces of rows once and records where every
 //                   row crosses every window boundary (lower bounds, one list per row; a transpose then makes
-//                   them window-major for the next kernel)
+//                   them window-major for the next kernel).  A row's list depends on its vertex alone: when
+//                   the lists of all n vertices fit in memory they are computed once per graph by this same
+//                   kernel (the "hop" being the whole graph) and a hop only copies the lists of its rows
 //   ldw_accumulate  one workgroup per (minibatch, window): 2^16 packed 16-bit counters in LDS
 //                   (128 KB); every row's piece of the window adds 1 per neighbour (e_v cannot
 //                   exceed the number of frontier rows, which this path keeps below 2^16); the
@@ -40,7 +42,13 @@ constexpr int kWaveWords = kWinWords / kAccWaves; // counter words compacted by 
 constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;
 constexpr int kExtThreads = 1024; // the waves of a workgroup share one hash table
 constexpr int kExtWaves = kExtThreads / kWave;
-constexpr int kAccUnroll = 16;
+constexpr int kAccUnroll = 8;              // 16-byte loads per lane in flight while a wave gathers
+constexpr int kAccLines = 8 * kAccUnroll;  // memory lines per span: 8 lanes per line
+static_assert(kAccLines == 64, "the piece starts of a span are one 64-bit mask");
+struct AccPiece {                          // one nonempty piece of a wave's 64 rows
+    int64_t origin;                        // byte address of its first line - 128 * lines of the wave before it
+    uint32_t lo_rel, hi_rel;               // its bytes, relative to origin
+};
 constexpr int kStreamUnroll = 8; // neighbours per lane in flight in the two streaming passes
 constexpr int kHashSlots = 2 * kMaxWinSampled;    // load factor <= 1/2
 
@@ -158,21 +166,27 @@ __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
 }
 
 // The boundary lists turned window-major (bounds_t[w * rows_bound + r]): the accumulation reads one window of
-// all rows at a time.  64 x 64 tiles through LDS, both sides coalesced.
+// all rows at a time.  64 x 64 tiles through LDS, both sides coalesced.  The list of row r comes from this
+// hop's boundary pass, or, when the graph carries an index of every vertex's list, from the index entry of
+// the row's vertex.
 __global__ __launch_bounds__(256) void ldw_bounds_transpose_kernel(LwHop a)
 {
     __shared__ uint32_t tile[64][65];
     const int64_t ncols = a.nwin + 1;
-    const int64_t tiles_c = (ncols + 63) / 64, tiles_r = (a.rows_bound + 63) / 64;
+    const int64_t nrows = a.index ? a.mb_rowoff[a.k] : a.rows_bound;
+    const int64_t tiles_c = (ncols + 63) / 64, tiles_r = (nrows + 63) / 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int64_t t = blockIdx.x; t < tiles_c * tiles_r; t += gridDim.x) {
         const int64_t r0 = (t / tiles_c) * 64, c0 = (t % tiles_c) * 64;
         for (int y = ty; y < 64; y += 4)
-            if (r0 + y < a.rows_bound && c0 + tx < ncols)
-                tile[y][tx] = a.bounds[(r0 + y) * ncols + c0 + tx];
+            if (r0 + y < nrows && c0 + tx < ncols) {
+                const uint32_t *__restrict__ src =
+                    a.index ? a.index + (int64_t)a.row_vertex[r0 + y] * ncols : a.bounds + (r0 + y) * ncols;
+                tile[y][tx] = src[c0 + tx];
+            }
         __syncthreads();
         for (int y = ty; y < 64; y += 4)
-            if (c0 + y < ncols && r0 + tx < a.rows_bound)
+            if (c0 + y < ncols && r0 + tx < nrows)
                 a.bounds_t[(c0 + y) * a.rows_bound + r0 + tx] = tile[tx][y];
         __syncthreads();
     }
@@ -189,10 +203,12 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
     uint32_t *wave_nz = lds + kWinWords + 2 * kAccWaves;               // kAccWaves
     uint64_t *base_s = reinterpret_cast<uint64_t *>(lds + kWinWords + 3 * kAccWaves); // 1
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    // per wave: address origins of its nonempty pieces (64) and the start bits of one span of positions
-    int64_t *origin_of = reinterpret_cast<int64_t *>(lds + kWinWords + 3 * kAccWaves + 4) + wave * (kWave + kAccUnroll);
-    uint64_t *starts = reinterpret_cast<uint64_t *>(origin_of + kWave);
-    const uint64_t below = (1ull << lane) - 1ull, below_incl = below | (1ull << lane);
+    // per wave: one record per nonempty piece (by rank) and the start bits of one span of memory lines
+    AccPiece *piece_rec = reinterpret_cast<AccPiece *>(lds + kWinWords + 3 * kAccWaves + 4) + wave * (kWave + 1);
+    uint32_t *starts = reinterpret_cast<uint32_t *>(piece_rec + kWave);
+    const uint64_t below = (1ull << lane) - 1ull;
+    const int octet = lane >> 3, chunk = lane & 7;
+    const int64_t A0 = (int64_t)reinterpret_cast<uintptr_t>(a.A_col);
     const int64_t nblk = (int64_t)a.k * a.nwin;
     // the counters start at zero and every (minibatch, window) leaves them at zero: the pass that emits the
     // nonzero ones clears them
@@ -236,43 +252,71 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         for (int64_t base = r0 + (int64_t)wave * kWave; base < r1; base += (int64_t)kAccWaves * kWave) {
             // the next 64 pieces are on their way while these are walked
             piece_of(base + (int64_t)kAccWaves * kWave + lane, next_len, next_addr);
-            // the 64 pieces of the wave laid end to end: lane f of a step takes position f of that order.
-            // Which piece that is follows from counting piece starts up to f: the starts inside the
-            // current span of positions are bits in LDS, the address origins of the nonempty pieces a
-            // small table in LDS indexed by their rank
-            const uint32_t inc = wave_inclusive_scan(len);
+            // A piece is read as the 128-byte memory lines it touches, every line by exactly one instruction: 8 lanes
+            // take a line, 16 aligned bytes each, so an instruction covers 8 lines and never shares a line with
+            // another instruction of the wave (a second access to a line whose fill is still on its way holds the
+            // cache's pipeline up for about the latency of the fill).  The lines of the wave's 64 pieces are
+            // numbered end to end; which piece a line belongs to follows from counting piece starts up to it:
+            // the starts inside the current span of 64 lines are bits in LDS, the pieces' records a small
+            // table in LDS indexed by their rank among the nonempty ones.  Entries of a line outside the piece
+            // (the neighbouring windows' or rows') are masked; an aligned 16-byte read that holds at least one
+            // entry of the piece stays inside that entry's page.
+            const int64_t lo_byte = A0 + addr * 4, hi_byte = lo_byte + (int64_t)len * 4;
+            const int64_t line0 = lo_byte & ~(int64_t)127;
+            const uint32_t nl = len ? (uint32_t)((hi_byte - 1 - line0) >> 7) + 1u : 0u;
+            const uint32_t inc = wave_inclusive_scan(nl);
             const uint32_t total = __shfl(inc, kWave - 1, kWave);
-            const uint32_t start = inc - len;
-            const bool nonempty = len != 0;
+            const uint32_t ustart = inc - nl;
+            const bool nonempty = nl != 0;
             const uint64_t ne_mask = __ballot(nonempty);
             __builtin_amdgcn_wave_barrier();
-            if (nonempty) // address of the piece's first neighbour - its position
-                origin_of[__popcll(ne_mask & below)] = addr - (int64_t)start;
-            for (uint32_t f0 = 0; f0 < total; f0 += kAccUnroll * kWave) {
+            if (nonempty) {
+                AccPiece rec;
+                rec.origin = line0 - (int64_t)ustart * 128; // line j of the wave's order starts at origin + 128 j
+                rec.lo_rel = (uint32_t)(lo_byte - rec.origin);
+                rec.hi_rel = (uint32_t)(hi_byte - rec.origin);
+                piece_rec[__popcll(ne_mask & below)] = rec;
+            }
+            for (uint32_t u0 = 0; u0 < total; u0 += kAccLines) {
                 __builtin_amdgcn_wave_barrier();
-                if (lane < kAccUnroll)
+                if (lane < 2)
                     starts[lane] = 0;
                 __builtin_amdgcn_wave_barrier();
-                const uint32_t rel = start - f0; // wraps for pieces that start before the span
-                if (nonempty && rel < (uint32_t)(kAccUnroll * kWave))
-                    atomicOr(reinterpret_cast<uint32_t *>(starts) + (rel >> 5), 1u << (rel & 31u));
+                const uint32_t rel = ustart - u0; // wraps for pieces that start before the span
+                if (nonempty && rel < (uint32_t)kAccLines)
+                    atomicOr(starts + (rel >> 5), 1u << (rel & 31u));
                 __builtin_amdgcn_wave_barrier();
-                int rank = __popcll(__ballot(nonempty && start < f0)) - 1; // piece that holds position f0 - 1
-                uint32_t v[kAccUnroll];
+                const uint64_t m = (uint64_t)starts[0] | ((uint64_t)starts[1] << 32);
+                const int rank0 = __popcll(__ballot(nonempty && ustart < u0)) - 1; // piece that holds line u0 - 1
+                uint4 v[kAccUnroll];
+                uint32_t keep = 0; // 4 bits per step: which of the 4 entries belong to the piece
 #pragma unroll
                 for (int u = 0; u < kAccUnroll; ++u) {
-                    const uint32_t f = f0 + u * kWave + lane;
-                    const uint64_t m = starts[u];
-                    const int mine = rank + __popcll(m & below_incl);
-                    rank += __popcll(m);
-                    v[u] = kEmptySlot;
-                    if (f < total)
-                        v[u] = (uint32_t)(a.A_col[origin_of[mine] + f] - id0);
+                    const uint32_t jj = (uint32_t)(u * 8 + octet), j = u0 + jj;
+                    const int mine = rank0 + __popcll(m & ((2ull << jj) - 1ull));
+                    v[u] = make_uint4(0, 0, 0, 0);
+                    if (j < total) {
+                        const AccPiece rec = piece_rec[mine];
+                        const uint32_t off = j * 128u + (uint32_t)chunk * 16u; // of the lane's 16 bytes, from origin
+                        uint32_t k4 = 0;
+#pragma unroll
+                        for (uint32_t e = 0; e < 4; ++e)
+                            k4 |= (off + 4u * e >= rec.lo_rel && off + 4u * e < rec.hi_rel) ? 1u << e : 0u;
+                        if (k4)
+                            v[u] = *reinterpret_cast<const uint4 *>(rec.origin + (int64_t)off);
+                        keep |= k4 << (4 * u);
+                    }
                 }
 #pragma unroll
-                for (int u = 0; u < kAccUnroll; ++u)
-                    if (v[u] != kEmptySlot)
-                        atomicAdd(&cnt[v[u] >> 1], 1u << ((v[u] & 1u) * 16));
+                for (int u = 0; u < kAccUnroll; ++u) {
+                    const uint32_t xs[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if ((keep >> (4 * u + e)) & 1u) {
+                            const uint32_t x = xs[e] - (uint32_t)id0;
+                            atomicAdd(&cnt[x >> 1], 1u << ((x & 1u) * 16));
+                        }
+                }
             }
             len = next_len;
             addr = next_addr;
@@ -738,18 +782,30 @@ __global__ __launch_bounds__(256) void ldw_extract_copy_kernel(LwHop a)
 // ---------------------------------------------------------------------------------------------
 size_t ldw_accumulate_lds_bytes()
 {
-    return (size_t)(kWinWords + 3 * kAccWaves + 4) * sizeof(uint32_t) + (size_t)kAccWaves * (kWave + kAccUnroll) * sizeof(uint64_t);
+    return (size_t)(kWinWords + 3 * kAccWaves + 4) * sizeof(uint32_t) + (size_t)kAccWaves * (kWave + 1) * sizeof(AccPiece);
+}
+
+static void launch_ldw_tiles(const Launch &L, const LwHop &a)
+{
+    hipLaunchKernelGGL(ldw_mb_goff_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, a);
+    launch_plan_tiles(L, a.mb_goff, a.k, a.tile, a.mb_gtileoff);
+    hipLaunchKernelGGL(ldw_tile_rows_kernel, dim3(grid_for(L, (a.tiles_bound + 255) / 256, 8)), dim3(256), 0, L.stream, a);
 }
 
 void launch_ldw_bounds(const Launch &L, const LwHop &a)
 {
-    hipLaunchKernelGGL(ldw_mb_goff_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, a);
-    launch_plan_tiles(L, a.mb_goff, a.k, a.tile, a.mb_gtileoff);
+    launch_ldw_tiles(L, a);
     (void)hipMemsetAsync(a.tile_queue, 0, ((size_t)a.k + 1) * sizeof(unsigned long long), L.stream);
-    hipLaunchKernelGGL(ldw_tile_rows_kernel, dim3(grid_for(L, (a.tiles_bound + 255) / 256, 8)), dim3(256), 0, L.stream, a);
-    hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.tiles_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
+    if (!a.index)
+        hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.tiles_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
     const int64_t ttiles = ((a.nwin + 1 + 63) / 64) * ((a.rows_bound + 63) / 64);
     hipLaunchKernelGGL(ldw_bounds_transpose_kernel, dim3(grid_for(L, ttiles, 8)), dim3(256), 0, L.stream, a);
+}
+
+void launch_ldw_index(const Launch &L, const LwHop &a)
+{
+    launch_ldw_tiles(L, a);
+    hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.tiles_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
 }
 
 int launch_ldw_accumulate(const Launch &L, const LwHop &a)

@@ -22,11 +22,13 @@ def _run_both(mods, rowptr, col, batches, s_per_layer, seed, mb_base=0, squared=
     if csr is None:
         csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
     ref = O.sample_ladies(rowptr, col, batches, s_per_layer, seed, mb_base, squared)
-    for dense in (True, False):  # both kernel paths: counters in HBM, counters in LDS windows
+    # the kernel paths: counters in HBM; counters in LDS windows, the rows' window boundaries found per hop;
+    # the same with the boundaries copied from the per-graph index (built by the first call that may use it)
+    for dense, index in ((True, True), (False, False), (False, True)):
         res = bms.sample_ladies(csr, torch.from_numpy(batches).cuda(), s_per_layer, seed, mb_base=mb_base,
-                                squared=squared, dense=dense)
+                                squared=squared, dense=dense, index=index)
         assert_hops_equal(res.hops(), ref, with_p=True,
-                          what="s=%s seed=%d squared=%s dense=%s" % (s_per_layer, seed, squared, dense))
+                          what="s=%s seed=%d squared=%s dense=%s index=%s" % (s_per_layer, seed, squared, dense, index))
     return csr, res, ref
 
 
