@@ -165,7 +165,7 @@ struct bms_csr {
     bool segcnt_clean = false; // every segment counter zero (kept so by the kernels; lost when a call is interrupted)
     BMS_BUF(un_rowptr); BMS_BUF(un_col); // BMS_UNION_DST: the hop's CSR while its rows still carry their own vertex
     BMS_BUF(row_cnt);                    // BMS_NODEWISE_REPLACE with a fanout above 32: distinct picks per row
-    BMS_BUF(lw_bounds); BMS_BUF(lw_win); BMS_BUF(lw_tmpcol); BMS_BUF(lw_tmpcnt); BMS_BUF(lw_sel); BMS_BUF(lw_xtmp);
+    BMS_BUF(lw_bounds); BMS_BUF(lw_win); BMS_BUF(lw_tmpcol); BMS_BUF(lw_parts); BMS_BUF(lw_sel); BMS_BUF(lw_xtmp);
     BMS_BUF(lw_count); BMS_BUF(lw_tiles); BMS_BUF(lw_rowcnt); // LADIES by LDS windows
     BMS_BUF(lw_index);           // where every vertex's adjacency list crosses the window boundaries: n * (nwin + 1)
     bool lw_index_ready = false; // built by the first layer-wise call that finds room for it
@@ -1035,6 +1035,7 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
     const int32_t nwin = (int32_t)((n1 + (1LL << kWinShift) - 1) >> kWinShift);
     const size_t nw = (size_t)c.k * nwin;
     BMS_TRY(csr->lw_win.ensure(nw * (sizeof(uint32_t) + 4 * sizeof(int64_t)) + 64));
+    BMS_TRY(csr->lw_parts.ensure(nw * kWinParts * (sizeof(uint32_t) + sizeof(uint64_t))));
     BMS_TRY(csr->lw_count.ensure((4 * (size_t)c.k + 4) * sizeof(int64_t)));
     if (!csr->lw_index_tried && !(c.flags & BMS_LADIES_NO_INDEX))
         BMS_TRY(build_window_index(c, nwin));
@@ -1103,6 +1104,8 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         w.win_base = reinterpret_cast<int64_t *>(w.win_woff + nw);
         w.win_poff = w.win_base + nw;
         w.win_cnt = reinterpret_cast<uint32_t *>(w.win_poff + nw);
+        w.part_woff = csr->lw_parts.as<uint64_t>();
+        w.part_off = reinterpret_cast<uint32_t *>(w.part_woff + nw * kWinParts);
         w.cursor = reinterpret_cast<unsigned long long *>(csr->scalars.as<int64_t>() + 61);
         w.mb_count = csr->lw_count.as<int64_t>();
         w.mb_goff = w.mb_count + c.k + 1;
@@ -1124,16 +1127,14 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
             BMS_TRY(seed_flag_error(c));
         const int64_t D = host_slot(c, h, 3);
         const int64_t tmp_cap = std::max<int64_t>(std::min<int64_t>(D, (int64_t)c.k * n1), 1);
-        const size_t tbytes = (size_t)tmp_cap * 8 + (size_t)std::max<int64_t>(D, 1) * 4;
+        const size_t tbytes = (size_t)tmp_cap * 4 + (size_t)std::max<int64_t>(D, 1) * 4;
         if ((int64_t)(tbytes + blists * bbytes) > c.scratch_limit)
             return fail(BMS_ENOMEM, "%lld gathered neighbours need %zu bytes of scratch, limit is %lld: raise "
                                     "bms_opts.scratch_limit or sample fewer minibatches per call",
                         (long long)D, tbytes + blists * bbytes, (long long)c.scratch_limit);
         BMS_TRY(csr->lw_tmpcol.ensure((size_t)tmp_cap * sizeof(int32_t)));
-        BMS_TRY(csr->lw_tmpcnt.ensure((size_t)tmp_cap * sizeof(uint32_t)));
         BMS_TRY(csr->lw_xtmp.ensure((size_t)std::max<int64_t>(D, 1) * sizeof(int32_t)));
-        w.tmp_col = csr->lw_tmpcol.as<int32_t>();
-        w.tmp_cnt = csr->lw_tmpcnt.as<uint32_t>();
+        w.tmp_ent = csr->lw_tmpcol.as<uint32_t>();
         w.xtmp = csr->lw_xtmp.as<int32_t>();
         w.tile = kLwTileMax; // about four tiles per wave slot of the chip, within the limits
         while (w.tile > kLwTileMin && D / w.tile < (int64_t)csr->num_cu * 128)

@@ -224,6 +224,7 @@ void launch_chunk_scan(const Launch &, int64_t *chunk_off, int32_t k, int32_t nc
 
 // ---- LADIES with the column counts accumulated in LDS, window by window ----
 constexpr int kWinShift = 16;            // a window = 2^16 vertex ids = 2^16 16-bit counters = 128 KB of LDS
+constexpr int kWinParts = 16;            // a window leaves the accumulation in this many parts of equal id range
 constexpr int32_t kMaxWinRows = 65535;   // frontier rows per minibatch (a 16-bit counter cannot overflow)
 constexpr int32_t kMaxWinSampled = 4096; // columns sampled per minibatch (sorted, then hashed, in LDS)
 constexpr int kLwTileMax = 4096;         // positions of the gathered order streamed by one wave at a time: at most
@@ -260,9 +261,10 @@ struct LwHop {
     int64_t *win_base;         // k * nwin: where the window's entries start in tmp_*
     int64_t *win_poff;         // k * nwin: columns of the minibatch before the window
     uint64_t *win_woff;        // k * nwin: weight of the minibatch before the window
+    uint32_t *part_off;        // k * nwin * kWinParts: columns of the window before each of its parts
+    uint64_t *part_woff;       // k * nwin * kWinParts: their weight
     unsigned long long *cursor; // device scalar: entries of tmp_* in use
-    int32_t *tmp_col;          // min(D, k n) entries
-    uint32_t *tmp_cnt;
+    uint32_t *tmp_ent;         // min(D, k n) entries of P, window by window: (column - the window's first id) << 16 | e_v
     int64_t *mb_count;         // k
     int64_t *p_off;            // k+1
     int32_t *p_col;

@@ -38,6 +38,7 @@ constexpr int kWinIds = 1 << kWinShift;
 constexpr int kWinWords = kWinIds / 2; // two 16-bit counters per LDS word
 constexpr int kAccThreads = 1024;
 constexpr int kAccWaves = kAccThreads / kWave;
+static_assert(kAccWaves == kWinParts, "one part of a window per wave of the accumulation");
 constexpr int kWaveWords = kWinWords / kAccWaves; // counter words compacted by one wave
 constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;
 constexpr int kExtThreads = 1024; // the waves of a workgroup share one hash table
@@ -220,35 +221,51 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
     // lines that hold the end of one window's piece and the start of the next one's are fetched once.
     const int64_t G = gridDim.x;
     const bool by_die = (G % 8) == 0;
-    for (int64_t slot = blockIdx.x; slot < (nblk + G - 1) / G * G; slot += G) {
+    auto block_of = [&](int64_t slot) {
         int64_t blk = slot;
         if (by_die) {
             const int64_t p = slot % G;
             blk = slot - p + (p % 8) * (G / 8) + p / 8;
         }
-        if (blk >= nblk)
+        return blk;
+    };
+    // the piece of window w in row r, r < r1: (length, address of its first neighbour); rows without
+    // neighbours have no boundaries on record: whatever is read there is dropped
+    auto piece_at = [&](int w, int64_t r, int64_t r1, uint32_t &len, int64_t &addr) {
+        len = 0;
+        addr = 0;
+        if (r < r1) {
+            const uint32_t *__restrict__ lo_b = a.bounds_t + (int64_t)w * a.rows_bound; // boundary w of every row
+            const uint32_t b0 = lo_b[r];
+            const uint32_t b1 = lo_b[a.rows_bound + r];
+            const bool empty = a.gather_off[r + 1] == a.gather_off[r];
+            len = empty ? 0u : b1 - b0;
+            addr = a.row_beg[r] + b0;
+        }
+    };
+    // the first pieces of a (minibatch, window) pair are fetched while the pair before it is compacted
+    auto first_pieces = [&](int64_t slot, uint32_t &len, int64_t &addr) {
+        const int64_t blk = block_of(slot);
+        len = 0;
+        addr = 0;
+        if (blk < nblk) {
+            const int i = (int)(blk / a.nwin);
+            piece_at((int)(blk % a.nwin), a.mb_rowoff[i] + (int64_t)wave * kWave + lane, a.mb_rowoff[i + 1], len, addr);
+        }
+    };
+    uint32_t len, next_len;
+    int64_t addr, next_addr;
+    first_pieces(blockIdx.x, len, addr);
+    for (int64_t slot = blockIdx.x; slot < (nblk + G - 1) / G * G; slot += G) {
+        const int64_t blk = block_of(slot);
+        if (blk >= nblk) { // no later slot of this workgroup holds a pair either
+            first_pieces(slot + G, len, addr);
             continue;
+        }
         const int i = (int)(blk / a.nwin), w = (int)(blk % a.nwin);
         const int64_t r0 = a.mb_rowoff[i], r1 = a.mb_rowoff[i + 1];
-        const uint32_t *__restrict__ lo_b = a.bounds_t + (int64_t)w * a.rows_bound; // boundary w of every row
-        const uint32_t *__restrict__ hi_b = lo_b + a.rows_bound;
         const int32_t id0 = w << kWinShift;
-        // the piece of this window in row r: (length, address of its first neighbour); rows without
-        // neighbours have no boundaries on record: whatever is read there is dropped
-        auto piece_of = [&](int64_t r, uint32_t &len, int64_t &addr) {
-            len = 0;
-            addr = 0;
-            if (r < r1) {
-                const uint32_t b0 = lo_b[r];
-                const uint32_t b1 = hi_b[r];
-                const bool empty = a.gather_off[r + 1] == a.gather_off[r];
-                len = empty ? 0u : b1 - b0;
-                addr = a.row_beg[r] + b0;
-            }
-        };
-        uint32_t len, next_len;
-        int64_t addr, next_addr;
-        piece_of(r0 + (int64_t)wave * kWave + lane, len, addr);
+        auto piece_of = [&](int64_t r, uint32_t &l, int64_t &ad) { piece_at(w, r, r1, l, ad); };
         for (int64_t base = r0 + (int64_t)wave * kWave; base < r1; base += (int64_t)kAccWaves * kWave) {
             // the next 64 pieces are on their way while these are walked
             piece_of(base + (int64_t)kAccWaves * kWave + lane, next_len, next_addr);
@@ -321,6 +338,7 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
             len = next_len;
             addr = next_addr;
         }
+        first_pieces(slot + G, len, addr);
         __syncthreads();
         // Each wave compacts kWaveWords consecutive words, 16 bytes (8 counters) per lane and access, quad
         // it * 64 + lane of its part in iteration it: nonzero counters and weight per quad; their running count over
@@ -360,11 +378,13 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         if (tid == 0) {
             uint32_t total = 0;
             uint64_t wsum = 0;
-            for (int x = 0; x < kAccWaves; ++x) {
+            for (int x = 0; x < kAccWaves; ++x) { // both exclusive from here on
                 const uint32_t c = wave_nz[x];
-                wave_nz[x] = total; // exclusive
+                const uint64_t t = wave_wt[x];
+                wave_nz[x] = total;
+                wave_wt[x] = wsum;
                 total += c;
-                wsum += wave_wt[x];
+                wsum += t;
             }
             const uint64_t base = total ? atomicAdd(a.cursor, (unsigned long long)total) : 0ull;
             *base_s = base;
@@ -373,6 +393,10 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
             a.win_base[blk] = (int64_t)base;
         }
         __syncthreads();
+        if (lane == 0) { // where the wave's part of the window starts among the window's columns, and its weight
+            a.part_off[blk * kWinParts + wave] = wave_nz[wave];
+            a.part_woff[blk * kWinParts + wave] = wave_wt[wave];
+        }
         if (nz * 4u > (uint32_t)kWaveWords) {
             // most counters are nonzero: word by word, the nonzero ones of 64 consecutive words packed by a ballot,
             // so that every store instruction writes a run of consecutive entries
@@ -394,14 +418,11 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
                         continue;
                     int64_t pos = run + __popcll(mlo & below) + __popcll(mhi & below);
                     if (lo) {
-                        a.tmp_col[pos] = id0 + 2 * word;
-                        a.tmp_cnt[pos] = lo;
+                        a.tmp_ent[pos] = (uint32_t)(2 * word) << 16 | lo;
                         ++pos;
                     }
-                    if (hi) {
-                        a.tmp_col[pos] = id0 + 2 * word + 1;
-                        a.tmp_cnt[pos] = hi;
-                    }
+                    if (hi)
+                        a.tmp_ent[pos] = (uint32_t)(2 * word + 1) << 16 | hi;
                     run += __popcll(mlo) + __popcll(mhi);
                 }
             }
@@ -416,20 +437,14 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
                 mine4w[it * kWave + lane] = make_uint4(0, 0, 0, 0);
                 const uint32_t xs[4] = {q.x, q.y, q.z, q.w};
                 int64_t pos = run + (incq[it] - nzq[it]);
-                const int32_t col0 = id0 + 2 * (wave * kWaveWords + 4 * (it * kWave + lane));
+                const uint32_t col0 = 2u * (uint32_t)(wave * kWaveWords + 4 * (it * kWave + lane)); // within the window
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const uint32_t lo = xs[u] & 0xFFFFu, hi = xs[u] >> 16;
-                    if (lo) {
-                        a.tmp_col[pos] = col0 + 2 * u;
-                        a.tmp_cnt[pos] = lo;
-                        ++pos;
-                    }
-                    if (hi) {
-                        a.tmp_col[pos] = col0 + 2 * u + 1;
-                        a.tmp_cnt[pos] = hi;
-                        ++pos;
-                    }
+                    if (lo)
+                        a.tmp_ent[pos++] = (col0 + 2 * u) << 16 | lo;
+                    if (hi)
+                        a.tmp_ent[pos++] = (col0 + 2 * u + 1) << 16 | hi;
                 }
             }
         }
@@ -472,66 +487,58 @@ __global__ __launch_bounds__(256) void ldw_win_scan_kernel(LwHop a)
         a.mb_count[i] = (int64_t)carry_c;
 }
 
-// windows to their place in P, with the inclusive prefix sums of the weights.  Global accesses are
-// coalesced (lane t of a step takes entries t, t + 512, ...); the running sums need consecutive entries per
-// lane, so weights and sums change layout through LDS.
+// Windows to their place in P, with the inclusive prefix sums of the weights.  A window left the accumulation in
+// kWinParts parts (one per wave) whose sizes and weights are on record, so every part has a known place and a
+// known weight before it: one wave per part streams it, 64 entries at a time, with lane scans for the sums and
+// no workgroup barrier.
 constexpr int kPrefixBlock = 64; // entries of P per kept prefix sum
-constexpr int kCopyThreads = 512;
-constexpr int kCopyStep = 4 * kCopyThreads;
-__global__ __launch_bounds__(kCopyThreads) void ldw_p_copy_kernel(LwHop a)
+constexpr int kCopyUnroll = 4;
+__global__ __launch_bounds__(256) void ldw_p_copy_kernel(LwHop a)
 {
-    __shared__ uint64_t smem[kCopyThreads / kWave];
-    __shared__ uint32_t wgt[kCopyStep];  // e_v^2 < 2^32 as well: e_v < 2^16 on this path
-    __shared__ uint64_t sums[kCopyStep];
-    const int tid = threadIdx.x;
-    const int64_t nblk = (int64_t)a.k * a.nwin;
-    for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
-        const uint32_t cw = a.win_cnt[blk];
-        if (cw == 0)
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t nparts = (int64_t)a.k * a.nwin * kWinParts;
+    for (int64_t part = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave; part < nparts; part += (int64_t)gridDim.x * 4) {
+        const int64_t blk = part / kWinParts;
+        const int q = (int)(part % kWinParts);
+        const uint32_t o0 = a.part_off[part];
+        const uint32_t o1 = q + 1 < kWinParts ? a.part_off[part + 1] : a.win_cnt[blk];
+        if (o1 == o0)
             continue;
+        const uint32_t cw = o1 - o0;
         const int i = (int)(blk / a.nwin);
-        const int32_t *__restrict__ src_col = a.tmp_col + a.win_base[blk];
-        const uint32_t *__restrict__ src_cnt = a.tmp_cnt + a.win_base[blk];
-        const int64_t dst = a.p_off[i] + a.win_poff[blk];
-        uint64_t carry = a.win_woff[blk];
-        for (uint32_t x0 = 0; x0 < cw; x0 += kCopyStep) {
+        const int32_t id0 = (int32_t)(blk % a.nwin) << kWinShift;
+        const uint32_t *__restrict__ src = a.tmp_ent + a.win_base[blk] + o0;
+        const int64_t dst = a.p_off[i] + a.win_poff[blk] + o0;
+        uint64_t carry = a.win_woff[blk] + a.part_woff[part];
+        for (uint32_t x0 = 0; x0 < cw; x0 += kCopyUnroll * kWave) {
+            uint32_t ent[kCopyUnroll];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t x = x0 + q * kCopyThreads + tid;
-                uint32_t c = 0;
-                if (x < cw) {
-                    c = src_cnt[x];
-                    a.p_col[dst + x] = src_col[x];
-                    a.p_cnt[dst + x] = c;
+            for (int u = 0; u < kCopyUnroll; ++u) {
+                const uint32_t x = x0 + u * kWave + lane;
+                ent[u] = x < cw ? src[x] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kCopyUnroll; ++u) {
+                const uint32_t x = x0 + u * kWave + lane;
+                const uint32_t c = ent[u] & 0xFFFFu;
+                // e_v < 2^16: sums of 64 weights e_v fit 32 bits; e_v^2 is summed as two 16-bit halves
+                uint64_t inc;
+                if (a.squared) {
+                    const uint32_t wq = c * c;
+                    inc = ((uint64_t)wave_inclusive_scan_dpp(wq >> 16) << 16) + wave_inclusive_scan_dpp(wq & 0xFFFFu);
+                } else {
+                    inc = wave_inclusive_scan_dpp(c);
                 }
-                wgt[q * kCopyThreads + tid] = (uint32_t)ldw_weight(c, a.squared);
+                if (x < cw) {
+                    a.p_col[dst + x] = id0 + (int32_t)(ent[u] >> 16);
+                    a.p_cnt[dst + x] = c;
+                    // the draws find their block of kPrefixBlock entries of P by these sums and walk the weights
+                    // inside it: only the sum at the last entry of every such block (absolute index in P) is kept
+                    if (((dst + x) & (kPrefixBlock - 1)) == kPrefixBlock - 1)
+                        a.prefix[(dst + x) / kPrefixBlock] = carry + inc;
+                }
+                carry += __shfl(inc, kWave - 1, kWave);
             }
-            __syncthreads();
-            uint32_t w[4];
-            uint64_t mine = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                w[q] = wgt[tid * 4 + q];
-                mine += w[q];
-            }
-            uint64_t total;
-            uint64_t run = carry + block_exclusive_scan<uint64_t, kCopyThreads>(mine, smem, total);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                run += w[q];
-                sums[tid * 4 + q] = run;
-            }
-            __syncthreads();
-            // the draws find their block of kPrefixBlock entries of P by these sums and walk the weights
-            // inside it: only the sum at the last entry of every such block (absolute index in P) is kept
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t x = x0 + q * kCopyThreads + tid;
-                if (x < cw && ((dst + x) & (kPrefixBlock - 1)) == kPrefixBlock - 1)
-                    a.prefix[(dst + x) / kPrefixBlock] = sums[q * kCopyThreads + tid];
-            }
-            carry += total;
-            __syncthreads();
         }
     }
 }
@@ -828,7 +835,7 @@ int launch_ldw_accumulate(const Launch &L, const LwHop &a)
 
 void launch_ldw_p_copy(const Launch &L, const LwHop &a)
 {
-    hipLaunchKernelGGL(ldw_p_copy_kernel, dim3(grid_for(L, (int64_t)a.k * a.nwin, 4)), dim3(kCopyThreads), 0, L.stream, a);
+    hipLaunchKernelGGL(ldw_p_copy_kernel, dim3(grid_for(L, ((int64_t)a.k * a.nwin * kWinParts + 3) / 4, 8)), dim3(256), 0, L.stream, a);
 }
 
 void launch_ldw_draw(const Launch &L, const LwHop &a)
