@@ -334,6 +334,46 @@ __global__ __launch_bounds__(1024) void scan_i64_add_kernel(int64_t *vals, const
     }
 }
 
+// Arrays of middling length, two steps: after the chunks kernel every workgroup adds up the sums of the chunks
+// before its own by itself (at most kScanSelfChunks of them), so no workgroup scans the sums in between.
+constexpr int64_t kScanSelfChunks = 1024;
+__global__ __launch_bounds__(1024) void scan_i64_add_self_kernel(int64_t *vals, const int64_t *__restrict__ count,
+                                                                 const int64_t *__restrict__ sums, int64_t *total_out,
+                                                                 int64_t *tail_ptr, const int64_t *__restrict__ tail_idx)
+{
+    __shared__ int64_t smem[16];
+    const int64_t m = *count;
+    const int64_t nchunks = (m + 4095) / 4096; // <= kScanSelfChunks = the workgroup's size
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    for (int64_t c = blockIdx.x; c < nchunks + 1; c += gridDim.x) { // "chunk" nchunks: the grand total
+        int64_t before = (int64_t)threadIdx.x < c ? sums[threadIdx.x] : 0;
+        before = wave_sum(before);
+        __syncthreads();
+        if (lane == 0)
+            smem[wave] = before;
+        __syncthreads();
+        before = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w)
+            before += smem[w];
+        if (c == nchunks) {
+            if (threadIdx.x == 0) {
+                vals[m] = before;
+                if (total_out)
+                    *total_out = before;
+                if (tail_ptr)
+                    tail_ptr[*tail_idx] = before;
+            }
+            continue;
+        }
+        const int64_t i0 = c * 4096 + (int64_t)threadIdx.x * 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (i0 + q < m)
+                vals[i0 + q] += before;
+    }
+}
+
 __global__ void scan_i64_count_kernel(const int64_t *__restrict__ count, int64_t *nchunks_plus_one)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0)
@@ -344,7 +384,14 @@ void launch_scan_i64(const Launch &L, int64_t *vals, const int64_t *count, int64
                      const int64_t *tail_idx, int64_t count_bound)
 {
     const int64_t chunks_bound = (count_bound + 4095) / 4096;
-    if (count_bound > 524288 && L.scan_tmp && chunks_bound + 3 <= L.scan_tmp_len) { // one workgroup below that: fewer launches
+    if (count_bound > 32768 && chunks_bound <= kScanSelfChunks && L.scan_tmp && chunks_bound + 3 <= L.scan_tmp_len) {
+        int64_t *sums = L.scan_tmp;
+        hipLaunchKernelGGL(scan_i64_chunks_kernel, dim3(grid_for(L, chunks_bound, 2)), dim3(1024), 0, L.stream, vals, count, sums);
+        hipLaunchKernelGGL(scan_i64_add_self_kernel, dim3(grid_for(L, chunks_bound + 1, 2)), dim3(1024), 0, L.stream, vals,
+                           count, sums, total_out, tail_ptr, tail_idx);
+        return;
+    }
+    if (count_bound > 32768 && L.scan_tmp && chunks_bound + 3 <= L.scan_tmp_len) { // one workgroup below that: fewer launches
         int64_t *sums = L.scan_tmp;                 // chunks_bound + 1 values
         int64_t *nsums = L.scan_tmp + chunks_bound + 2; // device-side length of `sums` for the middle scan
         const int grid = grid_for(L, chunks_bound, 2);
