@@ -1034,8 +1034,8 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
     const int64_t n1 = std::max<int64_t>(csr->n, 1);
     const int32_t nwin = (int32_t)((n1 + (1LL << kWinShift) - 1) >> kWinShift);
     const size_t nw = (size_t)c.k * nwin;
-    BMS_TRY(csr->lw_win.ensure(nw * (sizeof(uint32_t) + 4 * sizeof(int64_t)) + 64));
-    BMS_TRY(csr->lw_parts.ensure(nw * kWinParts * (sizeof(uint32_t) + sizeof(uint64_t))));
+    BMS_TRY(csr->lw_win.ensure(nw * (2 * sizeof(uint32_t) + 3 * sizeof(int64_t)) + 64));
+    BMS_TRY(csr->lw_parts.ensure(nw * kWinParts * (2 * sizeof(uint32_t) + 3 * sizeof(uint64_t))));
     BMS_TRY(csr->lw_count.ensure((4 * (size_t)c.k + 4) * sizeof(int64_t)));
     if (!csr->lw_index_tried && !(c.flags & BMS_LADIES_NO_INDEX))
         BMS_TRY(build_window_index(c, nwin));
@@ -1101,11 +1101,14 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         w.bounds_t = csr->lw_bounds.as<uint32_t>();
         w.win_wt = csr->lw_win.as<uint64_t>();
         w.win_woff = w.win_wt + nw;
-        w.win_base = reinterpret_cast<int64_t *>(w.win_woff + nw);
-        w.win_poff = w.win_base + nw;
+        w.win_poff = reinterpret_cast<int64_t *>(w.win_woff + nw);
         w.win_cnt = reinterpret_cast<uint32_t *>(w.win_poff + nw);
+        w.win_added = w.win_cnt + nw;
         w.part_woff = csr->lw_parts.as<uint64_t>();
-        w.part_off = reinterpret_cast<uint32_t *>(w.part_woff + nw * kWinParts);
+        w.part_wt = w.part_woff + nw * kWinParts;
+        w.part_base = reinterpret_cast<int64_t *>(w.part_wt + nw * kWinParts);
+        w.part_off = reinterpret_cast<uint32_t *>(w.part_base + nw * kWinParts);
+        w.part_cnt = w.part_off + nw * kWinParts;
         w.cursor = reinterpret_cast<unsigned long long *>(csr->scalars.as<int64_t>() + 61);
         w.mb_count = csr->lw_count.as<int64_t>();
         w.mb_goff = w.mb_count + c.k + 1;
@@ -1126,7 +1129,8 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         if (h == 0)
             BMS_TRY(seed_flag_error(c));
         const int64_t D = host_slot(c, h, 3);
-        const int64_t tmp_cap = std::max<int64_t>(std::min<int64_t>(D, (int64_t)c.k * n1), 1);
+        // every part of a window claims room for as many columns as it has ids, or as the window has neighbours
+        const int64_t tmp_cap = std::max<int64_t>(std::min<int64_t>(kWinParts * D, (int64_t)nw << kWinShift), 1);
         const size_t tbytes = (size_t)tmp_cap * 4 + (size_t)std::max<int64_t>(D, 1) * 4;
         if ((int64_t)(tbytes + blists * bbytes) > c.scratch_limit)
             return fail(BMS_ENOMEM, "%lld gathered neighbours need %zu bytes of scratch, limit is %lld: raise "
@@ -1155,7 +1159,7 @@ int sample_ladies_windows_impl(CallCtx &c, const int32_t *batches, const int32_t
         BMS_TRY(prof.end());
         // nnz(P) sizes P and its prefix sums.  When its bound min(D, k n) is modest the buffers take the bound
         // and the size is read back with everything else at the end of the call; else it is read back now.
-        int64_t pnnz = tmp_cap;
+        int64_t pnnz = std::max<int64_t>(std::min<int64_t>(D, (int64_t)c.k * n1), 1);
         if (pnnz > kNoWaitEntries) {
             BMS_TRY(read_scalars(c));
             pnnz = host_slot(c, h, 2);

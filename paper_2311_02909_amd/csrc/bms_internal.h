@@ -256,15 +256,18 @@ struct LwHop {
     uint32_t *bounds;          // rows_bound * (nwin+1), one list per row
     const uint32_t *index;     // n * (nwin+1): the list of every vertex's whole row, built once per graph; or null
     uint32_t *bounds_t;        // (nwin+1) * rows_bound, the same window-major
+    uint32_t *win_added;       // k * nwin: neighbours of the minibatch's rows inside the window
     uint32_t *win_cnt;         // k * nwin: columns of P inside the window
     uint64_t *win_wt;          // k * nwin: their weight
-    int64_t *win_base;         // k * nwin: where the window's entries start in tmp_*
     int64_t *win_poff;         // k * nwin: columns of the minibatch before the window
     uint64_t *win_woff;        // k * nwin: weight of the minibatch before the window
-    uint32_t *part_off;        // k * nwin * kWinParts: columns of the window before each of its parts
+    int64_t *part_base;        // k * nwin * kWinParts: where the part's entries start in tmp_ent
+    uint32_t *part_cnt;        // k * nwin * kWinParts: columns of P in the part
+    uint64_t *part_wt;         // k * nwin * kWinParts: their weight
+    uint32_t *part_off;        // k * nwin * kWinParts: columns of the window before the part
     uint64_t *part_woff;       // k * nwin * kWinParts: their weight
     unsigned long long *cursor; // device scalar: entries of tmp_* in use
-    uint32_t *tmp_ent;         // min(D, k n) entries of P, window by window: (column - the window's first id) << 16 | e_v
+    uint32_t *tmp_ent;         // entries of P, part by part: (column - the window's first id) << 16 | e_v
     int64_t *mb_count;         // k
     int64_t *p_off;            // k+1
     int32_t *p_col;

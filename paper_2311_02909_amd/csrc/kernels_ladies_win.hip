@@ -61,11 +61,39 @@ __device__ inline uint64_t ldw_weight(uint32_t cnt, int squared)
 // ---------------------------------------------------------------------------------------------
 // Tiles of the gathered order
 // ---------------------------------------------------------------------------------------------
-__global__ void ldw_mb_goff_kernel(LwHop a)
+// One workgroup: where each minibatch starts in the gathered order (mb_goff), the tiles before each minibatch
+// (mb_gtileoff); the tile counters of the extraction and the staging cursor of the accumulation start at zero.
+__global__ __launch_bounds__(1024) void ldw_plan_kernel(LwHop a)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i <= a.k)
-        a.mb_goff[i] = a.gather_off[a.mb_rowoff[i]];
+    __shared__ int64_t smem[16];
+    __shared__ int64_t carry_s;
+    if (threadIdx.x == 0) {
+        carry_s = 0;
+        if (a.cursor)
+            *a.cursor = 0;
+    }
+    __syncthreads();
+    for (int32_t base = 0; base <= a.k; base += 1024) {
+        const int32_t i = base + threadIdx.x;
+        int64_t cnt = 0;
+        if (i <= a.k) {
+            const int64_t g0 = a.gather_off[a.mb_rowoff[i]];
+            a.mb_goff[i] = g0;
+            if (a.tile_queue)
+                a.tile_queue[i] = 0;
+            if (i < a.k)
+                cnt = (a.gather_off[a.mb_rowoff[i + 1]] - g0 + a.tile - 1) / a.tile;
+        }
+        int64_t total;
+        const int64_t ex = block_exclusive_scan<int64_t, 1024>(cnt, smem, total);
+        const int64_t carry = carry_s;
+        if (i <= a.k)
+            a.mb_gtileoff[i] = carry + ex; // entry k: all tiles
+        __syncthreads();
+        if (threadIdx.x == 0)
+            carry_s = carry + total;
+        __syncthreads();
+    }
 }
 
 // tile_row[x] = the row that holds the first position of tile x (the last row starting at or before it)
@@ -193,16 +221,38 @@ __global__ __launch_bounds__(256) void ldw_bounds_transpose_kernel(LwHop a)
     }
 }
 
+// win_added[i * nwin + w] = neighbours of minibatch i's rows inside window w (the lengths of their pieces)
+__global__ __launch_bounds__(256) void ldw_win_added_kernel(LwHop a)
+{
+    __shared__ uint32_t wsum[4];
+    const int tid = threadIdx.x;
+    const int64_t nblk = (int64_t)a.k * a.nwin;
+    for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+        const int i = (int)(blk / a.nwin), w = (int)(blk % a.nwin);
+        const uint32_t *__restrict__ lo_b = a.bounds_t + (int64_t)w * a.rows_bound;
+        uint32_t sum = 0; // < 2^32: at most 65535 rows with at most 2^16 neighbours in a window each
+        for (int64_t r = a.mb_rowoff[i] + tid; r < a.mb_rowoff[i + 1]; r += 256)
+            if (a.gather_off[r + 1] != a.gather_off[r]) // rows without neighbours have no boundaries on record
+                sum += lo_b[a.rows_bound + r] - lo_b[r];
+        sum = wave_sum(sum);
+        __syncthreads();
+        if ((tid & (kWave - 1)) == 0)
+            wsum[tid / kWave] = sum;
+        __syncthreads();
+        if (tid == 0)
+            a.win_added[blk] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // P = Q A for one (minibatch, window) per workgroup
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
 {
     extern __shared__ uint32_t lds[];
-    uint32_t *cnt = lds;                                               // kWinWords packed counters
-    uint64_t *wave_wt = reinterpret_cast<uint64_t *>(lds + kWinWords); // kAccWaves
-    uint32_t *wave_nz = lds + kWinWords + 2 * kAccWaves;               // kAccWaves
-    uint64_t *base_s = reinterpret_cast<uint64_t *>(lds + kWinWords + 3 * kAccWaves); // 1
+    uint32_t *cnt = lds;                   // kWinWords packed counters
+    unsigned long long *claim_s = reinterpret_cast<unsigned long long *>(lds + kWinWords); // [2], in turn: where the
+                                           // entries of the current (minibatch, window) start in the staging array
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     // per wave: one record per nonempty piece (by rank) and the start bits of one span of memory lines
     AccPiece *piece_rec = reinterpret_cast<AccPiece *>(lds + kWinWords + 3 * kAccWaves + 4) + wave * (kWave + 1);
@@ -216,6 +266,7 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
     for (int x = tid; x < kWinWords; x += kAccThreads)
         cnt[x] = 0;
     __syncthreads();
+    int turn = 0;
     // Workgroups are handed to the chip's 8 dies in turn, and each die has its own last-level cache.  Within a
     // round of gridDim.x (minibatch, window) pairs, die x takes a run of consecutive windows, so the memory
     // lines that hold the end of one window's piece and the start of the next one's are fetched once.
@@ -266,6 +317,13 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         const int64_t r0 = a.mb_rowoff[i], r1 = a.mb_rowoff[i + 1];
         const int32_t id0 = w << kWinShift;
         auto piece_of = [&](int64_t r, uint32_t &l, int64_t &ad) { piece_at(w, r, r1, l, ad); };
+        // A part of the window (one wave's kWaveWords words) cannot hold more columns than it has counters, nor
+        // than the window gets neighbours: room for that many entries per part is claimed from the device-wide
+        // cursor now, and the answer is back long before the counters are compacted
+        const uint32_t added_blk = a.win_added[blk];
+        const uint32_t room = min(added_blk, (uint32_t)(2 * kWaveWords));
+        if (tid == 0)
+            claim_s[turn] = room ? atomicAdd(a.cursor, (unsigned long long)room * kWinParts) : 0ull;
         for (int64_t base = r0 + (int64_t)wave * kWave; base < r1; base += (int64_t)kAccWaves * kWave) {
             // the next 64 pieces are on their way while these are walked
             piece_of(base + (int64_t)kAccWaves * kWave + lane, next_len, next_addr);
@@ -340,67 +398,18 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         }
         first_pieces(slot + G, len, addr);
         __syncthreads();
-        // Each wave compacts kWaveWords consecutive words, 16 bytes (8 counters) per lane and access, quad
-        // it * 64 + lane of its part in iteration it: nonzero counters and weight per quad; their running count over
-        // the wave's part in ascending column order (lane scans, no LDS); then, where the whole window starts in the
-        // staging arrays (one cursor claim per workgroup), the nonzero counters are written out and cleared.
-        constexpr int kQuadIts = kWaveWords / 4 / kWave; // quads per lane
-        const uint4 *mine4 = reinterpret_cast<const uint4 *>(cnt + wave * kWaveWords);
-        uint32_t nzq[kQuadIts], incq[kQuadIts];
+        // Each wave compacts its part of the window, kWaveWords consecutive words, in one pass: the nonzero counters
+        // leave in ascending column order as (column - id0) << 16 | e_v, and are cleared; the wave records where its
+        // part went, how many entries it holds and what they weigh.
+        const int64_t claimed = (int64_t)claim_s[turn] + (int64_t)wave * room;
+        turn ^= 1;
+        const int64_t part = blk * kWinParts + wave;
         uint32_t nz = 0;
         uint64_t wt = 0;
-#pragma unroll
-        for (int it = 0; it < kQuadIts; ++it) {
-            const uint4 q = mine4[it * kWave + lane];
-            const uint32_t xs[4] = {q.x, q.y, q.z, q.w};
-            uint32_t c = 0, w32 = 0;
-            uint64_t w64 = 0;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t lo = xs[u] & 0xFFFFu, hi = xs[u] >> 16;
-                c += (lo != 0) + (hi != 0);
-                if (a.squared)
-                    w64 += (uint64_t)lo * lo + (uint64_t)hi * hi;
-                else
-                    w32 += lo + hi; // at most 64 values below 2^16 per lane
-            }
-            wt += a.squared ? w64 : (uint64_t)w32;
-            nzq[it] = c;
-            incq[it] = wave_inclusive_scan_dpp(c) + nz; // nonzero counters of the wave's part up to this quad
-            nz = (uint32_t)__builtin_amdgcn_readlane((int)incq[it], kWave - 1);
-        }
-        wt = wave_sum(wt);
-        if (lane == 0) {
-            wave_nz[wave] = nz;
-            wave_wt[wave] = wt;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t total = 0;
-            uint64_t wsum = 0;
-            for (int x = 0; x < kAccWaves; ++x) { // both exclusive from here on
-                const uint32_t c = wave_nz[x];
-                const uint64_t t = wave_wt[x];
-                wave_nz[x] = total;
-                wave_wt[x] = wsum;
-                total += c;
-                wsum += t;
-            }
-            const uint64_t base = total ? atomicAdd(a.cursor, (unsigned long long)total) : 0ull;
-            *base_s = base;
-            a.win_cnt[blk] = total;
-            a.win_wt[blk] = wsum;
-            a.win_base[blk] = (int64_t)base;
-        }
-        __syncthreads();
-        if (lane == 0) { // where the wave's part of the window starts among the window's columns, and its weight
-            a.part_off[blk * kWinParts + wave] = wave_nz[wave];
-            a.part_woff[blk * kWinParts + wave] = wave_wt[wave];
-        }
-        if (nz * 4u > (uint32_t)kWaveWords) {
+        if (added_blk > (uint32_t)(kWinWords / 4)) { // more than one neighbour per 8 counters
             // most counters are nonzero: word by word, the nonzero ones of 64 consecutive words packed by a ballot,
             // so that every store instruction writes a run of consecutive entries
-            int64_t run = (int64_t)*base_s + wave_nz[wave];
+            int64_t run = claimed;
             for (int it0 = 0; it0 < kWaveWords / kWave; it0 += 4) {
                 uint32_t x[4];
 #pragma unroll
@@ -416,6 +425,7 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
                     const uint64_t mlo = __ballot(lo != 0), mhi = __ballot(hi != 0);
                     if ((mlo | mhi) == 0)
                         continue;
+                    wt += ldw_weight(lo, a.squared) + ldw_weight(hi, a.squared);
                     int64_t pos = run + __popcll(mlo & below) + __popcll(mhi & below);
                     if (lo) {
                         a.tmp_ent[pos] = (uint32_t)(2 * word) << 16 | lo;
@@ -423,24 +433,37 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
                     }
                     if (hi)
                         a.tmp_ent[pos] = (uint32_t)(2 * word + 1) << 16 | hi;
-                    run += __popcll(mlo) + __popcll(mhi);
+                    const uint32_t step = (uint32_t)(__popcll(mlo) + __popcll(mhi));
+                    run += step;
+                    nz += step;
                 }
             }
-        } else if (nz) { // few: only the quads that hold any are read again (uniform per wave)
-            const int64_t run = (int64_t)*base_s + wave_nz[wave];
-            uint4 *mine4w = reinterpret_cast<uint4 *>(cnt + wave * kWaveWords);
+        } else if (added_blk) {
+            // few: 16 bytes (8 counters) per lane and access; a group of 64 such quads without any counter costs
+            // one LDS read
+            constexpr int kQuadIts = kWaveWords / 4 / kWave; // quads per lane
+            uint4 *mine4 = reinterpret_cast<uint4 *>(cnt + wave * kWaveWords);
+            const int64_t run0 = claimed;
 #pragma unroll
             for (int it = 0; it < kQuadIts; ++it) {
-                if (nzq[it] == 0)
-                    continue;
-                const uint4 q = mine4w[it * kWave + lane];
-                mine4w[it * kWave + lane] = make_uint4(0, 0, 0, 0);
+                const uint4 q = mine4[it * kWave + lane];
                 const uint32_t xs[4] = {q.x, q.y, q.z, q.w};
-                int64_t pos = run + (incq[it] - nzq[it]);
+                uint32_t c = 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    c += ((xs[u] & 0xFFFFu) != 0) + ((xs[u] >> 16) != 0);
+                if (__ballot(c != 0) == 0)
+                    continue;
+                if (c)
+                    mine4[it * kWave + lane] = make_uint4(0, 0, 0, 0);
+                const uint32_t inc = wave_inclusive_scan_dpp(c);
+                int64_t pos = run0 + nz + (inc - c);
+                nz += (uint32_t)__builtin_amdgcn_readlane((int)inc, kWave - 1);
                 const uint32_t col0 = 2u * (uint32_t)(wave * kWaveWords + 4 * (it * kWave + lane)); // within the window
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const uint32_t lo = xs[u] & 0xFFFFu, hi = xs[u] >> 16;
+                    wt += ldw_weight(lo, a.squared) + ldw_weight(hi, a.squared);
                     if (lo)
                         a.tmp_ent[pos++] = (col0 + 2 * u) << 16 | lo;
                     if (hi)
@@ -448,11 +471,18 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
                 }
             }
         }
+        wt = wave_sum(wt);
+        if (lane == 0) {
+            a.part_base[part] = claimed;
+            a.part_cnt[part] = nz;
+            a.part_wt[part] = wt;
+        }
         __syncthreads();
     }
 }
 
-// one workgroup per minibatch: columns and weight before each window; columns of the minibatch
+// one workgroup per minibatch: columns and weight of every window (the sums of its parts), before each of its
+// parts, and before each window; columns of the minibatch
 __global__ __launch_bounds__(256) void ldw_win_scan_kernel(LwHop a)
 {
     __shared__ uint64_t smem[4];
@@ -466,8 +496,18 @@ __global__ __launch_bounds__(256) void ldw_win_scan_kernel(LwHop a)
     for (int base = 0; base < a.nwin; base += 256) {
         const int w = base + tid;
         const int64_t x = (int64_t)i * a.nwin + w;
-        const uint64_t c = w < a.nwin ? a.win_cnt[x] : 0u;
-        const uint64_t wt = w < a.nwin ? a.win_wt[x] : 0u;
+        uint64_t c = 0, wt = 0;
+        if (w < a.nwin) {
+            for (int q = 0; q < kWinParts; ++q) {
+                const int64_t part = x * kWinParts + q;
+                a.part_off[part] = (uint32_t)c;
+                a.part_woff[part] = wt;
+                c += a.part_cnt[part];
+                wt += a.part_wt[part];
+            }
+            a.win_cnt[x] = (uint32_t)c;
+            a.win_wt[x] = wt;
+        }
         uint64_t tc, tw;
         const uint64_t ec = block_exclusive_scan<uint64_t, 256>(c, smem, tc);
         const uint64_t ew = block_exclusive_scan<uint64_t, 256>(wt, smem, tw);
@@ -499,15 +539,13 @@ __global__ __launch_bounds__(256) void ldw_p_copy_kernel(LwHop a)
     const int64_t nparts = (int64_t)a.k * a.nwin * kWinParts;
     for (int64_t part = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave; part < nparts; part += (int64_t)gridDim.x * 4) {
         const int64_t blk = part / kWinParts;
-        const int q = (int)(part % kWinParts);
-        const uint32_t o0 = a.part_off[part];
-        const uint32_t o1 = q + 1 < kWinParts ? a.part_off[part + 1] : a.win_cnt[blk];
-        if (o1 == o0)
+        const uint32_t cw = a.part_cnt[part];
+        if (cw == 0)
             continue;
-        const uint32_t cw = o1 - o0;
+        const uint32_t o0 = a.part_off[part];
         const int i = (int)(blk / a.nwin);
         const int32_t id0 = (int32_t)(blk % a.nwin) << kWinShift;
-        const uint32_t *__restrict__ src = a.tmp_ent + a.win_base[blk] + o0;
+        const uint32_t *__restrict__ src = a.tmp_ent + a.part_base[part];
         const int64_t dst = a.p_off[i] + a.win_poff[blk] + o0;
         uint64_t carry = a.win_woff[blk] + a.part_woff[part];
         for (uint32_t x0 = 0; x0 < cw; x0 += kCopyUnroll * kWave) {
@@ -794,15 +832,13 @@ size_t ldw_accumulate_lds_bytes()
 
 static void launch_ldw_tiles(const Launch &L, const LwHop &a)
 {
-    hipLaunchKernelGGL(ldw_mb_goff_kernel, dim3((a.k + 256) / 256), dim3(256), 0, L.stream, a);
-    launch_plan_tiles(L, a.mb_goff, a.k, a.tile, a.mb_gtileoff);
+    hipLaunchKernelGGL(ldw_plan_kernel, dim3(1), dim3(1024), 0, L.stream, a);
     hipLaunchKernelGGL(ldw_tile_rows_kernel, dim3(grid_for(L, (a.tiles_bound + 255) / 256, 8)), dim3(256), 0, L.stream, a);
 }
 
 void launch_ldw_bounds(const Launch &L, const LwHop &a)
 {
     launch_ldw_tiles(L, a);
-    (void)hipMemsetAsync(a.tile_queue, 0, ((size_t)a.k + 1) * sizeof(unsigned long long), L.stream);
     if (!a.index)
         hipLaunchKernelGGL(ldw_bounds_kernel, dim3(grid_for(L, (a.tiles_bound + 3) / 4, 8)), dim3(256), 0, L.stream, a);
     const int64_t ttiles = ((a.nwin + 1 + 63) / 64) * ((a.rows_bound + 63) / 64);
@@ -824,7 +860,7 @@ int launch_ldw_accumulate(const Launch &L, const LwHop &a)
             (void)hipGetLastError(); // not required on every runtime; the launch below reports real failures
         attr_set = true;
     }
-    (void)hipMemsetAsync(a.cursor, 0, sizeof(unsigned long long), L.stream);
+    hipLaunchKernelGGL(ldw_win_added_kernel, dim3(grid_for(L, (int64_t)a.k * a.nwin, 8)), dim3(256), 0, L.stream, a);
     hipLaunchKernelGGL(ldw_accumulate_kernel, dim3(grid_for(L, (int64_t)a.k * a.nwin, 1)), dim3(kAccThreads),
                        ldw_accumulate_lds_bytes(), L.stream, a);
     if (hipGetLastError() != hipSuccess)
