@@ -52,6 +52,7 @@ struct AccPiece {                          // one nonempty piece of a wave's 64 
 };
 constexpr int kStreamUnroll = 8; // neighbours per lane in flight in the two streaming passes
 constexpr int kHashSlots = 2 * kMaxWinSampled;    // load factor <= 1/2
+constexpr int kDrawTop = 2048;                    // recorded weight sums of P that a drawing workgroup keeps in LDS
 
 __device__ inline uint64_t ldw_weight(uint32_t cnt, int squared)
 {
@@ -531,7 +532,7 @@ __global__ __launch_bounds__(256) void ldw_win_scan_kernel(LwHop a)
 // kWinParts parts (one per wave) whose sizes and weights are on record, so every part has a known place and a
 // known weight before it: one wave per part streams it, 64 entries at a time, with lane scans for the sums and
 // no workgroup barrier.
-constexpr int kPrefixBlock = 64; // entries of P per kept prefix sum
+constexpr int kPrefixBlock = 16; // entries of P per kept prefix sum
 constexpr int kCopyUnroll = 4;
 __global__ __launch_bounds__(256) void ldw_p_copy_kernel(LwHop a)
 {
@@ -588,6 +589,7 @@ __global__ __launch_bounds__(1024) void ldw_draw_kernel(LwHop a)
 {
     __shared__ uint32_t key[kMaxWinSampled];
     __shared__ uint32_t smem[16];
+    __shared__ uint64_t top[kDrawTop];
     const int i = blockIdx.x, tid = threadIdx.x;
     const int64_t p0 = a.p_off[i], C = a.p_off[i + 1] - p0;
     uint32_t M = 1024; // sorted size: a power of two >= s, at least one slot per thread
@@ -600,11 +602,30 @@ __global__ __launch_bounds__(1024) void ldw_draw_kernel(LwHop a)
     const int64_t last_win = (int64_t)i * a.nwin + a.nwin - 1;
     const uint64_t W = a.win_woff[last_win] + a.win_wt[last_win];
     const uint64_t rk = row_key(a.hopkey, a.mb_base + (uint32_t)i, kNoVertex);
+    // Every draw searches the recorded sums; probes far apart in memory cost a trip to memory each and follow one
+    // another.  The sums at the end of every group of 2^st blocks (at most kDrawTop groups) are copied to LDS
+    // first: a draw finds its group there and only the last st probes go to memory, close to one another.
+    int st = 0;
+    while ((nb >> st) > kDrawTop)
+        ++st;
+    const int64_t ntop = nb >> st;
+    for (int64_t t = tid; t < ntop; t += 1024)
+        top[t] = pre[((t + 1) << st) - 1];
+    __syncthreads();
     for (uint32_t j = tid; j < M; j += 1024) {
         uint32_t v = kEmptySlot;
         if (j < (uint32_t)a.s && C > 0) { // an empty aggregated neighbourhood samples nothing
             const uint64_t r = bounded64(draw64(rk, j), W);
-            int64_t lo = 0, hi = nb; // first block whose recorded sum exceeds r (nb: the unrecorded tail)
+            int64_t lo = 0, hi = ntop; // first group whose last recorded sum exceeds r (ntop: the blocks after the groups)
+            while (lo < hi) {
+                const int64_t mid = lo + ((hi - lo) >> 1);
+                if (top[mid] > r)
+                    hi = mid;
+                else
+                    lo = mid + 1;
+            }
+            hi = lo < ntop ? ((lo + 1) << st) - 1 : nb; // first block whose recorded sum exceeds r (nb: the unrecorded tail)
+            lo <<= st;
             while (lo < hi) {
                 const int64_t mid = lo + ((hi - lo) >> 1);
                 if (pre[mid] > r)
