@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 # the line "bench constant ..." of profiles/<workload>_hbm_traffic.txt (tests/test_bench_constants.py compares
 # them); a kernel that has changed since its profile was taken has no entry (None in the output).
 MEASURED_TRAFFIC = {
-    ("dense_ladies", "ldw_accumulate"): 4_266_667_492,
-    ("dense_ladies", "ldw_extract"): 2_046_597_627,
+    ("dense_ladies", "ldw_accumulate"): 3_297_510_409,
+    ("dense_ladies", "ldw_extract"): 2_044_954_418,
     ("dense_sage", "nw_sample"): 10_771_843_227,
     ("dense_sage", "nw_rows"): 1_379_481_513,
     ("dense_sage", "dd_split"): 1_126_571_515,
@@ -47,8 +47,8 @@ MEASURED_TRAFFIC = {
     ("large_sage", "dd_unsplit"): 649_420_918,
     ("large_sage", "dd_rank"): 598_387_163,
     ("large_sage", "dd_front"): 473_538_464,
-    ("mid_ladies", "ldw_accumulate"): 196_442_491,
-    ("mid_ladies", "ldw_extract"): 89_716_772,
+    ("mid_ladies", "ldw_accumulate"): 148_744_475,
+    ("mid_ladies", "ldw_extract"): 89_763_702,
     ("mid_sage", "nw_sample"): 3_183_651_204,
     ("mid_sage", "dd_split"): 423_725_540,
     ("mid_sage", "dd_unsplit"): 358_696_429,
@@ -58,10 +58,10 @@ MEASURED_TRAFFIC = {
 }
 # the same summed over every kernel of one bulk call (bytes per step)
 MEASURED_CALL_TRAFFIC = {
-    "dense_ladies": 13_130_045_915,
+    "dense_ladies": 9_690_704_534,
     "dense_sage": 15_735_199_405,
     "large_sage": 10_101_181_440,
-    "mid_ladies": 629_599_807,
+    "mid_ladies": 490_863_145,
     "mid_sage": 4_836_655_373,
 }
 OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
@@ -96,7 +96,8 @@ def algorithmic_bytes(stage: str, rows: int, nnz: int, ncols: int, pnnz: int = 0
         "dd_place": 4 * E,
         "ld_rows": 20 * R,
         # LADIES by LDS windows (default): the neighbours are read once to build P (ldw_accumulate) and once
-        # to extract (ldw_extract); ldw_bounds is a third pass that moves scratch only
+        # to extract (ldw_extract); ldw_bounds (the rows' window boundaries, copied from the per-graph index)
+        # moves scratch only
         "ldw_accumulate": 4.0 * gathered,
         "ldw_p_copy": 8.0 * pnnz,
         "ldw_draw": 4 * U,
