@@ -44,8 +44,7 @@ constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;
 constexpr int kExtThreads = 1024; // the waves of a workgroup share one hash table
 constexpr int kExtWaves = kExtThreads / kWave;
 constexpr int kAccUnroll = 8;              // 16-byte loads per lane in flight while a wave gathers
-constexpr int kAccLines = 8 * kAccUnroll;  // memory lines per span: 8 lanes per line
-static_assert(kAccLines == 64, "the piece starts of a span are one 64-bit mask");
+constexpr int kAccChunks = kWave * kAccUnroll; // aligned 16-byte chunks per span: one per lane and load
 struct AccPiece {                          // one nonempty piece of a wave's 64 rows
     int64_t origin;                        // byte address of its first line - 128 * lines of the wave before it
     uint32_t lo_rel, hi_rel;               // its bytes, relative to origin
@@ -255,11 +254,10 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
     unsigned long long *claim_s = reinterpret_cast<unsigned long long *>(lds + kWinWords); // [2], in turn: where the
                                            // entries of the current (minibatch, window) start in the staging array
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    // per wave: one record per nonempty piece (by rank) and the start bits of one span of memory lines
-    AccPiece *piece_rec = reinterpret_cast<AccPiece *>(lds + kWinWords + 3 * kAccWaves + 4) + wave * (kWave + 1);
-    uint32_t *starts = reinterpret_cast<uint32_t *>(piece_rec + kWave);
-    const uint64_t below = (1ull << lane) - 1ull;
-    const int octet = lane >> 3, chunk = lane & 7;
+    // per wave: one record per nonempty piece (by rank) and the start bits of one span of chunks
+    AccPiece *piece_rec = reinterpret_cast<AccPiece *>(lds + kWinWords + 3 * kAccWaves + 4) + wave * (kWave + kAccUnroll / 2);
+    uint32_t *starts = reinterpret_cast<uint32_t *>(piece_rec + kWave); // kAccChunks bits
+    const uint64_t below = (1ull << lane) - 1ull, below_incl = below | (1ull << lane);
     const int64_t A0 = (int64_t)reinterpret_cast<uintptr_t>(a.A_col);
     const int64_t nblk = (int64_t)a.k * a.nwin;
     // the counters start at zero and every (minibatch, window) leaves them at zero: the pass that emits the
@@ -328,63 +326,67 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         for (int64_t base = r0 + (int64_t)wave * kWave; base < r1; base += (int64_t)kAccWaves * kWave) {
             // the next 64 pieces are on their way while these are walked
             piece_of(base + (int64_t)kAccWaves * kWave + lane, next_len, next_addr);
-            // A piece is read as the 128-byte memory lines it touches, every line by exactly one instruction: 8 lanes
-            // take a line, 16 aligned bytes each, so an instruction covers 8 lines and never shares a line with
-            // another instruction of the wave (a second access to a line whose fill is still on its way holds the
-            // cache's pipeline up for about the latency of the fill).  The lines of the wave's 64 pieces are
-            // numbered end to end; which piece a line belongs to follows from counting piece starts up to it:
-            // the starts inside the current span of 64 lines are bits in LDS, the pieces' records a small
-            // table in LDS indexed by their rank among the nonempty ones.  Entries of a line outside the piece
-            // (the neighbouring windows' or rows') are masked; an aligned 16-byte read that holds at least one
-            // entry of the piece stays inside that entry's page.
+            // A piece is read as the aligned 16-byte chunks it touches, one chunk per lane and load (four neighbours
+            // per lane keep the number of load instructions, and of the LDS additions behind them, at a quarter of
+            // what one neighbour per lane costs; a compute unit retires such instructions at a fixed pace whatever
+            // number of their lanes is active).  The chunks of the wave's 64 pieces are numbered end to end; which
+            // piece a chunk belongs to follows from counting piece starts up to it: the starts inside the current
+            // span of chunks are bits in LDS, the pieces' records a small table in LDS indexed by their rank among
+            // the nonempty ones.  The entries of a piece's first and last chunk that lie outside the piece (the
+            // neighbouring windows' or rows') are masked; an aligned 16-byte read that holds at least one entry of
+            // the piece stays inside that entry's page.
             const int64_t lo_byte = A0 + addr * 4, hi_byte = lo_byte + (int64_t)len * 4;
-            const int64_t line0 = lo_byte & ~(int64_t)127;
-            const uint32_t nl = len ? (uint32_t)((hi_byte - 1 - line0) >> 7) + 1u : 0u;
-            const uint32_t inc = wave_inclusive_scan(nl);
+            const int64_t chunk0 = lo_byte & ~(int64_t)15;
+            const uint32_t nc = len ? (uint32_t)((hi_byte - 1 - chunk0) >> 4) + 1u : 0u;
+            const uint32_t inc = wave_inclusive_scan(nc);
             const uint32_t total = __shfl(inc, kWave - 1, kWave);
-            const uint32_t ustart = inc - nl;
-            const bool nonempty = nl != 0;
+            const uint32_t ustart = inc - nc;
+            const bool nonempty = nc != 0;
             const uint64_t ne_mask = __ballot(nonempty);
             __builtin_amdgcn_wave_barrier();
             if (nonempty) {
                 AccPiece rec;
-                rec.origin = line0 - (int64_t)ustart * 128; // line j of the wave's order starts at origin + 128 j
+                rec.origin = chunk0 - (int64_t)ustart * 16; // chunk j of the wave's order starts at origin + 16 j
                 rec.lo_rel = (uint32_t)(lo_byte - rec.origin);
                 rec.hi_rel = (uint32_t)(hi_byte - rec.origin);
                 piece_rec[__popcll(ne_mask & below)] = rec;
             }
-            for (uint32_t u0 = 0; u0 < total; u0 += kAccLines) {
+            for (uint32_t u0 = 0; u0 < total; u0 += kAccChunks) {
                 __builtin_amdgcn_wave_barrier();
-                if (lane < 2)
+                if (lane < 2 * kAccUnroll)
                     starts[lane] = 0;
                 __builtin_amdgcn_wave_barrier();
                 const uint32_t rel = ustart - u0; // wraps for pieces that start before the span
-                if (nonempty && rel < (uint32_t)kAccLines)
+                if (nonempty && rel < (uint32_t)kAccChunks)
                     atomicOr(starts + (rel >> 5), 1u << (rel & 31u));
                 __builtin_amdgcn_wave_barrier();
-                const uint64_t m = (uint64_t)starts[0] | ((uint64_t)starts[1] << 32);
-                const int rank0 = __popcll(__ballot(nonempty && ustart < u0)) - 1; // piece that holds line u0 - 1
-                uint4 v[kAccUnroll];
+                int rank = __popcll(__ballot(nonempty && ustart < u0)) - 1; // piece that holds chunk u0 - 1
+                uint4 v[kAccUnroll] = {};
                 uint32_t keep = 0; // 4 bits per step: which of the 4 entries belong to the piece
 #pragma unroll
                 for (int u = 0; u < kAccUnroll; ++u) {
-                    const uint32_t jj = (uint32_t)(u * 8 + octet), j = u0 + jj;
-                    const int mine = rank0 + __popcll(m & ((2ull << jj) - 1ull));
+                    if (u0 + (uint32_t)(u * kWave) >= total) // (the same for all lanes)
+                        break;
+                    const uint32_t j = u0 + (uint32_t)(u * kWave + lane);
+                    const uint64_t m = reinterpret_cast<const uint64_t *>(starts)[u];
+                    const int mine = rank + __popcll(m & below_incl);
+                    rank += __popcll(m);
                     v[u] = make_uint4(0, 0, 0, 0);
                     if (j < total) {
                         const AccPiece rec = piece_rec[mine];
-                        const uint32_t off = j * 128u + (uint32_t)chunk * 16u; // of the lane's 16 bytes, from origin
+                        const uint32_t off = j * 16u; // of the lane's 16 bytes, from origin
                         uint32_t k4 = 0;
 #pragma unroll
                         for (uint32_t e = 0; e < 4; ++e)
                             k4 |= (off + 4u * e >= rec.lo_rel && off + 4u * e < rec.hi_rel) ? 1u << e : 0u;
-                        if (k4)
-                            v[u] = *reinterpret_cast<const uint4 *>(rec.origin + (int64_t)off);
+                        v[u] = *reinterpret_cast<const uint4 *>(rec.origin + (int64_t)off);
                         keep |= k4 << (4 * u);
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < kAccUnroll; ++u) {
+                    if (u0 + (uint32_t)(u * kWave) >= total)
+                        break;
                     const uint32_t xs[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
@@ -848,7 +850,7 @@ __global__ __launch_bounds__(256) void ldw_extract_copy_kernel(LwHop a)
 // ---------------------------------------------------------------------------------------------
 size_t ldw_accumulate_lds_bytes()
 {
-    return (size_t)(kWinWords + 3 * kAccWaves + 4) * sizeof(uint32_t) + (size_t)kAccWaves * (kWave + 1) * sizeof(AccPiece);
+    return (size_t)(kWinWords + 3 * kAccWaves + 4) * sizeof(uint32_t) + (size_t)kAccWaves * (kWave + kAccUnroll / 2) * sizeof(AccPiece);
 }
 
 static void launch_ldw_tiles(const Launch &L, const LwHop &a)
