@@ -727,13 +727,15 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
     const int64_t nrows = a.mb_rowoff[a.k];
     // tiles cost very different amounts (one long piece, or many short rows): the minibatch's tiles go to
     // whichever of its waves is free, off a shared counter, until none is left
-    while (true) {
-        int64_t t = 0;
+    // A wave's first tile is its own number among the minibatch's waves; the counter hands out the tiles after
+    // those.  The next tile is asked for before the current one is worked on, so that the answer (a trip to the
+    // counter's home in memory, shared by all waves of the minibatch) is there when it is needed.
+    const int64_t nwaves = (int64_t)gridDim.x * kExtWaves;
+    int64_t t = (int64_t)blockIdx.x * kExtWaves + tid / kWave;
+    while (t < ntiles) {
+        int64_t t_next = 0;
         if (lane == 0)
-            t = (int64_t)atomicAdd(a.tile_queue + i, 1ull);
-        t = __shfl(t, 0, kWave);
-        if (t >= ntiles)
-            break;
+            t_next = nwaves + (int64_t)atomicAdd(a.tile_queue + i, 1ull);
         const int64_t g0 = a.mb_goff[i] + t * a.tile;
         const int64_t g1 = min(g0 + a.tile, a.mb_goff[i + 1]);
         ldw_walk_tile(a, g0, g1, a.tile_row[x0 + t], nrows,
@@ -812,6 +814,7 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
                     atomicAdd(&rowcnt[r], (unsigned long long)kept);
             }
         });
+        t = __shfl(t_next, 0, kWave);
     }
 }
 
