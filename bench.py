@@ -33,36 +33,36 @@ HBM_PEAK_GBS = 8000.0
 # the line "bench constant ..." of profiles/<workload>_hbm_traffic.txt (tests/test_bench_constants.py compares
 # them); a kernel that has changed since its profile was taken has no entry (None in the output).
 MEASURED_TRAFFIC = {
-    ("dense_ladies", "ldw_accumulate"): 3_297_510_409,
-    ("dense_ladies", "ldw_extract"): 2_044_954_418,
-    ("dense_sage", "nw_sample"): 10_771_843_227,
-    ("dense_sage", "nw_rows"): 1_379_481_513,
-    ("dense_sage", "dd_split"): 1_126_571_515,
-    ("dense_sage", "dd_unsplit"): 963_112_969,
-    ("dense_sage", "dd_rank"): 875_177_261,
-    ("dense_sage", "dd_front"): 616_755_712,
-    ("large_sage", "nw_sample"): 5_987_876_772,
-    ("large_sage", "nw_rows"): 1_648_071_323,
-    ("large_sage", "dd_split"): 740_678_125,
-    ("large_sage", "dd_unsplit"): 649_420_918,
-    ("large_sage", "dd_rank"): 598_387_163,
-    ("large_sage", "dd_front"): 473_538_464,
-    ("mid_ladies", "ldw_accumulate"): 148_744_475,
-    ("mid_ladies", "ldw_extract"): 89_763_702,
-    ("mid_sage", "nw_sample"): 3_183_651_204,
-    ("mid_sage", "dd_split"): 423_725_540,
-    ("mid_sage", "dd_unsplit"): 358_696_429,
-    ("mid_sage", "nw_rows"): 352_067_442,
-    ("mid_sage", "dd_rank"): 313_301_188,
-    ("mid_sage", "dd_front"): 204_167_876,
+    ("dense_ladies", "ldw_accumulate"): 3_297_627_904,
+    ("dense_ladies", "ldw_extract"): 2_029_215_597,
+    ("dense_sage", "nw_sample"): 10_725_904_571,
+    ("dense_sage", "nw_rows"): 1_381_015_908,
+    ("dense_sage", "dd_split"): 1_126_015_387,
+    ("dense_sage", "dd_unsplit"): 963_375_990,
+    ("dense_sage", "dd_rank"): 875_149_545,
+    ("dense_sage", "dd_front"): 616_750_034,
+    ("large_sage", "nw_sample"): 5_886_878_400,
+    ("large_sage", "nw_rows"): 1_649_178_816,
+    ("large_sage", "dd_split"): 740_682_377,
+    ("large_sage", "dd_unsplit"): 650_024_790,
+    ("large_sage", "dd_rank"): 598_381_572,
+    ("large_sage", "dd_front"): 473_549_613,
+    ("mid_ladies", "ldw_accumulate"): 148_751_209,
+    ("mid_ladies", "ldw_extract"): 85_118_710,
+    ("mid_sage", "nw_sample"): 3_141_252_768,
+    ("mid_sage", "dd_split"): 423_528_909,
+    ("mid_sage", "dd_unsplit"): 358_784_100,
+    ("mid_sage", "nw_rows"): 351_990_637,
+    ("mid_sage", "dd_rank"): 315_096_384,
+    ("mid_sage", "dd_front"): 204_173_842,
 }
 # the same summed over every kernel of one bulk call (bytes per step)
 MEASURED_CALL_TRAFFIC = {
-    "dense_ladies": 9_690_704_534,
-    "dense_sage": 15_735_199_405,
-    "large_sage": 10_101_181_440,
-    "mid_ladies": 490_863_145,
-    "mid_sage": 4_836_655_373,
+    "dense_ladies": 9_675_852_800,
+    "dense_sage": 15_691_478_322,
+    "large_sage": 10_002_606_454,
+    "mid_ladies": 486_049_664,
+    "mid_sage": 4_795_596_182,
 }
 OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
 
