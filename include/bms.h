@@ -144,6 +144,11 @@ int bms_csr_load(const int64_t *rowptr, const int32_t *col, int64_t n, int64_t n
 /* n, nnz and the largest row length of a loaded matrix (any pointer may be NULL). */
 int bms_csr_info(const bms_csr *csr, int64_t *n, int64_t *nnz, int64_t *max_degree);
 
+/* Bytes of device memory the handle holds at this moment beyond the caller's arrays: its own copy of the matrix (if
+ * it made one), the scratch of the calls made so far (kept for the next call, bounded by bms_opts.scratch_limit) and
+ * the window index of bms_sample_ladies.  All of it goes back with bms_free(csr). */
+int bms_csr_held_bytes(const bms_csr *csr, int64_t *bytes);
+
 /*
  * Bulk node-wise (GraphSAGE) sampling, Sec. 4.1 with the stacking of Eq. 1.
  *   k, L    : 1 <= k <= 65535 minibatches per call, 1 <= L <= 15 hops (else BMS_EINVAL)

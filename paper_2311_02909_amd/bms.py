@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         L.bms_csr_load.restype = C.c_int
         L.bms_csr_load.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_void_p)]
+        L.bms_csr_held_bytes.restype = C.c_int
+        L.bms_csr_held_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         L.bms_csr_info.restype = C.c_int
         L.bms_csr_info.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         for fn in (L.bms_sample_nodewise, L.bms_sample_ladies):
@@ -231,6 +233,12 @@ class Csr:
         a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
         _check(lib().bms_csr_info(h, C.byref(a), C.byref(b), C.byref(c)))
         self.n, self.nnz, self.max_degree = a.value, b.value, c.value
+
+    def held_bytes(self) -> int:
+        """bms_csr_held_bytes: device memory the handle holds beyond the caller's arrays."""
+        v = C.c_int64()
+        _check(lib().bms_csr_held_bytes(self.handle, C.byref(v)))
+        return v.value
 
     def free(self):
         if getattr(self, "handle", None):

@@ -1462,6 +1462,17 @@ int bms_csr_info(const bms_csr *csr, int64_t *n, int64_t *nnz, int64_t *max_degr
     return BMS_OK;
 }
 
+int bms_csr_held_bytes(const bms_csr *csr, int64_t *bytes)
+{
+    if (!csr || csr->tag != kTagCsr || !bytes)
+        return fail(BMS_EINVAL, "not a csr handle, or no place for the answer");
+    size_t sum = 0;
+    for (const DevBuf *b : csr->bufs)
+        sum += b->p ? b->cap : 0;
+    *bytes = (int64_t)sum;
+    return BMS_OK;
+}
+
 int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *fanouts, int32_t L,
                         uint64_t seed, const bms_opts *opts, bms_result **out)
 {

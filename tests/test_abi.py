@@ -74,6 +74,6 @@ def test_header_compiles_as_c_and_cpp_and_structs_match_the_binding(tmp_path):
     # and the flag values the binding hard-codes are the header's
     text = open(os.path.join(inc, "bms.h")).read()
     for name in ("LADIES_SQUARED", "PROFILE", "EXTRACT_BUCKETS", "EXTRACT_BITMAP", "EXTRACT_SORT", "LADIES_DENSE",
-                 "PROFILE_MAIN", "UNION_DST", "NODEWISE_REPLACE", "ASYNC"):
+                 "PROFILE_MAIN", "UNION_DST", "NODEWISE_REPLACE", "ASYNC", "LADIES_NO_INDEX"):
         m = re.search(r"#define\s+BMS_%s\s+(\d+)u" % name, text)
         assert m and int(m.group(1)) == getattr(bms, name), name

@@ -136,3 +136,50 @@ def test_largest_batches_of_each_kernel_path(mods, b):
     ref = O.sample_ladies(rowptr, col, batches, (300, 100), 4)
     res = bms.sample_ladies(bms.Csr(g.rowptr, g.col), torch.from_numpy(batches).cuda(), (300, 100), 4)
     assert_hops_equal(res.hops(), ref, with_p=True, what="b=%d" % b)
+
+
+def test_window_index_is_built_once_when_it_fits_and_left_out_when_it_does_not(mods):
+    # the index of where adjacency lists cross the window boundaries: n * (windows + 1) 32-bit words held by the
+    # handle after the first call that may build it; not built under BMS_LADIES_NO_INDEX, with a scratch limit
+    # whose quarter it exceeds, or for a graph whose column array is less than half its size; same results always
+    O, bms, synth = mods
+    g = synth.rmat_graph(300_000, 2_000_000, 0.55, 0.2, 0.2, seed=5, device="cuda")
+    rowptr, col = g.rowptr.cpu().numpy(), g.col.cpu().numpy()
+    rng = np.random.default_rng(77)
+    batches = random_batches(g.n, 4, 200, rng)
+    s = (150, 100)
+    ref = O.sample_ladies(rowptr, col, batches, s, 8)
+    index_bytes = g.n * ((g.n + 65535) // 65536 + 1) * 4
+    dev_batches = torch.from_numpy(batches).cuda()
+
+    csr = bms.Csr(g.rowptr, g.col)
+    res = bms.sample_ladies(csr, dev_batches, s, 8, index=False)
+    assert_hops_equal(res.hops(), ref, with_p=True, what="no index")
+    without = csr.held_bytes()
+    res = bms.sample_ladies(csr, dev_batches, s, 8)
+    assert_hops_equal(res.hops(), ref, with_p=True, what="index built by this call")
+    held = csr.held_bytes()
+    assert held >= without + index_bytes - (g.n * 6 * 4) // 2  # the per-hop lists shrink to half without their row-major copy
+    res = bms.sample_ladies(csr, dev_batches, s, 8, recycle=res)
+    assert_hops_equal(res.hops(), ref, with_p=True, what="index reused")
+    assert csr.held_bytes() == held
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        res = bms.sample_ladies(csr, dev_batches, s, 9, stream=stream.cuda_stream)
+    assert_hops_equal(res.hops(), O.sample_ladies(rowptr, col, batches, s, 9), with_p=True, what="index on another stream")
+
+    small = bms.Csr(g.rowptr, g.col)
+    res = bms.sample_ladies(small, dev_batches, s, 8, scratch_limit=3 * index_bytes)
+    assert_hops_equal(res.hops(), ref, with_p=True, what="scratch limit of three times the index")
+    assert small.held_bytes() < index_bytes + without
+
+    # average degree 0.5: the index would be four times the column array
+    rng = np.random.default_rng(78)
+    rp, cl = random_csr(70_000, 0.5, rng)
+    bt = random_batches(70_000, 3, 100, rng)
+    sparse = bms.Csr(torch.from_numpy(rp).cuda(), torch.from_numpy(cl).cuda())
+    res = bms.sample_ladies(sparse, torch.from_numpy(bt).cuda(), (50, 50), 3)
+    assert_hops_equal(res.hops(), O.sample_ladies(rp, cl, bt, (50, 50), 3), with_p=True, what="sparse graph")
+    plain = bms.Csr(torch.from_numpy(rp).cuda(), torch.from_numpy(cl).cuda())
+    bms.sample_ladies(plain, torch.from_numpy(bt).cuda(), (50, 50), 3, index=False)
+    assert sparse.held_bytes() == plain.held_bytes()
