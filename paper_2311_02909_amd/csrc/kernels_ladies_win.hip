@@ -408,45 +408,17 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
         turn ^= 1;
         const int64_t part = blk * kWinParts + wave;
         uint32_t nz = 0;
-        uint64_t wt = 0;
-        if (added_blk > (uint32_t)(kWinWords / 4)) { // more than one neighbour per 8 counters
-            // most counters are nonzero: word by word, the nonzero ones of 64 consecutive words packed by a ballot,
-            // so that every store instruction writes a run of consecutive entries
-            int64_t run = claimed;
-            for (int it0 = 0; it0 < kWaveWords / kWave; it0 += 4) {
-                uint32_t x[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    x[q] = cnt[wave * kWaveWords + (it0 + q) * kWave + lane];
-                    if (x[q])
-                        cnt[wave * kWaveWords + (it0 + q) * kWave + lane] = 0;
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int word = wave * kWaveWords + (it0 + q) * kWave + lane;
-                    const uint32_t lo = x[q] & 0xFFFFu, hi = x[q] >> 16;
-                    const uint64_t mlo = __ballot(lo != 0), mhi = __ballot(hi != 0);
-                    if ((mlo | mhi) == 0)
-                        continue;
-                    wt += ldw_weight(lo, a.squared) + ldw_weight(hi, a.squared);
-                    int64_t pos = run + __popcll(mlo & below) + __popcll(mhi & below);
-                    if (lo) {
-                        a.tmp_ent[pos] = (uint32_t)(2 * word) << 16 | lo;
-                        ++pos;
-                    }
-                    if (hi)
-                        a.tmp_ent[pos] = (uint32_t)(2 * word + 1) << 16 | hi;
-                    const uint32_t step = (uint32_t)(__popcll(mlo) + __popcll(mhi));
-                    run += step;
-                    nz += step;
-                }
-            }
-        } else if (added_blk) {
-            // few: 16 bytes (8 counters) per lane and access; a group of 64 such quads without any counter costs
-            // one LDS read
+        uint32_t w32 = 0; // e_v: at most 64 values below 2^16 per lane
+        uint64_t w64 = 0; // e_v^2
+        if (added_blk) {
+            // 16 bytes (8 counters) per lane and access: the lanes' counts of nonzero counters are scanned, every lane
+            // writes its own run; a group of 64 such quads without any counter costs one LDS read.  (Packing the
+            // nonzero counters of 64 consecutive words by ballots instead, so that a store instruction writes one
+            // run of consecutive entries, took four times the steps and more instructions per counter: 9 us
+            // against 6 per full window.)
             constexpr int kQuadIts = kWaveWords / 4 / kWave; // quads per lane
             uint4 *mine4 = reinterpret_cast<uint4 *>(cnt + wave * kWaveWords);
-            const int64_t run0 = claimed;
+            uint32_t *__restrict__ out = a.tmp_ent + claimed;
 #pragma unroll
             for (int it = 0; it < kQuadIts; ++it) {
                 const uint4 q = mine4[it * kWave + lane];
@@ -460,21 +432,24 @@ __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
                 if (c)
                     mine4[it * kWave + lane] = make_uint4(0, 0, 0, 0);
                 const uint32_t inc = wave_inclusive_scan_dpp(c);
-                int64_t pos = run0 + nz + (inc - c);
+                uint32_t pos = nz + (inc - c);
                 nz += (uint32_t)__builtin_amdgcn_readlane((int)inc, kWave - 1);
                 const uint32_t col0 = 2u * (uint32_t)(wave * kWaveWords + 4 * (it * kWave + lane)); // within the window
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const uint32_t lo = xs[u] & 0xFFFFu, hi = xs[u] >> 16;
-                    wt += ldw_weight(lo, a.squared) + ldw_weight(hi, a.squared);
+                    if (a.squared)
+                        w64 += (uint64_t)(lo * lo) + (uint64_t)(hi * hi);
+                    else
+                        w32 += lo + hi;
                     if (lo)
-                        a.tmp_ent[pos++] = (col0 + 2 * u) << 16 | lo;
+                        out[pos++] = (col0 + 2 * u) << 16 | lo;
                     if (hi)
-                        a.tmp_ent[pos++] = (col0 + 2 * u + 1) << 16 | hi;
+                        out[pos++] = (col0 + 2 * u + 1) << 16 | hi;
                 }
             }
         }
-        wt = wave_sum(wt);
+        const uint64_t wt = wave_sum(a.squared ? w64 : (uint64_t)w32);
         if (lane == 0) {
             a.part_base[part] = claimed;
             a.part_cnt[part] = nz;
