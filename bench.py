@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 # the line "bench constant ..." of profiles/<workload>_hbm_traffic.txt (tests/test_bench_constants.py compares
 # them); a kernel that has changed since its profile was taken has no entry (None in the output).
 MEASURED_TRAFFIC = {
-    ("dense_ladies", "ldw_accumulate"): 3_297_627_904,
-    ("dense_ladies", "ldw_extract"): 2_029_215_597,
+    ("dense_ladies", "ldw_accumulate"): 3_303_733_883,
+    ("dense_ladies", "ldw_extract"): 2_029_111_515,
     ("dense_sage", "nw_sample"): 10_725_904_571,
     ("dense_sage", "nw_rows"): 1_381_015_908,
     ("dense_sage", "dd_split"): 1_126_015_387,
@@ -47,8 +47,8 @@ MEASURED_TRAFFIC = {
     ("large_sage", "dd_unsplit"): 650_024_790,
     ("large_sage", "dd_rank"): 598_381_572,
     ("large_sage", "dd_front"): 473_549_613,
-    ("mid_ladies", "ldw_accumulate"): 148_751_209,
-    ("mid_ladies", "ldw_extract"): 85_118_710,
+    ("mid_ladies", "ldw_accumulate"): 148_752_374,
+    ("mid_ladies", "ldw_extract"): 85_112_064,
     ("mid_sage", "nw_sample"): 3_141_252_768,
     ("mid_sage", "dd_split"): 423_528_909,
     ("mid_sage", "dd_unsplit"): 358_784_100,
@@ -58,10 +58,10 @@ MEASURED_TRAFFIC = {
 }
 # the same summed over every kernel of one bulk call (bytes per step)
 MEASURED_CALL_TRAFFIC = {
-    "dense_ladies": 9_675_852_800,
+    "dense_ladies": 9_681_670_125,
     "dense_sage": 15_691_478_322,
     "large_sage": 10_002_606_454,
-    "mid_ladies": 486_049_664,
+    "mid_ladies": 486_088_333,
     "mid_sage": 4_795_596_182,
 }
 OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
