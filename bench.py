@@ -136,6 +136,13 @@ def main() -> int:
     ap.add_argument("--gather-probe", type=int, default=0, metavar="LOG2",
                     help="instead of the benchmark, time 2^28 random 4-byte reads (torch.index_select) over an int32 "
                          "array of 2^LOG2 elements, 5 launches: the chip's rate for reads that share no memory line")
+    ap.add_argument("--line-probe", type=int, default=0, metavar="LOG2",
+                    help="instead of the benchmark, time reads of 2^24 short rows (1 and 8 four-byte entries) that start "
+                         "at random places of an int32 array of 2^LOG2 elements, one row per lane (libbms_probe.so): "
+                         "the chip's rate of 128-byte memory lines for the access pattern of the node-wise kernels")
+    ap.add_argument("--lds-probe", action="store_true",
+                    help="instead of the benchmark, time LDS adds and stores at random places of 128 KB by 16 waves per "
+                         "compute unit (libbms_probe.so): what one LDS instruction of a wave costs its compute unit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -156,6 +163,59 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read_per_launch": src.numel() * 4,
                           "copy_probe_bytes_written_per_launch": src.numel() * 4, "launches": 5}))
+        return 0
+    if args.line_probe or args.lds_probe:
+        import ctypes as C
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2311_02909_amd", "libbms_probe.so")
+        if not os.path.exists(path):
+            print("bench.py: %s is not built (python paper_2311_02909_amd/build.py)" % path, file=sys.stderr)
+            return 2
+        P = C.CDLL(path)
+        stream = torch.cuda.current_stream().cuda_stream
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        if args.line_probe:
+            span, nrows = 1 << args.line_probe, 1 << 24
+            array = torch.zeros(span + 64, dtype=torch.int32, device="cuda")
+            start = torch.randint(0, span, (nrows,), dtype=torch.int64, device="cuda",
+                                  generator=torch.Generator(device="cuda").manual_seed(1))
+            sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+            P.bms_probe_random_rows.restype = C.c_int
+            P.bms_probe_random_rows.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                                C.c_void_p, C.c_void_p]
+            out = {"line_probe_span_bytes": span * 4, "rows_per_launch": nrows, "launches": 6, "workgroups": cus * 8}
+            for entries in (1, 8):
+                def launch():
+                    rc = P.bms_probe_random_rows(array.data_ptr(), span + 64, start.data_ptr(), nrows, entries, cus * 8,
+                                                 sink.data_ptr(), stream)
+                    assert rc == 0
+                launch()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(5):
+                    launch()
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / 5
+                # a row of 32 bytes at a random 4-byte aligned place lies in one line 100/128 of the time, else in two
+                lines = nrows * (1.0 if entries == 1 else 1.0 + 28.0 / 128.0)
+                out["rows_of_%d" % entries] = {"ms_per_launch": round(ms, 4), "rows_per_sec": nrows / ms * 1e3,
+                                               "lines_per_sec": lines / ms * 1e3,
+                                               "tb_per_sec_at_128B_per_line": lines * 128 / ms / 1e9}
+            print(json.dumps(out))
+            return 0
+        P.bms_probe_lds_ops.restype = C.c_int
+        P.bms_probe_lds_ops.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        ticks = torch.zeros(cus, dtype=torch.int32, device="cuda")
+        iters, out = 200, {"lds_probe_waves_per_cu": 16, "wave_instructions_per_wave": 200 * 16, "lds_bytes": 131072}
+        for mode, name in ((0, "add16_random"), (1, "store32_random")):
+            for every in (1, 2, 4):
+                for _ in range(2):
+                    assert P.bms_probe_lds_ops(ticks.data_ptr(), cus, iters, mode, every, stream) == 0
+                torch.cuda.synchronize()
+                ns = float(ticks.to(torch.float64).mean().item()) * 10.0   # 100 MHz ticks
+                out["%s_1_lane_in_%d" % (name, every)] = {"ns_per_wave_instruction_per_cu": round(ns / (16.0 * iters * 16), 3)}
+        print(json.dumps(out))
         return 0
     if args.gather_probe:
         span, reads = 1 << args.gather_probe, 1 << 28
@@ -298,12 +358,14 @@ def run_workload(workload: str, steps: int, warmup: int, variant: str, cpu: bool
     }
     if dominant == "nw_sample":
         # what bounds this kernel is memory lines per second, not bytes asked for: every sampled neighbour of a long
-        # row is a 4-byte read that costs one 128-byte line.  Reads that share no line run at 3.87e10 /s on this chip
-        # (bench.py --gather-probe 31, profiles/random_gather_probe.txt); short rows and minibatches that work on
-        # the same id range at the same time share lines, which is how the kernel gets past that rate
+        # row is a 4-byte read that costs one 128-byte line.  Short rows at random places are read at 4.72e10 lines/s
+        # on this chip (bench.py --line-probe 30, profiles/random_line_probe.txt); the kernel's own lines per
+        # second follow from its fabric traffic
+        lines = MEASURED_TRAFFIC.get((traffic_key, dominant))
         roofline["sampled_reads"] = {
             "per_sec": round(edges / (dom["ms"] * 1e-3), 1),
-            "gather_probe_reads_per_sec": 3.87e10,   # reads that share no line with another (a measured rate, no ceiling)
+            "lines_per_sec": round(lines / 128.0 / (dom["ms"] * 1e-3), 1) if lines else None,
+            "line_probe_lines_per_sec": 4.72e10,   # reads of short rows that share no line (measured ceiling)
         }
     # whole call: algorithmic bytes of all stages ("effective") and the profiled HBM bytes ("achieved"),
     # both over the sum of the kernel times measured in this run

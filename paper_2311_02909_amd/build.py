@@ -54,6 +54,22 @@ def build_lib(verbose: bool = False, incremental: bool = False) -> str:
     return LIB
 
 
+PROBE_SRC = os.path.join(HERE, "csrc_probe", "probes.hip")
+PROBE_LIB = os.path.join(HERE, "libbms_probe.so")
+
+
+def build_probes(verbose: bool = False) -> str:
+    """The rate probes of bench.py (--line-probe, --lds-probe): a library of their own, paper_2311_02909_amd/libbms_probe.so."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = PROBE_LIB + ".tmp%d" % os.getpid()
+    cmd = [hipcc] + HIPCC_FLAGS + ["-shared", "-o", tmp, PROBE_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, PROBE_LIB)
+    return PROBE_LIB
+
+
 C_CLIENT_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "bms_c_client.c")
 C_CLIENT = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "bms_c_client")
 
@@ -74,4 +90,5 @@ def build_c_client(verbose: bool = False) -> str:
 if __name__ == "__main__":
     import sys
     print(build_lib(verbose=True, incremental="--incremental" in sys.argv))
+    print(build_probes(verbose=True))
     print(build_c_client(verbose=True))

@@ -3,6 +3,8 @@ import ctypes
 import os
 import re
 
+import pytest
+
 from paper_2311_02909_amd import bms
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -77,3 +79,18 @@ def test_header_compiles_as_c_and_cpp_and_structs_match_the_binding(tmp_path):
                  "PROFILE_MAIN", "UNION_DST", "NODEWISE_REPLACE", "ASYNC", "LADIES_NO_INDEX"):
         m = re.search(r"#define\s+BMS_%s\s+(\d+)u" % name, text)
         assert m and int(m.group(1)) == getattr(bms, name), name
+
+
+def test_probe_library_exports_its_two_entry_points():
+    # the rate probes behind `bench.py --line-probe / --lds-probe` live in a library of their own
+    import ctypes
+    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2311_02909_amd", "libbms_probe.so")
+    if not os.path.exists(path):
+        pytest.skip("libbms_probe.so is not built (python paper_2311_02909_amd/build.py)")
+    P = ctypes.CDLL(path)
+    for name in ("bms_probe_random_rows", "bms_probe_lds_ops"):
+        assert hasattr(P, name), name
+    # arguments are checked before anything is launched
+    P.bms_probe_random_rows.restype = ctypes.c_int
+    assert P.bms_probe_random_rows(None, 0, None, 0, 3, 0, None, None) == -1
+    assert P.bms_probe_lds_ops(None, 0, 0, 5, 0, None) == -1
