@@ -317,31 +317,54 @@ __global__ __launch_bounds__(kRankThreads) void dd_rank_kernel(DedupArgs a)
         return;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t nseg = (int64_t)a.k * a.C;
-    for (int64_t w = blockIdx.x; w < nseg; w += gridDim.x) {
-        // workgroups that run at the same time take segments of different minibatches
-        const int64_t i = w % a.k;
-        const uint32_t cseg = (uint32_t)(w / a.k);
-        const int64_t sg = i * a.C + cseg;
-        const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
-        const uint32_t s0 = soff[cseg], m = soff[cseg + 1] - s0;
-        if (m > (uint32_t)kRankCap)
-            continue; // listed for the bitmap kernel by the scan
-        if (m == 0) {
-            if (tid == 0)
-                a.seg_cnt[sg] = 0;
-            continue;
+    // The ids of the segment after this one are fetched while this one is ranked (a workgroup's segments follow one
+    // another as chains of dependent steps, and only two workgroups fit a compute unit).
+    // where segment w lies: first slot, ids, where its minibatch's ids start
+    auto where = [&](int64_t w, uint32_t &s0, uint32_t &m, int64_t &e0) {
+        s0 = m = 0;
+        e0 = 0;
+        if (w < nseg) {
+            const int64_t i = w % a.k; // workgroups that run at the same time take segments of different minibatches
+            const uint32_t cseg = (uint32_t)(w / a.k);
+            const uint32_t *__restrict__ soff = a.seg_off + i * (a.C + 1);
+            s0 = soff[cseg];
+            m = soff[cseg + 1] - s0;
+            e0 = a.mb_edgeoff[i];
         }
-        const int64_t e0 = a.mb_edgeoff[i];
+    };
+    // its ids as the kernel keeps them: slot j = q NT + tid, unused slots all ones (no segment, or one that another
+    // kernel ranks: nothing is read)
+    auto fetch = [&](uint32_t s0, uint32_t m, int64_t e0, uint32_t (&key)[PER]) {
         const uint32_t *__restrict__ ids = a.ids_seg + e0 + s0;
-        uint32_t id0;
-        int wbits;
-        seg_range(a, cseg, id0, wbits);
-        uint32_t key[PER];
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
             const uint32_t j = q * NT + tid;
-            key[q] = j < m ? ids[j] - id0 : 0xFFFFFFFFu;
+            key[q] = (m <= (uint32_t)kRankCap && j < m) ? ids[j] : 0xFFFFFFFFu;
         }
+    };
+    uint32_t s0, m, s0_next, m_next;
+    int64_t e0, e0_next;
+    uint32_t key[PER], key_next[PER];
+    where(blockIdx.x, s0, m, e0);
+    fetch(s0, m, e0, key);
+    for (int64_t w = blockIdx.x; w < nseg; w += gridDim.x, s0 = s0_next, m = m_next, e0 = e0_next) {
+        where(w + gridDim.x, s0_next, m_next, e0_next);
+        const int64_t i = w % a.k;
+        const uint32_t cseg = (uint32_t)(w / a.k);
+        const int64_t sg = i * a.C + cseg;
+        if (m > (uint32_t)kRankCap || m == 0) { // listed for the bitmap kernel by the scan, or empty
+            if (m == 0 && tid == 0)
+                a.seg_cnt[sg] = 0;
+            fetch(s0_next, m_next, e0_next, key);
+            continue;
+        }
+        uint32_t id0;
+        int wbits;
+        seg_range(a, cseg, id0, wbits);
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+            if (key[q] != 0xFFFFFFFFu)
+                key[q] -= id0;
         // buckets: a power of two >= m, 512..4096, no more than the segment has ids
         int nbits = 32 - __clz(m - 1u); // ceil(log2 m); m = 1: __clz(0) = 32
         if (m == 1u || nbits < 9)
@@ -360,6 +383,7 @@ __global__ __launch_bounds__(kRankThreads) void dd_rank_kernel(DedupArgs a)
         for (uint32_t x = tid; x < (m + 31u) / 32u; x += NT)
             hbits[x] = 0;
         __syncthreads();
+        fetch(s0_next, m_next, e0_next, key_next);
         uint32_t slot[PER];
 #pragma unroll
         for (int q = 0; q < PER; ++q)
@@ -395,6 +419,9 @@ __global__ __launch_bounds__(kRankThreads) void dd_rank_kernel(DedupArgs a)
                 else
                     atomicOr(a.fallback, 1);
             }
+#pragma unroll
+            for (int q = 0; q < PER; ++q)
+                key[q] = key_next[q];
             continue;
         }
         uint32_t run = 0;
@@ -479,6 +506,9 @@ __global__ __launch_bounds__(kRankThreads) void dd_rank_kernel(DedupArgs a)
         uint32_t *__restrict__ uids = a.uids + e0 + s0;
         for (uint32_t r = tid; r < cnt_distinct; r += NT)
             uids[r] = id0 + sorted[r];
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+            key[q] = key_next[q];
         __syncthreads();
     }
 }
