@@ -35,34 +35,34 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC = {
     ("dense_ladies", "ldw_accumulate"): 3_303_733_883,
     ("dense_ladies", "ldw_extract"): 2_029_111_515,
-    ("dense_sage", "nw_sample"): 10_725_904_571,
-    ("dense_sage", "nw_rows"): 1_381_015_908,
-    ("dense_sage", "dd_split"): 1_126_015_387,
-    ("dense_sage", "dd_unsplit"): 963_375_990,
-    ("dense_sage", "dd_rank"): 875_149_545,
-    ("dense_sage", "dd_front"): 616_750_034,
-    ("large_sage", "nw_sample"): 5_886_878_400,
-    ("large_sage", "nw_rows"): 1_649_178_816,
-    ("large_sage", "dd_split"): 740_682_377,
-    ("large_sage", "dd_unsplit"): 650_024_790,
-    ("large_sage", "dd_rank"): 598_381_572,
-    ("large_sage", "dd_front"): 473_549_613,
+    ("dense_sage", "nw_sample"): 10_725_266_816,
+    ("dense_sage", "nw_rows"): 1_381_184_365,
+    ("dense_sage", "dd_split"): 1_126_002_752,
+    ("dense_sage", "dd_unsplit"): 962_654_500,
+    ("dense_sage", "dd_rank"): 875_334_642,
+    ("dense_sage", "dd_front"): 616_757_746,
+    ("large_sage", "nw_sample"): 5_907_070_889,
+    ("large_sage", "nw_rows"): 1_649_367_766,
+    ("large_sage", "dd_split"): 740_625_197,
+    ("large_sage", "dd_unsplit"): 649_595_373,
+    ("large_sage", "dd_rank"): 599_131_113,
+    ("large_sage", "dd_front"): 473_539_835,
     ("mid_ladies", "ldw_accumulate"): 148_752_374,
     ("mid_ladies", "ldw_extract"): 85_112_064,
-    ("mid_sage", "nw_sample"): 3_141_252_768,
-    ("mid_sage", "dd_split"): 423_528_909,
-    ("mid_sage", "dd_unsplit"): 358_784_100,
-    ("mid_sage", "nw_rows"): 351_990_637,
-    ("mid_sage", "dd_rank"): 315_096_384,
-    ("mid_sage", "dd_front"): 204_173_842,
+    ("mid_sage", "nw_sample"): 3_146_607_341,
+    ("mid_sage", "dd_split"): 423_537_353,
+    ("mid_sage", "dd_unsplit"): 358_643_373,
+    ("mid_sage", "nw_rows"): 352_049_545,
+    ("mid_sage", "dd_rank"): 315_079_177,
+    ("mid_sage", "dd_front"): 204_167_108,
 }
 # the same summed over every kernel of one bulk call (bytes per step)
 MEASURED_CALL_TRAFFIC = {
     "dense_ladies": 9_681_670_125,
-    "dense_sage": 15_691_478_322,
-    "large_sage": 10_002_606_454,
+    "dense_sage": 15_690_468_000,
+    "large_sage": 10_023_240_850,
     "mid_ladies": 486_088_333,
-    "mid_sage": 4_795_596_182,
+    "mid_sage": 4_800_853_732,
 }
 OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
 
