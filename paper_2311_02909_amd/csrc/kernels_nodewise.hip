@@ -258,7 +258,25 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
                 seg_tab_l[x] = a.seg_tab[x];
         __syncthreads();
     }
-    for (int64_t v = blockIdx.x; v < most * a.k; v += gridDim.x) { // same order as nw_rows_kernel
+    // the extent of the lane's row in the workgroup's next tile is fetched while the current tile is sampled
+    auto extent = [&](int64_t v, int64_t &beg, int32_t &deg) {
+        beg = 0;
+        deg = 0;
+        if (v < most * a.k) {
+            const int i = (int)(v % a.k);
+            const int64_t j = v / a.k;
+            const int64_t r = a.mb_rowoff[i] + j * kRowTile + tid;
+            if (j < a.mb_tileoff[i + 1] - a.mb_tileoff[i] && r < a.mb_rowoff[i + 1]) {
+                beg = a.row_beg[r];
+                deg = a.row_deg[r];
+            }
+        }
+    };
+    int64_t beg, beg_next;
+    int32_t deg, deg_next;
+    extent(blockIdx.x, beg, deg);
+    for (int64_t v = blockIdx.x; v < most * a.k; v += gridDim.x, beg = beg_next, deg = deg_next) { // same order as nw_rows_kernel
+        extent(v + gridDim.x, beg_next, deg_next);
         const int i = (int)(v % a.k);
         const int64_t j = v / a.k;
         if (j >= a.mb_tileoff[i + 1] - a.mb_tileoff[i])
@@ -266,12 +284,9 @@ __global__ __launch_bounds__(kRowTile) void nw_sample_kernel(NwHop a, VSet vs)
         const int64_t t = a.mb_tileoff[i] + j;
         const int64_t r = a.mb_rowoff[i] + j * kRowTile + tid;
         const bool valid = r < a.mb_rowoff[i + 1];
-        int64_t beg = 0;
-        int32_t deg = 0, cnt = 0;
+        int32_t cnt = 0;
         uint32_t c[S];
         if (valid) {
-            beg = a.row_beg[r];
-            deg = a.row_deg[r];
             if (!REPLACE)
                 cnt = deg < s ? deg : s;
             else if (deg > 0) // independent draws: the row's length is the number of distinct picks
