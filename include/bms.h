@@ -177,6 +177,9 @@ int bms_sample_nodewise(bms_csr *csr, const int32_t *batches, int32_t k, int32_t
  * crosses the multiples of 2^16 in vertex id) and keep it in the handle until bms_free: n * (ceil(n / 2^16) + 1)
  * 32-bit words, built only when that is at most twice the size of the column array and a quarter of
  * opts->scratch_limit.  That call also waits for the stream once.  BMS_LADIES_NO_INDEX: neither build nor use it.
+ * A call on a recycled result whose last call had the same csr, k, b, s_per_layer and weight flag waits for the
+ * device only once, at its end (seed errors are reported then): its buffers are sized from what that call needed
+ * plus a quarter; when that does not suffice the call repeats itself with a wait per hop (bms_result_attempts = 2).
  */
 int bms_sample_ladies(bms_csr *csr, const int32_t *batches, int32_t k, int32_t b, const int32_t *s_per_layer,
                       int32_t L, uint64_t seed, const bms_opts *opts, bms_result **out);
@@ -192,6 +195,11 @@ int bms_result_ready(const bms_result *res);
 
 /* k and L of a result (either pointer may be NULL). */
 int bms_result_info(const bms_result *res, int32_t *k, int32_t *L);
+
+/* How many times the call that wrote this result enqueued its kernels: 1, or more when a kernel path gave up on
+ * the input (sizes beyond what a recycled result remembered, vertex ids crowded into a narrow range) and the call
+ * repeated itself on another path.  A count that stays above 1 call after call says the steady state is not reached. */
+int bms_result_attempts(const bms_result *res, int32_t *attempts);
 
 /* Fill *view for hop 0 <= hop < L. */
 int bms_result_hop(const bms_result *res, int32_t hop, bms_hop_view *view);

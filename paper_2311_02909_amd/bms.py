@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
         L.bms_result_wait.argtypes = [C.c_void_p]
         L.bms_result_ready.restype = C.c_int
         L.bms_result_ready.argtypes = [C.c_void_p]
+        L.bms_result_attempts.restype = C.c_int
+        L.bms_result_attempts.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         L.bms_result_info.restype = C.c_int
         L.bms_result_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.bms_result_hop.restype = C.c_int
@@ -268,6 +270,12 @@ class Result:
     def ready(self) -> bool:
         """bms_result_ready: False while an asynchronous call still runs."""
         return lib().bms_result_ready(self.handle) == 1
+
+    def attempts(self) -> int:
+        """bms_result_attempts: how many times the call that wrote this result enqueued its kernels."""
+        v = C.c_int32()
+        _check(lib().bms_result_attempts(self.handle, C.byref(v)))
+        return v.value
 
     def hop(self, h: int) -> Hop:
         v = _HopView()

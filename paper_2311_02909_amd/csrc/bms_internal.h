@@ -277,6 +277,13 @@ struct LwHop {
     int64_t *mb_coloff;        // k+1
     int32_t *col_vertex;
     int32_t *xtmp;             // D entries: the kept neighbours of row r start at gather_off[r]
+    // A call that sizes its buffers from what an earlier call of the same shape needed (no read-back of sizes on the
+    // way) runs every kernel behind a flag: the kernel that first sees a size beyond what was provided raises it,
+    // every kernel returns at once when it is up (the hop's minibatches then get no columns, so later hops have no
+    // rows), and the host repeats the call with read-backs.
+    int32_t *giveup;           // device flag, zero when the call starts
+    int64_t gathered_cap;      // gathered neighbours D that xtmp, the tiles and the staging array hold
+    int64_t p_cap, col_cap;    // entries that p_col / p_cnt, and out_col, hold
     int64_t *out_rowptr;       // rows+1
     int32_t *out_col;
 };

@@ -71,6 +71,8 @@ __global__ __launch_bounds__(1024) void ldw_plan_kernel(LwHop a)
         carry_s = 0;
         if (a.cursor)
             *a.cursor = 0;
+        if (a.giveup && a.gather_off[a.mb_rowoff[a.k]] > a.gathered_cap)
+            *a.giveup = 1; // the kernels after this one see it: they are launched after this one ends
     }
     __syncthreads();
     for (int32_t base = 0; base <= a.k; base += 1024) {
@@ -99,6 +101,8 @@ __global__ __launch_bounds__(1024) void ldw_plan_kernel(LwHop a)
 // tile_row[x] = the row that holds the first position of tile x (the last row starting at or before it)
 __global__ __launch_bounds__(256) void ldw_tile_rows_kernel(LwHop a)
 {
+    if (a.giveup && *a.giveup)
+        return;
     const int64_t ntiles = a.mb_gtileoff[a.k];
     for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < ntiles; x += (int64_t)gridDim.x * 256) {
         const int i = locate_segment(a.mb_gtileoff, a.k, x);
@@ -152,6 +156,8 @@ __device__ inline void ldw_walk_tile(const LwHop &a, int64_t g0, int64_t g1, int
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
 {
+    if (a.giveup && *a.giveup)
+        return;
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t ntiles = a.mb_gtileoff[a.k];
     const int64_t nrows = a.mb_rowoff[a.k];
@@ -201,6 +207,8 @@ __global__ __launch_bounds__(256) void ldw_bounds_kernel(LwHop a)
 __global__ __launch_bounds__(256) void ldw_bounds_transpose_kernel(LwHop a)
 {
     __shared__ uint32_t tile[64][65];
+    if (a.giveup && *a.giveup)
+        return;
     const int64_t ncols = a.nwin + 1;
     const int64_t nrows = a.index ? a.mb_rowoff[a.k] : a.rows_bound;
     const int64_t tiles_c = (ncols + 63) / 64, tiles_r = (nrows + 63) / 64;
@@ -209,9 +217,12 @@ __global__ __launch_bounds__(256) void ldw_bounds_transpose_kernel(LwHop a)
         const int64_t r0 = (t / tiles_c) * 64, c0 = (t % tiles_c) * 64;
         for (int y = ty; y < 64; y += 4)
             if (r0 + y < nrows && c0 + tx < ncols) {
-                const uint32_t *__restrict__ src =
-                    a.index ? a.index + (int64_t)a.row_vertex[r0 + y] * ncols : a.bounds + (r0 + y) * ncols;
-                tile[y][tx] = src[c0 + tx];
+                if (a.index) { // a seed outside [0, n) is an error reported elsewhere; its row has no neighbours
+                    const int64_t v = a.row_vertex[r0 + y];
+                    tile[y][tx] = (v >= 0 && v < a.n) ? a.index[v * ncols + c0 + tx] : 0u;
+                } else {
+                    tile[y][tx] = a.bounds[(r0 + y) * ncols + c0 + tx];
+                }
             }
         __syncthreads();
         for (int y = ty; y < 64; y += 4)
@@ -225,6 +236,8 @@ __global__ __launch_bounds__(256) void ldw_bounds_transpose_kernel(LwHop a)
 __global__ __launch_bounds__(256) void ldw_win_added_kernel(LwHop a)
 {
     __shared__ uint32_t wsum[4];
+    if (a.giveup && *a.giveup)
+        return;
     const int tid = threadIdx.x;
     const int64_t nblk = (int64_t)a.k * a.nwin;
     for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
@@ -250,6 +263,8 @@ __global__ __launch_bounds__(256) void ldw_win_added_kernel(LwHop a)
 __global__ __launch_bounds__(kAccThreads) void ldw_accumulate_kernel(LwHop a)
 {
     extern __shared__ uint32_t lds[];
+    if (a.giveup && *a.giveup)
+        return;
     uint32_t *cnt = lds;                   // kWinWords packed counters
     unsigned long long *claim_s = reinterpret_cast<unsigned long long *>(lds + kWinWords); // [2], in turn: where the
                                            // entries of the current (minibatch, window) start in the staging array
@@ -466,6 +481,11 @@ __global__ __launch_bounds__(256) void ldw_win_scan_kernel(LwHop a)
     __shared__ uint64_t smem[4];
     __shared__ uint64_t carry_c, carry_w;
     const int i = blockIdx.x, tid = threadIdx.x;
+    if (a.giveup && *a.giveup) {
+        if (tid == 0)
+            a.mb_count[i] = 0;
+        return;
+    }
     if (tid == 0) {
         carry_c = 0;
         carry_w = 0;
@@ -513,6 +533,15 @@ constexpr int kPrefixBlock = 16; // entries of P per kept prefix sum
 constexpr int kCopyUnroll = 4;
 __global__ __launch_bounds__(256) void ldw_p_copy_kernel(LwHop a)
 {
+    if (a.giveup) {
+        if (*a.giveup)
+            return;
+        if (a.p_off[a.k] > a.p_cap) { // P does not fit what was provided (the same in every workgroup)
+            if (blockIdx.x == 0 && threadIdx.x == 0)
+                *a.giveup = 1;
+            return;
+        }
+    }
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t nparts = (int64_t)a.k * a.nwin * kWinParts;
     for (int64_t part = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave; part < nparts; part += (int64_t)gridDim.x * 4) {
@@ -568,6 +597,11 @@ __global__ __launch_bounds__(1024) void ldw_draw_kernel(LwHop a)
     __shared__ uint32_t smem[16];
     __shared__ uint64_t top[kDrawTop];
     const int i = blockIdx.x, tid = threadIdx.x;
+    if (a.giveup && (*a.giveup || a.p_off[a.k] > a.p_cap)) { // no P: the minibatch gets no columns
+        if (tid == 0)
+            a.mb_count[i] = 0;
+        return;
+    }
     const int64_t p0 = a.p_off[i], C = a.p_off[i + 1] - p0;
     uint32_t M = 1024; // sorted size: a power of two >= s, at least one slot per thread
     while (M < (uint32_t)a.s)
@@ -656,6 +690,8 @@ __global__ __launch_bounds__(1024) void ldw_draw_kernel(LwHop a)
 
 __global__ __launch_bounds__(256) void ldw_sel_copy_kernel(LwHop a)
 {
+    if (a.giveup && *a.giveup)
+        return;
     const int i = blockIdx.x;
     const int64_t c0 = a.mb_coloff[i], cnt = a.mb_coloff[i + 1] - c0;
     for (int64_t j = threadIdx.x; j < cnt; j += 256)
@@ -676,6 +712,8 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
     __shared__ uint16_t hval[kHashSlots];
     __shared__ uint32_t maybe[kFilterWords]; // bit h set: some sampled column hashes to h
     __shared__ uint32_t queue_all[kExtWaves * 2 * kWave]; // per wave: neighbours that passed the filter, in row order
+    if (a.giveup && *a.giveup)
+        return;
     const int i = blockIdx.y, tid = threadIdx.x, lane = tid & (kWave - 1);
     uint32_t *queue = queue_all + (tid / kWave) * 2 * kWave;
     const int64_t c0 = a.mb_coloff[i];
@@ -797,6 +835,15 @@ __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
 __global__ __launch_bounds__(256) void ldw_extract_copy_kernel(LwHop a)
 {
     const int64_t R = a.mb_rowoff[a.k];
+    if (a.giveup) {
+        if (*a.giveup)
+            return;
+        if (a.out_rowptr[R] > a.col_cap) { // the kept neighbours do not fit what was provided
+            if (blockIdx.x == 0 && threadIdx.x == 0)
+                *a.giveup = 1;
+            return;
+        }
+    }
     const int sub = threadIdx.x & 15;
     const int64_t groups = (int64_t)gridDim.x * 16;
     for (int64_t r = (int64_t)blockIdx.x * 16 + threadIdx.x / 16; r < R; r += groups) {
