@@ -215,15 +215,23 @@ __global__ __launch_bounds__(256) void ldw_bounds_transpose_kernel(LwHop a)
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int64_t t = blockIdx.x; t < tiles_c * tiles_r; t += gridDim.x) {
         const int64_t r0 = (t / tiles_c) * 64, c0 = (t % tiles_c) * 64;
-        for (int y = ty; y < 64; y += 4)
-            if (r0 + y < nrows && c0 + tx < ncols) {
-                if (a.index) { // a seed outside [0, n) is an error reported elsewhere; its row has no neighbours
-                    const int64_t v = a.row_vertex[r0 + y];
-                    tile[y][tx] = (v >= 0 && v < a.n) ? a.index[v * ncols + c0 + tx] : 0u;
-                } else {
+        if (a.index) { // the rows' vertices first, then all of a thread's 16 reads of the index in flight together
+            int64_t v[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                v[q] = r0 + ty + 4 * q < nrows ? (int64_t)a.row_vertex[r0 + ty + 4 * q] : -1;
+            uint32_t x[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) // a seed outside [0, n) is an error reported elsewhere; its row has no neighbours
+                x[q] = (v[q] >= 0 && v[q] < a.n && c0 + tx < ncols) ? a.index[v[q] * ncols + c0 + tx] : 0u;
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                tile[ty + 4 * q][tx] = x[q];
+        } else {
+            for (int y = ty; y < 64; y += 4)
+                if (r0 + y < nrows && c0 + tx < ncols)
                     tile[y][tx] = a.bounds[(r0 + y) * ncols + c0 + tx];
-                }
-            }
+        }
         __syncthreads();
         for (int y = ty; y < 64; y += 4)
             if (c0 + y < ncols && r0 + tx < nrows)
