@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 # the line "bench constant ..." of profiles/<workload>_hbm_traffic.txt (tests/test_bench_constants.py compares
 # them); a kernel that has changed since its profile was taken has no entry (None in the output).
 MEASURED_TRAFFIC = {
-    ("dense_ladies", "ldw_accumulate"): 3_303_733_883,
-    ("dense_ladies", "ldw_extract"): 2_029_111_515,
+    ("dense_ladies", "ldw_accumulate"): 3_306_661_531,
+    ("dense_ladies", "ldw_extract"): 2_028_819_451,
     ("dense_sage", "nw_sample"): 10_725_266_816,
     ("dense_sage", "nw_rows"): 1_381_184_365,
     ("dense_sage", "dd_split"): 1_126_002_752,
@@ -47,8 +47,8 @@ MEASURED_TRAFFIC = {
     ("large_sage", "dd_unsplit"): 649_595_373,
     ("large_sage", "dd_rank"): 599_131_113,
     ("large_sage", "dd_front"): 473_539_835,
-    ("mid_ladies", "ldw_accumulate"): 148_752_374,
-    ("mid_ladies", "ldw_extract"): 85_112_064,
+    ("mid_ladies", "ldw_accumulate"): 148_766_249,
+    ("mid_ladies", "ldw_extract"): 85_081_901,
     ("mid_sage", "nw_sample"): 3_146_607_341,
     ("mid_sage", "dd_split"): 423_537_353,
     ("mid_sage", "dd_unsplit"): 358_643_373,
@@ -58,10 +58,10 @@ MEASURED_TRAFFIC = {
 }
 # the same summed over every kernel of one bulk call (bytes per step)
 MEASURED_CALL_TRAFFIC = {
-    "dense_ladies": 9_681_670_125,
+    "dense_ladies": 9_685_326_445,
     "dense_sage": 15_690_468_000,
     "large_sage": 10_023_240_850,
-    "mid_ladies": 486_088_333,
+    "mid_ladies": 486_398_610,
     "mid_sage": 4_800_853_732,
 }
 OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
