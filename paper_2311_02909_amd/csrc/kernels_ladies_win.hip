@@ -3,24 +3,25 @@
 //
 // The rows of A are sorted by column, so the neighbours of a frontier row that fall into a window
 // of 2^16 vertex ids form one contiguous piece of its adjacency list.  One hop, all k minibatches:
-//   ldw_tiles       the gathered order (the neighbour lists of the stacked frontier laid end to
-//                   end) cut into tiles of 1024..4096 positions (few gathered neighbours: small tiles, so that every
-//                   wave still gets some) that never straddle minibatches; the
-//                   row each tile starts in
-//   ldw_bounds      one wave per tile streams its pieces of rows once and records where every
-//                   row crosses every window boundary (lower bounds, one list per row; a transpose then makes
-//                   them window-major for the next kernel).  A row's list depends on its vertex alone: when
-//                   the lists of all n vertices fit in memory they are computed once per graph by this same
-//                   kernel (the "hop" being the whole graph) and a hop only copies the lists of its rows
-//   ldw_accumulate  one workgroup per (minibatch, window): 2^16 packed 16-bit counters in LDS
-//                   (128 KB); every row's piece of the window adds 1 per neighbour (e_v cannot
-//                   exceed the number of frontier rows, which this path keeps below 2^16); the
-//                   nonzero counters leave in ascending column order as (column, e_v) through a
-//                   device-wide cursor
-//   ldw_win_scan    per minibatch: columns and weight before every window
-//   ldw_p_copy      windows copied to their place in P; inclusive prefix sums of the integer
-//                   weights (e_v or e_v^2) on the way (NORM stays implicit: draws are integers
-//                   below the row sum)
+//   ldw_plan, ldw_tile_rows
+//                   the gathered order (the neighbour lists of the stacked frontier laid end to end) cut into
+//                   tiles of 1024..4096 positions (few gathered neighbours: small tiles, so that every wave still
+//                   gets some) that never straddle minibatches; the row each tile starts in
+//   ldw_bounds      where every row crosses every window boundary (lower bounds, one list per row).  A row's list
+//                   depends on its vertex alone: when the lists of all n vertices fit in memory they are computed
+//                   once per graph (one wave per tile streams its pieces of rows, the "hop" being the whole
+//                   graph) and a hop only copies the lists of its rows; else the hop streams its rows for them.
+//                   Either way the lists are turned window-major for the next kernel
+//   ldw_win_added   neighbours of every (minibatch, window): the lengths of its pieces added up
+//   ldw_accumulate  one workgroup per (minibatch, window): 2^16 packed 16-bit counters in LDS (128 KB); every
+//                   row's piece of the window adds 1 per neighbour (e_v cannot exceed the number of frontier
+//                   rows, which this path keeps below 2^16); each wave then compacts its sixteenth of the window
+//                   (a part): the nonzero counters leave in ascending column order as 4-byte entries
+//                   (column - window start, e_v) into room claimed from a device-wide cursor
+//   ldw_win_scan    per minibatch: columns and weight of every window, before each of its parts, before the window
+//   ldw_p_copy      parts copied to their place in P, one wave per part; inclusive prefix sums of the integer
+//                   weights (e_v or e_v^2) on the way, one kept per 16 entries (NORM stays implicit: draws are
+//                   integers below the row sum)
 //   ldw_draw        SAMPLE (Sec. 4.2.2): one workgroup per minibatch: s draws, each the smallest t
 //                   with prefix[t] > r, sorted in LDS, duplicates dropped -> sampled columns
 //   ldw_extract     EXTRACT (Sec. 4.2.3): the sampled columns of the minibatch sit in an LDS hash
@@ -28,6 +29,7 @@
 //                   second time and keeps the neighbours found in the table ((Q_R A) Q_C), in
 //                   row order, piece by piece; rows are then sized by a scan and their pieces
 //                   copied to their place
+// A call that sizes its buffers from an earlier call of the same shape runs all of these behind LwHop::giveup.
 #include "bms_device.h"
 #include "bms_internal.h"
 #include <algorithm>
