@@ -1166,6 +1166,10 @@ int sample_ladies_windows_once(CallCtx &c, const int32_t *batches, const int32_t
         // every part of a window claims room for as many columns as it has ids, or as the window has neighbours
         const int64_t tmp_cap = std::max<int64_t>(std::min<int64_t>(kWinParts * D, (int64_t)nw << kWinShift), 1);
         const size_t tbytes = (size_t)tmp_cap * 4 + (size_t)std::max<int64_t>(D, 1) * 4;
+        if (no_wait && (int64_t)(tbytes + blists * bbytes) > c.scratch_limit) {
+            *redo = true; // the margin does not fit the limit; the exact sizes may
+            return BMS_OK;
+        }
         if ((int64_t)(tbytes + blists * bbytes) > c.scratch_limit)
             return fail(BMS_ENOMEM, "%lld gathered neighbours need %zu bytes of scratch, limit is %lld: raise "
                                     "bms_opts.scratch_limit or sample fewer minibatches per call",

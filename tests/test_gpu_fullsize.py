@@ -57,9 +57,12 @@ def test_workload_with_ids_sorted_by_degree_matches_oracle(name):
     rp, cl, bt = g.rowptr.cpu().numpy(), g.col.cpu().numpy(), batches.cpu().numpy()
     ref = O.sample_nodewise(rp, cl, bt, w["params"], synth.SAMPLING_SEED)
     res = None
+    attempts = []
     for call in range(3):
         res = bms.sample_nodewise(csr, batches, w["params"], synth.SAMPLING_SEED, recycle=res, profile=True)
+        attempts.append(res.attempts())
         assert_hops_equal(res.hops(), ref, what="%s by degree, call %d" % (name, call))
+    assert attempts[0] > 1 and attempts[2] == 1, attempts  # the first call repeats itself, the steady state does not
     stages = {s for s, _, _ in res.stages()}
     assert "dd_unsplit" in stages, "no hop of the steady-state call went through the segment kernels: %s" % sorted(stages)
     # other batches of the same split keep using the table
