@@ -139,7 +139,7 @@ struct DedupArgs {
     uint16_t *ranks;     // nnz, parallel to ids_seg: rank of the id among the distinct ids of its segment
     uint32_t *uids;      // nnz: the distinct ids of a segment in ascending order, at the head of the segment's slots
 };
-constexpr int kSplitTile16 = 16384; // positions per tile of the count, split and un-split kernels
+constexpr int kSplitTile16 = 8192; // positions per tile of the count, split and un-split kernels
 constexpr int kSegCap = 65535;      // most entries a segment may hold: the rank of an id inside its segment has 16 bits
 constexpr int kMaxSegments = 2560;  // 3 words each beside the staging of the split / un-split kernels must fit in 160 KB of LDS
 constexpr int kMaxCells = 4096;      // cells of the table that maps ids to segments of unequal width

@@ -29,7 +29,7 @@
 
 namespace bms {
 
-constexpr int kLocShift = 14; // bits of the place inside a run (a tile holds 2^14 positions)
+constexpr int kLocShift = 13; // bits of the place inside a run (a tile holds 2^14 positions)
 static_assert(kSplitTile16 == (1 << kLocShift) && kMaxSegments <= (1 << (32 - kLocShift)), "loc word out of step");
 
 // The table of segments of unequal width, copied to LDS by the kernels that look ids up (tab_l: kMaxCells + 1 entries).
@@ -983,7 +983,7 @@ void launch_nw_extract_segments(const Launch &L, const DedupArgs &a, const int64
     const int64_t tiles = nnz / kSplitTile16 + a.k;
     hipLaunchKernelGGL(dd_plan_kernel, dim3(a.k + 1), dim3(256), 0, L.stream, a, out_rowptr, mb_rowoff, counted ? 1 : 0);
     if (!counted) {
-        hipLaunchKernelGGL((dd_count_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 2)), dim3(1024), 0, L.stream, a,
+        hipLaunchKernelGGL((dd_count_kernel<kSplitTile16, 512>), dim3(grid_for(L, tiles, 4)), dim3(512), 0, L.stream, a,
                            a.big_tileoff);
         hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
     }
@@ -992,13 +992,13 @@ void launch_nw_extract_segments(const Launch &L, const DedupArgs &a, const int64
         static bool attr_set = false;
         const size_t lds = (size_t)kSplitTile16 * sizeof(uint32_t) + 3 * (size_t)a.C * sizeof(uint32_t);
         if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_split_kernel<kSplitTile16, 1024>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_split_kernel<kSplitTile16, 512>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)(kSplitTile16 * sizeof(uint32_t) + 3 * kMaxSegments * sizeof(uint32_t))) != hipSuccess)
                 (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
             attr_set = true;
         }
-        hipLaunchKernelGGL((dd_split_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 2)), dim3(1024), lds,
+        hipLaunchKernelGGL((dd_split_kernel<kSplitTile16, 512>), dim3(grid_for(L, tiles, 4)), dim3(512), lds,
                            L.stream, a, a.big_tileoff);
     }
     mark("dd_rank");
@@ -1035,14 +1035,14 @@ void launch_nw_dedup_unsplit(const Launch &L, const DedupArgs &a, int64_t nnz)
     static bool attr_set = false;
     const size_t lds = 2 * (size_t)kSplitTile16 * sizeof(uint32_t) + (3 * (size_t)a.C + 1) * sizeof(uint32_t);
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_unsplit_kernel<kSplitTile16, 1024>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_unsplit_kernel<kSplitTile16, 512>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(2 * kSplitTile16 * sizeof(uint32_t) + (3 * kMaxSegments + 1) * sizeof(uint32_t))) != hipSuccess)
             (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
         attr_set = true;
     }
     const int64_t tiles = nnz / kSplitTile16 + a.k;
-    hipLaunchKernelGGL((dd_unsplit_kernel<kSplitTile16, 1024>), dim3(grid_for(L, tiles, 1)), dim3(1024), lds, L.stream, a,
+    hipLaunchKernelGGL((dd_unsplit_kernel<kSplitTile16, 512>), dim3(grid_for(L, tiles, 2)), dim3(512), lds, L.stream, a,
                        a.big_tileoff);
 }
 
