@@ -799,7 +799,7 @@ int sample_nodewise_once(CallCtx &c, const int32_t *batches, const int32_t *fano
             }
             const size_t stride = (size_t)std::max<int64_t>(nbuckets, C);
             const size_t kC = (size_t)c.k * (size_t)C;
-            const int64_t xtiles = nnz / kSplitTile16 + c.k; // tiles of the cut
+            const int64_t xtiles = nnz / kCutTile + c.k; // tiles of the cut
             BMS_TRY(csr->dd_uniq.ensure((size_t)c.k * stride * sizeof(uint32_t)));
             BMS_TRY(csr->dd_seg.ensure((3 * kC + (size_t)c.k + 16) * sizeof(uint32_t)));
             BMS_TRY(csr->dd_segcnt.ensure(std::max<size_t>(kC, 1) * sizeof(uint32_t)));

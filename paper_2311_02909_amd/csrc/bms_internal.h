@@ -127,7 +127,7 @@ struct DedupArgs {
     uint32_t *seg_cnt;   // k * C: entries per segment, later distinct ids per segment
     uint32_t *seg_off;   // k * (C+1): exclusive scan of the entry counts
     uint32_t *seg_cursor; // k * C
-    int64_t *big_tileoff; // k+1: tiles of kSplitTile16 positions
+    int64_t *big_tileoff; // k+1: tiles of kCutTile positions
     uint32_t *big_list;  // k * C: segments that one workgroup of the ranking kernel does not take (too many entries, or
                          // too many of them in one narrow id range): ranked through a bitmap of the id range
     uint32_t *big_count; // device counter of big_list (the word after `fallback`)
@@ -139,7 +139,7 @@ struct DedupArgs {
     uint16_t *ranks;     // nnz, parallel to ids_seg: rank of the id among the distinct ids of its segment
     uint32_t *uids;      // nnz: the distinct ids of a segment in ascending order, at the head of the segment's slots
 };
-constexpr int kSplitTile16 = 8192; // positions per tile of the count, split and un-split kernels
+constexpr int kCutTile = 8192; // positions per tile of the count, split and un-split kernels
 constexpr int kSegCap = 65535;      // most entries a segment may hold: the rank of an id inside its segment has 16 bits
 constexpr int kMaxSegments = 2560;  // 3 words each beside the staging of the split / un-split kernels must fit in 160 KB of LDS
 constexpr int kMaxCells = 4096;      // cells of the table that maps ids to segments of unequal width

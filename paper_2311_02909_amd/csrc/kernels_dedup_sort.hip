@@ -6,7 +6,7 @@
 // ranks come back along the same runs.  All kernels run on every compute unit, whatever the
 // number of minibatches.
 //
-//   count    per tile of 16384 positions: LDS histogram over the C segments -> global counts
+//   count    per tile of 8192 positions: LDS histogram over the C segments -> global counts
 //   scan     per minibatch: segment offsets; segments too long for one workgroup are listed for the
 //            bitmap kernel; raises the fallback flag when a segment fits neither (ids crowded into a
 //            narrow range) -- then these kernels do nothing and the per-minibatch kernel of
@@ -29,8 +29,8 @@
 
 namespace bms {
 
-constexpr int kLocShift = 13; // bits of the place inside a run (a tile holds 2^14 positions)
-static_assert(kSplitTile16 == (1 << kLocShift) && kMaxSegments <= (1 << (32 - kLocShift)), "loc word out of step");
+constexpr int kLocShift = 13; // bits of the place inside a run (a tile holds 2^13 positions)
+static_assert(kCutTile == (1 << kLocShift) && kMaxSegments <= (1 << (32 - kLocShift)), "loc word out of step");
 
 // The table of segments of unequal width, copied to LDS by the kernels that look ids up (tab_l: kMaxCells + 1 entries).
 __device__ inline void load_seg_table(const DedupArgs &a, uint16_t *tab_l, int nthreads)
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void dd_plan_kernel(DedupArgs a, const int64_t
             a.mb_edgeoff[i] = e0;
             if (i == a.k - 1)
                 a.mb_edgeoff[a.k] = e1;
-            cnt = (e1 - e0 + kSplitTile16 - 1) / kSplitTile16;
+            cnt = (e1 - e0 + kCutTile - 1) / kCutTile;
         }
         int64_t total;
         const int64_t ex = block_exclusive_scan<int64_t, 256>(cnt, smem64, total);
@@ -980,25 +980,25 @@ void launch_nw_extract_segments(const Launch &L, const DedupArgs &a, const int64
                                 uint32_t *done, int64_t nnz, bool counted, const StageMark &mark)
 {
     mark("dd_plan");
-    const int64_t tiles = nnz / kSplitTile16 + a.k;
+    const int64_t tiles = nnz / kCutTile + a.k;
     hipLaunchKernelGGL(dd_plan_kernel, dim3(a.k + 1), dim3(256), 0, L.stream, a, out_rowptr, mb_rowoff, counted ? 1 : 0);
     if (!counted) {
-        hipLaunchKernelGGL((dd_count_kernel<kSplitTile16, 512>), dim3(grid_for(L, tiles, 4)), dim3(512), 0, L.stream, a,
+        hipLaunchKernelGGL((dd_count_kernel<kCutTile, 512>), dim3(grid_for(L, tiles, 4)), dim3(512), 0, L.stream, a,
                            a.big_tileoff);
         hipLaunchKernelGGL(dd_seg_scan_kernel, dim3(a.k), dim3(256), 0, L.stream, a);
     }
     mark("dd_split");
-    { // 16384 ids per step, two workgroups of 16 waves per compute unit
+    { // 8192 ids per step, workgroups of 8 waves, several per compute unit
         static bool attr_set = false;
-        const size_t lds = (size_t)kSplitTile16 * sizeof(uint32_t) + 3 * (size_t)a.C * sizeof(uint32_t);
+        const size_t lds = (size_t)kCutTile * sizeof(uint32_t) + 3 * (size_t)a.C * sizeof(uint32_t);
         if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_split_kernel<kSplitTile16, 512>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_split_kernel<kCutTile, 512>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)(kSplitTile16 * sizeof(uint32_t) + 3 * kMaxSegments * sizeof(uint32_t))) != hipSuccess)
+                                    (int)(kCutTile * sizeof(uint32_t) + 3 * kMaxSegments * sizeof(uint32_t))) != hipSuccess)
                 (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
             attr_set = true;
         }
-        hipLaunchKernelGGL((dd_split_kernel<kSplitTile16, 512>), dim3(grid_for(L, tiles, 4)), dim3(512), lds,
+        hipLaunchKernelGGL((dd_split_kernel<kCutTile, 512>), dim3(grid_for(L, tiles, 4)), dim3(512), lds,
                            L.stream, a, a.big_tileoff);
     }
     mark("dd_rank");
@@ -1033,16 +1033,16 @@ void launch_nw_extract_segments(const Launch &L, const DedupArgs &a, const int64
 void launch_nw_dedup_unsplit(const Launch &L, const DedupArgs &a, int64_t nnz)
 {
     static bool attr_set = false;
-    const size_t lds = 2 * (size_t)kSplitTile16 * sizeof(uint32_t) + (3 * (size_t)a.C + 1) * sizeof(uint32_t);
+    const size_t lds = 2 * (size_t)kCutTile * sizeof(uint32_t) + (3 * (size_t)a.C + 1) * sizeof(uint32_t);
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_unsplit_kernel<kSplitTile16, 512>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(dd_unsplit_kernel<kCutTile, 512>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(2 * kSplitTile16 * sizeof(uint32_t) + (3 * kMaxSegments + 1) * sizeof(uint32_t))) != hipSuccess)
+                                (int)(2 * kCutTile * sizeof(uint32_t) + (3 * kMaxSegments + 1) * sizeof(uint32_t))) != hipSuccess)
             (void)hipGetLastError(); // not required on every runtime; a refused launch shows in the caller's error check
         attr_set = true;
     }
-    const int64_t tiles = nnz / kSplitTile16 + a.k;
-    hipLaunchKernelGGL((dd_unsplit_kernel<kSplitTile16, 512>), dim3(grid_for(L, tiles, 2)), dim3(512), lds, L.stream, a,
+    const int64_t tiles = nnz / kCutTile + a.k;
+    hipLaunchKernelGGL((dd_unsplit_kernel<kCutTile, 512>), dim3(grid_for(L, tiles, 2)), dim3(512), lds, L.stream, a,
                        a.big_tileoff);
 }
 
