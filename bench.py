@@ -35,34 +35,34 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC = {
     ("dense_ladies", "ldw_accumulate"): 3_306_661_531,
     ("dense_ladies", "ldw_extract"): 2_028_819_451,
-    ("dense_sage", "nw_sample"): 10_725_266_816,
-    ("dense_sage", "nw_rows"): 1_381_184_365,
-    ("dense_sage", "dd_split"): 1_126_002_752,
-    ("dense_sage", "dd_unsplit"): 962_654_500,
-    ("dense_sage", "dd_rank"): 875_334_642,
-    ("dense_sage", "dd_front"): 616_757_746,
-    ("large_sage", "nw_sample"): 5_907_070_889,
-    ("large_sage", "nw_rows"): 1_649_367_766,
-    ("large_sage", "dd_split"): 740_625_197,
-    ("large_sage", "dd_unsplit"): 649_595_373,
-    ("large_sage", "dd_rank"): 599_131_113,
-    ("large_sage", "dd_front"): 473_539_835,
+    ("dense_sage", "nw_sample"): 10_619_753_760,
+    ("dense_sage", "nw_rows"): 1_379_272_096,
+    ("dense_sage", "dd_split"): 1_138_991_268,
+    ("dense_sage", "dd_unsplit"): 1_001_343_017,
+    ("dense_sage", "dd_rank"): 875_271_634,
+    ("dense_sage", "dd_front"): 616_770_066,
+    ("large_sage", "nw_sample"): 5_716_071_922,
+    ("large_sage", "nw_rows"): 1_649_649_339,
+    ("large_sage", "dd_split"): 753_356_804,
+    ("large_sage", "dd_unsplit"): 682_846_788,
+    ("large_sage", "dd_rank"): 599_108_329,
+    ("large_sage", "dd_front"): 473_554_418,
     ("mid_ladies", "ldw_accumulate"): 148_766_249,
     ("mid_ladies", "ldw_extract"): 85_081_901,
-    ("mid_sage", "nw_sample"): 3_146_607_341,
-    ("mid_sage", "dd_split"): 423_537_353,
-    ("mid_sage", "dd_unsplit"): 358_643_373,
-    ("mid_sage", "nw_rows"): 352_049_545,
-    ("mid_sage", "dd_rank"): 315_079_177,
-    ("mid_sage", "dd_front"): 204_167_108,
+    ("mid_sage", "nw_sample"): 3_060_700_205,
+    ("mid_sage", "dd_split"): 426_376_214,
+    ("mid_sage", "dd_unsplit"): 366_985_101,
+    ("mid_sage", "nw_rows"): 351_932_041,
+    ("mid_sage", "dd_rank"): 314_712_068,
+    ("mid_sage", "dd_front"): 204_159_766,
 }
 # the same summed over every kernel of one bulk call (bytes per step)
 MEASURED_CALL_TRAFFIC = {
     "dense_ladies": 9_685_326_445,
-    "dense_sage": 15_690_468_000,
-    "large_sage": 10_023_240_850,
+    "dense_sage": 15_634_668_434,
+    "large_sage": 9_878_498_779,
     "mid_ladies": 486_398_610,
-    "mid_sage": 4_800_853_732,
+    "mid_sage": 4_725_634_948,
 }
 OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
 
