@@ -711,10 +711,13 @@ __global__ __launch_bounds__(256) void ldw_sel_copy_kernel(LwHop a)
 // ---------------------------------------------------------------------------------------------
 // EXTRACT: blockIdx.y = minibatch; the workgroups of a minibatch share its rows wave by wave
 // ---------------------------------------------------------------------------------------------
-// 16 hash bits: all of them index the filter bitmap, the low 13 the table
-__device__ inline uint32_t ldw_hash(uint32_t v) { return (v * 0x9E3779B1u) >> 16; }
+// kFilterBits hash bits: all of them index the filter bitmap (16 KB: with up to 4096 sampled columns about 1.5 % of
+// the neighbours pass, half of what a 2^16-bit filter lets through; twice the size would cost the second workgroup
+// per compute unit), the low 13 the table
+constexpr int kFilterBits = 17;
+__device__ inline uint32_t ldw_hash(uint32_t v) { return (v * 0x9E3779B1u) >> (32 - kFilterBits); }
 static_assert(kHashSlots == 1 << 13, "hash width out of step");
-constexpr int kFilterWords = 65536 / 32;
+constexpr int kFilterWords = (1 << kFilterBits) / 32;
 
 __global__ __launch_bounds__(kExtThreads) void ldw_extract_kernel(LwHop a)
 {
