@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 # the line "bench constant ..." of profiles/<workload>_hbm_traffic.txt (tests/test_bench_constants.py compares
 # them); a kernel that has changed since its profile was taken has no entry (None in the output).
 MEASURED_TRAFFIC = {
-    ("dense_ladies", "ldw_accumulate"): 3_306_661_531,
-    ("dense_ladies", "ldw_extract"): 2_028_819_451,
+    ("dense_ladies", "ldw_accumulate"): 3_308_734_816,
+    ("dense_ladies", "ldw_extract"): 2_026_395_190,
     ("dense_sage", "nw_sample"): 10_619_753_760,
     ("dense_sage", "nw_rows"): 1_379_272_096,
     ("dense_sage", "dd_split"): 1_138_991_268,
@@ -47,8 +47,8 @@ MEASURED_TRAFFIC = {
     ("large_sage", "dd_unsplit"): 682_846_788,
     ("large_sage", "dd_rank"): 599_108_329,
     ("large_sage", "dd_front"): 473_554_418,
-    ("mid_ladies", "ldw_accumulate"): 148_766_249,
-    ("mid_ladies", "ldw_extract"): 85_081_901,
+    ("mid_ladies", "ldw_accumulate"): 148_771_117,
+    ("mid_ladies", "ldw_extract"): 85_080_091,
     ("mid_sage", "nw_sample"): 3_060_700_205,
     ("mid_sage", "dd_split"): 426_376_214,
     ("mid_sage", "dd_unsplit"): 366_985_101,
@@ -58,10 +58,10 @@ MEASURED_TRAFFIC = {
 }
 # the same summed over every kernel of one bulk call (bytes per step)
 MEASURED_CALL_TRAFFIC = {
-    "dense_ladies": 9_685_326_445,
+    "dense_ladies": 9_685_282_825,
     "dense_sage": 15_634_668_434,
     "large_sage": 9_878_498_779,
-    "mid_ladies": 486_398_610,
+    "mid_ladies": 486_247_881,
     "mid_sage": 4_725_634_948,
 }
 OTHER_WORKLOADS = ("mid_sage", "dense_sage", "mid_ladies", "dense_ladies", "tiny_sage")
