@@ -222,3 +222,20 @@ def test_recycled_calls_without_size_read_backs_and_their_fallback(mods):
     # another shape on the same result: nothing remembered applies
     res = bms.sample_ladies(csr, torch.from_numpy(hubs[:2]).cuda(), s, 10, recycle=res)
     assert_hops_equal(res.hops(), O.sample_ladies(rowptr, col, hubs[:2], s, 10), with_p=True, what="other shape")
+
+
+def test_shapes_around_the_window_and_part_boundaries(mods):
+    # vertex counts just below, at and above one and two id windows (2^16); one seed per minibatch; one draw;
+    # as many draws as the LDS path takes; recycled calls (sizes remembered) in between
+    rng = np.random.default_rng(99)
+    cases = [(65535, 3, 7, (5, 3)), (65536, 2, 1, (1, 1, 1)), (65537, 4, 33, (64, 1)), (131071, 1, 50, (200,)),
+             (131072, 5, 20, (4096, 17)), (131073, 2, 64, (100, 100, 100)), (4097, 3, 16, (33, 9)), (70, 2, 5, (4, 4))]
+    for n, k, b, s in cases:
+        rowptr, col = random_csr(n, 12.0, rng)
+        batches = random_batches(n, k, b, rng)
+        csr, res, _ = _run_both(mods, rowptr, col, batches, s, 40 + k, mb_base=k, squared=bool(b & 1))
+        O, bms, _ = mods
+        for seed in (1, 2):
+            res = bms.sample_ladies(csr, torch.from_numpy(batches).cuda(), s, seed, squared=bool(b & 1), recycle=res)
+            assert_hops_equal(res.hops(), O.sample_ladies(rowptr, col, batches, s, seed, 0, bool(b & 1)), with_p=True,
+                              what="n=%d k=%d b=%d s=%s seed=%d" % (n, k, b, s, seed))
