@@ -456,3 +456,25 @@ def test_sort_extract_dense_hops_ranked_by_bitmap_with_many_duplicates(mods):
     for extract in ("sort", None):
         res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (8, 4), 22, extract=extract)
         assert_hops_equal(res.hops(), ref, what="extract=%s" % extract)
+
+
+@pytest.mark.parametrize("b", [1023, 1024, 1025, 2048, 3072])
+def test_sort_extract_minibatches_that_fill_tiles_of_the_cut_exactly(mods, b):
+    # every vertex has 10 neighbours, fanout 8: a minibatch samples exactly 8 b ids, i.e. one short of, exactly, or
+    # one more than whole tiles of 8192 positions of the cut; the second hop (fanout 2) does the same on distinct ids
+    O, bms, _ = mods
+    n = 150_000
+    v = np.arange(n, dtype=np.int64)
+    nb = np.stack([(v + d) % n for d in (-5, -4, -3, -2, -1, 1, 2, 3, 4, 5)], axis=1)
+    nb.sort(axis=1)
+    rowptr = np.arange(n + 1, dtype=np.int64) * 10
+    col = nb.reshape(-1).astype(np.int32)
+    rng = np.random.default_rng(b)
+    batches = random_batches(n, 3, b, rng)
+    ref = O.sample_nodewise(rowptr, col, batches, (8, 2), 31)
+    assert ref[0].nnz == 3 * 8 * b
+    csr = bms.Csr(torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda())
+    res = None
+    for _ in range(2):
+        res = bms.sample_nodewise(csr, torch.from_numpy(batches).cuda(), (8, 2), 31, extract="sort", recycle=res)
+        assert_hops_equal(res.hops(), ref, what="b=%d" % b)
